@@ -1,0 +1,101 @@
+/*
+ * path_attn.h -- C ABI of the PaTH attention hot path for AMD MI355X (gfx950).
+ *
+ * PaTH attention (paper Sec. 2.2) is causal softmax attention whose logit is
+ *
+ *     s_ij = scale * q_i^T H_i H_{i-1} ... H_{j+1} k_j ,   H_t = I - beta_t w_t w_t^T ,
+ *
+ * (j <= i; empty product for j = i), with o_i = sum_j softmax_j(s_ij) v_j and
+ * lse_i = log sum_j exp(s_ij).  The library evaluates it with the paper's
+ * blockwise algorithm (Sec. 3.2-3.3): per chunk of 64 tokens a UT transform
+ * (triangular solve) gives boundary-adjusted queries/keys and the chunk's
+ * transition product; a FlashAttention-style right-to-left sweep over key
+ * chunks then applies that product to the resident query tile after each
+ * chunk.  All arithmetic runs in hand-written gfx950 kernels.
+ *
+ * Conventions common to every entry point
+ *  - Every data pointer is DEVICE memory owned by the caller.  The library
+ *    never allocates, frees or synchronises; all kernels are enqueued on
+ *    `stream` (a hipStream_t passed as void*, NULL = the null stream).
+ *  - Layout: q, k, v, w, o, d_o, dq, dk, dv, dw are contiguous [B, H, L, d];
+ *    beta, dbeta, lse are contiguous [B, H, L].  w and beta are per token and
+ *    per head.  No grouped-query sharing.
+ *  - dtype `dt` is the storage type of q,k,v,w,beta,o and of all gradients
+ *    (PATH_F32: float, PATH_BF16: bfloat16).  lse is always float.
+ *    PATH_BF16 contracts on bf16 MFMA with fp32 accumulation; PATH_F32
+ *    contracts on fp32 MFMA.
+ *  - d must be 64 or 128; any L >= 1 (a ragged last chunk is handled inside).
+ *  - `scale` multiplies the finished bilinear form (the paper's logits are
+ *    unscaled: pass 1.0f for those).  lse uses the natural logarithm.
+ *  - w is used as given (no normalisation), beta as given (no clipping).
+ *  - Only causal attention is defined by the method (the transition product
+ *    runs along the path j -> i): causal == 0 returns PATH_ERR_UNSUPPORTED.
+ *  - `workspace` is caller-owned device scratch of at least
+ *    path_attn_workspace_bytes(...) bytes, 256-byte aligned; its contents are
+ *    undefined afterwards.  Calls that share a workspace must be ordered on
+ *    one stream.
+ *  - Errors are reported by return code before anything is launched (bad
+ *    arguments) or after a failed launch (PATH_ERR_HIP); the library never
+ *    aborts or throws.  Outputs are fully overwritten on PATH_OK.
+ */
+#ifndef PATH_ATTN_H
+#define PATH_ATTN_H
+
+#include <stddef.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { PATH_F32 = 0, PATH_BF16 = 1 } path_dtype_t;
+
+typedef enum {
+    PATH_OK = 0,
+    PATH_ERR_NULL = 1,        /* a required pointer is NULL                         */
+    PATH_ERR_SHAPE = 2,       /* B,H,L < 1, d not in {64,128}, or sizes overflow     */
+    PATH_ERR_DTYPE = 3,       /* dt is not PATH_F32 / PATH_BF16                      */
+    PATH_ERR_UNSUPPORTED = 4, /* causal == 0                                         */
+    PATH_ERR_WORKSPACE = 5,   /* workspace too small or misaligned                   */
+    PATH_ERR_HIP = 6          /* a kernel launch failed                              */
+} path_status_t;
+
+/* Human-readable name of a status code (static storage, never NULL). */
+const char* path_status_str(path_status_t status);
+
+/* Bytes of device workspace needed by path_attn_fwd (for_backward == 0) or
+ * path_attn_bwd (for_backward != 0) for this problem.  Returns 0 for
+ * arguments the entry points would reject. */
+size_t path_attn_workspace_bytes(int B, int H, int L, int d, path_dtype_t dt, int for_backward);
+
+/*
+ * Forward (paper Sec. 2.2 definition; Sec. 3.2-3.3 blockwise algorithm).
+ *   in : q, k, v, w [B,H,L,d] (dt), beta [B,H,L] (dt)       -- device, read-only
+ *   out: o [B,H,L,d] (dt), lse [B,H,L] (float)              -- device
+ */
+path_status_t path_attn_fwd(const void* q, const void* k, const void* v, const void* w,
+                            const void* beta, void* o, float* lse,
+                            int B, int H, int L, int d, int causal, float scale,
+                            path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+/*
+ * Backward of loss = sum(d_o * o) (the paper states no backward; this is the
+ * reverse-mode derivative of the forward above, through the chunk transform).
+ *   in : q, k, v, w, beta as in the forward; o, lse as the forward wrote them;
+ *        d_o [B,H,L,d] (dt)                                  -- device, read-only
+ *   out: dq, dk, dv, dw [B,H,L,d] (dt), dbeta [B,H,L] (dt)   -- device
+ * dw is the gradient with respect to the w passed in (no projection onto the
+ * unit sphere).  Accumulation across query tiles uses float atomics, so the
+ * low-order bits of dk, dv, dw, dbeta may differ from run to run.
+ */
+path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const void* w,
+                            const void* beta, const void* o, const float* lse, const void* d_o,
+                            void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                            int B, int H, int L, int d, int causal, float scale,
+                            path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                            void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PATH_ATTN_H */

@@ -1,0 +1,143 @@
+"""Thin ctypes binding over ``libpath_attn.so`` (the C ABI of include/path_attn.h).
+
+Argument marshalling only: every step of the hot path runs inside the HIP
+kernels of the library.  PyTorch is used for device memory and the current
+stream.  If the library has not been built the functions raise -- there is no
+CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+PATH_F32 = 0
+PATH_BF16 = 1
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpath_attn.so")
+_lib = None
+
+
+class PathAttnError(RuntimeError):
+    def __init__(self, code: int, name: str):
+        super().__init__(f"path_attn: {name} (status {code})")
+        self.code = code
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads the HIP library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} is missing: build it first (python -m paper_2505_16381_amd.build). "
+            "There is no fallback path.")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
+    lib.path_status_str.restype = ctypes.c_char_p
+    lib.path_status_str.argtypes = [ci]
+    lib.path_attn_workspace_bytes.restype = sz
+    lib.path_attn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+    lib.path_attn_fwd.restype = ci
+    lib.path_attn_fwd.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_bwd.restype = ci
+    lib.path_attn_bwd.argtypes = [vp] * 13 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    _lib = lib
+    return lib
+
+
+def path_status_str(code: int) -> str:
+    return load_library().path_status_str(int(code)).decode()
+
+
+def path_attn_workspace_bytes(B, H, L, d, dt, for_backward=False) -> int:
+    return int(load_library().path_attn_workspace_bytes(B, H, L, d, dt, int(bool(for_backward))))
+
+
+def _ptr(x):
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    return x.data_ptr()
+
+
+def _check(code):
+    if code != 0:
+        raise PathAttnError(code, path_status_str(code))
+
+
+def _dt_of(t):
+    import torch
+    if t.dtype == torch.float32:
+        return PATH_F32
+    if t.dtype == torch.bfloat16:
+        return PATH_BF16
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream_handle(stream):
+    import torch
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _workspace(nbytes, like, workspace):
+    import torch
+    if workspace is None:
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=like.device)
+    return workspace
+
+
+def path_attn_fwd(q, k, v, w, beta, scale=None, causal=True, o=None, lse=None,
+                  workspace=None, stream=None):
+    """o, lse = PaTH attention forward.  q,k,v,w: [B,H,L,d]; beta: [B,H,L] (CUDA tensors)."""
+    import torch
+    lib = load_library()
+    B, H, L, d = q.shape
+    dt = _dt_of(q)
+    for t in (q, k, v, w, beta):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == q.dtype
+    assert k.shape == q.shape and v.shape == q.shape and w.shape == q.shape
+    assert tuple(beta.shape) == (B, H, L)
+    if scale is None:
+        scale = float(d) ** -0.5
+    if o is None:
+        o = torch.empty_like(q)
+    if lse is None:
+        lse = torch.empty((B, H, L), dtype=torch.float32, device=q.device)
+    nbytes = path_attn_workspace_bytes(B, H, L, d, dt, False)
+    workspace = _workspace(nbytes, q, workspace)
+    _check(lib.path_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(o), _ptr(lse),
+                             B, H, L, d, int(bool(causal)), float(scale), dt,
+                             _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return o, lse
+
+
+def path_attn_bwd(q, k, v, w, beta, o, lse, d_o, scale=None, causal=True,
+                  workspace=None, stream=None):
+    """dq, dk, dv, dw, dbeta = gradients of sum(d_o * o)."""
+    import torch
+    lib = load_library()
+    B, H, L, d = q.shape
+    dt = _dt_of(q)
+    for t in (q, k, v, w, beta, o, d_o):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == q.dtype
+    assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32
+    if scale is None:
+        scale = float(d) ** -0.5
+    dq, dk, dv, dw = (torch.empty_like(q) for _ in range(4))
+    dbeta = torch.empty_like(beta)
+    nbytes = path_attn_workspace_bytes(B, H, L, d, dt, True)
+    workspace = _workspace(nbytes, q, workspace)
+    _check(lib.path_attn_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(o), _ptr(lse),
+                             _ptr(d_o), _ptr(dq), _ptr(dk), _ptr(dv), _ptr(dw), _ptr(dbeta),
+                             B, H, L, d, int(bool(causal)), float(scale), dt,
+                             _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return dq, dk, dv, dw, dbeta

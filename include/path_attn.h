@@ -56,7 +56,8 @@ typedef enum {
     PATH_ERR_DTYPE = 3,       /* dt is not PATH_F32 / PATH_BF16                      */
     PATH_ERR_UNSUPPORTED = 4, /* causal == 0                                         */
     PATH_ERR_WORKSPACE = 5,   /* workspace too small or misaligned                   */
-    PATH_ERR_HIP = 6          /* a kernel launch failed                              */
+    PATH_ERR_HIP = 6,         /* a kernel launch failed                              */
+    PATH_ERR_ALIGN = 7        /* q,k,v,w,o (or a gradient) not 16-byte aligned       */
 } path_status_t;
 
 /* Human-readable name of a status code (static storage, never NULL). */
@@ -66,6 +67,15 @@ const char* path_status_str(path_status_t status);
  * path_attn_bwd (for_backward != 0) for this problem.  Returns 0 for
  * arguments the entry points would reject. */
 size_t path_attn_workspace_bytes(int B, int H, int L, int d, path_dtype_t dt, int for_backward);
+
+/* Introspection for tests and profiling: byte offsets, inside the forward
+ * workspace, of the five intermediates the chunk-preprocessing kernel (paper
+ * Sec. 3.2) hands to the sweep kernel, in this order: boundary-adjusted key
+ * tiles, V^T tiles, negated chunk-product tiles (I - P), boundary-adjusted
+ * queries (fp32), diagonal-block logits (fp32); offsets[5] = total bytes.
+ * Returns PATH_ERR_SHAPE / PATH_ERR_DTYPE for arguments the forward rejects. */
+path_status_t path_attn_fwd_workspace_layout(int B, int H, int L, int d, path_dtype_t dt,
+                                             size_t offsets[6]);
 
 /*
  * Forward (paper Sec. 2.2 definition; Sec. 3.2-3.3 blockwise algorithm).

@@ -43,6 +43,8 @@ def load_library():
     lib.path_status_str.argtypes = [ci]
     lib.path_attn_workspace_bytes.restype = sz
     lib.path_attn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
+    lib.path_attn_fwd_workspace_layout.restype = ci
+    lib.path_attn_fwd_workspace_layout.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(sz)]
     lib.path_attn_fwd.restype = ci
     lib.path_attn_fwd.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_attn_bwd.restype = ci
@@ -57,6 +59,13 @@ def path_status_str(code: int) -> str:
 
 def path_attn_workspace_bytes(B, H, L, d, dt, for_backward=False) -> int:
     return int(load_library().path_attn_workspace_bytes(B, H, L, d, dt, int(bool(for_backward))))
+
+
+def path_attn_fwd_workspace_layout(B, H, L, d, dt):
+    """Byte offsets (kt, vt, dp, xinit, sd, total) of the forward workspace."""
+    arr = (ctypes.c_size_t * 6)()
+    _check(load_library().path_attn_fwd_workspace_layout(B, H, L, d, dt, arr))
+    return tuple(int(x) for x in arr)
 
 
 def _ptr(x):

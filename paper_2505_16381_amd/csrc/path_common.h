@@ -1,0 +1,165 @@
+// Shared device-side definitions of the PaTH attention kernels (gfx950 only).
+//
+// Register/fragment conventions used by every kernel
+// --------------------------------------------------
+// All contractions run on the 32x32 MFMA tile of a 64-lane wavefront.  Lane
+// l = 32*h + c (h = l/32, c = l%32) owns column c of the 32x32 fp32 result;
+// its 16 accumulator registers j = 0..15 hold rows
+//
+//        acc_row(j, h) = 8*(j/4) + 4*h + (j%4).
+//
+// An operand fragment is 16 bytes per lane: FE = 8 bf16 or 4 fp32 elements.
+// One "slab" is what one fragment pair contracts: KW = 2*FE indices
+// (bf16: one v_mfma_f32_32x32x16_bf16; fp32: four v_mfma_f32_32x32x2_f32).
+//
+// Activations (query state X, probabilities P) never leave registers: a
+// result in accumulator layout is re-used as the B operand of the next
+// contraction by packing registers [s*FE, (s+1)*FE) of a 32-row block into
+// slab s.  That fixes which contraction index sits in which fragment element,
+//
+//        index(block b, slab s, half h, element e) = 32*b + acc_row(s*FE+e, h),
+//
+// so the other operand (K, V^T, chunk products), which streams through LDS,
+// is stored by the preprocessing kernel in exactly that order ("fragment
+// order"): fragment ((rb*(Kc/KW) + slab)*64 + lane) of a tile with rows
+// 32*rb + c and Kc contraction indices.  Lanes then read consecutive 16-byte
+// fragments: conflict-free LDS reads and linear global->LDS copies.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace path {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half_t;
+typedef _Float16 halfx8 __attribute__((ext_vector_type(8)));
+typedef _Float16 halfx4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int CHUNK = 64;      // tokens per chunk (UT transform block)
+constexpr int QTILE = 128;     // query rows per workgroup of the sweep (4 waves x 32)
+
+__device__ __forceinline__ int acc_row(int j, int h) { return 8 * (j >> 2) + 4 * h + (j & 3); }
+
+template <typename T> struct Tr;
+
+template <> struct Tr<bf16_t> {
+    static constexpr int FE = 8;    // elements per 16-byte fragment
+    static constexpr int KW = 16;   // contraction indices per slab
+    typedef bf16x8 Frag;
+    typedef bf16x4 Vec4;            // 4 consecutive elements
+    static __device__ __forceinline__ f32x16 mma(Frag a, Frag b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+    }
+    // slab s of a 32-row accumulator block as an operand fragment
+    template <int S> static __device__ __forceinline__ Frag pack(const f32x16& a) {
+        Frag f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = (bf16_t)a[S * 8 + e];
+        return f;
+    }
+    static __device__ __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f[e] = (bf16_t)0.0f; return f; }
+};
+
+template <> struct Tr<half_t> {
+    static constexpr int FE = 8;
+    static constexpr int KW = 16;
+    typedef halfx8 Frag;
+    typedef halfx4 Vec4;
+    static __device__ __forceinline__ f32x16 mma(Frag a, Frag b, f32x16 c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+    }
+    template <int S> static __device__ __forceinline__ Frag pack(const f32x16& a) {
+        Frag f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) f[e] = (half_t)a[S * 8 + e];
+        return f;
+    }
+    static __device__ __forceinline__ Frag zero() { Frag f; for (int e = 0; e < 8; ++e) f[e] = (half_t)0.0f; return f; }
+};
+
+template <> struct Tr<float> {
+    static constexpr int FE = 4;
+    static constexpr int KW = 8;
+    typedef f32x4 Frag;
+    typedef f32x4 Vec4;
+    static __device__ __forceinline__ f32x16 mma(Frag a, Frag b, f32x16 c) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) c = __builtin_amdgcn_mfma_f32_32x32x2f32(a[e], b[e], c, 0, 0, 0);
+        return c;
+    }
+    template <int S> static __device__ __forceinline__ Frag pack(const f32x16& a) {
+        Frag f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) f[e] = a[S * 4 + e];
+        return f;
+    }
+    static __device__ __forceinline__ Frag zero() { Frag f = {0.f, 0.f, 0.f, 0.f}; return f; }
+};
+
+// Operand type of the TRANSPORTED quantities (query state, boundary-adjusted
+// keys, chunk products and everything inside the chunk transform) for a given
+// I/O type.  With bf16 I/O these are carried in fp16: they are not
+// representable in the input precision, and their rounding -- not the
+// inputs' -- sets the error of the logits; bf16's 8 significand bits leave the
+// log-sum-exp about 1.1e-3..2.8e-3 off, fp16's 11 bits about 2e-4, at the same
+// MFMA rate.  (The method's transitions are contractions for beta in [0,2],
+// |w| <= 1, so these operands are bounded by the norms of q and k, which must
+// stay below the fp16 maximum 65504.)  P and V stay in the I/O type.
+template <typename TIO> struct Compute { typedef TIO type; };
+template <> struct Compute<bf16_t> { typedef half_t type; };
+
+template <typename TO, typename TI>
+__device__ __forceinline__ typename Tr<TO>::Frag cvt_frag(const typename Tr<TI>::Frag& f) {
+    typename Tr<TO>::Frag o;
+#pragma unroll
+    for (int e = 0; e < Tr<TI>::FE; ++e) o[e] = (TO)(float)f[e];
+    return o;
+}
+
+// Number of slabs in a 32-index block / in Kc indices.
+template <typename T> constexpr int slabs_per_block() { return 32 / Tr<T>::KW; }
+
+// All slabs of one 32-row accumulator block -> operand fragments dst[0 .. 32/KW).
+template <typename T> __device__ __forceinline__ void pack_block(const f32x16& a, typename Tr<T>::Frag* dst);
+template <> __device__ __forceinline__ void pack_block<bf16_t>(const f32x16& a, bf16x8* dst) {
+    dst[0] = Tr<bf16_t>::pack<0>(a);
+    dst[1] = Tr<bf16_t>::pack<1>(a);
+}
+template <> __device__ __forceinline__ void pack_block<half_t>(const f32x16& a, halfx8* dst) {
+    dst[0] = Tr<half_t>::pack<0>(a);
+    dst[1] = Tr<half_t>::pack<1>(a);
+}
+template <> __device__ __forceinline__ void pack_block<float>(const f32x16& a, f32x4* dst) {
+    dst[0] = Tr<float>::pack<0>(a);
+    dst[1] = Tr<float>::pack<1>(a);
+    dst[2] = Tr<float>::pack<2>(a);
+    dst[3] = Tr<float>::pack<3>(a);
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int j = 0; j < 16; ++j) z[j] = 0.f;
+    return z;
+}
+
+// Workspace carve-up shared by host launch code and kernels (byte offsets, 256-aligned).
+struct FwdWorkspace {
+    size_t kt, vt, dp, xinit, sd, total;
+};
+
+struct FwdParams {
+    const void *q, *k, *v, *w, *beta;
+    void* o;
+    float* lse;
+    void *kt, *vt, *dp;   // fragment-order tiles written by prep, read by the sweep
+    float *xinit, *sd;    // accumulator-order fp32 tiles
+    int B, H, L, NC;      // NC = number of 64-token chunks = ceil(L/64)
+    float scale;
+};
+
+}  // namespace path

@@ -1,0 +1,366 @@
+// Chunk preprocessing of PaTH attention (paper Sec. 3.2: UT transform of a
+// chunk, boundary-adjusted queries and keys, chunk transition product).
+//
+// One workgroup (4 waves) per (batch*head, chunk of 64 tokens).  With
+// Q, K, W the chunk's rows and beta its transition strengths:
+//
+//   G   = W W^T                       A = I + strictLower(diag(beta) G)
+//   N   = A^{-1} diag(beta)           (the chunk's "T^{-1}", Sec. 3 UT paragraph)
+//   U   = N W                         dP = W^T U   (chunk product P = I - dP)
+//   F   = tril(Q W^T)                 Y  = N strictLower(W K^T)
+//   Qb  = Q - F U                     Kb = K - Y^T W            (Sec. 3.2 matrix forms)
+//   Sd  = Q K^T - F Y                 (diagonal block logits, Sec. 3.2 case i = j)
+//
+// The triangular system is solved by forward substitution in fp32 (never
+// through 1/beta, so beta = 0 is regular); everything else is MFMA.
+// Outputs go to the workspace in the layouts the sweep kernel consumes
+// without any shuffling: K-tile, V^T-tile and -dP-tile in fragment order,
+// Qb and Sd in accumulator order (fp32).  Rows past L are treated as
+// beta = 0, w = k = q = v = 0.
+#include "path_common.h"
+
+namespace path {
+
+// TIO: storage type of the inputs; T = Compute<TIO>::type: operand type of the transform.
+template <typename TIO, int D> struct PrepCfg {
+    typedef typename Compute<TIO>::type T;
+    static constexpr int FE = Tr<T>::FE;
+    static constexpr int KW = Tr<T>::KW;
+    static constexpr bool STAGE_QK = sizeof(TIO) == 2;   // fp32 reads Q,K fragments from global
+    static constexpr int LDD = D + FE;                 // padded length-D rows
+    static constexpr int LDC = CHUNK + FE;             // padded length-64 rows
+    static constexpr int LDA = CHUNK + 4;              // fp32 solve matrix
+    static constexpr int WSUT = (CHUNK * LDD > D * LDC) ? CHUNK * LDD : D * LDC;
+    // element offsets (in T) -- every block is a multiple of 16 bytes
+    static constexpr size_t off_ws = 0;                               // W rows, later U^T
+    static constexpr size_t off_wt = off_ws + WSUT;                   // W^T
+    static constexpr size_t off_f = off_wt + (size_t)D * LDC;         // F
+    static constexpr size_t off_gk = off_f + (size_t)CHUNK * LDC;     // (strictLower(W K^T))^T
+    static constexpr size_t off_yt = off_gk + (size_t)CHUNK * LDC;    // Y^T
+    static constexpr size_t off_nt = off_yt + (size_t)CHUNK * LDC;    // N (operand precision)
+    static constexpr size_t off_qs = off_nt + (size_t)CHUNK * LDC;    // Q rows (staged only)
+    static constexpr size_t off_ks = off_qs + (STAGE_QK ? (size_t)CHUNK * LDD : 0);
+    static constexpr size_t t_elems = off_ks + (STAGE_QK ? (size_t)CHUNK * LDD : 0);
+    static constexpr size_t off_af_bytes = ((t_elems * sizeof(T) + 15) / 16) * 16;   // fp32 A / solve
+    static constexpr size_t off_beta_bytes = off_af_bytes + (size_t)CHUNK * LDA * 4;
+    static constexpr size_t smem_bytes = off_beta_bytes + CHUNK * 4;
+};
+
+template <typename T>
+__device__ __forceinline__ typename Tr<T>::Frag ld_frag(const T* p) {
+    return *reinterpret_cast<const typename Tr<T>::Frag*>(p);
+}
+
+// acc += A[arow0 + c][0..Kc) . B[brow0 + c'][0..Kc)  for a 32x32 block; both
+// operands are stored with the contraction index contiguous.
+template <typename T, int Kc>
+__device__ __forceinline__ f32x16 gemm32(const T* A, int lda, int arow0, const T* Bm, int ldb,
+                                         int brow0, int l32, int h, f32x16 acc) {
+    constexpr int FE = Tr<T>::FE, KW = Tr<T>::KW;
+    const T* ap = A + (size_t)(arow0 + l32) * lda + FE * h;
+    const T* bp = Bm + (size_t)(brow0 + l32) * ldb + FE * h;
+#pragma unroll
+    for (int k0 = 0; k0 < Kc; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
+    return acc;
+}
+
+template <typename TIO, int D>
+__global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
+    using C = PrepCfg<TIO, D>;
+    using T = typename C::T;
+    using Frag = typename Tr<T>::Frag;
+    using FragV = typename Tr<TIO>::Frag;
+    using Vec4 = typename Tr<T>::Vec4;
+    constexpr int FE = C::FE, KW = C::KW, LDD = C::LDD, LDC = C::LDC, LDA = C::LDA;
+    constexpr int SPB = 32 / KW;   // slabs per 32-index block
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    T* sT = reinterpret_cast<T*>(smem);
+    T* Ws = sT + C::off_ws;
+    T* Ut = Ws;                      // U^T re-uses W's rows once phase 1 is over
+    T* Wt = sT + C::off_wt;
+    T* Fs = sT + C::off_f;
+    T* Gk = sT + C::off_gk;
+    T* Yt = sT + C::off_yt;
+    T* Nt = sT + C::off_nt;
+    float* Af = reinterpret_cast<float*>(smem + C::off_af_bytes);
+    float* bs = reinterpret_cast<float*>(smem + C::off_beta_bytes);
+
+    const int chunk = blockIdx.x, bh = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int L = p.L, NC = p.NC;
+    const int t0 = chunk * CHUNK;
+    const int nvalid = (L - t0 < CHUNK) ? (L - t0) : CHUNK;
+    const size_t rowbase = ((size_t)bh * L + t0) * D;
+    const TIO* Qg = reinterpret_cast<const TIO*>(p.q) + rowbase;
+    const TIO* Kg = reinterpret_cast<const TIO*>(p.k) + rowbase;
+    const TIO* Vg = reinterpret_cast<const TIO*>(p.v) + rowbase;
+    const TIO* Wg = reinterpret_cast<const TIO*>(p.w) + rowbase;
+    const TIO* Bg = reinterpret_cast<const TIO*>(p.beta) + (size_t)bh * L + t0;
+
+    // ---- phase 0: stage the chunk (zero rows past L) ---------------------------
+    for (int idx = tid; idx < CHUNK * (D / FE); idx += 256) {
+        const int row = idx / (D / FE), cf = idx % (D / FE);
+        Frag wv_ = Tr<T>::zero(), qv = Tr<T>::zero(), kv = Tr<T>::zero();
+        if (row < nvalid) {
+            wv_ = cvt_frag<T, TIO>(ld_frag<TIO>(Wg + (size_t)row * D + cf * FE));
+            if (C::STAGE_QK) {
+                qv = cvt_frag<T, TIO>(ld_frag<TIO>(Qg + (size_t)row * D + cf * FE));
+                kv = cvt_frag<T, TIO>(ld_frag<TIO>(Kg + (size_t)row * D + cf * FE));
+            }
+        }
+        *reinterpret_cast<Frag*>(Ws + row * LDD + cf * FE) = wv_;
+#pragma unroll
+        for (int e = 0; e < FE; ++e) Wt[(cf * FE + e) * LDC + row] = wv_[e];
+        if (C::STAGE_QK) {
+            *reinterpret_cast<Frag*>(sT + C::off_qs + row * LDD + cf * FE) = qv;
+            *reinterpret_cast<Frag*>(sT + C::off_ks + row * LDD + cf * FE) = kv;
+        }
+    }
+    if (tid < CHUNK) bs[tid] = (tid < nvalid) ? (float)Bg[tid] : 0.f;
+    __syncthreads();
+
+    // Operand views of Q and K (LDS when staged; global otherwise -- then rows
+    // past L must not be touched, so those lanes are redirected to row 0 and
+    // their products masked out by the zero W / explicit masks below).
+    const T* Qp; const T* Kp; int ldqk;
+    if (C::STAGE_QK) { Qp = sT + C::off_qs; Kp = sT + C::off_ks; ldqk = LDD; }
+    else { Qp = reinterpret_cast<const T*>(Qg); Kp = reinterpret_cast<const T*>(Kg); ldqk = D; }   // T == TIO here
+
+    const int bi = wv >> 1, bj = wv & 1;   // this wave's 32x32 block of a 64x64 result
+
+    // Row of Q/K this lane supplies as an operand row (clamped for the global path).
+    auto qk_row = [&](int r) { return (C::STAGE_QK || r < nvalid) ? r : 0; };
+    auto qk_ok = [&](int r) { return C::STAGE_QK || r < nvalid; };
+
+    // ---- phase 1: products of the inputs ----------------------------------------
+    // G block -> Af[t][s] = beta_t G[t][s] for s < t, else 0.
+    {
+        f32x16 acc = gemm32<T, D>(Ws, LDD, 32 * bi, Ws, LDD, 32 * bj, l32, h, zero16());
+        const int s = 32 * bj + l32;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int t = 32 * bi + acc_row(j, h);
+            Af[t * LDA + s] = (s < t) ? bs[t] * acc[j] : 0.f;
+        }
+    }
+    // F block: rows t (Q), cols t' (W); keep t' <= t.
+    {
+        const int ar = 32 * bi + l32;
+        f32x16 acc = zero16();
+        {
+            const T* ap = Qp + (size_t)qk_row(ar) * ldqk + FE * h;
+            const T* bp = Ws + (size_t)(32 * bj + l32) * LDD + FE * h;
+#pragma unroll
+            for (int k0 = 0; k0 < D; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
+        }
+        const int tp = 32 * bj + l32;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int t = 32 * bi + acc_row(j, h);
+            Fs[t * LDC + tp] = (tp <= t && t < nvalid) ? (T)acc[j] : (T)0.f;
+        }
+    }
+    // Gk block: rows t' (W), cols s (K); stored transposed Gk[s][t'], keep t' > s.
+    {
+        f32x16 acc = zero16();
+        {
+            const T* ap = Ws + (size_t)(32 * bi + l32) * LDD + FE * h;
+            const T* bp = Kp + (size_t)qk_row(32 * bj + l32) * ldqk + FE * h;
+#pragma unroll
+            for (int k0 = 0; k0 < D; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
+        }
+        const int s = 32 * bj + l32;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            Vec4 v4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int tp = 32 * bi + 8 * g + 4 * h + r;
+                v4[r] = (tp > s && qk_ok(s)) ? (T)acc[4 * g + r] : (T)0.f;
+            }
+            *reinterpret_cast<Vec4*>(Gk + s * LDC + 32 * bi + 8 * g + 4 * h) = v4;
+        }
+    }
+    // K Q^T block (rows s = keys, cols t = queries): first term of Sd^T, kept in registers.
+    f32x16 accS = zero16();
+    {
+        const T* ap = Kp + (size_t)qk_row(32 * bi + l32) * ldqk + FE * h;
+        const T* bp = Qp + (size_t)qk_row(32 * bj + l32) * ldqk + FE * h;
+#pragma unroll
+        for (int k0 = 0; k0 < D; k0 += KW) accS = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), accS);
+    }
+    __syncthreads();
+
+    // ---- phase 2: N = A^{-1} diag(beta) by forward substitution (one wave) -------
+    // Column c of N depends only on itself: lane c computes N[0..63][c].
+    if (wv == 0) {
+        float n[CHUNK];
+#pragma unroll
+        for (int t = 0; t < CHUNK; ++t) n[t] = 0.f;
+        const int c = lane;
+#pragma unroll
+        for (int t = 0; t < CHUNK; ++t) {
+            float acc = (t == c) ? bs[t] : 0.f;
+#pragma unroll
+            for (int s4 = 0; s4 < (t + 3) / 4; ++s4) {
+                const f32x4 a4 = *reinterpret_cast<const f32x4*>(Af + t * LDA + 4 * s4);   // zeros for s >= t
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc -= a4[r] * n[4 * s4 + r];
+            }
+            n[t] = acc;
+            Nt[t * LDC + c] = (T)acc;
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 3: U^T = W^T N^T  and  Y^T -----------------------------------------
+    // Y block: rows t (N), cols s (Gk rows); stored transposed Yt[s][t].
+    {
+        f32x16 acc = gemm32<T, CHUNK>(Nt, LDC, 32 * bi, Gk, LDC, 32 * bj, l32, h, zero16());
+        const int s = 32 * bj + l32;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            Vec4 v4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v4[r] = (T)acc[4 * g + r];
+            *reinterpret_cast<Vec4*>(Yt + s * LDC + 32 * bi + 8 * g + 4 * h) = v4;
+        }
+    }
+    // U^T blocks: rows c (W^T), cols t (N rows).  (Ut aliases Ws: all reads of Ws are done.)
+    {
+        f32x16 accU[D / 64];
+#pragma unroll
+        for (int i = 0; i < D / 64; ++i) {
+            const int blk = wv + 4 * i;                 // (D/32)*2 blocks over 4 waves
+            const int cb = blk >> 1, tb = blk & 1;
+            accU[i] = gemm32<T, CHUNK>(Wt, LDC, 32 * cb, Nt, LDC, 32 * tb, l32, h, zero16());
+        }
+        __syncthreads();                                 // nobody still reads Ws (phase 1) -- and keeps phases apart
+#pragma unroll
+        for (int i = 0; i < D / 64; ++i) {
+            const int blk = wv + 4 * i;
+            const int cb = blk >> 1, tb = blk & 1;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) Ut[(32 * cb + acc_row(j, h)) * LDC + 32 * tb + l32] = (T)accU[i][j];
+        }
+    }
+    __syncthreads();
+
+    // ---- phase 4: outputs -----------------------------------------------------------
+    const size_t bhc = (size_t)bh * NC + chunk;
+    // (a) Sd^T = K Q^T - Y^T F^T, accumulator order: [bhc][qb][kb][g][lane][4]
+    {
+        f32x16 corr = gemm32<T, CHUNK>(Yt, LDC, 32 * bi, Fs, LDC, 32 * bj, l32, h, zero16());
+        float* dst = p.sd + (bhc * 4 + (size_t)(bj * 2 + bi)) * 1024;
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            f32x4 v4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v4[r] = accS[4 * g + r] - corr[4 * g + r];
+            *reinterpret_cast<f32x4*>(dst + (g * 64 + lane) * 4) = v4;
+        }
+    }
+    // (b) -dP tile (rows = output column b of dP, contraction = a): acc rows a, cols b.
+    {
+        Frag* dst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dp) + bhc * (size_t)D * D);
+        constexpr int NB = (D / 32) * (D / 32);
+#pragma unroll
+        for (int i = 0; i < NB / 4; ++i) {
+            const int blk = wv + 4 * i;
+            const int ab = blk / (D / 32), bb = blk % (D / 32);
+            f32x16 acc = gemm32<T, CHUNK>(Wt, LDC, 32 * ab, Ut, LDC, 32 * bb, l32, h, zero16());
+#pragma unroll
+            for (int j = 0; j < 16; ++j) acc[j] = -acc[j];
+            Frag fr[SPB];
+            pack_block<T>(acc, fr);
+#pragma unroll
+            for (int s = 0; s < SPB; ++s) dst[((size_t)bb * (D / KW) + ab * SPB + s) * 64 + lane] = fr[s];
+        }
+    }
+    // (c) Kb tile (rows = key s, contraction = c): acc rows c, cols s;  Kb^T = K^T - W^T Y.
+    // (d) Qb in accumulator order (rows c, cols t): Qb^T = Q^T - U^T F^T.
+    {
+        Frag* kdst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt) + bhc * (size_t)CHUNK * D);
+        constexpr int NB = (D / 32) * 2;
+#pragma unroll
+        for (int i = 0; i < NB / 4; ++i) {
+            const int blk = wv + 4 * i;
+            const int cb = blk >> 1, sb = blk & 1;
+            f32x16 acc = gemm32<T, CHUNK>(Wt, LDC, 32 * cb, Yt, LDC, 32 * sb, l32, h, zero16());
+            const int s = 32 * sb + l32;
+            const T* krow = Kp + (size_t)qk_row(s) * ldqk + 32 * cb + 4 * h;
+            const bool ok = qk_ok(s);
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                Vec4 k4 = *reinterpret_cast<const Vec4*>(krow + 8 * g);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) acc[4 * g + r] = (ok ? (float)k4[r] : 0.f) - acc[4 * g + r];
+            }
+            Frag fr[SPB];
+            pack_block<T>(acc, fr);
+#pragma unroll
+            for (int s2 = 0; s2 < SPB; ++s2) kdst[((size_t)sb * (D / KW) + cb * SPB + s2) * 64 + lane] = fr[s2];
+        }
+#pragma unroll
+        for (int i = 0; i < NB / 4; ++i) {
+            const int blk = wv + 4 * i;
+            const int cb = blk >> 1, tb = blk & 1;
+            f32x16 acc = gemm32<T, CHUNK>(Ut, LDC, 32 * cb, Fs, LDC, 32 * tb, l32, h, zero16());
+            const int t = 32 * tb + l32;
+            const T* qrow = Qp + (size_t)qk_row(t) * ldqk + 32 * cb + 4 * h;
+            const bool ok = qk_ok(t);
+            // xinit: [bh][query block of 32][d block][g][lane][4]
+            float* xdst = p.xinit + ((((size_t)bh * NC + chunk) * 2 + tb) * (D / 32) + cb) * 1024;
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                Vec4 q4 = *reinterpret_cast<const Vec4*>(qrow + 8 * g);
+                f32x4 v4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v4[r] = (ok ? (float)q4[r] : 0.f) - acc[4 * g + r];
+                *reinterpret_cast<f32x4*>(xdst + (g * 64 + lane) * 4) = v4;
+            }
+        }
+        // (e) V^T tile (rows = c, contraction = key s): plain re-layout of V.
+        FragV* vdst = reinterpret_cast<FragV*>(reinterpret_cast<TIO*>(p.vt) + bhc * (size_t)CHUNK * D);
+#pragma unroll
+        for (int i = 0; i < NB / 4; ++i) {
+            const int blk = wv + 4 * i;
+            const int cb = blk >> 1, sb = blk & 1;
+            const int c = 32 * cb + l32;
+            f32x16 acc;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int s = 32 * sb + acc_row(j, h);
+                acc[j] = (s < nvalid) ? (float)Vg[(size_t)s * D + c] : 0.f;
+            }
+            FragV fr[SPB];
+            pack_block<TIO>(acc, fr);
+#pragma unroll
+            for (int s2 = 0; s2 < SPB; ++s2) vdst[((size_t)cb * (CHUNK / KW) + sb * SPB + s2) * 64 + lane] = fr[s2];
+        }
+    }
+}
+
+template <typename T, int D>
+hipError_t launch_prep_fwd_t(const FwdParams& p, hipStream_t stream) {
+    using C = PrepCfg<T, D>;
+    static_assert(sizeof(typename C::T) == sizeof(T), "tile sizes assume equal operand and I/O width");
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep_fwd_kernel<T, D>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    dim3 grid(p.NC, p.B * p.H);
+    hipLaunchKernelGGL((prep_fwd_kernel<T, D>), grid, dim3(256), C::smem_bytes, stream, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_prep_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {
+    if (is_bf16) return d == 64 ? launch_prep_fwd_t<bf16_t, 64>(p, stream) : launch_prep_fwd_t<bf16_t, 128>(p, stream);
+    return d == 64 ? launch_prep_fwd_t<float, 64>(p, stream) : launch_prep_fwd_t<float, 128>(p, stream);
+}
+
+}  // namespace path

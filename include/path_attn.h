@@ -89,6 +89,21 @@ path_status_t path_attn_fwd(const void* q, const void* k, const void* v, const v
                             void* stream);
 
 /*
+ * The two stages of the forward as separate launches, for callers that want
+ * to time or overlap them; path_attn_fwd is exactly path_attn_fwd_prep
+ * followed by path_attn_fwd_sweep on the same stream and workspace.
+ *   prep  (Sec. 3.2): chunk UT transform -> workspace (reads q,k,v,w,beta)
+ *   sweep (Sec. 3.3): right-to-left scan over key chunks -> o, lse (reads workspace only)
+ * Same argument rules and error codes as path_attn_fwd.
+ */
+path_status_t path_attn_fwd_prep(const void* q, const void* k, const void* v, const void* w,
+                                 const void* beta, int B, int H, int L, int d, path_dtype_t dt,
+                                 void* workspace, size_t workspace_bytes, void* stream);
+path_status_t path_attn_fwd_sweep(void* o, float* lse, int B, int H, int L, int d, float scale,
+                                  path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                                  void* stream);
+
+/*
  * Backward of loss = sum(d_o * o) (the paper states no backward; this is the
  * reverse-mode derivative of the forward above, through the chunk transform).
  *   in : q, k, v, w, beta as in the forward; o, lse as the forward wrote them;

@@ -1,5 +1,5 @@
 """PaTH attention hot path for MI355X (gfx950): thin binding over the C-ABI library."""
 from .binding import (  # noqa: F401
     PATH_F32, PATH_BF16, PathAttnError, library_path, load_library,
-    path_attn_workspace_bytes, path_attn_fwd_workspace_layout, path_attn_fwd, path_attn_bwd, path_status_str,
+    path_attn_workspace_bytes, path_attn_fwd_workspace_layout, path_attn_fwd, path_attn_fwd_prep, path_attn_fwd_sweep, path_attn_bwd, path_status_str,
 )

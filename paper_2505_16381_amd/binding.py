@@ -47,6 +47,10 @@ def load_library():
     lib.path_attn_fwd_workspace_layout.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(sz)]
     lib.path_attn_fwd.restype = ci
     lib.path_attn_fwd.argtypes = [vp] * 7 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_fwd_prep.restype = ci
+    lib.path_attn_fwd_prep.argtypes = [vp] * 5 + [ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.path_attn_fwd_sweep.restype = ci
+    lib.path_attn_fwd_sweep.argtypes = [vp, vp, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_attn_bwd.restype = ci
     lib.path_attn_bwd.argtypes = [vp] * 13 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     _lib = lib
@@ -127,6 +131,21 @@ def path_attn_fwd(q, k, v, w, beta, scale=None, causal=True, o=None, lse=None,
                              B, H, L, d, int(bool(causal)), float(scale), dt,
                              _ptr(workspace), workspace.numel(), _stream_handle(stream)))
     return o, lse
+
+
+def path_attn_fwd_prep(q, k, v, w, beta, workspace, stream=None):
+    """Stage 1 of the forward (chunk transform) into ``workspace``."""
+    B, H, L, d = q.shape
+    _check(load_library().path_attn_fwd_prep(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), B, H, L, d,
+                                             _dt_of(q), _ptr(workspace), workspace.numel(),
+                                             _stream_handle(stream)))
+
+
+def path_attn_fwd_sweep(o, lse, scale, workspace, stream=None):
+    """Stage 2 of the forward (sweep over key chunks) from ``workspace`` into o, lse."""
+    B, H, L, d = o.shape
+    _check(load_library().path_attn_fwd_sweep(_ptr(o), _ptr(lse), B, H, L, d, float(scale), _dt_of(o),
+                                              _ptr(workspace), workspace.numel(), _stream_handle(stream)))
 
 
 def path_attn_bwd(q, k, v, w, beta, o, lse, d_o, scale=None, causal=True,

@@ -7,6 +7,11 @@ namespace path {
 hipError_t launch_prep_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 hipError_t launch_attn_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 
+hipError_t launch_attn_states(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
+}  // namespace path
+#include "bwd_decl.h"
+namespace path {
+
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static bool shape_ok(int B, int H, int L, int d) {
@@ -26,6 +31,38 @@ static FwdWorkspace fwd_workspace(int B, int H, int L, int d, size_t es) {
     w.dp = off;    off = align256(off + BH * NC * d * d * es);
     w.xinit = off; off = align256(off + BH * Lp * d * 4);
     w.sd = off;    off = align256(off + BH * NC * CHUNK * CHUNK * 4);
+    w.total = off;
+    return w;
+}
+// Backward workspace: the forward's five regions first (same carve-up), then everything else.
+struct BwdWorkspace {
+    FwdWorkspace f;
+    size_t knat, ktnat, dpnat, xs, gs, fm, gktm, nm, aim, ytm, utm, gm, sdm, delta, dqb, dkb, dvp, ddp;
+    size_t dpd, pd, dsd, df, dy, dn, dgk, rr, mm, dgs, du, dqf, dkf, dwf, dbf, total;
+};
+
+static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
+    const size_t BH = (size_t)B * H, NC = (size_t)(L + CHUNK - 1) / CHUNK, Lp = NC * CHUNK;
+    const size_t npairs = NC * (NC - 1) / 2;
+    BwdWorkspace w;
+    w.f = fwd_workspace(B, H, L, d, es);
+    size_t off = w.f.total;
+    auto take = [&](size_t& field, size_t bytes) { field = off; off = align256(off + bytes); };
+    take(w.knat, BH * Lp * d * es);
+    take(w.ktnat, BH * Lp * d * es);
+    take(w.dpnat, BH * NC * d * d * es);
+    take(w.xs, BH * npairs * CHUNK * d * es);
+    take(w.gs, BH * npairs * CHUNK * d * es);
+    for (size_t* f : {&w.fm, &w.gktm, &w.nm, &w.aim, &w.ytm}) take(*f, BH * NC * 4096 * es);
+    take(w.utm, BH * NC * d * CHUNK * es);
+    take(w.gm, BH * NC * 4096 * 4);
+    take(w.sdm, BH * NC * 4096 * 4);
+    take(w.delta, BH * Lp * 4);
+    for (size_t* f : {&w.dqb, &w.dkb, &w.dvp}) take(*f, BH * Lp * d * 4);
+    take(w.ddp, BH * NC * d * d * 4);
+    for (size_t* f : {&w.dpd, &w.pd, &w.dsd, &w.df, &w.dy, &w.dn, &w.dgk, &w.rr, &w.mm, &w.dgs}) take(*f, BH * NC * 4096 * 4);
+    for (size_t* f : {&w.du, &w.dqf, &w.dkf, &w.dwf}) take(*f, BH * Lp * d * 4);
+    take(w.dbf, BH * Lp * 4);
     w.total = off;
     return w;
 }
@@ -51,7 +88,7 @@ extern "C" size_t path_attn_workspace_bytes(int B, int H, int L, int d, path_dty
     if (!shape_ok(B, H, L, d)) return 0;
     if (dt != PATH_F32 && dt != PATH_BF16) return 0;
     const size_t es = dt == PATH_BF16 ? 2 : 4;
-    if (for_backward) return 0;   // backward: not built yet
+    if (for_backward) return bwd_workspace(B, H, L, d, es).total;
     return fwd_workspace(B, H, L, d, es).total;
 }
 
@@ -68,6 +105,47 @@ extern "C" path_status_t path_attn_fwd_workspace_layout(int B, int H, int L, int
 
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
 
+static path_status_t fwd_setup(FwdParams& p, int B, int H, int L, int d, path_dtype_t dt, void* workspace,
+                               size_t workspace_bytes) {
+    if (!workspace) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
+    const FwdWorkspace ws = fwd_workspace(B, H, L, d, dt == PATH_BF16 ? 2 : 4);
+    if (workspace_bytes < ws.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PATH_ERR_WORKSPACE;
+    unsigned char* base = static_cast<unsigned char*>(workspace);
+    p.kt = base + ws.kt; p.vt = base + ws.vt; p.dp = base + ws.dp;
+    p.xinit = reinterpret_cast<float*>(base + ws.xinit);
+    p.sd = reinterpret_cast<float*>(base + ws.sd);
+    p.B = B; p.H = H; p.L = L; p.NC = (L + CHUNK - 1) / CHUNK;
+    return PATH_OK;
+}
+
+extern "C" path_status_t path_attn_fwd_prep(const void* q, const void* k, const void* v, const void* w,
+                                            const void* beta, int B, int H, int L, int d, path_dtype_t dt,
+                                            void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !w || !beta) return PATH_ERR_NULL;
+    FwdParams p = {};
+    const path_status_t st = fwd_setup(p, B, H, L, d, dt, workspace, workspace_bytes);
+    if (st != PATH_OK) return st;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(w)) return PATH_ERR_ALIGN;
+    p.q = q; p.k = k; p.v = v; p.w = w; p.beta = beta;
+    if (launch_prep_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)) != hipSuccess) return PATH_ERR_HIP;
+    return PATH_OK;
+}
+
+extern "C" path_status_t path_attn_fwd_sweep(void* o, float* lse, int B, int H, int L, int d, float scale,
+                                             path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                                             void* stream) {
+    if (!o || !lse) return PATH_ERR_NULL;
+    FwdParams p = {};
+    const path_status_t st = fwd_setup(p, B, H, L, d, dt, workspace, workspace_bytes);
+    if (st != PATH_OK) return st;
+    if (misaligned(o)) return PATH_ERR_ALIGN;
+    p.o = o; p.lse = lse; p.scale = scale;
+    if (launch_attn_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)) != hipSuccess) return PATH_ERR_HIP;
+    return PATH_OK;
+}
+
 extern "C" path_status_t path_attn_fwd(const void* q, const void* k, const void* v, const void* w,
                                        const void* beta, void* o, float* lse, int B, int H, int L, int d,
                                        int causal, float scale, path_dtype_t dt, void* workspace,
@@ -76,22 +154,10 @@ extern "C" path_status_t path_attn_fwd(const void* q, const void* k, const void*
     if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
     if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
     if (!causal) return PATH_ERR_UNSUPPORTED;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(w) || misaligned(o)) return PATH_ERR_ALIGN;
-    const size_t es = dt == PATH_BF16 ? 2 : 4;
-    const FwdWorkspace ws = fwd_workspace(B, H, L, d, es);
-    if (workspace_bytes < ws.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PATH_ERR_WORKSPACE;
-
-    unsigned char* base = static_cast<unsigned char*>(workspace);
-    FwdParams p;
-    p.q = q; p.k = k; p.v = v; p.w = w; p.beta = beta; p.o = o; p.lse = lse;
-    p.kt = base + ws.kt; p.vt = base + ws.vt; p.dp = base + ws.dp;
-    p.xinit = reinterpret_cast<float*>(base + ws.xinit);
-    p.sd = reinterpret_cast<float*>(base + ws.sd);
-    p.B = B; p.H = H; p.L = L; p.NC = (L + CHUNK - 1) / CHUNK; p.scale = scale;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (launch_prep_fwd(p, d, dt == PATH_BF16, st) != hipSuccess) return PATH_ERR_HIP;
-    if (launch_attn_fwd(p, d, dt == PATH_BF16, st) != hipSuccess) return PATH_ERR_HIP;
-    return PATH_OK;
+    if (misaligned(o)) return PATH_ERR_ALIGN;
+    path_status_t st = path_attn_fwd_prep(q, k, v, w, beta, B, H, L, d, dt, workspace, workspace_bytes, stream);
+    if (st != PATH_OK) return st;
+    return path_attn_fwd_sweep(o, lse, B, H, L, d, scale, dt, workspace, workspace_bytes, stream);
 }
 
 extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const void* w,
@@ -99,8 +165,108 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
                                        void* dq, void* dk, void* dv, void* dw, void* dbeta, int B, int H,
                                        int L, int d, int causal, float scale, path_dtype_t dt,
                                        void* workspace, size_t workspace_bytes, void* stream) {
-    (void)q; (void)k; (void)v; (void)w; (void)beta; (void)o; (void)lse; (void)d_o; (void)dq; (void)dk;
-    (void)dv; (void)dw; (void)dbeta; (void)B; (void)H; (void)L; (void)d; (void)causal; (void)scale;
-    (void)dt; (void)workspace; (void)workspace_bytes; (void)stream;
-    return PATH_ERR_UNSUPPORTED;
+    if (!q || !k || !v || !w || !beta || !o || !lse || !d_o || !dq || !dk || !dv || !dw || !dbeta || !workspace)
+        return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
+    if (!causal) return PATH_ERR_UNSUPPORTED;
+    const void* al[] = {q, k, v, w, o, d_o, dq, dk, dv, dw};
+    for (const void* ptr : al) if (misaligned(ptr)) return PATH_ERR_ALIGN;
+    const int bf = dt == PATH_BF16;
+    const size_t es = bf ? 2 : 4;
+    const BwdWorkspace ws = bwd_workspace(B, H, L, d, es);
+    if (workspace_bytes < ws.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PATH_ERR_WORKSPACE;
+    unsigned char* base = static_cast<unsigned char*>(workspace);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int NC = (L + CHUNK - 1) / CHUNK, BH = B * H;
+    const long long Lp = (long long)NC * CHUNK;
+    auto F = [&](size_t off) { return reinterpret_cast<float*>(base + off); };
+
+    // 1. chunk transform (forward kernel, with the row-major extras) and query states
+    FwdParams fp = {};
+    fp.q = q; fp.k = k; fp.v = v; fp.w = w; fp.beta = beta;
+    fp.kt = base + ws.f.kt; fp.vt = base + ws.f.vt; fp.dp = base + ws.f.dp;
+    fp.xinit = F(ws.f.xinit); fp.sd = F(ws.f.sd);
+    fp.B = B; fp.H = H; fp.L = L; fp.NC = NC; fp.scale = scale;
+    fp.knat = base + ws.knat; fp.ktnat = base + ws.ktnat; fp.dpnat = base + ws.dpnat; fp.xs = base + ws.xs;
+    fp.fm = base + ws.fm; fp.gktm = base + ws.gktm; fp.nm = base + ws.nm; fp.aim = base + ws.aim;
+    fp.ytm = base + ws.ytm; fp.utm = base + ws.utm; fp.gm = F(ws.gm); fp.sdm = F(ws.sdm);
+    if (launch_prep_fwd(fp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;
+    if (NC > 1 && launch_attn_states(fp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;
+
+    // 2.-4. delta, adjoint scan over key chunks, key-side reductions
+    BwdParams bp = {};
+    bp.q = q; bp.k = k; bp.v = v; bp.w = w; bp.beta = beta; bp.o = o; bp.dO = d_o; bp.lse = lse;
+    bp.knat = fp.knat; bp.ktnat = fp.ktnat; bp.dpnat = fp.dpnat; bp.xs = fp.xs; bp.gs = base + ws.gs;
+    bp.delta = F(ws.delta); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
+    bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale;
+    if (launch_bwd_scan(bp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;
+
+    // 5. adjoint of the chunk transform
+    const long long c_bh = (long long)NC * 4096, c_ch = 4096;          // 64x64 per chunk
+    const long long t_bh = Lp * d, t_ch = (long long)CHUNK * d;        // padded token-major [Lp][d]
+    const long long u_bh = (long long)L * d;                           // user token-major [L][d]
+    auto chunk_n = [&](const void* p, int type) { return MatRef{p, c_bh, c_ch, 64, 1, type, TOK_NONE}; };   // [r][k]
+    auto chunk_t = [&](const void* p, int type) { return MatRef{p, c_bh, c_ch, 1, 64, type, TOK_NONE}; };   // [k][r]
+    auto tokws_n = [&](const void* p) { return MatRef{p, t_bh, t_ch, d, 1, EL_F32, TOK_NONE}; };            // rows = tokens
+    auto tokws_t = [&](const void* p) { return MatRef{p, t_bh, t_ch, 1, d, EL_F32, TOK_NONE}; };            // k = tokens
+    auto user_n = [&](const void* p) { return MatRef{p, u_bh, t_ch, d, 1, EL_IO, TOK_ROW}; };
+    auto user_t = [&](const void* p) { return MatRef{p, u_bh, t_ch, 1, d, EL_IO, TOK_K}; };
+    const MatRef U_rows{base + ws.utm, (long long)NC * d * CHUNK, (long long)d * CHUNK, 1, 64, EL_OP, TOK_NONE};  // U[t'][c]
+    const MatRef ddp_kfirst{F(ws.ddp), (long long)NC * d * d, (long long)d * d, 1, d, EL_F32, TOK_NONE};   // (n=c, k=a): ddP[a][c]
+    const MatRef ddp_nfirst{F(ws.ddp), (long long)NC * d * d, (long long)d * d, d, 1, EL_F32, TOK_NONE};   // (n=c, k=b): ddP[c][b]
+
+    bool ok = true;
+    auto gemm = [&](float* C, bool tokC, const float* Cin, MatRef A, MatRef Bm, int M, int N, int K, float alpha, int mask) {
+        if (!ok) return;
+        GemmArgs a;
+        a.A = A; a.B = Bm; a.C = C; a.Cin = Cin;
+        if (tokC) { a.c_bh = t_bh; a.c_ch = t_ch; a.crs = d; a.ccs = 1; }
+        else { a.c_bh = c_bh; a.c_ch = c_ch; a.crs = 64; a.ccs = 1; }
+        a.M = M; a.N = N; a.K = K; a.alpha = alpha; a.mask = mask; a.NC = NC; a.L = L;
+        ok = launch_batched_gemm(a, BH, bf, st) == hipSuccess;
+    };
+    float *dpd = F(ws.dpd), *pd = F(ws.pd), *dsd = F(ws.dsd), *df = F(ws.df), *dy = F(ws.dy), *dn = F(ws.dn);
+    float *dgk = F(ws.dgk), *rr = F(ws.rr), *mm = F(ws.mm), *dgs = F(ws.dgs), *du = F(ws.du);
+    float *dqf = F(ws.dqf), *dkf = F(ws.dkf), *dwf = F(ws.dwf), *dbf = F(ws.dbf);
+    float *dqb = bp.dqb, *dkb = bp.dkb, *dvp = bp.dvp;
+    void *fm = fp.fm, *gktm = fp.gktm, *nm = fp.nm, *aim = fp.aim, *ytm = fp.ytm;
+
+    // diagonal block: dPd = dO V^T, then P and dSd
+    gemm(dpd, false, nullptr, user_n(d_o), user_n(v), 64, 64, d, 1.f, MASK_NONE);
+    if (ok) {
+        DiagArgs da{fp.sdm, dpd, bp.delta, lse, pd, dsd, L, NC, scale};
+        ok = launch_bwd_diag(da, BH, st) == hipSuccess;
+    }
+    gemm(dvp, true, dvp, chunk_t(pd, EL_F32), user_t(d_o), 64, d, 64, 1.f, MASK_NONE);          // dV += P^T dO
+    gemm(dqf, true, dqb, chunk_n(dsd, EL_F32), user_t(k), 64, d, 64, 1.f, MASK_NONE);           // dQ = dQb + dSd K
+    gemm(dkf, true, dkb, chunk_t(dsd, EL_F32), user_t(q), 64, d, 64, 1.f, MASK_NONE);           // dK = dKb + dSd^T Q
+    gemm(df, false, nullptr, chunk_n(dsd, EL_F32), chunk_t(ytm, EL_OP), 64, 64, 64, -1.f, MASK_TRIL);   // dF = -dSd Y^T
+    gemm(df, false, df, tokws_n(dqb), U_rows, 64, 64, d, -1.f, MASK_TRIL);                              //      - dQb U^T
+    gemm(dy, false, nullptr, chunk_t(fm, EL_OP), chunk_t(dsd, EL_F32), 64, 64, 64, -1.f, MASK_NONE);    // dY = -F^T dSd
+    gemm(dy, false, dy, user_n(w), tokws_n(dkb), 64, 64, d, -1.f, MASK_NONE);                            //      - W dKb^T
+    gemm(du, true, nullptr, chunk_t(fm, EL_OP), tokws_t(dqb), 64, d, 64, -1.f, MASK_NONE);              // dU = -F^T dQb
+    gemm(du, true, du, user_n(w), ddp_kfirst, 64, d, d, 1.f, MASK_NONE);                                 //      + W ddP
+    gemm(dn, false, nullptr, chunk_n(dy, EL_F32), chunk_t(gktm, EL_OP), 64, 64, 64, 1.f, MASK_NONE);    // dN = dY Gk^T
+    gemm(dn, false, dn, tokws_n(du), user_n(w), 64, 64, d, 1.f, MASK_NONE);                              //      + dU W^T
+    gemm(dgk, false, nullptr, chunk_t(nm, EL_OP), chunk_t(dy, EL_F32), 64, 64, 64, 1.f, MASK_SLOWER);   // dGk = sl(N^T dY)
+    gemm(rr, false, nullptr, chunk_t(aim, EL_OP), chunk_t(dn, EL_F32), 64, 64, 64, 1.f, MASK_NONE);     // R = A^-T dN
+    gemm(mm, false, nullptr, chunk_n(rr, EL_F32), chunk_n(nm, EL_OP), 64, 64, 64, -1.f, MASK_SLOWER);   // M = sl(-R N^T)
+    if (ok) {
+        BetaArgs ba{rr, mm, fp.gm, beta, dgs, dbf, L, NC};
+        ok = launch_bwd_beta(ba, BH, bf, st) == hipSuccess;
+    }
+    gemm(dwf, true, nullptr, chunk_t(ytm, EL_OP), tokws_t(dkb), 64, d, 64, -1.f, MASK_NONE);            // dW = -Y dKb
+    gemm(dwf, true, dwf, U_rows, ddp_nfirst, 64, d, d, 1.f, MASK_NONE);                                  //    + U ddP^T
+    gemm(dwf, true, dwf, chunk_t(df, EL_F32), user_t(q), 64, d, 64, 1.f, MASK_NONE);                     //    + dF^T Q
+    gemm(dwf, true, dwf, chunk_n(dgk, EL_F32), user_t(k), 64, d, 64, 1.f, MASK_NONE);                    //    + dGk K
+    gemm(dwf, true, dwf, chunk_t(nm, EL_OP), tokws_t(du), 64, d, 64, 1.f, MASK_NONE);                    //    + N^T dU
+    gemm(dwf, true, dwf, chunk_n(dgs, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE);                    //    + (dG+dG^T) W
+    gemm(dqf, true, dqf, chunk_n(df, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE);                     // dQ += dF W
+    gemm(dkf, true, dkf, chunk_t(dgk, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE);                    // dK += dGk^T W
+    if (ok) {
+        OutArgs oa{dqf, dkf, dvp, dwf, dbf, dq, dk, dv, dw, dbeta, L, NC, d};
+        ok = launch_bwd_store(oa, BH, bf, st) == hipSuccess;
+    }
+    return ok ? PATH_OK : PATH_ERR_HIP;
 }

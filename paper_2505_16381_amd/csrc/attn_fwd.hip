@@ -29,7 +29,9 @@ template <typename T, int D> struct FwdCfg {
 };
 
 // TIO: storage type of v and o (and of P as an operand); T: operand type of X, Kb, dP.
-template <typename TIO, int D>
+// STATES_ONLY (backward): no logits, softmax or output; instead the query state of
+// every (query block, key chunk) pair is written row-major to p.xs for the backward.
+template <typename TIO, int D, bool STATES_ONLY>
 __global__ __launch_bounds__(256) void attn_fwd_kernel(FwdParams p) {
     using C = FwdCfg<TIO, D>;
     using T = typename Compute<TIO>::type;
@@ -94,12 +96,14 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(FwdParams p) {
         const bool need_dp = j < jtop && j > 0;     // some wave of the tile lies right of chunk j
         __syncthreads();
         {
-            const Frag* gk = reinterpret_cast<const Frag*>(ktg + (size_t)j * CHUNK * D);
-            const FragV* gv = reinterpret_cast<const FragV*>(vtg + (size_t)j * CHUNK * D);
+            if (!STATES_ONLY) {
+                const Frag* gk = reinterpret_cast<const Frag*>(ktg + (size_t)j * CHUNK * D);
+                const FragV* gv = reinterpret_cast<const FragV*>(vtg + (size_t)j * CHUNK * D);
 #pragma unroll
-            for (int i = 0; i < C::KV_FRAGS / 256; ++i) {
-                sK[i * 256 + tid] = gk[i * 256 + tid];
-                sV[i * 256 + tid] = gv[i * 256 + tid];
+                for (int i = 0; i < C::KV_FRAGS / 256; ++i) {
+                    sK[i * 256 + tid] = gk[i * 256 + tid];
+                    sV[i * 256 + tid] = gv[i * 256 + tid];
+                }
             }
             if (need_dp) {
                 const Frag* gp = reinterpret_cast<const Frag*>(dpg + (size_t)j * D * D);
@@ -109,6 +113,31 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(FwdParams p) {
         }
         __syncthreads();
         if (!active || j > cq) continue;
+
+        if (STATES_ONLY) {
+            if (j == cq) continue;
+            // state of this wave's 32 queries against key chunk j: xs[bh][pair(cq,j)][64][D], row-major
+            T* xrow = reinterpret_cast<T*>(p.xs) +
+                      (((size_t)bh * NC * (NC - 1) / 2 + pair_slot(cq, j)) * CHUNK + 32 * qb + l32) * D + 4 * h;
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    typename Tr<T>::Vec4 v4;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v4[r] = (T)Xm[b][4 * g + r];
+                    *reinterpret_cast<typename Tr<T>::Vec4*>(xrow + 32 * b + 8 * g) = v4;
+                }
+            if (j > 0) {
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int s = 0; s < DS; ++s) Xm[b] = Tr<T>::mma(sP[(b * DS + s) * 64 + lane], Xb[s], Xm[b]);
+#pragma unroll
+                for (int b = 0; b < DB; ++b) pack_block<T>(Xm[b], Xb + b * SPB);
+            }
+            continue;
+        }
 
         // ---- logits S^T: two 32-key blocks ----------------------------------------
         f32x16 S[2];
@@ -184,7 +213,7 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(FwdParams p) {
     }
 
     // ---- epilogue: normalise, store o and lse (paper Sec. 3.3 last step) -----------------
-    if (!active) return;
+    if (!active || STATES_ONLY) return;
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = 1.f / l_tot;
     const int tq = qblk * 32 + l32;
@@ -203,25 +232,31 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(FwdParams p) {
     }
 }
 
-template <typename T, int D>
+template <typename T, int D, bool STATES_ONLY>
 hipError_t launch_attn_fwd_t(const FwdParams& p, hipStream_t stream) {
     using C = FwdCfg<T, D>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<T, D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd_kernel<T, D, STATES_ONLY>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     const int ntiles = (p.NC + 1) / 2;
     dim3 grid((unsigned)(ntiles * p.B * p.H));
-    hipLaunchKernelGGL((attn_fwd_kernel<T, D>), grid, dim3(256), C::smem_bytes, stream, p);
+    hipLaunchKernelGGL((attn_fwd_kernel<T, D, STATES_ONLY>), grid, dim3(256), C::smem_bytes, stream, p);
     return hipGetLastError();
 }
 
 hipError_t launch_attn_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {
-    if (is_bf16) return d == 64 ? launch_attn_fwd_t<bf16_t, 64>(p, stream) : launch_attn_fwd_t<bf16_t, 128>(p, stream);
-    return d == 64 ? launch_attn_fwd_t<float, 64>(p, stream) : launch_attn_fwd_t<float, 128>(p, stream);
+    if (is_bf16) return d == 64 ? launch_attn_fwd_t<bf16_t, 64, false>(p, stream) : launch_attn_fwd_t<bf16_t, 128, false>(p, stream);
+    return d == 64 ? launch_attn_fwd_t<float, 64, false>(p, stream) : launch_attn_fwd_t<float, 128, false>(p, stream);
+}
+
+// Backward helper: the same sweep, query states only (written to p.xs).
+hipError_t launch_attn_states(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {
+    if (is_bf16) return d == 64 ? launch_attn_fwd_t<bf16_t, 64, true>(p, stream) : launch_attn_fwd_t<bf16_t, 128, true>(p, stream);
+    return d == 64 ? launch_attn_fwd_t<float, 64, true>(p, stream) : launch_attn_fwd_t<float, 128, true>(p, stream);
 }
 
 }  // namespace path

@@ -1,0 +1,66 @@
+// Host/device argument structs of the backward kernels and their launchers.
+#pragma once
+#include "path_common.h"
+
+namespace path {
+
+struct BwdParams {
+    const void *q, *k, *v, *w, *beta, *o, *dO;
+    const float* lse;
+    const void *knat, *ktnat, *dpnat, *xs;
+    void* gs;                 // adjoint states g(i,j-1) at slot (i,j), row-major, operand type
+    float *delta;             // [BH][Lp]
+    float *dqb, *dkb, *dvp;   // [BH][Lp][d] fp32: dQb, dKb, dV (off-diagonal part)
+    float *ddp;               // [BH][NC][d][d] fp32: ddP[a][b]
+    int B, H, L, NC;
+    float scale;
+};
+
+enum { EL_F32 = 0, EL_OP = 1, EL_IO = 2 };           // element type: float, operand type, I/O type
+enum { TOK_NONE = 0, TOK_ROW = 1, TOK_K = 2 };       // which index (if any) is a token of the chunk (zero past L)
+enum { MASK_NONE = 0, MASK_TRIL = 1, MASK_SLOWER = 2 };
+
+struct MatRef {
+    const void* p;
+    long long s_bh, s_ch;   // element strides per (batch*head) and per chunk
+    int rs, ks;             // element strides of the row (m or n) and contraction index
+    int type, tok;
+};
+
+struct GemmArgs {
+    MatRef A, B;
+    float* C;
+    const float* Cin;
+    long long c_bh, c_ch;
+    int crs, ccs;
+    int M, N, K;
+    float alpha;
+    int mask;
+    int NC, L;
+};
+
+struct DiagArgs {
+    const float *sdm, *dpd, *delta, *lse;
+    float *pd, *dsd;
+    int L, NC;
+    float scale;
+};
+struct BetaArgs {
+    const float *r, *m, *g;
+    const void* beta;
+    float *dgs, *dbf;
+    int L, NC;
+};
+struct OutArgs {
+    const float *dqf, *dkf, *dvf, *dwf, *dbf;
+    void *dq, *dk, *dv, *dw, *dbeta;
+    int L, NC, d;
+};
+
+hipError_t launch_bwd_scan(const BwdParams& p, int d, int is_bf16, hipStream_t st);
+hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream_t st);
+hipError_t launch_bwd_diag(const DiagArgs& a, int BH, hipStream_t st);
+hipError_t launch_bwd_beta(const BetaArgs& a, int BH, int is_bf16, hipStream_t st);
+hipError_t launch_bwd_store(const OutArgs& a, int BH, int is_bf16, hipStream_t st);
+
+}  // namespace path

@@ -147,6 +147,33 @@ __device__ __forceinline__ f32x16 zero16() {
     return z;
 }
 
+template <typename T>
+__device__ __forceinline__ typename Tr<T>::Frag ld_frag(const T* p) {
+    return *reinterpret_cast<const typename Tr<T>::Frag*>(p);
+}
+
+// acc += A[arow0 + c][0..Kc) . B[brow0 + c'][0..Kc)  for a 32x32 block; both
+// operands are stored with the contraction index contiguous.
+template <typename T, int Kc>
+__device__ __forceinline__ f32x16 gemm32(const T* A, int lda, int arow0, const T* Bm, int ldb,
+                                         int brow0, int l32, int h, f32x16 acc) {
+    constexpr int FE = Tr<T>::FE, KW = Tr<T>::KW;
+    const T* ap = A + (size_t)(arow0 + l32) * lda + FE * h;
+    const T* bp = Bm + (size_t)(brow0 + l32) * ldb + FE * h;
+#pragma unroll
+    for (int k0 = 0; k0 < Kc; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
+    return acc;
+}
+
+// Same with lane-specific row pointers (already offset by the row and by FE*h).
+template <typename T, int Kc>
+__device__ __forceinline__ f32x16 gemm_rows(const T* ap, const T* bp, f32x16 acc) {
+    constexpr int KW = Tr<T>::KW;
+#pragma unroll
+    for (int k0 = 0; k0 < Kc; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
+    return acc;
+}
+
 // Workspace carve-up shared by host launch code and kernels (byte offsets, 256-aligned).
 struct FwdWorkspace {
     size_t kt, vt, dp, xinit, sd, total;
@@ -160,6 +187,18 @@ struct FwdParams {
     float *xinit, *sd;    // accumulator-order fp32 tiles
     int B, H, L, NC;      // NC = number of 64-token chunks = ceil(L/64)
     float scale;
+    // Backward only (NULL in the forward): row-major copies in the operand type,
+    // knat [bh][NC*64][d] = Kb, ktnat [bh][NC][d][64] = Kb^T, dpnat [bh][NC][d][d] = dP,
+    // and xs [bh][pair(i,j)][64][d]: query state of chunk i as used against key chunk j < i.
+    void *knat, *ktnat, *dpnat, *xs;
+    // Backward only: per-chunk matrices of the transform, row-major 64x64 (operand type) --
+    // fm = F[t][t'], gktm[s][t'] = strictLower(W K^T)[t'][s], nm = N, aim = A^{-1},
+    // ytm[s][t] = Y[t][s]; utm [d][64]: utm[c][t] = U[t][c]; fp32: gm = W W^T, sdm[t][s] = Sd.
+    void *fm, *gktm, *nm, *aim, *ytm, *utm;
+    float *gm, *sdm;
 };
+
+// slot of the (query chunk i, key chunk j < i) pair in the per-head state arrays
+__host__ __device__ __forceinline__ size_t pair_slot(int i, int j) { return (size_t)i * (i - 1) / 2 + j; }
 
 }  // namespace path

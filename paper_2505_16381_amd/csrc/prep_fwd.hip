@@ -46,24 +46,6 @@ template <typename TIO, int D> struct PrepCfg {
     static constexpr size_t smem_bytes = off_beta_bytes + CHUNK * 4;
 };
 
-template <typename T>
-__device__ __forceinline__ typename Tr<T>::Frag ld_frag(const T* p) {
-    return *reinterpret_cast<const typename Tr<T>::Frag*>(p);
-}
-
-// acc += A[arow0 + c][0..Kc) . B[brow0 + c'][0..Kc)  for a 32x32 block; both
-// operands are stored with the contraction index contiguous.
-template <typename T, int Kc>
-__device__ __forceinline__ f32x16 gemm32(const T* A, int lda, int arow0, const T* Bm, int ldb,
-                                         int brow0, int l32, int h, f32x16 acc) {
-    constexpr int FE = Tr<T>::FE, KW = Tr<T>::KW;
-    const T* ap = A + (size_t)(arow0 + l32) * lda + FE * h;
-    const T* bp = Bm + (size_t)(brow0 + l32) * ldb + FE * h;
-#pragma unroll
-    for (int k0 = 0; k0 < Kc; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
-    return acc;
-}
-
 template <typename TIO, int D>
 __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     using C = PrepCfg<TIO, D>;
@@ -128,6 +110,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     else { Qp = reinterpret_cast<const T*>(Qg); Kp = reinterpret_cast<const T*>(Kg); ldqk = D; }   // T == TIO here
 
     const int bi = wv >> 1, bj = wv & 1;   // this wave's 32x32 block of a 64x64 result
+    const size_t bhc = (size_t)bh * NC + chunk;
 
     // Row of Q/K this lane supplies as an operand row (clamped for the global path).
     auto qk_row = [&](int r) { return (C::STAGE_QK || r < nvalid) ? r : 0; };
@@ -142,6 +125,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         for (int j = 0; j < 16; ++j) {
             const int t = 32 * bi + acc_row(j, h);
             Af[t * LDA + s] = (s < t) ? bs[t] * acc[j] : 0.f;
+            if (p.gm) p.gm[bhc * 4096 + t * 64 + s] = acc[j];
         }
     }
     // F block: rows t (Q), cols t' (W); keep t' <= t.
@@ -192,8 +176,8 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     }
     __syncthreads();
 
-    // ---- phase 2: N = A^{-1} diag(beta) by forward substitution (one wave) -------
-    // Column c of N depends only on itself: lane c computes N[0..63][c].
+    // ---- phase 2: A^{-1} by forward substitution (one wave), N = A^{-1} diag(beta) ----
+    // Column c of A^{-1} depends only on itself: lane c computes rows 0..63 of it.
     if (wv == 0) {
         float n[CHUNK];
 #pragma unroll
@@ -201,7 +185,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         const int c = lane;
 #pragma unroll
         for (int t = 0; t < CHUNK; ++t) {
-            float acc = (t == c) ? bs[t] : 0.f;
+            float acc = (t == c) ? 1.f : 0.f;
 #pragma unroll
             for (int s4 = 0; s4 < (t + 3) / 4; ++s4) {
                 const f32x4 a4 = *reinterpret_cast<const f32x4*>(Af + t * LDA + 4 * s4);   // zeros for s >= t
@@ -209,7 +193,8 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
                 for (int r = 0; r < 4; ++r) acc -= a4[r] * n[4 * s4 + r];
             }
             n[t] = acc;
-            Nt[t * LDC + c] = (T)acc;
+            Nt[t * LDC + c] = (T)(acc * bs[c]);
+            if (p.aim) reinterpret_cast<T*>(p.aim)[bhc * 4096 + t * 64 + c] = (T)acc;
         }
     }
     __syncthreads();
@@ -248,7 +233,21 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     __syncthreads();
 
     // ---- phase 4: outputs -----------------------------------------------------------
-    const size_t bhc = (size_t)bh * NC + chunk;
+    if (p.fm) {   // backward: keep the chunk's matrices (row-major, operand type)
+        T* fm = reinterpret_cast<T*>(p.fm) + bhc * 4096;
+        T* gk = reinterpret_cast<T*>(p.gktm) + bhc * 4096;
+        T* nm = reinterpret_cast<T*>(p.nm) + bhc * 4096;
+        T* yt = reinterpret_cast<T*>(p.ytm) + bhc * 4096;
+        T* ut = reinterpret_cast<T*>(p.utm) + bhc * (size_t)D * 64;
+        for (int idx = tid; idx < 4096; idx += 256) {
+            const int r = idx >> 6, c = idx & 63;
+            fm[idx] = Fs[r * LDC + c];
+            gk[idx] = Gk[r * LDC + c];
+            nm[idx] = Nt[r * LDC + c];
+            yt[idx] = Yt[r * LDC + c];
+        }
+        for (int idx = tid; idx < D * 64; idx += 256) ut[idx] = Ut[(idx >> 6) * LDC + (idx & 63)];
+    }
     // (a) Sd^T = K Q^T - Y^T F^T, accumulator order: [bhc][qb][kb][g][lane][4]
     {
         f32x16 corr = gemm32<T, CHUNK>(Yt, LDC, 32 * bi, Fs, LDC, 32 * bj, l32, h, zero16());
@@ -259,6 +258,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) v4[r] = accS[4 * g + r] - corr[4 * g + r];
             *reinterpret_cast<f32x4*>(dst + (g * 64 + lane) * 4) = v4;
+            if (p.sdm) *reinterpret_cast<f32x4*>(p.sdm + bhc * 4096 + (32 * bj + l32) * 64 + 32 * bi + 8 * g + 4 * h) = v4;
         }
     }
     // (b) -dP tile (rows = output column b of dP, contraction = a): acc rows a, cols b.
@@ -270,6 +270,11 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             const int blk = wv + 4 * i;
             const int ab = blk / (D / 32), bb = blk % (D / 32);
             f32x16 acc = gemm32<T, CHUNK>(Wt, LDC, 32 * ab, Ut, LDC, 32 * bb, l32, h, zero16());
+            if (p.dpnat) {     // row-major dP[a][b] for the backward
+                T* nat = reinterpret_cast<T*>(p.dpnat) + bhc * (size_t)D * D;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) nat[(size_t)(32 * ab + acc_row(j, h)) * D + 32 * bb + l32] = (T)acc[j];
+            }
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[j] = -acc[j];
             Frag fr[SPB];
@@ -296,6 +301,20 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
                 Vec4 k4 = *reinterpret_cast<const Vec4*>(krow + 8 * g);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[4 * g + r] = (ok ? (float)k4[r] : 0.f) - acc[4 * g + r];
+            }
+            if (p.knat) {      // row-major Kb[s][c] and Kb^T[c][s] for the backward
+                T* nat = reinterpret_cast<T*>(p.knat) + (bhc * CHUNK + s) * (size_t)D + 32 * cb + 4 * h;
+                T* natt = reinterpret_cast<T*>(p.ktnat) + bhc * (size_t)CHUNK * D + s;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    Vec4 v4;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        v4[r] = (T)acc[4 * g + r];
+                        natt[(size_t)(32 * cb + 8 * g + 4 * h + r) * CHUNK] = v4[r];
+                    }
+                    *reinterpret_cast<Vec4*>(nat + 8 * g) = v4;
+                }
             }
             Frag fr[SPB];
             pack_block<T>(acc, fr);

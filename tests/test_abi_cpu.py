@@ -1,0 +1,80 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol the
+header declares, and rejects bad arguments with the documented codes before
+anything is launched (no GPU needed: validation precedes every HIP call)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2505_16381_amd as pa
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "path_attn.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(path_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = pa.load_library()
+    names = _declared_functions()
+    assert {"path_attn_fwd", "path_attn_bwd", "path_attn_workspace_bytes", "path_status_str"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def test_status_strings():
+    assert pa.path_status_str(0) == "PATH_OK"
+    assert pa.path_status_str(4) == "PATH_ERR_UNSUPPORTED"
+    assert pa.path_status_str(99) == "PATH_ERR_UNKNOWN"
+
+
+def test_workspace_bytes():
+    assert pa.path_attn_workspace_bytes(1, 2, 256, 64, pa.PATH_F32) > 0
+    assert pa.path_attn_workspace_bytes(1, 2, 256, 96, pa.PATH_F32) == 0      # d not in {64,128}
+    assert pa.path_attn_workspace_bytes(0, 2, 256, 64, pa.PATH_F32) == 0
+    assert pa.path_attn_workspace_bytes(1, 2, 256, 64, 7) == 0
+    a = pa.path_attn_workspace_bytes(1, 1, 64, 64, pa.PATH_BF16)
+    b = pa.path_attn_workspace_bytes(1, 1, 65, 64, pa.PATH_BF16)               # ragged tail = one more chunk
+    assert b == 2 * a
+    off = pa.path_attn_fwd_workspace_layout(4, 16, 8192, 128, pa.PATH_BF16)
+    assert list(off) == sorted(off) and all(o % 256 == 0 for o in off)
+    assert off[5] == pa.path_attn_workspace_bytes(4, 16, 8192, 128, pa.PATH_BF16)
+
+
+def _fwd(lib, ptrs, B=1, H=1, L=64, d=64, causal=1, dt=0, ws=0x1000, ws_bytes=1 << 30):
+    q, k, v, w, beta, o, lse = ptrs
+    return lib.path_attn_fwd(q, k, v, w, beta, o, lse, B, H, L, d, causal, 0.125, dt, ws, ws_bytes, None)
+
+
+def test_forward_argument_validation_without_gpu():
+    lib = pa.load_library()
+    ok = [0x1000] * 7                      # never dereferenced: every case below fails validation first
+    assert _fwd(lib, [None] + ok[1:]) == 1                       # PATH_ERR_NULL
+    assert _fwd(lib, ok[:6] + [None]) == 1
+    assert _fwd(lib, ok, ws=None) == 1
+    assert _fwd(lib, ok, dt=5) == 3                              # PATH_ERR_DTYPE
+    assert _fwd(lib, ok, d=96) == 2                              # PATH_ERR_SHAPE
+    assert _fwd(lib, ok, L=0) == 2
+    assert _fwd(lib, ok, B=70000) == 2
+    assert _fwd(lib, ok, causal=0) == 4                          # PATH_ERR_UNSUPPORTED
+    assert _fwd(lib, ok, ws_bytes=16) == 5                       # PATH_ERR_WORKSPACE
+    assert _fwd(lib, ok, ws=0x1010) == 5                         # workspace not 256-aligned
+    assert _fwd(lib, [0x1004] + ok[1:]) == 7                     # PATH_ERR_ALIGN
+    assert _fwd(lib, ok[:5] + [0x1008] + ok[6:]) == 7
+
+
+def test_backward_argument_validation_without_gpu():
+    lib = pa.load_library()
+    args = [0x1000] * 13
+    call = lambda a, **kw: lib.path_attn_bwd(*a, kw.get("B", 1), 1, kw.get("L", 64), kw.get("d", 64),
+                                             kw.get("causal", 1), 0.125, kw.get("dt", 1),
+                                             kw.get("ws", 0x1000), kw.get("wsb", 1 << 40), None)
+    assert call([None] + args[1:]) == 1
+    assert call(args, d=32) == 2
+    assert call(args, dt=9) == 3
+    assert call(args, causal=0) == 4
+    assert call(args, wsb=8) == 5

@@ -1,0 +1,91 @@
+"""GPU parity of the backward path against the oracle's adjoint walk (run with -m gpu).
+
+Bar (the benchmark states none for gradients): per tensor,
+max|g - g_oracle| / max(max|g_oracle|, 1e-2) <= 1e-4 (fp32 I/O) or 2e-2 (bf16 I/O).
+"""
+import numpy as np
+import pytest
+
+from paper_2505_16381_amd import synth_inputs as si
+
+pytestmark = pytest.mark.gpu
+TOL = {"fp32": 1e-4, "bf16": 2e-2}
+NAMES = ("dq", "dk", "dv", "dw", "dbeta")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    import paper_2505_16381_amd as pa
+    assert torch.cuda.is_available()
+    pa.load_library()
+    return torch, pa
+
+
+def _run_bwd(gpu, x, dtype, scale):
+    torch, pa = gpu
+    td = torch.float32 if dtype == "fp32" else torch.bfloat16
+    dv = {n: torch.from_numpy(a).to("cuda").to(td).contiguous() for n, a in x.items()}
+    o, lse = pa.path_attn_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], scale=scale)
+    grads = pa.path_attn_bwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], o, lse, dv["dO"], scale=scale)
+    torch.cuda.synchronize()
+    return [g.float().cpu().numpy().astype(np.float64) for g in grads]
+
+
+def _check(gpu, oracle, x, dtype, scale, heads=None, tag=""):
+    got = _run_bwd(gpu, x, dtype, scale)
+    if heads is not None:
+        B, H = x["q"].shape[:2]
+        sel = lambda a: np.stack([a.reshape((B * H,) + a.shape[2:])[h] for h in heads])[None]
+        xs = {n: sel(a) for n, a in x.items()}
+        got = [sel(g) for g in got]
+    else:
+        xs = x
+    ref = oracle.bwd(xs["q"], xs["k"], xs["v"], xs["w"], xs["beta"], xs["dO"], scale)
+    msg = []
+    worst = 0.0
+    for n, g, r in zip(NAMES, got, ref):
+        assert np.isfinite(g).all(), n
+        e = np.abs(g - r).max() / max(np.abs(r).max(), 1e-2)   # floor: exact-zero gradients (L = 1)
+        msg.append(f"{n}={e:.2e}")
+        worst = max(worst, e)
+    print(f"[{tag}] dtype={dtype} rel err " + " ".join(msg), flush=True)
+    assert worst <= TOL[dtype], (tag, msg)
+
+
+@pytest.mark.parametrize("L,d", [(64, 64), (130, 64), (200, 128), (1, 64), (65, 128)])
+def test_bwd_fp32_small(gpu, oracle, L, d):
+    x = si.make_inputs(1, 2, L, d, "fp32", 500 + L + d, 0.0, with_do=True)
+    _check(gpu, oracle, x, "fp32", d ** -0.5, tag=f"bwd fp32 L={L} d={d}")
+
+
+@pytest.mark.parametrize("L,d", [(64, 64), (300, 64), (512, 128), (77, 128)])
+def test_bwd_bf16_small(gpu, oracle, L, d):
+    x = si.make_inputs(2, 2, L, d, "bf16", 600 + L + d, 0.0, with_do=True)
+    _check(gpu, oracle, x, "bf16", d ** -0.5, tag=f"bwd bf16 L={L} d={d}")
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+def test_bwd_special_betas(gpu, oracle, dtype):
+    x = si.make_inputs(1, 2, 200, 64, dtype, 700, 0.0, with_do=True)
+    x["beta"][..., 0::3] = 0.0
+    x["beta"][..., 1::3] = 1.0
+    x["beta"][..., 2::3] = 2.0
+    _check(gpu, oracle, x, dtype, 0.125, tag="bwd special betas")
+
+
+def test_bwd_gradient_identities_on_gpu(gpu):
+    """w.dw = 2 beta dbeta and dw_0 = dbeta_0 = 0 hold for the GPU gradients too (fp32)."""
+    x = si.make_inputs(1, 2, 192, 64, "fp32", 800, 0.0, with_do=True)
+    dq, dk, dv, dw, db = _run_bwd(gpu, x, "fp32", 0.125)
+    lhs = (x["w"].astype(np.float64) * dw).sum(-1)
+    rhs = 2 * x["beta"].astype(np.float64) * db
+    assert np.abs(lhs - rhs).max() <= 1e-4 * max(1.0, np.abs(rhs).max())
+    assert np.abs(dw[:, :, 0]).max() <= 1e-6 and np.abs(db[:, :, 0]).max() <= 1e-6
+    assert np.abs(dv.sum(2) - x["dO"].astype(np.float64).sum(2)).max() <= 1e-3
+
+
+def test_config3_backward_full_shape_sampled_heads(gpu, oracle):
+    """Full benchmark shape on the GPU; the oracle (not row-separable) on a sample of heads."""
+    x, c = si.make_config(3)
+    _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, heads=[0, 37, 127], tag="cfg3")

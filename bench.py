@@ -43,7 +43,7 @@ def path_extra_flops(B, H, L, d):
     return (prep + upd) * B * H
 
 
-def cpu_baseline(x, cfg, scale, n_heads=4, n_rows=48):
+def cpu_baseline(x, cfg, scale, n_heads=16, n_rows=1024):
     """The fp64 oracle, as it stands, on a bounded row sample of the same workload."""
     import numpy as np
     from oracle import path_oracle

@@ -72,7 +72,8 @@ size_t path_attn_workspace_bytes(int B, int H, int L, int d, path_dtype_t dt, in
  * workspace, of the five intermediates the chunk-preprocessing kernel (paper
  * Sec. 3.2) hands to the sweep kernel, in this order: boundary-adjusted key
  * tiles, V^T tiles, negated chunk-product tiles (I - P), boundary-adjusted
- * queries (fp32), diagonal-block logits (fp32); offsets[5] = total bytes.
+ * queries (fp32), diagonal-block logits (fp32); offsets[5] = end of the last of them
+ * (further regions follow, up to path_attn_workspace_bytes).
  * Returns PATH_ERR_SHAPE / PATH_ERR_DTYPE for arguments the forward rejects. */
 path_status_t path_attn_fwd_workspace_layout(int B, int H, int L, int d, path_dtype_t dt,
                                              size_t offsets[6]);

@@ -7,6 +7,8 @@ namespace path {
 hipError_t launch_prep_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 hipError_t launch_attn_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 
+hipError_t launch_prep2_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
+hipError_t launch_attn_fwd2(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 hipError_t launch_attn_states(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 }  // namespace path
 #include "bwd_decl.h"
@@ -31,6 +33,11 @@ static FwdWorkspace fwd_workspace(int B, int H, int L, int d, size_t es) {
     w.dp = off;    off = align256(off + BH * NC * d * d * es);
     w.xinit = off; off = align256(off + BH * Lp * d * 4);
     w.sd = off;    off = align256(off + BH * NC * CHUNK * CHUNK * 4);
+    const size_t NSB = (NC + SBC - 1) / SBC;
+    w.kt2 = off;    off = align256(off + BH * Lp * d * es);
+    w.dp2 = off;    off = align256(off + BH * NSB * d * d * es);
+    w.knat = off;   off = align256(off + BH * Lp * d * es);
+    w.dptnat = off; off = align256(off + BH * NC * d * d * es);
     w.total = off;
     return w;
 }
@@ -99,7 +106,7 @@ extern "C" path_status_t path_attn_fwd_workspace_layout(int B, int H, int L, int
     if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
     const FwdWorkspace ws = fwd_workspace(B, H, L, d, dt == PATH_BF16 ? 2 : 4);
     offsets[0] = ws.kt; offsets[1] = ws.vt; offsets[2] = ws.dp; offsets[3] = ws.xinit; offsets[4] = ws.sd;
-    offsets[5] = ws.total;
+    offsets[5] = ws.kt2;   // end of the fifth region
     return PATH_OK;
 }
 
@@ -116,6 +123,7 @@ static path_status_t fwd_setup(FwdParams& p, int B, int H, int L, int d, path_dt
     p.kt = base + ws.kt; p.vt = base + ws.vt; p.dp = base + ws.dp;
     p.xinit = reinterpret_cast<float*>(base + ws.xinit);
     p.sd = reinterpret_cast<float*>(base + ws.sd);
+    p.kt2 = base + ws.kt2; p.dp2 = base + ws.dp2; p.knat = base + ws.knat; p.dptnat = base + ws.dptnat;
     p.B = B; p.H = H; p.L = L; p.NC = (L + CHUNK - 1) / CHUNK;
     return PATH_OK;
 }
@@ -130,6 +138,8 @@ extern "C" path_status_t path_attn_fwd_prep(const void* q, const void* k, const 
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(w)) return PATH_ERR_ALIGN;
     p.q = q; p.k = k; p.v = v; p.w = w; p.beta = beta;
     if (launch_prep_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)) != hipSuccess) return PATH_ERR_HIP;
+    if (p.NC > SBC && launch_prep2_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return PATH_ERR_HIP;     // the second level is only read when there is a super-block to the left
     return PATH_OK;
 }
 
@@ -142,7 +152,7 @@ extern "C" path_status_t path_attn_fwd_sweep(void* o, float* lse, int B, int H, 
     if (st != PATH_OK) return st;
     if (misaligned(o)) return PATH_ERR_ALIGN;
     p.o = o; p.lse = lse; p.scale = scale;
-    if (launch_attn_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)) != hipSuccess) return PATH_ERR_HIP;
+    if (launch_attn_fwd2(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)) != hipSuccess) return PATH_ERR_HIP;
     return PATH_OK;
 }
 

@@ -40,7 +40,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int CHUNK = 64;      // tokens per chunk (UT transform block)
-constexpr int QTILE = 128;     // query rows per workgroup of the sweep (4 waves x 32)
+constexpr int SBC = 4;         // chunks per super-block (second blocking level of the forward sweep)
 
 __device__ __forceinline__ int acc_row(int j, int h) { return 8 * (j >> 2) + 4 * h + (j & 3); }
 
@@ -176,7 +176,7 @@ __device__ __forceinline__ f32x16 gemm_rows(const T* ap, const T* bp, f32x16 acc
 
 // Workspace carve-up shared by host launch code and kernels (byte offsets, 256-aligned).
 struct FwdWorkspace {
-    size_t kt, vt, dp, xinit, sd, total;
+    size_t kt, vt, dp, xinit, sd, kt2, dp2, knat, dptnat, total;
 };
 
 struct FwdParams {
@@ -184,6 +184,8 @@ struct FwdParams {
     void* o;
     float* lse;
     void *kt, *vt, *dp;   // fragment-order tiles written by prep, read by the sweep
+    void *kt2, *dp2;      // second level: keys carried to their super-block's right edge; -(I - P_superblock)
+    void *dptnat;         // row-major dP^T per chunk (operand type): dptnat[b][a] = dP[a][b]
     float *xinit, *sd;    // accumulator-order fp32 tiles
     int B, H, L, NC;      // NC = number of 64-token chunks = ceil(L/64)
     float scale;

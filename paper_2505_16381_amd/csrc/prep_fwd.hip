@@ -270,6 +270,16 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             const int blk = wv + 4 * i;
             const int ab = blk / (D / 32), bb = blk % (D / 32);
             f32x16 acc = gemm32<T, CHUNK>(Wt, LDC, 32 * ab, Ut, LDC, 32 * bb, l32, h, zero16());
+            if (p.dptnat) {    // row-major dP^T[b][a] for the second blocking level
+                T* nat = reinterpret_cast<T*>(p.dptnat) + bhc * (size_t)D * D + (size_t)(32 * bb + l32) * D + 32 * ab + 4 * h;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    Vec4 v4;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) v4[r] = (T)acc[4 * g + r];
+                    *reinterpret_cast<Vec4*>(nat + 8 * g) = v4;
+                }
+            }
             if (p.dpnat) {     // row-major dP[a][b] for the backward
                 T* nat = reinterpret_cast<T*>(p.dpnat) + bhc * (size_t)D * D;
 #pragma unroll
@@ -304,14 +314,14 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             }
             if (p.knat) {      // row-major Kb[s][c] and Kb^T[c][s] for the backward
                 T* nat = reinterpret_cast<T*>(p.knat) + (bhc * CHUNK + s) * (size_t)D + 32 * cb + 4 * h;
-                T* natt = reinterpret_cast<T*>(p.ktnat) + bhc * (size_t)CHUNK * D + s;
+                T* natt = p.ktnat ? reinterpret_cast<T*>(p.ktnat) + bhc * (size_t)CHUNK * D + s : nullptr;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     Vec4 v4;
 #pragma unroll
                     for (int r = 0; r < 4; ++r) {
                         v4[r] = (T)acc[4 * g + r];
-                        natt[(size_t)(32 * cb + 8 * g + 4 * h + r) * CHUNK] = v4[r];
+                        if (natt) natt[(size_t)(32 * cb + 8 * g + 4 * h + r) * CHUNK] = v4[r];
                     }
                     *reinterpret_cast<Vec4*>(nat + 8 * g) = v4;
                 }

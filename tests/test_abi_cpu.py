@@ -42,7 +42,7 @@ def test_workspace_bytes():
     assert b == 2 * a
     off = pa.path_attn_fwd_workspace_layout(4, 16, 8192, 128, pa.PATH_BF16)
     assert list(off) == sorted(off) and all(o % 256 == 0 for o in off)
-    assert off[5] == pa.path_attn_workspace_bytes(4, 16, 8192, 128, pa.PATH_BF16)
+    assert off[5] <= pa.path_attn_workspace_bytes(4, 16, 8192, 128, pa.PATH_BF16)
 
 
 def _fwd(lib, ptrs, B=1, H=1, L=64, d=64, causal=1, dt=0, ws=0x1000, ws_bytes=1 << 30):

@@ -72,6 +72,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="benchmark configuration index (default: headline)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fwd-only", action="store_true")
+    ap.add_argument("--shape", type=str, default=None, help="override B,H,L,d of the chosen configuration (exploration only)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (each (batch, head) is independent; "
@@ -86,7 +87,13 @@ def main():
     pa.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    x, cfg = si.make_config(args.config, with_do=True)
+    over = {}
+    if args.shape:
+        over = dict(zip(("B", "H", "L", "d"), (int(v) for v in args.shape.split(","))))
+    x, cfg = si.make_config(args.config, with_do=True, **over)
+    if over:
+        cfg["name"] += "_shape_override"
+
     B, H, L, d = cfg["B"], cfg["H"], cfg["L"], cfg["d"]
     td = torch.bfloat16 if cfg["dtype"] == "bf16" else torch.float32
     dt_code = pa.PATH_BF16 if cfg["dtype"] == "bf16" else pa.PATH_F32

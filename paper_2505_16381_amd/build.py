@@ -12,7 +12,10 @@ OUT = os.path.join(HERE, "libpath_attn.so")
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         "-fno-honor-nans", "-mno-amdgpu-ieee",      # infinities are used, NaNs never: no canonicalisation of max operands
          "-Wno-unused-command-line-argument"]
+# per-file extras: the sweep keeps MFMA results in architectural VGPRs (two waves per SIMD, 256 registers each)
+PER_FILE = {"attn_fwd2.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def build(verbose: bool = True, extra=()) -> str:
@@ -23,7 +26,7 @@ def build(verbose: bool = True, extra=()) -> str:
     for s in srcs:
         o = os.path.join(HERE, "_build", os.path.basename(s) + ".o")
         objs.append(o)
-        cmd = [HIPCC, *FLAGS, *extra, "-c", s, "-o", o]
+        cmd = [HIPCC, *FLAGS, *PER_FILE.get(os.path.basename(s), []), *extra, "-c", s, "-o", o]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append(subprocess.Popen(cmd, stderr=subprocess.PIPE, text=True))

@@ -1,14 +1,15 @@
 // Forward sweep of PaTH attention, two blocking levels (paper Sec. 3.3 workflow;
 // the second level is this library's own, see prep2_fwd.hip).
 //
-// One workgroup = 256 queries = one super-block of SBC = 4 chunks; wave w owns
-// chunk 4*tile + w (64 queries = two 32-column MFMA blocks, so every operand
-// fragment read from LDS feeds two MFMAs).  Everything is transposed so that
-// activations stay in registers:
+// One workgroup = 8 waves = 256 queries = one super-block of SBC = 4 chunks; waves
+// 2c and 2c+1 own the two 32-query halves of chunk 4*tile + c.  Two waves share a
+// SIMD, so the vector work (softmax) of one runs under the matrix work of the other;
+// each wave's working set fits the 256 architectural VGPRs (no accumulator-register
+// copies).  Everything is transposed so that activations stay in registers:
 //
-//     S^T (64 keys x 64 q)  = Kb   X^T        A = key tile (LDS),  B = X (registers)
-//     O^T (d x 64 q)       += V^T  P^T        A = V^T tile (LDS),  B = P (registers)
-//     X^T (d x 64 q)       += (-dP)^T X^T     A = -dP tile (LDS),  B = X (registers)
+//     S^T (64 keys x 32 q)  = Kb   X^T        A = key tile (LDS),  B = X (registers)
+//     O^T (d x 32 q)       += V^T  P^T        A = V^T tile (LDS),  B = P (registers)
+//     X^T (d x 32 q)       += (-dP)^T X^T     A = -dP tile (LDS),  B = X (registers)
 //
 // Phase A (inside the query tile's own super-block): chunk by chunk, with the
 // chunk-level keys and one state update per chunk; the wave's own chunk uses
@@ -31,10 +32,11 @@ template <typename TIO, int D, int NBUF> struct Fwd2Cfg {
 };
 
 // Linear copy of nfrag 16-byte fragments global -> LDS, asynchronous (direct-to-LDS):
-// wave wv moves fragments [i*256 + 64*wv, +64) of every 256-fragment group.
+// wave wv moves fragments [i*512 + 64*wv, +64) of every 512-fragment group.
+constexpr int FWD2_THREADS = 512;
 template <typename Frag>
 __device__ __forceinline__ void async_tile(const Frag* g, Frag* s, int nfrag, int tid, int wv) {
-    for (int i = 0; i < nfrag; i += 256)
+    for (int i = 0; i < nfrag; i += FWD2_THREADS)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + i + tid),
                                          (__attribute__((address_space(3))) void*)(s + i + 64 * wv), 16, 0, 0);
 }
@@ -45,7 +47,7 @@ __device__ __forceinline__ void wait_tiles_and_sync() {
 }
 
 template <typename TIO, int D, int NBUF>
-__global__ __launch_bounds__(256) void attn_fwd2_kernel(FwdParams p) {
+__global__ __launch_bounds__(FWD2_THREADS) void attn_fwd2_kernel(FwdParams p) {
     using C = Fwd2Cfg<TIO, D, NBUF>;
     using T = typename C::T;
     using Frag = typename Tr<T>::Frag;
@@ -68,36 +70,45 @@ __global__ __launch_bounds__(256) void attn_fwd2_kernel(FwdParams p) {
     if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
 
-    const int cq = tile * SBC + wv;                 // this wave's chunk
+    const int cq = tile * SBC + (wv >> 1);          // this wave's chunk
+    const int qb = wv & 1;                          // ... and which 32-query half of it
     const bool active = cq < NC;
     const int jtop = (tile * SBC + SBC - 1 < NC) ? tile * SBC + SBC - 1 : NC - 1;
     const float sl2 = p.scale * 1.44269504088896340736f;
 
-    // ---- query state (fp32 master + operand copy), output accumulator, softmax statistics ----
-    f32x16 Xm[2][DB], O[2][DB];
-    Frag Xb[2][DS];
-    float m_run[2] = {-INFINITY, -INFINITY}, l_run[2] = {0.f, 0.f};
+    // ---- query state, output accumulator, softmax statistics -----------------------------------
+    // The state is kept as two operand-type fragments per slab, X = Xh + Xl (Xl = what
+    // rounding X to the operand type lost): Xh is the MFMA operand, and the pair restores
+    // the fp32 value when the state is updated, at two thirds of the registers of an fp32
+    // master plus operand copy.  (fp32 I/O: Xh is exact, Xl unused.)
+    constexpr bool HAS_LO = sizeof(T) == 2;
+    f32x16 O[DB];
+    Frag Xh[DS], Xl[HAS_LO ? DS : 1];
+    float m_run = -INFINITY, l_run = 0.f;           // m in base-2 logit units
+    auto split_state = [&](int b, const f32x16& x) {
+        pack_block<T>(x, Xh + b * SPB);
+        if (HAS_LO) {
+            f32x16 r;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
+            for (int jj = 0; jj < 16; ++jj) r[jj] = x[jj] - (float)Xh[b * SPB + jj / Tr<T>::FE][jj % Tr<T>::FE];
+            pack_block<T>(r, Xl + b * SPB);
+        }
+    };
 #pragma unroll
-        for (int b = 0; b < DB; ++b) { Xm[qb][b] = zero16(); O[qb][b] = zero16(); }
-    if (active) {
-        const float* xs = p.xinit + ((size_t)bh * NC + cq) * 2 * (size_t)DB * 1024;
+    for (int b = 0; b < DB; ++b) {
+        O[b] = zero16();
+        f32x16 x = zero16();
+        if (active) {
+            const float* xs = p.xinit + (((size_t)bh * NC + cq) * 2 + qb) * (size_t)DB * 1024 + (size_t)b * 1024;
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 v4 = *reinterpret_cast<const f32x4*>(xs + g * 256 + lane * 4);
 #pragma unroll
-            for (int b = 0; b < DB; ++b)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const f32x4 v4 = *reinterpret_cast<const f32x4*>(xs + (((size_t)qb * DB + b) * 4 + g) * 256 + lane * 4);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) Xm[qb][b][4 * g + r] = v4[r];
-                }
+                for (int r = 0; r < 4; ++r) x[4 * g + r] = v4[r];
+            }
+        }
+        split_state(b, x);
     }
-#pragma unroll
-    for (int qb = 0; qb < 2; ++qb)
-#pragma unroll
-        for (int b = 0; b < DB; ++b) pack_block<T>(Xm[qb][b], Xb[qb] + b * SPB);
 
     const T* ktg = reinterpret_cast<const T*>(p.kt) + (size_t)bh * NC * CHUNK * D;
     const T* kt2g = reinterpret_cast<const T*>(p.kt2) + (size_t)bh * NC * CHUNK * D;
@@ -105,90 +116,88 @@ __global__ __launch_bounds__(256) void attn_fwd2_kernel(FwdParams p) {
     const T* dpg = reinterpret_cast<const T*>(p.dp) + (size_t)bh * NC * D * D;
     const T* dp2g = reinterpret_cast<const T*>(p.dp2) + (size_t)bh * ntiles * D * D;
 
-    // one key chunk: logits (or the given diagonal logits), online softmax, O += V^T P^T
+    // Online softmax of one 32-key block (raw logits S) -> P fragments.  The reference
+    // maximum is only moved when the block's maximum exceeds it by more than 2^16 (so O
+    // and l are rescaled practically never after the first block); probabilities may then
+    // be as large as 2^16, which bf16/fp32 operands and the fp32 sums hold without loss.
+    auto softmax_block = [&](f32x16& S, FragV (&Pb)[SPB]) {
+        float mloc = fmaxf(S[0], S[1]);
+#pragma unroll
+        for (int jj = 2; jj < 16; jj += 2) mloc = fmaxf(mloc, fmaxf(S[jj], S[jj + 1]));
+        mloc = fmaxf(mloc, __shfl_xor(mloc, 32)) * sl2;
+        const bool move = mloc - m_run > 16.f;          // true on the first block (m_run = -inf)
+        if (__builtin_amdgcn_ballot_w64(move) != 0) {
+            const float m_new = move ? mloc : m_run;
+            const float alpha = move ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) O[b][jj] *= alpha;
+        }
+        const float mneg = -m_run;
+        float rs = 0.f;
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, mneg));
+            S[jj] = e;
+            rs += e;
+        }
+        l_run += rs;
+        pack_block<TIO>(S, Pb);
+    };
+    // one key chunk: logits (or the given diagonal logits) per 32-key block, softmax, O += V^T P^T
     auto attend = [&](const Frag* sK, const FragV* sV, const float* diag) {
-        f32x16 S[2][2];     // [query block][key block]
+        f32x16 S[2];        // [key block], raw (unscaled) logits
         if (diag) {
 #pragma unroll
-            for (int qb = 0; qb < 2; ++qb)
+            for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-                for (int kb = 0; kb < 2; ++kb)
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 v4 = *reinterpret_cast<const f32x4*>(diag + (((size_t)qb * 2 + kb) * 4 + g) * 256 + lane * 4);
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const f32x4 v4 = *reinterpret_cast<const f32x4*>(diag + (((size_t)qb * 2 + kb) * 4 + g) * 256 + lane * 4);
-#pragma unroll
-                        for (int r = 0; r < 4; ++r) {
-                            const int sk = 32 * kb + 8 * g + 4 * h + r, tq = 32 * qb + l32;
-                            S[qb][kb][4 * g + r] = (sk <= tq) ? v4[r] * sl2 : -INFINITY;
-                        }
+                    for (int r = 0; r < 4; ++r) {
+                        const int sk = 32 * kb + 8 * g + 4 * h + r, tq = 32 * qb + l32;
+                        S[kb][4 * g + r] = (sk <= tq) ? v4[r] : -INFINITY;
                     }
+                }
         } else {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
-                f32x16 a0 = zero16(), a1 = zero16();
+                f32x16 a0 = zero16();
 #pragma unroll
-                for (int s = 0; s < DS; ++s) {
-                    const Frag a = sK[(kb * DS + s) * 64 + lane];
-                    a0 = Tr<T>::mma(a, Xb[0][s], a0);
-                    a1 = Tr<T>::mma(a, Xb[1][s], a1);
-                }
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) { a0[jj] *= sl2; a1[jj] *= sl2; }
-                S[0][kb] = a0; S[1][kb] = a1;
+                for (int s = 0; s < DS; ++s) a0 = Tr<T>::mma(sK[(kb * DS + s) * 64 + lane], Xh[s], a0);
+                S[kb] = a0;
             }
         }
-        FragV Pb[2][CS];
-        float alpha[2];
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb) {
-            float mloc = S[qb][0][0];
+        for (int kb = 0; kb < 2; ++kb) {
+            FragV Pb[SPB];
+            softmax_block(S[kb], Pb);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+            for (int b = 0; b < DB; ++b)
 #pragma unroll
-                for (int jj = 0; jj < 16; ++jj) mloc = fmaxf(mloc, S[qb][kb][jj]);
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32));
-            const float m_new = fmaxf(m_run[qb], mloc);      // finite: the diagonal chunk comes first
-            alpha[qb] = __builtin_amdgcn_exp2f(m_run[qb] - m_new);
-            float rs = 0.f;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) {
-                    const float e = __builtin_amdgcn_exp2f(S[qb][kb][jj] - m_new);
-                    S[qb][kb][jj] = e;
-                    rs += e;
-                }
-            l_run[qb] = l_run[qb] * alpha[qb] + rs;
-            m_run[qb] = m_new;
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) pack_block<TIO>(S[qb][kb], Pb[qb] + kb * SPB);
-        }
-#pragma unroll
-        for (int b = 0; b < DB; ++b) {
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) { O[0][b][jj] *= alpha[0]; O[1][b][jj] *= alpha[1]; }
-#pragma unroll
-            for (int s = 0; s < CS; ++s) {
-                const FragV a = sV[(b * CS + s) * 64 + lane];
-                O[0][b] = Tr<TIO>::mma(a, Pb[0][s], O[0][b]);
-                O[1][b] = Tr<TIO>::mma(a, Pb[1][s], O[1][b]);
-            }
+                for (int s = 0; s < SPB; ++s) O[b] = Tr<TIO>::mma(sV[(b * CS + kb * SPB + s) * 64 + lane], Pb[s], O[b]);
         }
     };
     // X <- X (I - dP) with the -dP tile in sP
     auto update = [&]() {
+        f32x16 Xn[DB];
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
-            for (int s = 0; s < DS; ++s) {
-                const Frag a = sP[(b * DS + s) * 64 + lane];
-                Xm[0][b] = Tr<T>::mma(a, Xb[0][s], Xm[0][b]);
-                Xm[1][b] = Tr<T>::mma(a, Xb[1][s], Xm[1][b]);
+            for (int jj = 0; jj < 16; ++jj) {
+                float x = (float)Xh[b * SPB + jj / Tr<T>::FE][jj % Tr<T>::FE];
+                if (HAS_LO) x += (float)Xl[b * SPB + jj / Tr<T>::FE][jj % Tr<T>::FE];
+                Xn[b][jj] = x;
             }
 #pragma unroll
-        for (int qb = 0; qb < 2; ++qb)
+        for (int b = 0; b < DB; ++b)
 #pragma unroll
-            for (int b = 0; b < DB; ++b) pack_block<T>(Xm[qb][b], Xb[qb] + b * SPB);
+            for (int s = 0; s < DS; ++s) Xn[b] = Tr<T>::mma(sP[(b * DS + s) * 64 + lane], Xh[s], Xn[b]);
+#pragma unroll
+        for (int b = 0; b < DB; ++b) split_state(b, Xn[b]);
     };
 
     // ---- phase A: the tile's own super-block, chunk granularity -----------------------------
@@ -241,24 +250,21 @@ __global__ __launch_bounds__(256) void attn_fwd2_kernel(FwdParams p) {
 
     // ---- epilogue: normalise, store o and lse (paper Sec. 3.3, last step) ---------------------
     if (!active) return;
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = 1.f / l_tot;
+    const int tq = cq * CHUNK + 32 * qb + l32;
+    if (tq < L) {
+        TIO* orow = reinterpret_cast<TIO*>(p.o) + ((size_t)bh * L + tq) * D + 4 * h;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-        const float l_tot = l_run[qb] + __shfl_xor(l_run[qb], 32);
-        const float inv = 1.f / l_tot;
-        const int tq = cq * CHUNK + 32 * qb + l32;
-        if (tq < L) {
-            TIO* orow = reinterpret_cast<TIO*>(p.o) + ((size_t)bh * L + tq) * D + 4 * h;
+        for (int b = 0; b < DB; ++b)
 #pragma unroll
-            for (int b = 0; b < DB; ++b)
+            for (int g = 0; g < 4; ++g) {
+                Vec4 v4;
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    Vec4 v4;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) v4[r] = (TIO)(O[qb][b][4 * g + r] * inv);
-                    *reinterpret_cast<Vec4*>(orow + 32 * b + 8 * g) = v4;
-                }
-            if (h == 0) p.lse[(size_t)bh * L + tq] = (m_run[qb] + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
-        }
+                for (int r = 0; r < 4; ++r) v4[r] = (TIO)(O[b][4 * g + r] * inv);
+                *reinterpret_cast<Vec4*>(orow + 32 * b + 8 * g) = v4;
+            }
+        if (h == 0) p.lse[(size_t)bh * L + tq] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
     }
 }
 
@@ -276,7 +282,7 @@ hipError_t launch_attn_fwd2_t(const FwdParams& p, hipStream_t stream) {
     const int BH = p.B * p.H;
     dim3 grid((unsigned)(((BH + 7) / 8) * 8 * ntiles));
     const size_t bytes = C::smem_bytes;
-    hipLaunchKernelGGL((attn_fwd2_kernel<TIO, D, NBUF>), grid, dim3(256), bytes, stream, p);
+    hipLaunchKernelGGL((attn_fwd2_kernel<TIO, D, NBUF>), grid, dim3(FWD2_THREADS), bytes, stream, p);
     return hipGetLastError();
 }
 

@@ -38,12 +38,19 @@ template <typename TIO, int D> struct PrepCfg {
     static constexpr size_t off_gk = off_f + (size_t)CHUNK * LDC;     // (strictLower(W K^T))^T
     static constexpr size_t off_yt = off_gk + (size_t)CHUNK * LDC;    // Y^T
     static constexpr size_t off_nt = off_yt + (size_t)CHUNK * LDC;    // N (operand precision)
-    static constexpr size_t off_qs = off_nt + (size_t)CHUNK * LDC;    // Q rows (staged only)
+    static constexpr bool NT_IN_XF = sizeof(T) == 4;                  // fp32: N overwrites A^{-1} in place (same shape)
+    static constexpr size_t off_qs = off_nt + (NT_IN_XF ? 0 : (size_t)CHUNK * LDC);    // Q rows (staged only)
     static constexpr size_t off_ks = off_qs + (STAGE_QK ? (size_t)CHUNK * LDD : 0);
     static constexpr size_t t_elems = off_ks + (STAGE_QK ? (size_t)CHUNK * LDD : 0);
     static constexpr size_t off_af_bytes = ((t_elems * sizeof(T) + 15) / 16) * 16;   // fp32 A / solve
     static constexpr size_t off_beta_bytes = off_af_bytes + (size_t)CHUNK * LDA * 4;
-    static constexpr size_t smem_bytes = off_beta_bytes + CHUNK * 4;
+    static constexpr int LDH = 32 + 4;                 // fp32 32x32 helpers of the blocked inverse
+    static constexpr size_t off_xf_bytes = off_beta_bytes + CHUNK * 4;            // A^{-1}, fp32 [64][LDA]
+    // the two 32x32 fp32 helpers live in Y^T's space (Y^T is written only after the inverse is done)
+    static constexpr size_t off_xt1_bytes = off_yt * sizeof(T);                       // (A^{-1})_11^T
+    static constexpr size_t off_tt_bytes = off_xt1_bytes + (size_t)32 * LDH * 4;      // (A_21 (A^{-1})_11)^T
+    static_assert(2 * 32 * LDH * 4 <= CHUNK * LDC * sizeof(T), "helpers must fit in Y^T");
+    static constexpr size_t smem_bytes = off_xf_bytes + (size_t)CHUNK * LDA * 4;
 };
 
 template <typename TIO, int D>
@@ -64,9 +71,14 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     T* Fs = sT + C::off_f;
     T* Gk = sT + C::off_gk;
     T* Yt = sT + C::off_yt;
-    T* Nt = sT + C::off_nt;
+    T* Nt = C::NT_IN_XF ? reinterpret_cast<T*>(smem + C::off_xf_bytes) : sT + C::off_nt;
+    static_assert(!C::NT_IN_XF || C::LDC == C::LDA, "in-place N needs equal row pitch");
     float* Af = reinterpret_cast<float*>(smem + C::off_af_bytes);
     float* bs = reinterpret_cast<float*>(smem + C::off_beta_bytes);
+    float* Xf = reinterpret_cast<float*>(smem + C::off_xf_bytes);
+    float* XT1 = reinterpret_cast<float*>(smem + C::off_xt1_bytes);
+    float* TT = reinterpret_cast<float*>(smem + C::off_tt_bytes);
+    constexpr int LDH = C::LDH;
 
     const int chunk = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
@@ -176,26 +188,59 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     }
     __syncthreads();
 
-    // ---- phase 2: A^{-1} by forward substitution (one wave), N = A^{-1} diag(beta) ----
-    // Column c of A^{-1} depends only on itself: lane c computes rows 0..63 of it.
-    if (wv == 0) {
-        float n[CHUNK];
+    // ---- phase 2: X = A^{-1} (A unit lower triangular), then N = X diag(beta) --------------
+    // Blocked: the two 32x32 diagonal blocks by forward substitution (waves 0 and 1, one
+    // lane per column -- a column of the inverse depends only on itself), the off-diagonal
+    // block X_21 = -X_22 (A_21 X_11) by two fp32 MFMA products.
+    if (wv < 2) {
+        if (lane < 32) {
+            const int r0 = 32 * wv, c = lane;
+            float n[32];
 #pragma unroll
-        for (int t = 0; t < CHUNK; ++t) n[t] = 0.f;
-        const int c = lane;
+            for (int t = 0; t < 32; ++t) n[t] = 0.f;
 #pragma unroll
-        for (int t = 0; t < CHUNK; ++t) {
-            float acc = (t == c) ? 1.f : 0.f;
+            for (int t = 0; t < 32; ++t) {
+                float a0 = (t == c) ? 1.f : 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;
 #pragma unroll
-            for (int s4 = 0; s4 < (t + 3) / 4; ++s4) {
-                const f32x4 a4 = *reinterpret_cast<const f32x4*>(Af + t * LDA + 4 * s4);   // zeros for s >= t
-#pragma unroll
-                for (int r = 0; r < 4; ++r) acc -= a4[r] * n[4 * s4 + r];
+                for (int s4 = 0; s4 < (t + 3) / 4; ++s4) {
+                    const f32x4 a4 = *reinterpret_cast<const f32x4*>(Af + (r0 + t) * LDA + r0 + 4 * s4);   // zeros for s >= t
+                    a0 -= a4[0] * n[4 * s4 + 0];
+                    a1 -= a4[1] * n[4 * s4 + 1];
+                    a2 -= a4[2] * n[4 * s4 + 2];
+                    a3 -= a4[3] * n[4 * s4 + 3];
+                }
+                const float acc = (a0 + a1) + (a2 + a3);
+                n[t] = acc;
+                Xf[(r0 + t) * LDA + r0 + c] = acc;
+                if (wv == 0) XT1[c * LDH + t] = acc;
             }
-            n[t] = acc;
-            Nt[t * LDC + c] = (T)(acc * bs[c]);
-            if (p.aim) reinterpret_cast<T*>(p.aim)[bhc * 4096 + t * 64 + c] = (T)acc;
         }
+    } else if (wv == 2) {
+        for (int idx = lane; idx < 32 * 32; idx += 64) Xf[(idx >> 5) * LDA + 32 + (idx & 31)] = 0.f;   // upper-right block
+    }
+    __syncthreads();
+    if (wv == 0) {      // T = A_21 X_11, stored transposed
+        f32x16 acc = gemm32<float, 32>(Af + 32 * LDA, LDA, 0, XT1, LDH, 0, l32, h, zero16());
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            f32x4 v4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v4[r] = acc[4 * g + r];
+            *reinterpret_cast<f32x4*>(TT + l32 * LDH + 8 * g + 4 * h) = v4;
+        }
+    }
+    __syncthreads();
+    if (wv == 0) {      // X_21 = -X_22 T
+        f32x16 acc = gemm32<float, 32>(Xf + 32 * LDA + 32, LDA, 0, TT, LDH, 0, l32, h, zero16());
+#pragma unroll
+        for (int j = 0; j < 16; ++j) Xf[(32 + acc_row(j, h)) * LDA + l32] = -acc[j];
+    }
+    __syncthreads();
+    for (int idx = tid; idx < CHUNK * CHUNK; idx += 256) {
+        const int t = idx >> 6, c = idx & 63;
+        const float x = Xf[t * LDA + c];
+        Nt[t * LDC + c] = (T)(x * bs[c]);
+        if (p.aim) reinterpret_cast<T*>(p.aim)[bhc * 4096 + idx] = (T)x;
     }
     __syncthreads();
 

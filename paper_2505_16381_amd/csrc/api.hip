@@ -5,7 +5,6 @@
 
 namespace path {
 hipError_t launch_prep_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
-hipError_t launch_attn_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 
 hipError_t launch_prep2_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 hipError_t launch_attn_fwd2(const FwdParams& p, int d, int is_bf16, hipStream_t stream);

@@ -248,11 +248,6 @@ hipError_t launch_attn_fwd_t(const FwdParams& p, hipStream_t stream) {
     return hipGetLastError();
 }
 
-hipError_t launch_attn_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {
-    if (is_bf16) return d == 64 ? launch_attn_fwd_t<bf16_t, 64, false>(p, stream) : launch_attn_fwd_t<bf16_t, 128, false>(p, stream);
-    return d == 64 ? launch_attn_fwd_t<float, 64, false>(p, stream) : launch_attn_fwd_t<float, 128, false>(p, stream);
-}
-
 // Backward helper: the same sweep, query states only (written to p.xs).
 hipError_t launch_attn_states(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {
     if (is_bf16) return d == 64 ? launch_attn_fwd_t<bf16_t, 64, true>(p, stream) : launch_attn_fwd_t<bf16_t, 128, true>(p, stream);

@@ -411,7 +411,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             FragV fr[SPB];
             pack_block<TIO>(acc, fr);
 #pragma unroll
-            for (int s2 = 0; s2 < SPB; ++s2) vdst[((size_t)cb * (CHUNK / KW) + sb * SPB + s2) * 64 + lane] = fr[s2];
+            for (int s2 = 0; s2 < SPB; ++s2) vdst[(((size_t)sb * (D / 32) + cb) * SPB + s2) * 64 + lane] = fr[s2];   // [key half][d block][slab]
         }
     }
 }

@@ -65,7 +65,9 @@ def test_prep_intermediates_fp32(gpu, oracle):
     NC = -(-L // 64)
     f32 = lambda a, b_: raw[a:b_].view(np.float32).astype(np.float64)
     kt = wl.unfrag(f32(off[0], off[1])[: B * H * NC * 64 * d].reshape(B * H, NC, 64 * d), 64, d, 4)
-    vt = wl.unfrag(f32(off[1], off[2])[: B * H * NC * 64 * d].reshape(B * H, NC, 64 * d), d, 64, 4)
+    # V^T tiles: [32-key half][...] -- each half is a fragment-order tile with d rows and 32 contraction indices
+    vth = wl.unfrag(f32(off[1], off[2])[: B * H * NC * 64 * d].reshape(B * H, NC, 2, 32 * d), d, 32, 4)
+    vt = np.concatenate([vth[:, :, 0], vth[:, :, 1]], axis=-1)
     dp = wl.unfrag(f32(off[2], off[3])[: B * H * NC * d * d].reshape(B * H, NC, d * d), d, d, 4)
     xi = wl.unacc(f32(off[3], off[4])[: B * H * NC * 64 * d].reshape(B * H, NC, 2, d // 32, 1024))
     sd = wl.unacc(f32(off[4], off[5])[: B * H * NC * 4096].reshape(B * H, NC, 2, 2, 1024))

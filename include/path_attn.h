@@ -26,7 +26,8 @@
  *    contracts on fp32 MFMA.
  *  - d must be 64 or 128; any L >= 1 (a ragged last chunk is handled inside).
  *  - `scale` multiplies the finished bilinear form (the paper's logits are
- *    unscaled: pass 1.0f for those).  lse uses the natural logarithm.
+ *    unscaled: pass 1.0f for those); it must be > 0 (else PATH_ERR_UNSUPPORTED).
+ *    lse uses the natural logarithm.
  *  - w is used as given (no normalisation), beta as given (no clipping).
  *  - Only causal attention is defined by the method (the transition product
  *    runs along the path j -> i): causal == 0 returns PATH_ERR_UNSUPPORTED.
@@ -54,7 +55,7 @@ typedef enum {
     PATH_ERR_NULL = 1,        /* a required pointer is NULL                         */
     PATH_ERR_SHAPE = 2,       /* B,H,L < 1, d not in {64,128}, or sizes overflow     */
     PATH_ERR_DTYPE = 3,       /* dt is not PATH_F32 / PATH_BF16                      */
-    PATH_ERR_UNSUPPORTED = 4, /* causal == 0                                         */
+    PATH_ERR_UNSUPPORTED = 4, /* causal == 0, or scale <= 0                          */
     PATH_ERR_WORKSPACE = 5,   /* workspace too small or misaligned                   */
     PATH_ERR_HIP = 6,         /* a kernel launch failed                              */
     PATH_ERR_ALIGN = 7        /* q,k,v,w,o (or a gradient) not 16-byte aligned       */
@@ -111,8 +112,7 @@ path_status_t path_attn_fwd_sweep(void* o, float* lse, int B, int H, int L, int 
  *        d_o [B,H,L,d] (dt)                                  -- device, read-only
  *   out: dq, dk, dv, dw [B,H,L,d] (dt), dbeta [B,H,L] (dt)   -- device
  * dw is the gradient with respect to the w passed in (no projection onto the
- * unit sphere).  Accumulation across query tiles uses float atomics, so the
- * low-order bits of dk, dv, dw, dbeta may differ from run to run.
+ * unit sphere).  No atomics are used: results are bit-reproducible.
  */
 path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const void* w,
                             const void* beta, const void* o, const float* lse, const void* d_o,

@@ -146,6 +146,7 @@ extern "C" path_status_t path_attn_fwd_sweep(void* o, float* lse, int B, int H, 
                                              path_dtype_t dt, void* workspace, size_t workspace_bytes,
                                              void* stream) {
     if (!o || !lse) return PATH_ERR_NULL;
+    if (!(scale > 0.f)) return PATH_ERR_UNSUPPORTED;     // the online softmax tracks max(s) * scale
     FwdParams p = {};
     const path_status_t st = fwd_setup(p, B, H, L, d, dt, workspace, workspace_bytes);
     if (st != PATH_OK) return st;
@@ -162,7 +163,7 @@ extern "C" path_status_t path_attn_fwd(const void* q, const void* k, const void*
     if (!q || !k || !v || !w || !beta || !o || !lse || !workspace) return PATH_ERR_NULL;
     if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
     if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
-    if (!causal) return PATH_ERR_UNSUPPORTED;
+    if (!causal || !(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
     if (misaligned(o)) return PATH_ERR_ALIGN;
     path_status_t st = path_attn_fwd_prep(q, k, v, w, beta, B, H, L, d, dt, workspace, workspace_bytes, stream);
     if (st != PATH_OK) return st;
@@ -178,7 +179,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
         return PATH_ERR_NULL;
     if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
     if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
-    if (!causal) return PATH_ERR_UNSUPPORTED;
+    if (!causal || !(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
     const void* al[] = {q, k, v, w, o, d_o, dq, dk, dv, dw};
     for (const void* ptr : al) if (misaligned(ptr)) return PATH_ERR_ALIGN;
     const int bf = dt == PATH_BF16;

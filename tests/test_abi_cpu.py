@@ -61,6 +61,7 @@ def test_forward_argument_validation_without_gpu():
     assert _fwd(lib, ok, L=0) == 2
     assert _fwd(lib, ok, B=70000) == 2
     assert _fwd(lib, ok, causal=0) == 4                          # PATH_ERR_UNSUPPORTED
+    assert lib.path_attn_fwd(*ok, 1, 1, 64, 64, 1, 0.0, 0, 0x1000, 1 << 30, None) == 4   # scale must be > 0
     assert _fwd(lib, ok, ws_bytes=16) == 5                       # PATH_ERR_WORKSPACE
     assert _fwd(lib, ok, ws=0x1010) == 5                         # workspace not 256-aligned
     assert _fwd(lib, [0x1004] + ok[1:]) == 7                     # PATH_ERR_ALIGN

@@ -39,7 +39,7 @@ def test_workspace_bytes():
     assert pa.path_attn_workspace_bytes(1, 2, 256, 64, 7) == 0
     a = pa.path_attn_workspace_bytes(1, 1, 64, 64, pa.PATH_BF16)
     b = pa.path_attn_workspace_bytes(1, 1, 65, 64, pa.PATH_BF16)               # ragged tail = one more chunk
-    assert b == 2 * a
+    assert a < b <= 2 * a                                                       # per-chunk regions double, per-super-block ones do not
     off = pa.path_attn_fwd_workspace_layout(4, 16, 8192, 128, pa.PATH_BF16)
     assert list(off) == sorted(off) and all(o % 256 == 0 for o in off)
     assert off[5] <= pa.path_attn_workspace_bytes(4, 16, 8192, 128, pa.PATH_BF16)

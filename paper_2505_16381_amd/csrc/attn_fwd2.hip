@@ -156,35 +156,47 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
             for (int s = 0; s < DS; ++s) S = Tr<T>::mma(sK[s * 64 + lane], Xh[s], S);
         }
 
-        // ---- online softmax.  The reference maximum only moves when the block's maximum
-        // exceeds it by more than 2^16 (O and l are then rescaled: practically only on the
-        // first block); probabilities may be as large as 2^16, which bf16/fp32 operands and
-        // the fp32 sums hold without loss.
+        // ---- online softmax.  Fast path: exponentiate against the current reference maximum
+        // without looking at the block's own maximum; only if a lane's partial row sum is not
+        // below 2^16 (a logit beat the reference by more than ~16 bits, or overflowed), or on
+        // the wave's first block, take the slow path: find the block maximum, move the
+        // reference, rescale O and l, and exponentiate again.  Probabilities may thus be as
+        // large as 2^16, which bf16/fp32 operands and the fp32 sums hold without loss.
         {
-            float mloc = fmaxf(S[0], S[1]);
+            f32x16 E;
+            float rs = 0.f;
+            bool slow = j == cq && kb == 0;             // first block of this wave: no reference yet
+            if (!slow) {
+                const float mneg = -m_run;
 #pragma unroll
-            for (int jj = 2; jj < 16; jj += 2) mloc = fmaxf(mloc, fmaxf(S[jj], S[jj + 1]));
-            mloc = fmaxf(mloc, __shfl_xor(mloc, 32)) * sl2;
-            const bool move = mloc - m_run > 16.f;          // true on the first block (m_run = -inf)
-            if (__builtin_amdgcn_ballot_w64(move) != 0) {
-                const float m_new = move ? mloc : m_run;
-                const float alpha = move ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.f;
+                for (int jj = 0; jj < 16; ++jj) {
+                    E[jj] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, mneg));
+                    rs += E[jj];
+                }
+                slow = __builtin_amdgcn_ballot_w64(!(rs < 65536.f)) != 0;
+            }
+            if (slow) {
+                float mloc = fmaxf(S[0], S[1]);
+#pragma unroll
+                for (int jj = 2; jj < 16; jj += 2) mloc = fmaxf(mloc, fmaxf(S[jj], S[jj + 1]));
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 32)) * sl2;
+                const float m_new = fmaxf(m_run, mloc);     // finite: the first block holds the diagonal
+                const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
                 m_run = m_new;
                 l_run *= alpha;
 #pragma unroll
                 for (int b = 0; b < DB; ++b)
 #pragma unroll
                     for (int jj = 0; jj < 16; ++jj) O[b][jj] *= alpha;
-            }
-            const float mneg = -m_run;
-            float rs = 0.f;
+                rs = 0.f;
 #pragma unroll
-            for (int jj = 0; jj < 16; ++jj) {
-                const float e = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, mneg));
-                S[jj] = e;
-                rs += e;
+                for (int jj = 0; jj < 16; ++jj) {
+                    E[jj] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -m_new));
+                    rs += E[jj];
+                }
             }
             l_run += rs;
+            S = E;
         }
         FragV Pb[SPB];
         pack_block<TIO>(S, Pb);

@@ -43,7 +43,7 @@ static FwdWorkspace fwd_workspace(int B, int H, int L, int d, size_t es) {
 // Backward workspace: the forward's five regions first (same carve-up), then everything else.
 struct BwdWorkspace {
     FwdWorkspace f;
-    size_t knat, ktnat, dpnat, xs, gs, fm, gktm, nm, aim, ytm, utm, gm, sdm, delta, dqb, dkb, dvp, ddp;
+    size_t ktT, vk, dpt, doq, doT, xs, xsT, gs, fm, gktm, nm, aim, ytm, utm, gm, sdm, delta, dqb, dkb, dvp, ddp;
     size_t dpd, pd, dsd, df, dy, dn, dgk, rr, mm, dgs, du, dqf, dkf, dwf, dbf, total;
 };
 
@@ -54,11 +54,9 @@ static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
     w.f = fwd_workspace(B, H, L, d, es);
     size_t off = w.f.total;
     auto take = [&](size_t& field, size_t bytes) { field = off; off = align256(off + bytes); };
-    take(w.knat, BH * Lp * d * es);
-    take(w.ktnat, BH * Lp * d * es);
-    take(w.dpnat, BH * NC * d * d * es);
-    take(w.xs, BH * npairs * CHUNK * d * es);
-    take(w.gs, BH * npairs * CHUNK * d * es);
+    for (size_t* f : {&w.ktT, &w.vk, &w.doq, &w.doT}) take(*f, BH * Lp * d * es);
+    take(w.dpt, BH * NC * d * d * es);
+    for (size_t* f : {&w.xs, &w.xsT, &w.gs}) take(*f, BH * npairs * CHUNK * d * es);
     for (size_t* f : {&w.fm, &w.gktm, &w.nm, &w.aim, &w.ytm}) take(*f, BH * NC * 4096 * es);
     take(w.utm, BH * NC * d * CHUNK * es);
     take(w.gm, BH * NC * 4096 * 4);
@@ -198,7 +196,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     fp.kt = base + ws.f.kt; fp.vt = base + ws.f.vt; fp.dp = base + ws.f.dp;
     fp.xinit = F(ws.f.xinit); fp.sd = F(ws.f.sd);
     fp.B = B; fp.H = H; fp.L = L; fp.NC = NC; fp.scale = scale;
-    fp.knat = base + ws.knat; fp.ktnat = base + ws.ktnat; fp.dpnat = base + ws.dpnat; fp.xs = base + ws.xs;
+    fp.ktT = base + ws.ktT; fp.vk = base + ws.vk; fp.dpt = base + ws.dpt; fp.xs = base + ws.xs; fp.xsT = base + ws.xsT;
     fp.fm = base + ws.fm; fp.gktm = base + ws.gktm; fp.nm = base + ws.nm; fp.aim = base + ws.aim;
     fp.ytm = base + ws.ytm; fp.utm = base + ws.utm; fp.gm = F(ws.gm); fp.sdm = F(ws.sdm);
     if (launch_prep_fwd(fp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;
@@ -207,7 +205,8 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     // 2.-4. delta, adjoint scan over key chunks, key-side reductions
     BwdParams bp = {};
     bp.q = q; bp.k = k; bp.v = v; bp.w = w; bp.beta = beta; bp.o = o; bp.dO = d_o; bp.lse = lse;
-    bp.knat = fp.knat; bp.ktnat = fp.ktnat; bp.dpnat = fp.dpnat; bp.xs = fp.xs; bp.gs = base + ws.gs;
+    bp.kt = fp.kt; bp.vk = fp.vk; bp.ktT = fp.ktT; bp.dpt = fp.dpt; bp.xs = fp.xs; bp.xsT = fp.xsT;
+    bp.doq = base + ws.doq; bp.doT = base + ws.doT; bp.gs = base + ws.gs;
     bp.delta = F(ws.delta); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
     bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale;
     if (launch_bwd_scan(bp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;

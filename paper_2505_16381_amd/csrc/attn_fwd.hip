@@ -116,18 +116,26 @@ __global__ __launch_bounds__(256) void attn_fwd_kernel(FwdParams p) {
 
         if (STATES_ONLY) {
             if (j == cq) continue;
-            // state of this wave's 32 queries against key chunk j: xs[bh][pair(cq,j)][64][D], row-major
-            T* xrow = reinterpret_cast<T*>(p.xs) +
-                      (((size_t)bh * NC * (NC - 1) / 2 + pair_slot(cq, j)) * CHUNK + 32 * qb + l32) * D + 4 * h;
+            // state of this wave's 32 queries against key chunk j, as two fragment-order tiles of
+            // the pair (cq, j): xs (rows q, contraction c) is the operand copy itself; xsT (rows c,
+            // contraction q) is its transpose, taken through the matrix unit.
+            {
+                const size_t slot = ((size_t)bh * NC * (NC - 1) / 2 + pair_slot(cq, j)) * (size_t)CHUNK * D;
+                Frag* xd = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xs) + slot);
 #pragma unroll
-            for (int b = 0; b < DB; ++b)
+                for (int s = 0; s < DS; ++s) xd[((size_t)qb * DS + s) * 64 + lane] = Xb[s];
+                Frag* xt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xsT) + slot);
+                Frag idf[SPB];
+                identity_frags<T>(idf, l32, h);
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    typename Tr<T>::Vec4 v4;
+                for (int b = 0; b < DB; ++b) {
+                    const f32x16 tr = transpose32<T>(Xb + b * SPB, idf);     // rows q, lane c (block b)
+                    Frag fr[SPB];
+                    pack_block<T>(tr, fr);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) v4[r] = (T)Xm[b][4 * g + r];
-                    *reinterpret_cast<typename Tr<T>::Vec4*>(xrow + 32 * b + 8 * g) = v4;
+                    for (int s2 = 0; s2 < SPB; ++s2) xt[((size_t)b * (CHUNK / KW) + qb * SPB + s2) * 64 + lane] = fr[s2];
                 }
+            }
             if (j > 0) {
 #pragma unroll
                 for (int b = 0; b < DB; ++b)

@@ -4,17 +4,19 @@
 //   1. prep (forward kernel, extra row-major outputs) and a states-only sweep:
 //      Xs(i,j) = query state of chunk i as used against key chunk j < i.
 //   2. bwd_delta:    delta_t = dO_t . o_t.
-//   3. bwd_adjoint:  per query chunk i, left-to-right over key chunks j:
+//   3. bwd_adjoint2: per query chunk i, left-to-right over key chunks j:
 //        dS = scale * P o (dO V_j^T - delta),   P = exp(scale * Xs Kb_j^T - lse)
 //        g(i,j) = dS Kb_j + g(i,j-1) (I - dP_j)^T          (g(i,-1) = 0)
 //      g(i,i-1) is the gradient of the boundary-adjusted queries Qb_i.
-//   4. bwd_keyside:  per key chunk j, over query chunks i > j (no atomics):
+//   4. bwd_keyside2 / bwd_ddp: per key chunk j, over query chunks i > j (no atomics):
 //        dV_j += P^T dO_i,  dKb_j += dS^T Xs(i,j),  ddP_j -= Xs(i,j)^T g(i,j-1).
 //   5. chunk transform adjoint (Qb, Kb, dP, Sd -> q, k, w, beta): a short
 //      sequence of batched 64x64xd products (batched_gemm) and elementwise steps.
 //
-// Steps 3 and 4 read their operands row-major from the workspace and stage the
-// transposed copies they need through LDS.
+// Steps 3 and 4 follow the forward's scheme: activations stay in registers in
+// transposed form, streamed operands are fragment-order tiles (written by prep, the
+// states sweep and bwd_dotile), and the transposes that a change of contraction axis
+// needs are taken through the matrix unit (product with an identity operand).
 #include "path_common.h"
 #include "bwd_decl.h"
 
@@ -39,218 +41,335 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------------
-template <typename TIO, int D> struct AdjCfg {
-    typedef typename Compute<TIO>::type T;
-    static constexpr int FE = Tr<T>::FE;
-    static constexpr int LDD = D + FE, LDC = CHUNK + FE;
-    static constexpr size_t smem_bytes = ((size_t)CHUNK * LDD + (size_t)CHUNK * LDC) * sizeof(T) + 2 * CHUNK * 4;
-};
-
+// dO of a query chunk as two fragment-order tiles (I/O type; rows past L are zero):
+//   doq (rows q, contraction c)  and  doT (rows c, contraction q).
 template <typename TIO, int D>
-__global__ __launch_bounds__(256) void bwd_adjoint_kernel(BwdParams p) {
-    using C = AdjCfg<TIO, D>;
-    using T = typename C::T;
-    constexpr int FE = C::FE, LDD = C::LDD, LDC = C::LDC;
-    constexpr int DB = D / 32, NOWN = 2 * DB / 4;
-
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    T* gT = reinterpret_cast<T*>(smem);                 // g(i,j-1), rows t
-    T* dST = gT + CHUNK * LDD;                          // dS[t][s]
-    float* lse2 = reinterpret_cast<float*>(dST + CHUNK * LDC);
-    float* dl = lse2 + CHUNK;
-
+__global__ __launch_bounds__(256) void bwd_dotile_kernel(BwdParams p) {
+    using FragV = typename Tr<TIO>::Frag;
+    constexpr int KW = Tr<TIO>::KW, SPB = 32 / KW, DB = D / 32, QS = CHUNK / KW;
     const int i = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
     const int L = p.L, NC = p.NC;
-    const size_t Lp = (size_t)NC * CHUNK, npairs = (size_t)NC * (NC - 1) / 2;
-    const float sl2 = p.scale * 1.44269504088896340736f;
-
-    f32x16 gm[NOWN];
+    const TIO* dO = reinterpret_cast<const TIO*>(p.dO) + ((size_t)bh * L + (size_t)i * CHUNK) * D;
+    const int nvalid = (L - i * CHUNK < CHUNK) ? L - i * CHUNK : CHUNK;
+    FragV* dq = reinterpret_cast<FragV*>(reinterpret_cast<TIO*>(p.doq) + ((size_t)bh * NC + i) * CHUNK * D);
+    FragV* dt = reinterpret_cast<FragV*>(reinterpret_cast<TIO*>(p.doT) + ((size_t)bh * NC + i) * CHUNK * D);
+    for (int blk = wv; blk < 2 * DB; blk += 4) {
+        const int cb = blk >> 1, qb = blk & 1;
+        f32x16 a, b;
 #pragma unroll
-    for (int o = 0; o < NOWN; ++o) gm[o] = zero16();
-
-    for (int idx = tid; idx < CHUNK * LDD; idx += 256) gT[idx] = (T)0.f;
-    if (tid < CHUNK) {
-        const int tg = i * CHUNK + tid;
-        lse2[tid] = (tg < L) ? p.lse[(size_t)bh * L + tg] * 1.44269504088896340736f : 0.f;
-        dl[tid] = p.delta[(size_t)bh * Lp + tg];
-    }
-    __syncthreads();
-
-    const int tb = wv >> 1, sb = wv & 1;
-    const int trow = i * CHUNK + 32 * tb + l32;
-    const TIO* dop = reinterpret_cast<const TIO*>(p.dO) + ((size_t)bh * L + (trow < L ? trow : L - 1)) * D + FE * h;
-
-    for (int j = 0; j < i; ++j) {
-        const T* xst = reinterpret_cast<const T*>(p.xs) + ((size_t)bh * npairs + pair_slot(i, j)) * CHUNK * D;
-        const T* kn = reinterpret_cast<const T*>(p.knat) + ((size_t)bh * NC + j) * CHUNK * D;
-        const T* ktn = reinterpret_cast<const T*>(p.ktnat) + ((size_t)bh * NC + j) * CHUNK * D;
-        const T* dpn = reinterpret_cast<const T*>(p.dpnat) + ((size_t)bh * NC + j) * D * D;
-        const TIO* vp = reinterpret_cast<const TIO*>(p.v) + ((size_t)bh * L + j * CHUNK + 32 * sb + l32) * D + FE * h;
-
-        f32x16 S = gemm_rows<T, D>(xst + (size_t)(32 * tb + l32) * D + FE * h,
-                                   kn + (size_t)(32 * sb + l32) * D + FE * h, zero16());
-        f32x16 dP = gemm_rows<TIO, D>(dop, vp, zero16());
-#pragma unroll
-        for (int jj = 0; jj < 16; ++jj) {
-            const int t = 32 * tb + acc_row(jj, h);
-            const float P = (i * CHUNK + t < L) ? __builtin_amdgcn_exp2f(S[jj] * sl2 - lse2[t]) : 0.f;
-            dST[t * LDC + 32 * sb + l32] = (T)(P * (dP[jj] - dl[t]) * p.scale);
+        for (int j = 0; j < 16; ++j) {
+            const int q1 = 32 * qb + l32, c1 = 32 * cb + acc_row(j, h);      // registers rows c, lane q
+            a[j] = (q1 < nvalid) ? (float)dO[(size_t)q1 * D + c1] : 0.f;
+            const int q2 = 32 * qb + acc_row(j, h), c2 = 32 * cb + l32;      // registers rows q, lane c
+            b[j] = (q2 < nvalid) ? (float)dO[(size_t)q2 * D + c2] : 0.f;
         }
-        __syncthreads();
+        FragV fa[SPB], fb[SPB];
+        pack_block<TIO>(a, fa);
+        pack_block<TIO>(b, fb);
 #pragma unroll
-        for (int o = 0; o < NOWN; ++o) {
-            const int blk = wv + 4 * o, tb2 = blk / DB, cb = blk % DB;
-            f32x16 a1 = gemm32<T, CHUNK>(dST, LDC, 32 * tb2, ktn, CHUNK, 32 * cb, l32, h, zero16());
-            f32x16 a2 = gemm32<T, D>(gT, LDD, 32 * tb2, dpn, D, 32 * cb, l32, h, zero16());
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) gm[o][jj] += a1[jj] - a2[jj];
+        for (int s = 0; s < SPB; ++s) {
+            dq[((size_t)qb * (D / KW) + cb * SPB + s) * 64 + lane] = fa[s];
+            dt[((size_t)cb * QS + qb * SPB + s) * 64 + lane] = fb[s];
         }
-        __syncthreads();
-        T* gst = reinterpret_cast<T*>(p.gs) + ((size_t)bh * npairs + pair_slot(i, j + 1 < i ? j + 1 : j)) * CHUNK * D;
-        const bool store = j + 1 < i;
-#pragma unroll
-        for (int o = 0; o < NOWN; ++o) {
-            const int blk = wv + 4 * o, tb2 = blk / DB, cb = blk % DB;
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) {
-                const int t = 32 * tb2 + acc_row(jj, h), c = 32 * cb + l32;
-                const T v = (T)gm[o][jj];
-                gT[t * LDD + c] = v;
-                if (store) gst[(size_t)t * D + c] = v;
-            }
-        }
-        __syncthreads();
-    }
-#pragma unroll
-    for (int o = 0; o < NOWN; ++o) {
-        const int blk = wv + 4 * o, tb2 = blk / DB, cb = blk % DB;
-#pragma unroll
-        for (int jj = 0; jj < 16; ++jj)
-            p.dqb[((size_t)bh * Lp + i * CHUNK + 32 * tb2 + acc_row(jj, h)) * D + 32 * cb + l32] = gm[o][jj];
     }
 }
 
 // ---------------------------------------------------------------------------------------
-template <typename TIO, int D> struct KeyCfg {
+// Adjoint scan.  One workgroup = 4 waves = two query chunks; wave w owns the 32-query half
+// (w & 1) of chunk 2*tile + (w >> 1), exactly as in the states sweep.  Everything is transposed
+// (wave = 32 queries = the MFMA columns), so the adjoint state g^T (rows c, lane q) stays in
+// registers across the key chunks j = 0 .. cq-1:
+//     S^T  = Kb_j Xs^T            A = kt tile,   B = Xs fragments (loaded per pair)
+//     dP^T = V_j dO^T             A = vk tile,   B = dO fragments (resident)
+//     dS^T = scale * P o (dP^T - delta),   P = exp(scale S^T - lse)
+//     g^T <- g^T + Kb_j^T dS^T - dP_j g^T      A = ktT tile / dpt tile,  B = dS^T / g^T (registers)
+// After step j the state is also written, transposed through the matrix unit, as the tile
+// gT (rows b, contraction q) of pair (cq, j+1) for the key-side kernels.
+template <typename TIO, int D> struct Adj2Cfg {
     typedef typename Compute<TIO>::type T;
     static constexpr int FE = Tr<T>::FE;
-    static constexpr int LDC = CHUNK + FE;
-    static constexpr size_t smem_bytes = (size_t)D * LDC * (2 * sizeof(T) + sizeof(TIO)) +
-                                         (size_t)CHUNK * LDC * (sizeof(T) + sizeof(TIO)) + 2 * CHUNK * 4;
+    static constexpr int KV_FRAGS = CHUNK * D / FE, DP_FRAGS = D * D / FE;
+    static constexpr size_t smem_bytes = (size_t)(3 * KV_FRAGS + DP_FRAGS) * 16;   // kt | vk | ktT | dpt
 };
 
 template <typename TIO, int D>
-__global__ __launch_bounds__(256) void bwd_keyside_kernel(BwdParams p) {
-    using C = KeyCfg<TIO, D>;
+__global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
+    using C = Adj2Cfg<TIO, D>;
     using T = typename C::T;
     using Frag = typename Tr<T>::Frag;
-    using FragIO = typename Tr<TIO>::Frag;
-    constexpr int FE = C::FE, LDC = C::LDC;
-    constexpr int DB = D / 32, NOWN = 2 * DB / 4, NDP = DB * DB / 4;
+    using FragV = typename Tr<TIO>::Frag;
+    constexpr int KW = Tr<T>::KW, SPB = 32 / KW, DB = D / 32, DS = D / KW, QS = CHUNK / KW;
+    constexpr int KVF = C::KV_FRAGS, DPF = C::DP_FRAGS;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    T* Xt = reinterpret_cast<T*>(smem);                       // [c][t]
-    T* Gt = Xt + D * LDC;                                     // [b][t]
-    TIO* dOt = reinterpret_cast<TIO*>(Gt + D * LDC);          // [c][t]
-    TIO* Pt = dOt + D * LDC;                                  // [s][t]
-    T* dSt = reinterpret_cast<T*>(Pt + CHUNK * LDC);          // [s][t]
-    float* lse2 = reinterpret_cast<float*>(dSt + CHUNK * LDC);
+    Frag* sK = reinterpret_cast<Frag*>(smem);
+    FragV* sV = reinterpret_cast<FragV*>(sK + KVF);
+    Frag* sKT = sK + 2 * KVF;
+    Frag* sDP = sK + 3 * KVF;
+
+    const int BH = p.B * p.H, L = p.L, NC = p.NC;
+    const int ntiles = (NC + 1) / 2;
+    const int tile = ntiles - 1 - (int)(blockIdx.x / BH);
+    const int bh = blockIdx.x % BH;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
+    const bool active = cq < NC;
+    const int jmax = ((tile * 2 + 1 < NC) ? tile * 2 + 1 : NC - 1) - 1;     // last key chunk any wave needs
+    const size_t Lp = (size_t)NC * CHUNK, npairs = (size_t)NC * (NC - 1) / 2;
+    const float sl2 = p.scale * 1.44269504088896340736f;
+    const int tq = cq * CHUNK + 32 * qb + l32;                             // this lane's query
+
+    // resident: dO fragments of the wave's 32 queries, lse and delta of the lane's query
+    FragV dOb[DS];
+    float lse2 = 0.f, dl = 0.f;
+    if (active) {
+        const FragV* dq = reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.doq) + ((size_t)bh * NC + cq) * CHUNK * D);
+#pragma unroll
+        for (int s = 0; s < DS; ++s) dOb[s] = dq[((size_t)qb * DS + s) * 64 + lane];
+        if (tq < L) lse2 = p.lse[(size_t)bh * L + tq] * 1.44269504088896340736f;
+        dl = p.delta[(size_t)bh * Lp + tq];
+    }
+    f32x16 Gm[DB];
+    Frag Gb[DS];
+#pragma unroll
+    for (int b = 0; b < DB; ++b) { Gm[b] = zero16(); pack_block<T>(Gm[b], Gb + b * SPB); }
+    Frag idf[SPB];
+    identity_frags<T>(idf, l32, h);
+
+    for (int j = 0; j <= jmax; ++j) {
+        const size_t bhc = (size_t)bh * NC + j;
+        __syncthreads();
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * CHUNK * D), sK, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), sV, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.ktT) + bhc * CHUNK * D), sKT, KVF, tid, wv);
+        if (j > 0) async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D), sDP, DPF, tid, wv);
+        wait_async_and_sync();
+        if (!active || j >= cq) continue;
+
+        const size_t slot = ((size_t)bh * npairs + pair_slot(cq, j)) * (size_t)CHUNK * D;
+        const Frag* xg = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot);
+        Frag Xb[DS];
+#pragma unroll
+        for (int s = 0; s < DS; ++s) Xb[s] = xg[((size_t)qb * DS + s) * 64 + lane];
+
+        Frag dSb[QS];
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            f32x16 S = zero16(), dP = zero16();
+#pragma unroll
+            for (int s = 0; s < DS; ++s) {
+                S = Tr<T>::mma(sK[(kb * DS + s) * 64 + lane], Xb[s], S);
+                dP = Tr<TIO>::mma(sV[(kb * DS + s) * 64 + lane], dOb[s], dP);
+            }
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const float P = (tq < L) ? __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -lse2)) : 0.f;
+                S[jj] = P * (dP[jj] - dl) * p.scale;
+            }
+            pack_block<T>(S, dSb + kb * SPB);
+        }
+#pragma unroll
+        for (int b = 0; b < DB; ++b) {
+#pragma unroll
+            for (int s = 0; s < QS; ++s) Gm[b] = Tr<T>::mma(sKT[(b * QS + s) * 64 + lane], dSb[s], Gm[b]);
+            if (j > 0) {
+#pragma unroll
+                for (int s = 0; s < DS; ++s) Gm[b] = Tr<T>::mma(sDP[(b * DS + s) * 64 + lane], Gb[s], Gm[b]);
+            }
+        }
+#pragma unroll
+        for (int b = 0; b < DB; ++b) pack_block<T>(Gm[b], Gb + b * SPB);
+        if (j + 1 < cq) {      // g(cq, j) as tile gT (rows b, contraction q) of pair (cq, j+1)
+            const size_t slot2 = ((size_t)bh * npairs + pair_slot(cq, j + 1)) * (size_t)CHUNK * D;
+            Frag* gt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.gs) + slot2);
+#pragma unroll
+            for (int b = 0; b < DB; ++b) {
+                const f32x16 tr = transpose32<T>(Gb + b * SPB, idf);       // rows q, lane b
+                Frag fr[SPB];
+                pack_block<T>(tr, fr);
+#pragma unroll
+                for (int s2 = 0; s2 < SPB; ++s2) gt[((size_t)b * QS + qb * SPB + s2) * 64 + lane] = fr[s2];
+            }
+        }
+    }
+    // dQb of the wave's queries: row-major fp32 [q][c] from registers (rows c, lane q)
+    if (active) {
+        float* dst = p.dqb + ((size_t)bh * Lp + tq) * D + 4 * h;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v4[r] = Gm[b][4 * g + r];
+                *reinterpret_cast<f32x4*>(dst + 32 * b + 8 * g) = v4;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// Key-side reduction of dV and dKb.  One workgroup per key chunk j; wave w owns the 32 keys of
+// half (w & 1) (= the MFMA columns) and the 32-query half (w >> 1) of every query chunk i > j:
+//     S  = Xs Kb_j^T              A = xs tile,   B = Kb fragments (resident)
+//     dP = dO V_j^T               A = doq tile,  B = V fragments (resident)
+//     dV^T  += dO^T P             A = doT tile,  B = P   (registers)
+//     dKb^T += Xs^T dS            A = xsT tile,  B = dS  (registers)
+// The two query halves are summed through LDS at the end (no atomics).
+template <typename TIO, int D> struct Key2Cfg {
+    typedef typename Compute<TIO>::type T;
+    static constexpr int FE = Tr<T>::FE;
+    static constexpr int KV_FRAGS = CHUNK * D / FE;
+    static constexpr size_t tile_bytes = (size_t)4 * KV_FRAGS * 16;           // xs | xsT | doq | doT
+    static constexpr size_t red_bytes = (size_t)2 * 2 * (D / 32) * 1024 * 4;   // dV, dKb of the two upper waves
+    static constexpr size_t smem_bytes = (tile_bytes > red_bytes ? tile_bytes : red_bytes) + 2 * CHUNK * 4;
+};
+
+template <typename TIO, int D>
+__global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
+    using C = Key2Cfg<TIO, D>;
+    using T = typename C::T;
+    using Frag = typename Tr<T>::Frag;
+    using FragV = typename Tr<TIO>::Frag;
+    constexpr int KW = Tr<T>::KW, SPB = 32 / KW, DB = D / 32, DS = D / KW, QS = CHUNK / KW;
+    constexpr int KVF = C::KV_FRAGS;
+
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    Frag* sX = reinterpret_cast<Frag*>(smem);
+    Frag* sXT = sX + KVF;
+    FragV* sDQ = reinterpret_cast<FragV*>(sX + 2 * KVF);
+    FragV* sDT = reinterpret_cast<FragV*>(sX + 3 * KVF);
+    constexpr size_t data_bytes = C::tile_bytes > C::red_bytes ? C::tile_bytes : C::red_bytes;
+    float* lse2 = reinterpret_cast<float*>(smem + data_bytes);
     float* dl = lse2 + CHUNK;
 
     const int j = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int kh = wv & 1, qh = wv >> 1;
     const int L = p.L, NC = p.NC;
     const size_t Lp = (size_t)NC * CHUNK, npairs = (size_t)NC * (NC - 1) / 2;
     const float sl2 = p.scale * 1.44269504088896340736f;
 
-    f32x16 dV[NOWN], dK[NOWN], dDP[NDP];
+    Frag Kb[DS];
+    FragV Vb[DS];
+    {
+        const Frag* kg = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + ((size_t)bh * NC + j) * CHUNK * D);
+        const FragV* vg = reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.vk) + ((size_t)bh * NC + j) * CHUNK * D);
 #pragma unroll
-    for (int o = 0; o < NOWN; ++o) { dV[o] = zero16(); dK[o] = zero16(); }
+        for (int s = 0; s < DS; ++s) { Kb[s] = kg[((size_t)kh * DS + s) * 64 + lane]; Vb[s] = vg[((size_t)kh * DS + s) * 64 + lane]; }
+    }
+    f32x16 dVt[DB], dKt[DB];
 #pragma unroll
-    for (int o = 0; o < NDP; ++o) dDP[o] = zero16();
-
-    const int tb = wv >> 1, sb = wv & 1;
-    const T* kn = reinterpret_cast<const T*>(p.knat) + ((size_t)bh * NC + j) * CHUNK * D;
-    // rows of V_j: chunk j < NC-1 is always complete when the loop below runs
-    const TIO* vp = reinterpret_cast<const TIO*>(p.v) + ((size_t)bh * L + j * CHUNK + 32 * sb + l32) * D + FE * h;
+    for (int b = 0; b < DB; ++b) { dVt[b] = zero16(); dKt[b] = zero16(); }
 
     for (int i = j + 1; i < NC; ++i) {
-        const T* xst = reinterpret_cast<const T*>(p.xs) + ((size_t)bh * npairs + pair_slot(i, j)) * CHUNK * D;
-        const T* gst = reinterpret_cast<const T*>(p.gs) + ((size_t)bh * npairs + pair_slot(i, j)) * CHUNK * D;
-        for (int idx = tid; idx < CHUNK * (D / FE); idx += 256) {
-            const int row = idx / (D / FE), cf = idx % (D / FE);
-            const int tg = i * CHUNK + row;
-            const Frag xv = ld_frag<T>(xst + (size_t)row * D + cf * FE);
-            Frag gv = Tr<T>::zero();
-            if (j >= 1) gv = ld_frag<T>(gst + (size_t)row * D + cf * FE);
-            FragIO ov = Tr<TIO>::zero();
-            if (tg < L) ov = ld_frag<TIO>(reinterpret_cast<const TIO*>(p.dO) + ((size_t)bh * L + tg) * D + cf * FE);
-#pragma unroll
-            for (int e = 0; e < FE; ++e) {
-                Xt[(cf * FE + e) * LDC + row] = xv[e];
-                Gt[(cf * FE + e) * LDC + row] = gv[e];
-                dOt[(cf * FE + e) * LDC + row] = ov[e];
-            }
-        }
+        const size_t slot = ((size_t)bh * npairs + pair_slot(i, j)) * (size_t)CHUNK * D;
+        const size_t bhi = ((size_t)bh * NC + i) * CHUNK * D;
+        __syncthreads();
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot), sX, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), sXT, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.doq) + bhi), sDQ, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.doT) + bhi), sDT, KVF, tid, wv);
         if (tid < CHUNK) {
             const int tg = i * CHUNK + tid;
             lse2[tid] = (tg < L) ? p.lse[(size_t)bh * L + tg] * 1.44269504088896340736f : 0.f;
             dl[tid] = p.delta[(size_t)bh * Lp + tg];
         }
-        __syncthreads();
+        wait_async_and_sync();
 
-        const int trow = i * CHUNK + 32 * tb + l32;
-        const TIO* dop = reinterpret_cast<const TIO*>(p.dO) + ((size_t)bh * L + (trow < L ? trow : L - 1)) * D + FE * h;
-        f32x16 S = gemm_rows<T, D>(xst + (size_t)(32 * tb + l32) * D + FE * h,
-                                   kn + (size_t)(32 * sb + l32) * D + FE * h, zero16());
-        f32x16 dP = gemm_rows<TIO, D>(dop, vp, zero16());
+        f32x16 S = zero16(), dP = zero16();                    // rows q (half qh), lane s
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            typename Tr<TIO>::Vec4 p4;
-            typename Tr<T>::Vec4 s4;
+        for (int s = 0; s < DS; ++s) {
+            S = Tr<T>::mma(sX[(qh * DS + s) * 64 + lane], Kb[s], S);
+            dP = Tr<TIO>::mma(sDQ[(qh * DS + s) * 64 + lane], Vb[s], dP);
+        }
+        f32x16 Pm;
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int t = 32 * tb + 8 * g + 4 * h + r;
-                const float P = (i * CHUNK + t < L) ? __builtin_amdgcn_exp2f(S[4 * g + r] * sl2 - lse2[t]) : 0.f;
-                p4[r] = (TIO)P;
-                s4[r] = (T)(P * (dP[4 * g + r] - dl[t]) * p.scale);
+        for (int jj = 0; jj < 16; ++jj) {
+            const int q = 32 * qh + acc_row(jj, h);
+            const float P = (i * CHUNK + q < L) ? __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -lse2[q])) : 0.f;
+            Pm[jj] = P;
+            S[jj] = P * (dP[jj] - dl[q]) * p.scale;
+        }
+        FragV Pb[SPB];
+        Frag dSb[SPB];
+        pack_block<TIO>(Pm, Pb);
+        pack_block<T>(S, dSb);
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int s = 0; s < SPB; ++s) {
+                dVt[b] = Tr<TIO>::mma(sDT[(b * QS + qh * SPB + s) * 64 + lane], Pb[s], dVt[b]);
+                dKt[b] = Tr<T>::mma(sXT[(b * QS + qh * SPB + s) * 64 + lane], dSb[s], dKt[b]);
             }
-            *reinterpret_cast<typename Tr<TIO>::Vec4*>(Pt + (32 * sb + l32) * LDC + 32 * tb + 8 * g + 4 * h) = p4;
-            *reinterpret_cast<typename Tr<T>::Vec4*>(dSt + (32 * sb + l32) * LDC + 32 * tb + 8 * g + 4 * h) = s4;
-        }
-        __syncthreads();
+    }
+    // sum the two query halves, write row-major fp32 [s][c] from registers (rows c, lane s)
+    __syncthreads();
+    float* red = reinterpret_cast<float*>(smem);
+    if (qh == 1) {
 #pragma unroll
-        for (int o = 0; o < NOWN; ++o) {
-            const int blk = wv + 4 * o, sb2 = blk / DB, cb = blk % DB;
-            dV[o] = gemm32<TIO, CHUNK>(Pt, LDC, 32 * sb2, dOt, LDC, 32 * cb, l32, h, dV[o]);
-            dK[o] = gemm32<T, CHUNK>(dSt, LDC, 32 * sb2, Xt, LDC, 32 * cb, l32, h, dK[o]);
-        }
-        if (j >= 1) {
+        for (int b = 0; b < DB; ++b)
 #pragma unroll
-            for (int o = 0; o < NDP; ++o) {
+            for (int jj = 0; jj < 16; ++jj) {
+                red[((kh * 2 + 0) * DB + b) * 1024 + jj * 64 + lane] = dVt[b][jj];
+                red[((kh * 2 + 1) * DB + b) * 1024 + jj * 64 + lane] = dKt[b][jj];
+            }
+    }
+    __syncthreads();
+    if (qh == 0) {
+        const size_t row = ((size_t)bh * Lp + j * CHUNK + 32 * kh + l32) * D + 4 * h;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v4, k4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    v4[r] = dVt[b][4 * g + r] + red[((kh * 2 + 0) * DB + b) * 1024 + (4 * g + r) * 64 + lane];
+                    k4[r] = dKt[b][4 * g + r] + red[((kh * 2 + 1) * DB + b) * 1024 + (4 * g + r) * 64 + lane];
+                }
+                *reinterpret_cast<f32x4*>(p.dvp + row + 32 * b + 8 * g) = v4;
+                *reinterpret_cast<f32x4*>(p.dkb + row + 32 * b + 8 * g) = k4;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// ddP_j[a][b] = - sum_{i>j} sum_q Xs(i,j)[q][a] g(i,j-1)[q][b]: one workgroup per key chunk, a plain
+// product over the stacked query axis; both operands are read as fragments straight from global
+// memory (tiles xsT and gT, contraction q).
+template <typename TIO, int D>
+__global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
+    using T = typename Compute<TIO>::type;
+    using Frag = typename Tr<T>::Frag;
+    constexpr int KW = Tr<T>::KW, DB = D / 32, QS = CHUNK / KW, NOWN = DB * DB / 4;
+    const int j = blockIdx.x, bh = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int NC = p.NC;
+    const size_t npairs = (size_t)NC * (NC - 1) / 2;
+    f32x16 acc[NOWN];
+#pragma unroll
+    for (int o = 0; o < NOWN; ++o) acc[o] = zero16();
+    if (j >= 1) {
+        for (int i = j + 1; i < NC; ++i) {
+            const size_t slot = ((size_t)bh * npairs + pair_slot(i, j)) * (size_t)CHUNK * D;
+            const Frag* xt = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot);
+            const Frag* gt = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.gs) + slot);
+#pragma unroll
+            for (int o = 0; o < NOWN; ++o) {
                 const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
-                dDP[o] = gemm32<T, CHUNK>(Xt, LDC, 32 * ab, Gt, LDC, 32 * bb, l32, h, dDP[o]);
+#pragma unroll
+                for (int s = 0; s < QS; ++s)
+                    acc[o] = Tr<T>::mma(xt[((size_t)ab * QS + s) * 64 + lane], gt[((size_t)bb * QS + s) * 64 + lane], acc[o]);
             }
         }
-        __syncthreads();
     }
 #pragma unroll
     for (int o = 0; o < NOWN; ++o) {
-        const int blk = wv + 4 * o, sb2 = blk / DB, cb = blk % DB;
-#pragma unroll
-        for (int jj = 0; jj < 16; ++jj) {
-            const size_t off = ((size_t)bh * Lp + j * CHUNK + 32 * sb2 + acc_row(jj, h)) * D + 32 * cb + l32;
-            p.dvp[off] = dV[o][jj];
-            p.dkb[off] = dK[o][jj];
-        }
-    }
-#pragma unroll
-    for (int o = 0; o < NDP; ++o) {
         const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj)
-            p.ddp[(((size_t)bh * NC + j) * D + 32 * ab + acc_row(jj, h)) * D + 32 * bb + l32] = -dDP[o][jj];
+            p.ddp[(((size_t)bh * NC + j) * D + 32 * ab + acc_row(jj, h)) * D + 32 * bb + l32] = -acc[o][jj];
     }
 }
 
@@ -383,12 +502,17 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     hipError_t e;
     hipLaunchKernelGGL((bwd_delta_kernel<TIO, D>), grid, dim3(256), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    const size_t adj_bytes = AdjCfg<TIO, D>::smem_bytes, key_bytes = KeyCfg<TIO, D>::smem_bytes;
-    if ((e = set_smem(&bwd_adjoint_kernel<TIO, D>, adj_bytes)) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_adjoint_kernel<TIO, D>), grid, dim3(256), adj_bytes, st, p);
+    hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D>), grid, dim3(256), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = set_smem(&bwd_keyside_kernel<TIO, D>, key_bytes)) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_keyside_kernel<TIO, D>), grid, dim3(256), key_bytes, st, p);
+    const size_t adj_bytes = Adj2Cfg<TIO, D>::smem_bytes, key_bytes = Key2Cfg<TIO, D>::smem_bytes;
+    if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D>, adj_bytes)) != hipSuccess) return e;
+    const int ntiles = (p.NC + 1) / 2;
+    hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D>), dim3((unsigned)(ntiles * p.B * p.H)), dim3(256), adj_bytes, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if ((e = set_smem(&bwd_keyside2_kernel<TIO, D>, key_bytes)) != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D>), grid, dim3(256), key_bytes, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D>), grid, dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

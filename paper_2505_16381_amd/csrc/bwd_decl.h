@@ -7,8 +7,10 @@ namespace path {
 struct BwdParams {
     const void *q, *k, *v, *w, *beta, *o, *dO;
     const float* lse;
-    const void *knat, *ktnat, *dpnat, *xs;
-    void* gs;                 // adjoint states g(i,j-1) at slot (i,j), row-major, operand type
+    const void *kt, *vk, *ktT, *dpt;   // per-chunk fragment tiles from the chunk transform
+    const void *xs, *xsT;              // per-pair query-state tiles from the states sweep
+    void *doq, *doT;                   // per-chunk dO tiles (I/O type)
+    void* gs;                          // per-pair adjoint-state tiles gT (rows b, contraction q): g(i,j-1) at slot (i,j)
     float *delta;             // [BH][Lp]
     float *dqb, *dkb, *dvp;   // [BH][Lp][d] fp32: dQb, dKb, dV (off-diagonal part)
     float *ddp;               // [BH][NC][d][d] fp32: ddP[a][b]

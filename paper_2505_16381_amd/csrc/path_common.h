@@ -174,6 +174,40 @@ __device__ __forceinline__ f32x16 gemm_rows(const T* ap, const T* bp, f32x16 acc
     return acc;
 }
 
+// Linear copy of nfrag 16-byte fragments global -> LDS, asynchronous (direct-to-LDS): in a
+// workgroup of NT threads wave wv moves fragments [i*NT + 64*wv, +64) of every NT-fragment group.
+template <int NT, typename Frag>
+__device__ __forceinline__ void async_copy_tile(const Frag* g, Frag* s, int nfrag, int tid, int wv) {
+    for (int i = 0; i < nfrag; i += NT)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + i + tid),
+                                         (__attribute__((address_space(3))) void*)(s + i + 64 * wv), 16, 0, 0);
+}
+__device__ __forceinline__ void wait_async_and_sync() {
+    __builtin_amdgcn_s_waitcnt(0x0000);   // vmcnt(0) expcnt(0) lgkmcnt(0): this wave's copies have landed
+    __syncthreads();
+}
+
+// Identity operand for transposing a 32x32 block through the matrix unit: with the block given as
+// an A operand (rows r, contraction k; i.e. packed from accumulators that hold it as rows k, lane r),
+// D = A * I comes out with rows r, lane k -- the transposed register layout.  Slab s of the identity
+// B operand for lane (column l32, half h): element e is 1 where the contraction index equals l32.
+template <typename T>
+__device__ __forceinline__ void identity_frags(typename Tr<T>::Frag* id, int l32, int h) {
+    constexpr int FE = Tr<T>::FE, SPB = 32 / Tr<T>::KW;
+#pragma unroll
+    for (int s = 0; s < SPB; ++s)
+#pragma unroll
+        for (int e = 0; e < FE; ++e) id[s][e] = (T)((acc_row(s * FE + e, h) == l32) ? 1.f : 0.f);
+}
+// out (rows r, lane k) = transpose of the 32x32 block whose operand fragments (rows r, contraction k) are a[0..SPB)
+template <typename T>
+__device__ __forceinline__ f32x16 transpose32(const typename Tr<T>::Frag* a, const typename Tr<T>::Frag* id) {
+    f32x16 o = zero16();
+#pragma unroll
+    for (int s = 0; s < 32 / Tr<T>::KW; ++s) o = Tr<T>::mma(a[s], id[s], o);
+    return o;
+}
+
 // Workspace carve-up shared by host launch code and kernels (byte offsets, 256-aligned).
 struct FwdWorkspace {
     size_t kt, vt, dp, xinit, sd, kt2, dp2, knat, dptnat, total;
@@ -189,10 +223,15 @@ struct FwdParams {
     float *xinit, *sd;    // accumulator-order fp32 tiles
     int B, H, L, NC;      // NC = number of 64-token chunks = ceil(L/64)
     float scale;
-    // Backward only (NULL in the forward): row-major copies in the operand type,
-    // knat [bh][NC*64][d] = Kb, ktnat [bh][NC][d][64] = Kb^T, dpnat [bh][NC][d][d] = dP,
-    // and xs [bh][pair(i,j)][64][d]: query state of chunk i as used against key chunk j < i.
-    void *knat, *ktnat, *dpnat, *xs;
+    // knat [bh][NC*64][d]: row-major Kb (operand type), read by the second blocking level.
+    void* knat;
+    // Backward only (NULL in the forward), all in fragment order:
+    //   per chunk:  ktT (rows c, contraction s) = Kb[s][c];  vk (rows s, contraction c) = V[s][c] (I/O type);
+    //               dpt (rows c, contraction b) = -dP[c][b]
+    //   per pair (query chunk i, key chunk j < i), slot pair_slot(i,j):
+    //               xs  (rows q, contraction c) and xsT (rows c, contraction q): the query state of
+    //               chunk i as used against key chunk j
+    void *ktT, *vk, *dpt, *xs, *xsT;
     // Backward only: per-chunk matrices of the transform, row-major 64x64 (operand type) --
     // fm = F[t][t'], gktm[s][t'] = strictLower(W K^T)[t'][s], nm = N, aim = A^{-1},
     // ytm[s][t] = Y[t][s]; utm [d][64]: utm[c][t] = U[t][c]; fp32: gm = W W^T, sdm[t][s] = Sd.

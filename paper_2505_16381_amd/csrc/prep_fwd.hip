@@ -325,11 +325,6 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
                     *reinterpret_cast<Vec4*>(nat + 8 * g) = v4;
                 }
             }
-            if (p.dpnat) {     // row-major dP[a][b] for the backward
-                T* nat = reinterpret_cast<T*>(p.dpnat) + bhc * (size_t)D * D;
-#pragma unroll
-                for (int j = 0; j < 16; ++j) nat[(size_t)(32 * ab + acc_row(j, h)) * D + 32 * bb + l32] = (T)acc[j];
-            }
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[j] = -acc[j];
             Frag fr[SPB];
@@ -357,17 +352,13 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[4 * g + r] = (ok ? (float)k4[r] : 0.f) - acc[4 * g + r];
             }
-            if (p.knat) {      // row-major Kb[s][c] and Kb^T[c][s] for the backward
+            if (p.knat) {      // row-major Kb[s][c] for the second blocking level
                 T* nat = reinterpret_cast<T*>(p.knat) + (bhc * CHUNK + s) * (size_t)D + 32 * cb + 4 * h;
-                T* natt = p.ktnat ? reinterpret_cast<T*>(p.ktnat) + bhc * (size_t)CHUNK * D + s : nullptr;
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     Vec4 v4;
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) {
-                        v4[r] = (T)acc[4 * g + r];
-                        if (natt) natt[(size_t)(32 * cb + 8 * g + 4 * h + r) * CHUNK] = v4[r];
-                    }
+                    for (int r = 0; r < 4; ++r) v4[r] = (T)acc[4 * g + r];
                     *reinterpret_cast<Vec4*>(nat + 8 * g) = v4;
                 }
             }
@@ -412,6 +403,60 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             pack_block<TIO>(acc, fr);
 #pragma unroll
             for (int s2 = 0; s2 < SPB; ++s2) vdst[(((size_t)sb * (D / 32) + cb) * SPB + s2) * 64 + lane] = fr[s2];   // [key half][d block][slab]
+        }
+        if (p.ktT) {
+            // ---- backward-only tiles ------------------------------------------------------------
+            constexpr int QS = CHUNK / KW;
+            // ktT (rows c, contraction s) = Kb[s][c]: accumulate with rows s, lane c
+            Frag* tdst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.ktT) + bhc * (size_t)CHUNK * D);
+#pragma unroll
+            for (int i = 0; i < NB / 4; ++i) {
+                const int blk = wv + 4 * i;
+                const int cb = blk >> 1, sb = blk & 1;
+                f32x16 acc = gemm32<T, CHUNK>(Yt, LDC, 32 * sb, Wt, LDC, 32 * cb, l32, h, zero16());
+                const int c = 32 * cb + l32;
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const int s = 32 * sb + acc_row(j, h);
+                    const float kv = qk_ok(s) ? (float)Kp[(size_t)qk_row(s) * ldqk + c] : 0.f;
+                    acc[j] = kv - acc[j];
+                }
+                Frag fr[SPB];
+                pack_block<T>(acc, fr);
+#pragma unroll
+                for (int s2 = 0; s2 < SPB; ++s2) tdst[((size_t)cb * QS + sb * SPB + s2) * 64 + lane] = fr[s2];
+            }
+            // vk (rows s, contraction c) = V[s][c] (I/O type): registers rows c, lane s
+            FragV* vkd = reinterpret_cast<FragV*>(reinterpret_cast<TIO*>(p.vk) + bhc * (size_t)CHUNK * D);
+#pragma unroll
+            for (int i = 0; i < NB / 4; ++i) {
+                const int blk = wv + 4 * i;
+                const int cb = blk >> 1, sb = blk & 1;
+                const int s = 32 * sb + l32;
+                f32x16 acc;
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    acc[j] = (s < nvalid) ? (float)Vg[(size_t)s * D + 32 * cb + acc_row(j, h)] : 0.f;
+                FragV fr[SPB];
+                pack_block<TIO>(acc, fr);
+#pragma unroll
+                for (int s2 = 0; s2 < SPB; ++s2) vkd[((size_t)sb * (D / KW) + cb * SPB + s2) * 64 + lane] = fr[s2];
+            }
+            // dpt (rows c, contraction b) = -dP[c][b]: accumulate with rows b, lane c
+            Frag* pdst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dpt) + bhc * (size_t)D * D);
+            constexpr int NBP = (D / 32) * (D / 32);
+#pragma unroll
+            for (int i = 0; i < NBP / 4; ++i) {
+                const int blk = wv + 4 * i;
+                const int bb = blk / (D / 32), cb = blk % (D / 32);
+                f32x16 acc = gemm32<T, CHUNK>(Ut, LDC, 32 * bb, Wt, LDC, 32 * cb, l32, h, zero16());
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[j] = -acc[j];
+                Frag fr[SPB];
+                pack_block<T>(acc, fr);
+#pragma unroll
+                for (int s2 = 0; s2 < SPB; ++s2) pdst[((size_t)cb * (D / KW) + bb * SPB + s2) * 64 + lane] = fr[s2];
+            }
         }
     }
 }

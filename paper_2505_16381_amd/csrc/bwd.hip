@@ -378,12 +378,41 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
 //   C[m][n] = mask( alpha * sum_k A[m][k] B[n][k] + Cin[m][n] )
 // Operands are addressed with explicit strides (so either orientation of a stored
 // matrix can be used), converted to the operand type while being staged in LDS.
-template <typename TIO>
-__device__ __forceinline__ float load_el(const MatRef& r, long long off) {
+// Stage R x K elements of one operand into LDS (row-major, pitch ld, operand type), eight
+// elements per thread along whichever index is contiguous in memory (one 16/32-byte load).
+template <typename TIO, typename E>
+__device__ __forceinline__ void stage_mat_t(const MatRef& r, typename Compute<TIO>::type* dst, int ld, int R, int K,
+                                            long long base, int ntok, int tid) {
     typedef typename Compute<TIO>::type T;
-    if (r.type == EL_F32) return reinterpret_cast<const float*>(r.p)[off];
-    if (r.type == EL_OP) return (float)reinterpret_cast<const T*>(r.p)[off];
-    return (float)reinterpret_cast<const TIO*>(r.p)[off];
+    const E* src = reinterpret_cast<const E*>(r.p) + base;
+    typedef E Vec8 __attribute__((ext_vector_type(8)));
+    if (r.ks == 1) {                       // contraction index contiguous
+        const int kg = K / 8;
+        for (int idx = tid; idx < R * kg; idx += 256) {
+            const int m = idx / kg, k0 = (idx % kg) * 8;
+            Vec8 v;
+            const bool row_ok = r.tok != TOK_ROW || m < ntok;
+            if (row_ok) v = *reinterpret_cast<const Vec8*>(src + (long long)m * r.rs + k0);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool ok = row_ok && (r.tok != TOK_K || k0 + e < ntok);
+                dst[m * ld + k0 + e] = ok ? (T)(float)v[e] : (T)0.f;
+            }
+        }
+    } else {                               // row index contiguous (rs == 1)
+        const int mg = R / 8;
+        for (int idx = tid; idx < K * mg; idx += 256) {
+            const int k = idx / mg, m0 = (idx % mg) * 8;
+            Vec8 v;
+            const bool k_ok = r.tok != TOK_K || k < ntok;
+            if (k_ok) v = *reinterpret_cast<const Vec8*>(src + (long long)k * r.ks + m0);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const bool ok = k_ok && (r.tok != TOK_ROW || m0 + e < ntok);
+                dst[(m0 + e) * ld + k] = ok ? (T)(float)v[e] : (T)0.f;
+            }
+        }
+    }
 }
 
 template <typename TIO>
@@ -392,13 +421,9 @@ __device__ __forceinline__ void stage_mat(const MatRef& r, typename Compute<TIO>
     typedef typename Compute<TIO>::type T;
     const long long base = bh * r.s_bh + chunk * r.s_ch;
     const int ntok = L - chunk * CHUNK;     // tokens of this chunk that exist
-    for (int idx = tid; idx < R * K; idx += 256) {
-        int m, k;
-        if (r.ks == 1) { m = idx / K; k = idx % K; } else { k = idx / R; m = idx % R; }
-        const bool ok = (r.tok == TOK_NONE) || ((r.tok == TOK_ROW ? m : k) < ntok);
-        const float v = ok ? load_el<TIO>(r, base + (long long)m * r.rs + (long long)k * r.ks) : 0.f;
-        dst[m * ld + k] = (T)v;
-    }
+    if (r.type == EL_F32) stage_mat_t<TIO, float>(r, dst, ld, R, K, base, ntok, tid);
+    else if (r.type == EL_OP) stage_mat_t<TIO, T>(r, dst, ld, R, K, base, ntok, tid);
+    else stage_mat_t<TIO, TIO>(r, dst, ld, R, K, base, ntok, tid);
 }
 
 template <typename TIO>
@@ -526,13 +551,14 @@ hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream
     const size_t bytes = (size_t)(a.M + a.N) * (a.K + fe) * es;
     dim3 grid(a.NC, BH);
     hipError_t e;
-    if (is_bf16) {
-        if ((e = set_smem(&batched_gemm_kernel<bf16_t>, 160 * 1024)) != hipSuccess) return e;
-        hipLaunchKernelGGL((batched_gemm_kernel<bf16_t>), grid, dim3(256), bytes, st, a);
-    } else {
-        if ((e = set_smem(&batched_gemm_kernel<float>, 160 * 1024)) != hipSuccess) return e;
-        hipLaunchKernelGGL((batched_gemm_kernel<float>), grid, dim3(256), bytes, st, a);
+    static bool attr_set[2] = {false, false};
+    if (!attr_set[is_bf16 ? 1 : 0]) {
+        e = is_bf16 ? set_smem(&batched_gemm_kernel<bf16_t>, 160 * 1024) : set_smem(&batched_gemm_kernel<float>, 160 * 1024);
+        if (e != hipSuccess) return e;
+        attr_set[is_bf16 ? 1 : 0] = true;
     }
+    if (is_bf16) hipLaunchKernelGGL((batched_gemm_kernel<bf16_t>), grid, dim3(256), bytes, st, a);
+    else hipLaunchKernelGGL((batched_gemm_kernel<float>), grid, dim3(256), bytes, st, a);
     return hipGetLastError();
 }
 

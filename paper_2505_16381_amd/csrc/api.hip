@@ -43,7 +43,7 @@ static FwdWorkspace fwd_workspace(int B, int H, int L, int d, size_t es) {
 // Backward workspace: the forward's five regions first (same carve-up), then everything else.
 struct BwdWorkspace {
     FwdWorkspace f;
-    size_t ktT, vk, dpt, doq, doT, xs, xsT, gs, fm, gktm, nm, aim, ytm, utm, gm, sdm, delta, dqb, dkb, dvp, ddp;
+    size_t ktT, vk, dpt, doq, doT, xs, xsT, gs, fm, gktm, nm, aim, ytm, utm, gm, sdm, delta, lse2p, dqb, dkb, dvp, ddp;
     size_t dpd, pd, dsd, df, dy, dn, dgk, rr, mm, dgs, du, dqf, dkf, dwf, dbf, total;
 };
 
@@ -62,6 +62,7 @@ static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
     take(w.gm, BH * NC * 4096 * 4);
     take(w.sdm, BH * NC * 4096 * 4);
     take(w.delta, BH * Lp * 4);
+    take(w.lse2p, BH * Lp * 4);
     for (size_t* f : {&w.dqb, &w.dkb, &w.dvp}) take(*f, BH * Lp * d * 4);
     take(w.ddp, BH * NC * d * d * 4);
     for (size_t* f : {&w.dpd, &w.pd, &w.dsd, &w.df, &w.dy, &w.dn, &w.dgk, &w.rr, &w.mm, &w.dgs}) take(*f, BH * NC * 4096 * 4);
@@ -207,7 +208,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     bp.q = q; bp.k = k; bp.v = v; bp.w = w; bp.beta = beta; bp.o = o; bp.dO = d_o; bp.lse = lse;
     bp.kt = fp.kt; bp.vk = fp.vk; bp.ktT = fp.ktT; bp.dpt = fp.dpt; bp.xs = fp.xs; bp.xsT = fp.xsT;
     bp.doq = base + ws.doq; bp.doT = base + ws.doT; bp.gs = base + ws.gs;
-    bp.delta = F(ws.delta); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
+    bp.delta = F(ws.delta); bp.lse2p = F(ws.lse2p); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
     bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale;
     if (launch_bwd_scan(bp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;
 

@@ -37,7 +37,10 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(BwdParams p) {
     }
     s += __shfl_xor(s, 1);
     s += __shfl_xor(s, 2);
-    if (part == 0) p.delta[(size_t)bh * p.NC * CHUNK + tg] = s;
+    if (part == 0) {
+        p.delta[(size_t)bh * p.NC * CHUNK + tg] = s;
+        p.lse2p[(size_t)bh * p.NC * CHUNK + tg] = (tg < p.L) ? p.lse[(size_t)bh * p.L + tg] * 1.44269504088896340736f : 0.f;
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -90,7 +93,9 @@ template <typename TIO, int D> struct Adj2Cfg {
     typedef typename Compute<TIO>::type T;
     static constexpr int FE = Tr<T>::FE;
     static constexpr int KV_FRAGS = CHUNK * D / FE, DP_FRAGS = D * D / FE;
-    static constexpr size_t smem_bytes = (size_t)(3 * KV_FRAGS + DP_FRAGS) * 16;   // kt | vk | ktT | dpt
+    static constexpr int NBUF = (sizeof(T) == 2) ? 2 : 1;
+    static constexpr int STAGE_FRAGS = 3 * KV_FRAGS + DP_FRAGS;                    // kt | vk | ktT | dpt
+    static constexpr size_t smem_bytes = (size_t)NBUF * STAGE_FRAGS * 16;
 };
 
 template <typename TIO, int D>
@@ -102,11 +107,9 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     constexpr int KW = Tr<T>::KW, SPB = 32 / KW, DB = D / 32, DS = D / KW, QS = CHUNK / KW;
     constexpr int KVF = C::KV_FRAGS, DPF = C::DP_FRAGS;
 
+    constexpr int NBUF = C::NBUF, STF = C::STAGE_FRAGS;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    Frag* sK = reinterpret_cast<Frag*>(smem);
-    FragV* sV = reinterpret_cast<FragV*>(sK + KVF);
-    Frag* sKT = sK + 2 * KVF;
-    Frag* sDP = sK + 3 * KVF;
+    Frag* sbase = reinterpret_cast<Frag*>(smem);
 
     const int BH = p.B * p.H, L = p.L, NC = p.NC;
     const int ntiles = (NC + 1) / 2;
@@ -137,21 +140,46 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     Frag idf[SPB];
     identity_frags<T>(idf, l32, h);
 
-    for (int j = 0; j <= jmax; ++j) {
+    auto issue = [&](int j) {
+        Frag* buf = sbase + (size_t)(j & (NBUF - 1)) * STF;
         const size_t bhc = (size_t)bh * NC + j;
-        __syncthreads();
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * CHUNK * D), sK, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), sV, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.ktT) + bhc * CHUNK * D), sKT, KVF, tid, wv);
-        if (j > 0) async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D), sDP, DPF, tid, wv);
-        wait_async_and_sync();
-        if (!active || j >= cq) continue;
-
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * CHUNK * D), buf, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), buf + KVF, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.ktT) + bhc * CHUNK * D), buf + 2 * KVF, KVF, tid, wv);
+        if (j > 0) async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D), buf + 3 * KVF, DPF, tid, wv);
+    };
+    // the wave's own state fragments of pair (cq, j): fetched one step ahead
+    auto load_x = [&](int j, Frag* x) {
         const size_t slot = ((size_t)bh * npairs + pair_slot(cq, j)) * (size_t)CHUNK * D;
         const Frag* xg = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot);
+#pragma unroll
+        for (int s = 0; s < DS; ++s) x[s] = xg[((size_t)qb * DS + s) * 64 + lane];
+    };
+    Frag Xnext[DS];
+#pragma unroll
+    for (int s = 0; s < DS; ++s) Xnext[s] = Tr<T>::zero();
+    if (active && cq > 0) load_x(0, Xnext);
+    if (jmax >= 0 && NBUF == 2) issue(0);
+
+    for (int j = 0; j <= jmax; ++j) {
+        if (NBUF == 2) {
+            wait_async_and_sync();                 // chunk j has landed; everyone is done with chunk j-1
+            if (j + 1 <= jmax) issue(j + 1);
+        } else {
+            __syncthreads();
+            issue(j);
+            wait_async_and_sync();
+        }
+        if (!active || j >= cq) continue;
+        const Frag* sK = sbase + (size_t)(j & (NBUF - 1)) * STF;
+        const FragV* sV = reinterpret_cast<const FragV*>(sK + KVF);
+        const Frag* sKT = sK + 2 * KVF;
+        const Frag* sDP = sK + 3 * KVF;
+
         Frag Xb[DS];
 #pragma unroll
-        for (int s = 0; s < DS; ++s) Xb[s] = xg[((size_t)qb * DS + s) * 64 + lane];
+        for (int s = 0; s < DS; ++s) Xb[s] = Xnext[s];
+        if (j + 1 < cq) load_x(j + 1, Xnext);
 
         Frag dSb[QS];
 #pragma unroll
@@ -220,9 +248,11 @@ template <typename TIO, int D> struct Key2Cfg {
     typedef typename Compute<TIO>::type T;
     static constexpr int FE = Tr<T>::FE;
     static constexpr int KV_FRAGS = CHUNK * D / FE;
-    static constexpr size_t tile_bytes = (size_t)4 * KV_FRAGS * 16;           // xs | xsT | doq | doT
+    static constexpr int NBUF = (sizeof(T) == 2) ? 2 : 1;                     // fp32 tiles are too big to double-buffer
+    static constexpr int STAGE_FRAGS = 4 * KV_FRAGS + 32;                     // xs | xsT | doq | doT | lse2 | delta
+    static constexpr size_t tile_bytes = (size_t)NBUF * STAGE_FRAGS * 16;
     static constexpr size_t red_bytes = (size_t)2 * 2 * (D / 32) * 1024 * 4;   // dV, dKb of the two upper waves
-    static constexpr size_t smem_bytes = (tile_bytes > red_bytes ? tile_bytes : red_bytes) + 2 * CHUNK * 4;
+    static constexpr size_t smem_bytes = tile_bytes > red_bytes ? tile_bytes : red_bytes;
 };
 
 template <typename TIO, int D>
@@ -232,16 +262,10 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     using Frag = typename Tr<T>::Frag;
     using FragV = typename Tr<TIO>::Frag;
     constexpr int KW = Tr<T>::KW, SPB = 32 / KW, DB = D / 32, DS = D / KW, QS = CHUNK / KW;
-    constexpr int KVF = C::KV_FRAGS;
+    constexpr int KVF = C::KV_FRAGS, NBUF = C::NBUF, STF = C::STAGE_FRAGS;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    Frag* sX = reinterpret_cast<Frag*>(smem);
-    Frag* sXT = sX + KVF;
-    FragV* sDQ = reinterpret_cast<FragV*>(sX + 2 * KVF);
-    FragV* sDT = reinterpret_cast<FragV*>(sX + 3 * KVF);
-    constexpr size_t data_bytes = C::tile_bytes > C::red_bytes ? C::tile_bytes : C::red_bytes;
-    float* lse2 = reinterpret_cast<float*>(smem + data_bytes);
-    float* dl = lse2 + CHUNK;
+    Frag* sbase = reinterpret_cast<Frag*>(smem);
 
     const int j = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
@@ -262,20 +286,38 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
 #pragma unroll
     for (int b = 0; b < DB; ++b) { dVt[b] = zero16(); dKt[b] = zero16(); }
 
-    for (int i = j + 1; i < NC; ++i) {
+    // all operands of query chunk i, asynchronously, into stage buffer (i & (NBUF-1))
+    auto issue = [&](int i) {
+        Frag* buf = sbase + (size_t)(i & (NBUF - 1)) * STF;
         const size_t slot = ((size_t)bh * npairs + pair_slot(i, j)) * (size_t)CHUNK * D;
         const size_t bhi = ((size_t)bh * NC + i) * CHUNK * D;
-        __syncthreads();
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot), sX, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), sXT, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.doq) + bhi), sDQ, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.doT) + bhi), sDT, KVF, tid, wv);
-        if (tid < CHUNK) {
-            const int tg = i * CHUNK + tid;
-            lse2[tid] = (tg < L) ? p.lse[(size_t)bh * L + tg] * 1.44269504088896340736f : 0.f;
-            dl[tid] = p.delta[(size_t)bh * Lp + tg];
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot), buf, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf + KVF, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doq) + bhi), buf + 2 * KVF, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doT) + bhi), buf + 3 * KVF, KVF, tid, wv);
+        if (tid < 32) {     // 64 floats of lse2 (lanes 0-15) and of delta (lanes 16-31): 16 bytes per lane
+            const float* src = (tid < 16 ? p.lse2p : p.delta) + (size_t)bh * Lp + (size_t)i * CHUNK + 4 * (tid & 15);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(buf + 4 * KVF), 16, 0, 0);
         }
-        wait_async_and_sync();
+    };
+
+    if (j + 1 < NC && NBUF == 2) issue(j + 1);
+    for (int i = j + 1; i < NC; ++i) {
+        if (NBUF == 2) {
+            wait_async_and_sync();                 // chunk i has landed; everyone is done with chunk i-1
+            if (i + 1 < NC) issue(i + 1);
+        } else {
+            __syncthreads();
+            issue(i);
+            wait_async_and_sync();
+        }
+        const Frag* sX = sbase + (size_t)(i & (NBUF - 1)) * STF;
+        const Frag* sXT = sX + KVF;
+        const FragV* sDQ = reinterpret_cast<const FragV*>(sX + 2 * KVF);
+        const FragV* sDT = reinterpret_cast<const FragV*>(sX + 3 * KVF);
+        const float* lse2 = reinterpret_cast<const float*>(sX + 4 * KVF);
+        const float* dl = lse2 + CHUNK;
 
         f32x16 S = zero16(), dP = zero16();                    // rows q (half qh), lane s
 #pragma unroll
@@ -338,11 +380,21 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
 // ddP_j[a][b] = - sum_{i>j} sum_q Xs(i,j)[q][a] g(i,j-1)[q][b]: one workgroup per key chunk, a plain
 // product over the stacked query axis; both operands are read as fragments straight from global
 // memory (tiles xsT and gT, contraction q).
+template <typename TIO, int D> struct DdpCfg {
+    typedef typename Compute<TIO>::type T;
+    static constexpr int KV_FRAGS = CHUNK * D / Tr<T>::FE;
+    static constexpr int NBUF = 2;
+    static constexpr size_t smem_bytes = (size_t)NBUF * 2 * KV_FRAGS * 16;     // NBUF x (xsT | gT)
+};
+
 template <typename TIO, int D>
 __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
+    using C = DdpCfg<TIO, D>;
     using T = typename Compute<TIO>::type;
     using Frag = typename Tr<T>::Frag;
-    constexpr int KW = Tr<T>::KW, DB = D / 32, QS = CHUNK / KW, NOWN = DB * DB / 4;
+    constexpr int KW = Tr<T>::KW, DB = D / 32, QS = CHUNK / KW, NOWN = DB * DB / 4, KVF = C::KV_FRAGS;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    Frag* sbase = reinterpret_cast<Frag*>(smem);
     const int j = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
     const int NC = p.NC;
@@ -351,16 +403,24 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
 #pragma unroll
     for (int o = 0; o < NOWN; ++o) acc[o] = zero16();
     if (j >= 1) {
-        for (int i = j + 1; i < NC; ++i) {
+        auto issue = [&](int i) {
+            Frag* buf = sbase + (size_t)(i & 1) * 2 * KVF;
             const size_t slot = ((size_t)bh * npairs + pair_slot(i, j)) * (size_t)CHUNK * D;
-            const Frag* xt = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot);
-            const Frag* gt = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.gs) + slot);
+            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf, KVF, tid, wv);
+            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.gs) + slot), buf + KVF, KVF, tid, wv);
+        };
+        if (j + 1 < NC) issue(j + 1);
+        for (int i = j + 1; i < NC; ++i) {
+            wait_async_and_sync();                 // pair (i, j) has landed; everyone is done with pair (i-1, j)
+            if (i + 1 < NC) issue(i + 1);
+            const Frag* xt = sbase + (size_t)(i & 1) * 2 * KVF;
+            const Frag* gt = xt + KVF;
 #pragma unroll
             for (int o = 0; o < NOWN; ++o) {
                 const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
 #pragma unroll
                 for (int s = 0; s < QS; ++s)
-                    acc[o] = Tr<T>::mma(xt[((size_t)ab * QS + s) * 64 + lane], gt[((size_t)bb * QS + s) * 64 + lane], acc[o]);
+                    acc[o] = Tr<T>::mma(xt[(ab * QS + s) * 64 + lane], gt[(bb * QS + s) * 64 + lane], acc[o]);
             }
         }
     }
@@ -537,7 +597,9 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     if ((e = set_smem(&bwd_keyside2_kernel<TIO, D>, key_bytes)) != hipSuccess) return e;
     hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D>), grid, dim3(256), key_bytes, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D>), grid, dim3(256), 0, st, p);
+    const size_t ddp_bytes = DdpCfg<TIO, D>::smem_bytes;
+    if ((e = set_smem(&bwd_ddp_kernel<TIO, D>, ddp_bytes)) != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D>), grid, dim3(256), ddp_bytes, st, p);
     return hipGetLastError();
 }
 

@@ -12,6 +12,7 @@ struct BwdParams {
     void *doq, *doT;                   // per-chunk dO tiles (I/O type)
     void* gs;                          // per-pair adjoint-state tiles gT (rows b, contraction q): g(i,j-1) at slot (i,j)
     float *delta;             // [BH][Lp]
+    float *lse2p;             // [BH][Lp]: lse * log2(e), zero past L
     float *dqb, *dkb, *dvp;   // [BH][Lp][d] fp32: dQb, dKb, dV (off-diagonal part)
     float *ddp;               // [BH][NC][d][d] fp32: ddP[a][b]
     int B, H, L, NC;

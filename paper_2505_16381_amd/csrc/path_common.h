@@ -210,7 +210,7 @@ __device__ __forceinline__ f32x16 transpose32(const typename Tr<T>::Frag* a, con
 
 // Workspace carve-up shared by host launch code and kernels (byte offsets, 256-aligned).
 struct FwdWorkspace {
-    size_t kt, vt, dp, xinit, sd, kt2, dp2, knat, dptnat, total;
+    size_t kt, vt, dp, xinit, sd, kt2, dp2, dpt, total;
 };
 
 struct FwdParams {
@@ -219,19 +219,16 @@ struct FwdParams {
     float* lse;
     void *kt, *vt, *dp;   // fragment-order tiles written by prep, read by the sweep
     void *kt2, *dp2;      // second level: keys carried to their super-block's right edge; -(I - P_superblock)
-    void *dptnat;         // row-major dP^T per chunk (operand type): dptnat[b][a] = dP[a][b]
+    void *dpt;            // -dP per chunk in the transposed arrangement (rows a, contraction b) = -dP[a][b]
     float *xinit, *sd;    // accumulator-order fp32 tiles
     int B, H, L, NC;      // NC = number of 64-token chunks = ceil(L/64)
     float scale;
-    // knat [bh][NC*64][d]: row-major Kb (operand type), read by the second blocking level.
-    void* knat;
     // Backward only (NULL in the forward), all in fragment order:
     //   per chunk:  ktT (rows c, contraction s) = Kb[s][c];  vk (rows s, contraction c) = V[s][c] (I/O type);
-    //               dpt (rows c, contraction b) = -dP[c][b]
     //   per pair (query chunk i, key chunk j < i), slot pair_slot(i,j):
     //               xs  (rows q, contraction c) and xsT (rows c, contraction q): the query state of
     //               chunk i as used against key chunk j
-    void *ktT, *vk, *dpt, *xs, *xsT;
+    void *ktT, *vk, *xs, *xsT;
     // Backward only: per-chunk matrices of the transform, row-major 64x64 (operand type) --
     // fm = F[t][t'], gktm[s][t'] = strictLower(W K^T)[t'][s], nm = N, aim = A^{-1},
     // ytm[s][t] = Y[t][s]; utm [d][64]: utm[c][t] = U[t][c]; fp32: gm = W W^T, sdm[t][s] = Sd.

@@ -8,30 +8,32 @@
 //
 // so that the sweep applies ONE d x d product per super-block instead of one
 // per chunk.  With E_c = I - R_c:  E_{c-1} = E_c + dP_c - E_c dP_c  and
-// Kb2_c = Kb_c - Kb_c E_c^T.  E is kept in fp32 registers; only its operand
-// copy (LDS) is rounded.  One workgroup per (batch*head, super-block).
+// Kb2_c = Kb_c - Kb_c E_c^T.
+//
+// One workgroup per (batch*head, super-block).  E is kept TRANSPOSED in fp32
+// registers (rows b, lane a): in that layout its operand copy is directly the
+// fragment-order tile (rows a, contraction b) that both products need -- as the
+// A operand of the key transport and as the B operand of the update -- and the
+// other operands are the fragment tiles the chunk kernel already wrote (keys,
+// -dP, and -dP in the transposed arrangement), read straight from global memory.
 #include "path_common.h"
 
 namespace path {
 
 template <typename TIO, int D> struct Prep2Cfg {
     typedef typename Compute<TIO>::type T;
-    static constexpr int FE = Tr<T>::FE;
-    static constexpr int LDE = D + FE;
-    static constexpr size_t smem_bytes = (size_t)D * LDE * sizeof(T);
+    static constexpr size_t smem_bytes = (size_t)D * D * sizeof(T);      // operand copy of E (fragment order)
 };
 
 template <typename TIO, int D>
 __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
-    using C = Prep2Cfg<TIO, D>;
-    using T = typename C::T;
+    using T = typename Compute<TIO>::type;
     using Frag = typename Tr<T>::Frag;
-    using Vec4 = typename Tr<T>::Vec4;
-    constexpr int FE = C::FE, KW = Tr<T>::KW, LDE = C::LDE;
-    constexpr int SPB = 32 / KW, DB = D / 32, NE = DB * DB / 4, NK = 2 * DB / 4;
+    constexpr int FE = Tr<T>::FE, KW = Tr<T>::KW;
+    constexpr int SPB = 32 / KW, DB = D / 32, DS = D / KW, NE = DB * DB / 4, NK = 2 * DB / 4;
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    T* Es = reinterpret_cast<T*>(smem);        // operand copy of E, row-major [a][m]
+    Frag* Es = reinterpret_cast<Frag*>(smem);      // tile (rows a, contraction b) of E
 
     const int sb = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
@@ -39,74 +41,84 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
     const int c0 = sb * SBC;
     const int clast = (c0 + SBC - 1 < NC) ? c0 + SBC - 1 : NC - 1;
 
-    f32x16 Em[NE];
-#pragma unroll
-    for (int o = 0; o < NE; ++o) Em[o] = zero16();
+    f32x16 Fm[NE];      // E^T: block o = (rows b-block bb, lane a-block ab), blk = wv + 4*o, bb = blk / DB, ab = blk % DB
 
     for (int c = clast; c >= c0; --c) {
         const size_t bhc = (size_t)bh * NC + c;
-        const T* kn = reinterpret_cast<const T*>(p.knat) + bhc * CHUNK * D;       // Kb_c [s][b]
-        const T* dpt = reinterpret_cast<const T*>(p.dptnat) + bhc * (size_t)D * D;  // dP_c^T [b][m]
+        const Frag* k1 = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * (size_t)CHUNK * D);
+        const Frag* dpn = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dp) + bhc * (size_t)D * D);    // (rows b, contr a) = -dP[a][b]
+        const Frag* dpt = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D);   // (rows a, contr b) = -dP[a][b]
         Frag* k2 = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2) + bhc * (size_t)CHUNK * D);
         if (c == clast) {
-            const Frag* k1 = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * (size_t)CHUNK * D);
             for (int idx = tid; idx < CHUNK * D / FE; idx += 256) k2[idx] = k1[idx];
         } else {
-            // Kb2^T[cc][s] = Kb^T[cc][s] - sum_b E[cc][b] Kb[s][b]   (acc rows cc, lane s)
+            // Kb2^T[cc][s] = Kb^T[cc][s] - sum_b E[cc][b] Kb[s][b]   (registers rows cc, lane s)
 #pragma unroll
             for (int o = 0; o < NK; ++o) {
                 const int blk = wv + 4 * o, cb = blk >> 1, sb2 = blk & 1;
-                f32x16 acc = gemm32<T, D>(Es, LDE, 32 * cb, kn, D, 32 * sb2, l32, h, zero16());
-                const T* krow = kn + (size_t)(32 * sb2 + l32) * D + 32 * cb + 4 * h;
+                f32x16 acc = zero16();
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const Vec4 k4 = *reinterpret_cast<const Vec4*>(krow + 8 * g);
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) acc[4 * g + r] = (float)k4[r] - acc[4 * g + r];
-                }
+                for (int s = 0; s < DS; ++s) acc = Tr<T>::mma(Es[(cb * DS + s) * 64 + lane], k1[((size_t)sb2 * DS + s) * 64 + lane], acc);
                 Frag fr[SPB];
-                pack_block<T>(acc, fr);
 #pragma unroll
-                for (int s2 = 0; s2 < SPB; ++s2) k2[((size_t)sb2 * (D / KW) + cb * SPB + s2) * 64 + lane] = fr[s2];
+                for (int s2 = 0; s2 < SPB; ++s2) {
+                    const Frag kf = k1[((size_t)sb2 * DS + cb * SPB + s2) * 64 + lane];
+#pragma unroll
+                    for (int e = 0; e < FE; ++e) fr[s2][e] = (T)((float)kf[e] - acc[s2 * FE + e]);
+                }
+#pragma unroll
+                for (int s2 = 0; s2 < SPB; ++s2) k2[((size_t)sb2 * DS + cb * SPB + s2) * 64 + lane] = fr[s2];
             }
         }
-        // E <- E + dP_c - E dP_c   (acc rows a, lane b)
+        // E^T <- E^T + dP^T - dP^T E^T   (registers rows b, lane a)
 #pragma unroll
         for (int o = 0; o < NE; ++o) {
-            const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
+            const int blk = wv + 4 * o, bb = blk / DB, ab = blk % DB;
             f32x16 acc = zero16();
-            if (c != clast) acc = gemm32<T, D>(Es, LDE, 32 * ab, dpt, D, 32 * bb, l32, h, zero16());
-            const T* drow = dpt + (size_t)(32 * bb + l32) * D + 32 * ab + 4 * h;
+            if (c != clast) {
 #pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const Vec4 d4 = *reinterpret_cast<const Vec4*>(drow + 8 * g);
+                for (int s = 0; s < DS; ++s) acc = Tr<T>::mma(dpn[((size_t)bb * DS + s) * 64 + lane], Es[(ab * DS + s) * 64 + lane], acc);
+            }
 #pragma unroll
-                for (int r = 0; r < 4; ++r) Em[o][4 * g + r] += (float)d4[r] - acc[4 * g + r];
+            for (int s2 = 0; s2 < SPB; ++s2) {
+                const Frag df = dpt[((size_t)ab * DS + bb * SPB + s2) * 64 + lane];      // -dP[a][b] in this block's register layout
+#pragma unroll
+                for (int e = 0; e < FE; ++e) {
+                    const float prev = (c == clast) ? 0.f : Fm[o][s2 * FE + e];
+                    Fm[o][s2 * FE + e] = prev - (float)df[e] + acc[s2 * FE + e];
+                }
             }
         }
         __syncthreads();      // every read of the old operand copy is done
         if (c > c0) {
 #pragma unroll
             for (int o = 0; o < NE; ++o) {
-                const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
+                const int blk = wv + 4 * o, bb = blk / DB, ab = blk % DB;
+                Frag fr[SPB];
+                pack_block<T>(Fm[o], fr);
 #pragma unroll
-                for (int jj = 0; jj < 16; ++jj) Es[(32 * ab + acc_row(jj, h)) * LDE + 32 * bb + l32] = (T)Em[o][jj];
+                for (int s2 = 0; s2 < SPB; ++s2) Es[(ab * DS + bb * SPB + s2) * 64 + lane] = fr[s2];
             }
         }
         __syncthreads();
     }
-    // -(I - P_superblock) as a fragment-order tile: rows = output column b, contraction = a
+    // -(I - P_superblock) as the sweep's tile (rows b, contraction a): E itself (rows a, lane b) is the
+    // transpose of what the registers hold -- taken through the matrix unit.
     Frag* dst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dp2) + ((size_t)bh * gridDim.x + sb) * (size_t)D * D);
+    Frag idf[SPB];
+    identity_frags<T>(idf, l32, h);
 #pragma unroll
     for (int o = 0; o < NE; ++o) {
-        const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
-        f32x16 acc;
+        const int blk = wv + 4 * o, bb = blk / DB, ab = blk % DB;
+        Frag fin[SPB];
+        pack_block<T>(Fm[o], fin);                              // tile piece (rows a, contraction b)
+        f32x16 tr = transpose32<T>(fin, idf);                   // rows a, lane b
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj) acc[jj] = -Em[o][jj];
+        for (int jj = 0; jj < 16; ++jj) tr[jj] = -tr[jj];
         Frag fr[SPB];
-        pack_block<T>(acc, fr);
+        pack_block<T>(tr, fr);
 #pragma unroll
-        for (int s = 0; s < SPB; ++s) dst[((size_t)bb * (D / KW) + ab * SPB + s) * 64 + lane] = fr[s];
+        for (int s = 0; s < SPB; ++s) dst[((size_t)bb * DS + ab * SPB + s) * 64 + lane] = fr[s];
     }
 }
 

@@ -315,16 +315,6 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             const int blk = wv + 4 * i;
             const int ab = blk / (D / 32), bb = blk % (D / 32);
             f32x16 acc = gemm32<T, CHUNK>(Wt, LDC, 32 * ab, Ut, LDC, 32 * bb, l32, h, zero16());
-            if (p.dptnat) {    // row-major dP^T[b][a] for the second blocking level
-                T* nat = reinterpret_cast<T*>(p.dptnat) + bhc * (size_t)D * D + (size_t)(32 * bb + l32) * D + 32 * ab + 4 * h;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    Vec4 v4;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) v4[r] = (T)acc[4 * g + r];
-                    *reinterpret_cast<Vec4*>(nat + 8 * g) = v4;
-                }
-            }
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[j] = -acc[j];
             Frag fr[SPB];
@@ -351,16 +341,6 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
                 Vec4 k4 = *reinterpret_cast<const Vec4*>(krow + 8 * g);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[4 * g + r] = (ok ? (float)k4[r] : 0.f) - acc[4 * g + r];
-            }
-            if (p.knat) {      // row-major Kb[s][c] for the second blocking level
-                T* nat = reinterpret_cast<T*>(p.knat) + (bhc * CHUNK + s) * (size_t)D + 32 * cb + 4 * h;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    Vec4 v4;
-#pragma unroll
-                    for (int r = 0; r < 4; ++r) v4[r] = (T)acc[4 * g + r];
-                    *reinterpret_cast<Vec4*>(nat + 8 * g) = v4;
-                }
             }
             Frag fr[SPB];
             pack_block<T>(acc, fr);
@@ -404,6 +384,24 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
 #pragma unroll
             for (int s2 = 0; s2 < SPB; ++s2) vdst[(((size_t)sb * (D / 32) + cb) * SPB + s2) * 64 + lane] = fr[s2];   // [key half][d block][slab]
         }
+        if (p.dpt) {
+            // -dP in the transposed arrangement (rows c, contraction b) = -dP[c][b]: accumulate with rows b,
+            // lane c.  Read by the second blocking level and by the backward's adjoint scan.
+            Frag* pdst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dpt) + bhc * (size_t)D * D);
+            constexpr int NBP = (D / 32) * (D / 32);
+#pragma unroll
+            for (int i = 0; i < NBP / 4; ++i) {
+                const int blk = wv + 4 * i;
+                const int bb = blk / (D / 32), cb = blk % (D / 32);
+                f32x16 acc = gemm32<T, CHUNK>(Ut, LDC, 32 * bb, Wt, LDC, 32 * cb, l32, h, zero16());
+#pragma unroll
+                for (int j = 0; j < 16; ++j) acc[j] = -acc[j];
+                Frag fr[SPB];
+                pack_block<T>(acc, fr);
+#pragma unroll
+                for (int s2 = 0; s2 < SPB; ++s2) pdst[((size_t)cb * (D / KW) + bb * SPB + s2) * 64 + lane] = fr[s2];
+            }
+        }
         if (p.ktT) {
             // ---- backward-only tiles ------------------------------------------------------------
             constexpr int QS = CHUNK / KW;
@@ -441,21 +439,6 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
                 pack_block<TIO>(acc, fr);
 #pragma unroll
                 for (int s2 = 0; s2 < SPB; ++s2) vkd[((size_t)sb * (D / KW) + cb * SPB + s2) * 64 + lane] = fr[s2];
-            }
-            // dpt (rows c, contraction b) = -dP[c][b]: accumulate with rows b, lane c
-            Frag* pdst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dpt) + bhc * (size_t)D * D);
-            constexpr int NBP = (D / 32) * (D / 32);
-#pragma unroll
-            for (int i = 0; i < NBP / 4; ++i) {
-                const int blk = wv + 4 * i;
-                const int bb = blk / (D / 32), cb = blk % (D / 32);
-                f32x16 acc = gemm32<T, CHUNK>(Ut, LDC, 32 * bb, Wt, LDC, 32 * cb, l32, h, zero16());
-#pragma unroll
-                for (int j = 0; j < 16; ++j) acc[j] = -acc[j];
-                Frag fr[SPB];
-                pack_block<T>(acc, fr);
-#pragma unroll
-                for (int s2 = 0; s2 < SPB; ++s2) pdst[((size_t)cb * (D / KW) + bb * SPB + s2) * 64 + lane] = fr[s2];
             }
         }
     }

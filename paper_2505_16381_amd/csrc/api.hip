@@ -35,14 +35,13 @@ static FwdWorkspace fwd_workspace(int B, int H, int L, int d, size_t es) {
     const size_t NSB = (NC + SBC - 1) / SBC;
     w.kt2 = off;    off = align256(off + BH * Lp * d * es);
     w.dp2 = off;    off = align256(off + BH * NSB * d * d * es);
-    w.dpt = off;    off = align256(off + BH * NC * d * d * es);
     w.total = off;
     return w;
 }
 // Backward workspace: the forward's five regions first (same carve-up), then everything else.
 struct BwdWorkspace {
     FwdWorkspace f;
-    size_t ktT, vk, doq, doT, xs, xsT, gs, fm, gktm, nm, aim, ytm, utm, gm, sdm, delta, lse2p, dqb, dkb, dvp, ddp;
+    size_t ktT, vk, dpt, doq, doT, xs, xsT, gs, fm, gktm, nm, aim, ytm, utm, gm, sdm, delta, lse2p, dqb, dkb, dvp, ddp;
     size_t dpd, pd, dsd, df, dy, dn, dgk, rr, mm, dgs, du, dqf, dkf, dwf, dbf, total;
 };
 
@@ -54,6 +53,7 @@ static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
     size_t off = w.f.total;
     auto take = [&](size_t& field, size_t bytes) { field = off; off = align256(off + bytes); };
     for (size_t* f : {&w.ktT, &w.vk, &w.doq, &w.doT}) take(*f, BH * Lp * d * es);
+    take(w.dpt, BH * NC * d * d * es);
     for (size_t* f : {&w.xs, &w.xsT, &w.gs}) take(*f, BH * npairs * CHUNK * d * es);
     for (size_t* f : {&w.fm, &w.gktm, &w.nm, &w.aim, &w.ytm}) take(*f, BH * NC * 4096 * es);
     take(w.utm, BH * NC * d * CHUNK * es);
@@ -120,7 +120,7 @@ static path_status_t fwd_setup(FwdParams& p, int B, int H, int L, int d, path_dt
     p.xinit = reinterpret_cast<float*>(base + ws.xinit);
     p.sd = reinterpret_cast<float*>(base + ws.sd);
     p.kt2 = base + ws.kt2; p.dp2 = base + ws.dp2;
-    p.dpt = (L > SBC * CHUNK) ? base + ws.dpt : nullptr;     // only the second blocking level reads it
+    p.dpt = nullptr;                                         // transposed -dP tile: backward only
     p.B = B; p.H = H; p.L = L; p.NC = (L + CHUNK - 1) / CHUNK;
     return PATH_OK;
 }
@@ -196,7 +196,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     fp.kt = base + ws.f.kt; fp.vt = base + ws.f.vt; fp.dp = base + ws.f.dp;
     fp.xinit = F(ws.f.xinit); fp.sd = F(ws.f.sd);
     fp.B = B; fp.H = H; fp.L = L; fp.NC = NC; fp.scale = scale;
-    fp.ktT = base + ws.ktT; fp.vk = base + ws.vk; fp.dpt = base + ws.f.dpt; fp.xs = base + ws.xs; fp.xsT = base + ws.xsT;
+    fp.ktT = base + ws.ktT; fp.vk = base + ws.vk; fp.dpt = base + ws.dpt; fp.xs = base + ws.xs; fp.xsT = base + ws.xsT;
     fp.fm = base + ws.fm; fp.gktm = base + ws.gktm; fp.nm = base + ws.nm; fp.aim = base + ws.aim;
     fp.ytm = base + ws.ytm; fp.utm = base + ws.utm; fp.gm = F(ws.gm); fp.sdm = F(ws.sdm);
     if (launch_prep_fwd(fp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;

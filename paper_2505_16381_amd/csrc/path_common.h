@@ -210,7 +210,7 @@ __device__ __forceinline__ f32x16 transpose32(const typename Tr<T>::Frag* a, con
 
 // Workspace carve-up shared by host launch code and kernels (byte offsets, 256-aligned).
 struct FwdWorkspace {
-    size_t kt, vt, dp, xinit, sd, kt2, dp2, dpt, total;
+    size_t kt, vt, dp, xinit, sd, kt2, dp2, total;
 };
 
 struct FwdParams {
@@ -219,7 +219,7 @@ struct FwdParams {
     float* lse;
     void *kt, *vt, *dp;   // fragment-order tiles written by prep, read by the sweep
     void *kt2, *dp2;      // second level: keys carried to their super-block's right edge; -(I - P_superblock)
-    void *dpt;            // -dP per chunk in the transposed arrangement (rows a, contraction b) = -dP[a][b]
+    void *dpt;            // backward only: -dP per chunk in the transposed arrangement (rows a, contraction b) = -dP[a][b]
     float *xinit, *sd;    // accumulator-order fp32 tiles
     int B, H, L, NC;      // NC = number of 64-token chunks = ceil(L/64)
     float scale;

@@ -14,8 +14,9 @@
 // registers (rows b, lane a): in that layout its operand copy is directly the
 // fragment-order tile (rows a, contraction b) that both products need -- as the
 // A operand of the key transport and as the B operand of the update -- and the
-// other operands are the fragment tiles the chunk kernel already wrote (keys,
-// -dP, and -dP in the transposed arrangement), read straight from global memory.
+// other operands are the fragment tiles the chunk kernel already wrote (keys and
+// -dP), read straight from global memory; where -dP is needed element-wise in the
+// transposed register layout it is transposed through the matrix unit.
 #include "path_common.h"
 
 namespace path {
@@ -41,13 +42,14 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
     const int c0 = sb * SBC;
     const int clast = (c0 + SBC - 1 < NC) ? c0 + SBC - 1 : NC - 1;
 
+    Frag idf[SPB];
+    identity_frags<T>(idf, l32, h);
     f32x16 Fm[NE];      // E^T: block o = (rows b-block bb, lane a-block ab), blk = wv + 4*o, bb = blk / DB, ab = blk % DB
 
     for (int c = clast; c >= c0; --c) {
         const size_t bhc = (size_t)bh * NC + c;
         const Frag* k1 = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * (size_t)CHUNK * D);
         const Frag* dpn = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dp) + bhc * (size_t)D * D);    // (rows b, contr a) = -dP[a][b]
-        const Frag* dpt = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D);   // (rows a, contr b) = -dP[a][b]
         Frag* k2 = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2) + bhc * (size_t)CHUNK * D);
         if (c == clast) {
             for (int idx = tid; idx < CHUNK * D / FE; idx += 256) k2[idx] = k1[idx];
@@ -79,14 +81,16 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
 #pragma unroll
                 for (int s = 0; s < DS; ++s) acc = Tr<T>::mma(dpn[((size_t)bb * DS + s) * 64 + lane], Es[(ab * DS + s) * 64 + lane], acc);
             }
+            // -dP[a][b] in this block's register layout (rows b, lane a): the tile piece (rows b,
+            // contraction a) transposed through the matrix unit
+            Frag dfr[SPB];
 #pragma unroll
-            for (int s2 = 0; s2 < SPB; ++s2) {
-                const Frag df = dpt[((size_t)ab * DS + bb * SPB + s2) * 64 + lane];      // -dP[a][b] in this block's register layout
+            for (int s2 = 0; s2 < SPB; ++s2) dfr[s2] = dpn[((size_t)bb * DS + ab * SPB + s2) * 64 + lane];
+            const f32x16 dpT = transpose32<T>(dfr, idf);
 #pragma unroll
-                for (int e = 0; e < FE; ++e) {
-                    const float prev = (c == clast) ? 0.f : Fm[o][s2 * FE + e];
-                    Fm[o][s2 * FE + e] = prev - (float)df[e] + acc[s2 * FE + e];
-                }
+            for (int jj = 0; jj < 16; ++jj) {
+                const float prev = (c == clast) ? 0.f : Fm[o][jj];
+                Fm[o][jj] = prev - dpT[jj] + acc[jj];
             }
         }
         __syncthreads();      // every read of the old operand copy is done
@@ -105,8 +109,6 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
     // -(I - P_superblock) as the sweep's tile (rows b, contraction a): E itself (rows a, lane b) is the
     // transpose of what the registers hold -- taken through the matrix unit.
     Frag* dst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dp2) + ((size_t)bh * gridDim.x + sb) * (size_t)D * D);
-    Frag idf[SPB];
-    identity_frags<T>(idf, l32, h);
 #pragma unroll
     for (int o = 0; o < NE; ++o) {
         const int blk = wv + 4 * o, bb = blk / DB, ab = blk % DB;

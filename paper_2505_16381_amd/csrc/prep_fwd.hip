@@ -386,7 +386,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         }
         if (p.dpt) {
             // -dP in the transposed arrangement (rows c, contraction b) = -dP[c][b]: accumulate with rows b,
-            // lane c.  Read by the second blocking level and by the backward's adjoint scan.
+            // lane c.  Read by the backward's adjoint scan.
             Frag* pdst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dpt) + bhc * (size_t)D * D);
             constexpr int NBP = (D / 32) * (D / 32);
 #pragma unroll

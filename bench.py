@@ -25,6 +25,7 @@ if ROOT not in sys.path:
 
 METRIC = "PaTH attn fwd+bwd TFLOP/s and % bf16 MFMA peak at B=4,H=16,L=8192,d=128"
 PEAK_TFLOPS = 2500.0      # MI355X dense bf16/fp16 MFMA
+SWEEP_HBM_BYTES = 1.95e9  # measured HBM traffic of one sweep launch at the headline shape (see profiles/)
 CHUNK = 64
 
 
@@ -43,14 +44,15 @@ def path_extra_flops(B, H, L, d):
     return (prep + upd) * B * H
 
 
-def cpu_baseline(x, cfg, scale, n_heads=16, n_rows=1024):
+def cpu_baseline(x, cfg, scale, n_rows=3072):
     """The fp64 oracle, as it stands, on a bounded row sample of the same workload."""
     import numpy as np
     from oracle import path_oracle
     rng = np.random.default_rng(0)
     L, d = cfg["L"], cfg["d"]
+    n_heads = cfg["B"] * cfg["H"]
     rows = np.unique(rng.integers(0, L, n_rows))
-    sub = {n: x[n][:1, :n_heads] for n in ("q", "k", "v", "w", "beta")}
+    sub = {n: x[n].reshape((1, n_heads) + x[n].shape[2:]) for n in ("q", "k", "v", "w", "beta")}
     path_oracle.fwd(sub["q"], sub["k"], sub["v"], sub["w"], sub["beta"], scale, rows=rows[:2])  # warm
     t0 = time.perf_counter()
     path_oracle.fwd(sub["q"], sub["k"], sub["v"], sub["w"], sub["beta"], scale, rows=rows)
@@ -59,7 +61,7 @@ def cpu_baseline(x, cfg, scale, n_heads=16, n_rows=1024):
     return {
         "value": pairs * 4.0 * d / dt / 1e12, "unit": "TFLOP/s", "cores": path_oracle.num_threads(),
         "kind": "oracle", "seconds": dt,
-        "sample": f"forward only, {n_heads} heads x {len(rows)} random query rows of the headline shape "
+        "sample": f"forward only, all {n_heads} heads x {len(rows)} random query rows of the headline shape "
                   f"({pairs:.3g} query-key pairs), attention-equivalent flops 4d per pair",
     }
 
@@ -158,8 +160,10 @@ def main():
         "bwd": ({"ms": bwd_ms, "attn_equiv_tflops": 2.5 * fl_f / (bwd_ms * 1e-3) / 1e12} if do_bwd else None),
         "roofline": {"kernel": "attn_fwd_kernel (sweep)", "bound": "mfma", "achieved": sweep_tflops,
                      "peak": PEAK_TFLOPS, "unit": "TFLOP/s", "frac": sweep_tflops / PEAK_TFLOPS,
-                     "traffic": None,
-                     "note": "achieved = attention-equivalent flops of the launch / HIP-event time of the sweep kernel"},
+                     "traffic": SWEEP_HBM_BYTES if (args.config == 2 and not args.shape) else None,
+                     "note": "achieved = attention-equivalent flops of the launch / HIP-event time of the sweep kernel; "
+                             "traffic = HBM bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE "
+                             "(profiles/fwd_headline_L8192_d128_hbm_traffic.txt), vs 1.2e9 algorithmic"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, cfg, scale)

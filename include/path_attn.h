@@ -64,6 +64,13 @@ typedef enum {
 /* Human-readable name of a status code (static storage, never NULL). */
 const char* path_status_str(path_status_t status);
 
+/* After an entry point returned PATH_ERR_HIP on this thread: which step failed
+ * and the runtime's name for the error, e.g. "forward sweep: hipErrorInvalidValue (1)".
+ * The entry points clear, on entry, a runtime error state left behind by other code in
+ * the process and note it here ("inherited and cleared on entry: ...") without failing.
+ * Thread-local storage owned by the library, never NULL; empty before any such event. */
+const char* path_attn_last_error(void);
+
 /* Bytes of device workspace needed by path_attn_fwd (for_backward == 0) or
  * path_attn_bwd (for_backward != 0) for this problem.  Returns 0 for
  * arguments the entry points would reject. */

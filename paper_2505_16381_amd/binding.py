@@ -37,10 +37,16 @@ def load_library():
         raise RuntimeError(
             f"{_LIB_PATH} is missing: build it first (python -m paper_2505_16381_amd.build). "
             "There is no fallback path.")
+    # The process must hold ONE HIP runtime, the one PyTorch ships, because the tensors whose pointers
+    # are handed to the library are allocated through it.  Importing torch first makes the loader
+    # resolve this library's runtime dependency to that already loaded copy.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     vp, ci, cf, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_float, ctypes.c_size_t
     lib.path_status_str.restype = ctypes.c_char_p
     lib.path_status_str.argtypes = [ci]
+    lib.path_attn_last_error.restype = ctypes.c_char_p
+    lib.path_attn_last_error.argtypes = []
     lib.path_attn_workspace_bytes.restype = sz
     lib.path_attn_workspace_bytes.argtypes = [ci, ci, ci, ci, ci, ci]
     lib.path_attn_fwd_workspace_layout.restype = ci
@@ -80,9 +86,14 @@ def _ptr(x):
     return x.data_ptr()
 
 
+def path_attn_last_error() -> str:
+    return load_library().path_attn_last_error().decode()
+
+
 def _check(code):
     if code != 0:
-        raise PathAttnError(code, path_status_str(code))
+        detail = path_attn_last_error() if code == 6 else ""
+        raise PathAttnError(code, path_status_str(code) + (f" [{detail}]" if detail else ""))
 
 
 def _dt_of(t):

@@ -1,5 +1,6 @@
 // C ABI of the PaTH attention library: argument checks, workspace carve-up,
 // kernel launches on the caller's stream.  No allocation, no synchronisation.
+#include <cstdio>
 #include "../../include/path_attn.h"
 #include "path_common.h"
 
@@ -73,6 +74,27 @@ static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
 
 using namespace path;
 
+// Last HIP failure seen by an entry point on this thread: "<step>: <hip error name>".
+static thread_local char g_last_error[160] = "";
+
+static bool hip_ok(hipError_t e, const char* step) {
+    if (e == hipSuccess) return true;
+    snprintf(g_last_error, sizeof g_last_error, "%s: %s (%d)", step, hipGetErrorName(e), static_cast<int>(e));
+    return false;
+}
+
+// The runtime keeps one "last error" per thread, shared with every other user of it in the process; a
+// value left there by someone else must not be taken for a failed launch of ours.  It is cleared on
+// entry and noted, so that the caller can still see it.
+static void clear_inherited_error() {
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        snprintf(g_last_error, sizeof g_last_error, "inherited and cleared on entry: %s (%d)", hipGetErrorName(e),
+                 static_cast<int>(e));
+}
+
+extern "C" const char* path_attn_last_error(void) { return g_last_error; }
+
 extern "C" const char* path_status_str(path_status_t s) {
     switch (s) {
         case PATH_OK: return "PATH_OK";
@@ -134,9 +156,12 @@ extern "C" path_status_t path_attn_fwd_prep(const void* q, const void* k, const 
     if (st != PATH_OK) return st;
     if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(w)) return PATH_ERR_ALIGN;
     p.q = q; p.k = k; p.v = v; p.w = w; p.beta = beta;
-    if (launch_prep_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)) != hipSuccess) return PATH_ERR_HIP;
-    if (p.NC > SBC && launch_prep2_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)) != hipSuccess)
-        return PATH_ERR_HIP;     // the second level is only read when there is a super-block to the left
+    clear_inherited_error();
+    if (!hip_ok(launch_prep_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "chunk transform"))
+        return PATH_ERR_HIP;
+    if (p.NC > SBC &&            // the second level is only read when there is a super-block to the left
+        !hip_ok(launch_prep2_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "second-level transform"))
+        return PATH_ERR_HIP;
     return PATH_OK;
 }
 
@@ -150,7 +175,9 @@ extern "C" path_status_t path_attn_fwd_sweep(void* o, float* lse, int B, int H, 
     if (st != PATH_OK) return st;
     if (misaligned(o)) return PATH_ERR_ALIGN;
     p.o = o; p.lse = lse; p.scale = scale;
-    if (launch_attn_fwd2(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)) != hipSuccess) return PATH_ERR_HIP;
+    clear_inherited_error();
+    if (!hip_ok(launch_attn_fwd2(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "forward sweep"))
+        return PATH_ERR_HIP;
     return PATH_OK;
 }
 
@@ -199,8 +226,9 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     fp.ktT = base + ws.ktT; fp.vk = base + ws.vk; fp.dpt = base + ws.dpt; fp.xs = base + ws.xs; fp.xsT = base + ws.xsT;
     fp.fm = base + ws.fm; fp.gktm = base + ws.gktm; fp.nm = base + ws.nm; fp.aim = base + ws.aim;
     fp.ytm = base + ws.ytm; fp.utm = base + ws.utm; fp.gm = F(ws.gm); fp.sdm = F(ws.sdm);
-    if (launch_prep_fwd(fp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;
-    if (NC > 1 && launch_attn_states(fp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;
+    clear_inherited_error();
+    if (!hip_ok(launch_prep_fwd(fp, d, bf, st), "chunk transform (backward)")) return PATH_ERR_HIP;
+    if (NC > 1 && !hip_ok(launch_attn_states(fp, d, bf, st), "query states")) return PATH_ERR_HIP;
 
     // 2.-4. delta, adjoint scan over key chunks, key-side reductions
     BwdParams bp = {};
@@ -209,7 +237,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     bp.doq = base + ws.doq; bp.doT = base + ws.doT; bp.gs = base + ws.gs;
     bp.delta = F(ws.delta); bp.lse2p = F(ws.lse2p); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
     bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale;
-    if (launch_bwd_scan(bp, d, bf, st) != hipSuccess) return PATH_ERR_HIP;
+    if (!hip_ok(launch_bwd_scan(bp, d, bf, st), "backward pair kernels")) return PATH_ERR_HIP;
 
     // 5. adjoint of the chunk transform
     const long long c_bh = (long long)NC * 4096, c_ch = 4096;          // 64x64 per chunk
@@ -233,7 +261,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
         if (tokC) { a.c_bh = t_bh; a.c_ch = t_ch; a.crs = d; a.ccs = 1; }
         else { a.c_bh = c_bh; a.c_ch = c_ch; a.crs = 64; a.ccs = 1; }
         a.M = M; a.N = N; a.K = K; a.alpha = alpha; a.mask = mask; a.NC = NC; a.L = L;
-        ok = launch_batched_gemm(a, BH, bf, st) == hipSuccess;
+        ok = hip_ok(launch_batched_gemm(a, BH, bf, st), "chunk-transform adjoint product");
     };
     float *dpd = F(ws.dpd), *pd = F(ws.pd), *dsd = F(ws.dsd), *df = F(ws.df), *dy = F(ws.dy), *dn = F(ws.dn);
     float *dgk = F(ws.dgk), *rr = F(ws.rr), *mm = F(ws.mm), *dgs = F(ws.dgs), *du = F(ws.du);
@@ -245,7 +273,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     gemm(dpd, false, nullptr, user_n(d_o), user_n(v), 64, 64, d, 1.f, MASK_NONE);
     if (ok) {
         DiagArgs da{fp.sdm, dpd, bp.delta, lse, pd, dsd, L, NC, scale};
-        ok = launch_bwd_diag(da, BH, st) == hipSuccess;
+        ok = hip_ok(launch_bwd_diag(da, BH, st), "diagonal block adjoint");
     }
     gemm(dvp, true, dvp, chunk_t(pd, EL_F32), user_t(d_o), 64, d, 64, 1.f, MASK_NONE);          // dV += P^T dO
     gemm(dqf, true, dqb, chunk_n(dsd, EL_F32), user_t(k), 64, d, 64, 1.f, MASK_NONE);           // dQ = dQb + dSd K
@@ -263,7 +291,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     gemm(mm, false, nullptr, chunk_n(rr, EL_F32), chunk_n(nm, EL_OP), 64, 64, 64, -1.f, MASK_SLOWER);   // M = sl(-R N^T)
     if (ok) {
         BetaArgs ba{rr, mm, fp.gm, beta, dgs, dbf, L, NC};
-        ok = launch_bwd_beta(ba, BH, bf, st) == hipSuccess;
+        ok = hip_ok(launch_bwd_beta(ba, BH, bf, st), "beta adjoint");
     }
     gemm(dwf, true, nullptr, chunk_t(ytm, EL_OP), tokws_t(dkb), 64, d, 64, -1.f, MASK_NONE);            // dW = -Y dKb
     gemm(dwf, true, dwf, U_rows, ddp_nfirst, 64, d, d, 1.f, MASK_NONE);                                  //    + U ddP^T
@@ -275,7 +303,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     gemm(dkf, true, dkf, chunk_t(dgk, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE);                    // dK += dGk^T W
     if (ok) {
         OutArgs oa{dqf, dkf, dvp, dwf, dbf, dq, dk, dv, dw, dbeta, L, NC, d};
-        ok = launch_bwd_store(oa, BH, bf, st) == hipSuccess;
+        ok = hip_ok(launch_bwd_store(oa, BH, bf, st), "gradient store");
     }
     return ok ? PATH_OK : PATH_ERR_HIP;
 }

@@ -21,7 +21,7 @@ def _declared_functions():
 def test_library_exports_every_declared_symbol():
     lib = pa.load_library()
     names = _declared_functions()
-    assert {"path_attn_fwd", "path_attn_bwd", "path_attn_workspace_bytes", "path_status_str"} <= set(names)
+    assert {"path_attn_fwd", "path_attn_bwd", "path_attn_workspace_bytes", "path_status_str", "path_attn_last_error"} <= set(names)
     for n in names:
         assert hasattr(lib, n), n
 

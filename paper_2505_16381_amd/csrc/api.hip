@@ -43,19 +43,27 @@ static FwdWorkspace fwd_workspace(int B, int H, int L, int d, size_t es) {
 struct BwdWorkspace {
     FwdWorkspace f;
     size_t ktT, vk, dpt, doq, doT, xs, xsT, gs, fm, gktm, nm, aim, ytm, utm, gm, sdm, delta, lse2p, dqb, dkb, dvp, ddp;
+    size_t kt2T, dpt2, kbm, rm, dk2, dchain, t1;       // second level and its adjoint
     size_t dpd, pd, dsd, df, dy, dn, dgk, rr, mm, dgs, du, dqf, dkf, dwf, dbf, total;
 };
 
 static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
     const size_t BH = (size_t)B * H, NC = (size_t)(L + CHUNK - 1) / CHUNK, Lp = NC * CHUNK;
-    const size_t npairs = NC * (NC - 1) / 2;
+    const size_t nslots = num_block_slots((int)NC), NSB = (NC + SBC - 1) / SBC;
     BwdWorkspace w;
     w.f = fwd_workspace(B, H, L, d, es);
     size_t off = w.f.total;
     auto take = [&](size_t& field, size_t bytes) { field = off; off = align256(off + bytes); };
     for (size_t* f : {&w.ktT, &w.vk, &w.doq, &w.doT}) take(*f, BH * Lp * d * es);
     take(w.dpt, BH * NC * d * d * es);
-    for (size_t* f : {&w.xs, &w.xsT, &w.gs}) take(*f, BH * npairs * CHUNK * d * es);
+    for (size_t* f : {&w.xs, &w.xsT, &w.gs}) take(*f, BH * nslots * CHUNK * d * es);
+    take(w.kt2T, BH * Lp * d * es);
+    take(w.dpt2, BH * NSB * d * d * es);
+    take(w.kbm, BH * Lp * d * es);
+    take(w.rm, BH * NC * d * d * es);
+    take(w.dk2, BH * Lp * d * 4);
+    take(w.dchain, BH * (NC + 1) * d * d * 4);
+    take(w.t1, BH * NC * d * CHUNK * 4);
     for (size_t* f : {&w.fm, &w.gktm, &w.nm, &w.aim, &w.ytm}) take(*f, BH * NC * 4096 * es);
     take(w.utm, BH * NC * d * CHUNK * es);
     take(w.gm, BH * NC * 4096 * 4);
@@ -222,18 +230,22 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     fp.q = q; fp.k = k; fp.v = v; fp.w = w; fp.beta = beta;
     fp.kt = base + ws.f.kt; fp.vt = base + ws.f.vt; fp.dp = base + ws.f.dp;
     fp.xinit = F(ws.f.xinit); fp.sd = F(ws.f.sd);
+    fp.kt2 = base + ws.f.kt2; fp.dp2 = base + ws.f.dp2;
+    fp.kt2T = base + ws.kt2T; fp.dpt2 = base + ws.dpt2; fp.kbm = base + ws.kbm; fp.rm = base + ws.rm;
     fp.B = B; fp.H = H; fp.L = L; fp.NC = NC; fp.scale = scale;
     fp.ktT = base + ws.ktT; fp.vk = base + ws.vk; fp.dpt = base + ws.dpt; fp.xs = base + ws.xs; fp.xsT = base + ws.xsT;
     fp.fm = base + ws.fm; fp.gktm = base + ws.gktm; fp.nm = base + ws.nm; fp.aim = base + ws.aim;
     fp.ytm = base + ws.ytm; fp.utm = base + ws.utm; fp.gm = F(ws.gm); fp.sdm = F(ws.sdm);
     clear_inherited_error();
     if (!hip_ok(launch_prep_fwd(fp, d, bf, st), "chunk transform (backward)")) return PATH_ERR_HIP;
+    if (!hip_ok(launch_prep2_fwd(fp, d, bf, st), "second-level transform (backward)")) return PATH_ERR_HIP;
     if (NC > 1 && !hip_ok(launch_attn_states(fp, d, bf, st), "query states")) return PATH_ERR_HIP;
 
     // 2.-4. delta, adjoint scan over key chunks, key-side reductions
     BwdParams bp = {};
     bp.q = q; bp.k = k; bp.v = v; bp.w = w; bp.beta = beta; bp.o = o; bp.dO = d_o; bp.lse = lse;
     bp.kt = fp.kt; bp.vk = fp.vk; bp.ktT = fp.ktT; bp.dpt = fp.dpt; bp.xs = fp.xs; bp.xsT = fp.xsT;
+    bp.kt2 = fp.kt2; bp.kt2T = fp.kt2T; bp.dpt2 = fp.dpt2; bp.dk2 = F(ws.dk2); bp.dchain = F(ws.dchain);
     bp.doq = base + ws.doq; bp.doT = base + ws.doT; bp.gs = base + ws.gs;
     bp.delta = F(ws.delta); bp.lse2p = F(ws.lse2p); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
     bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale;
@@ -254,13 +266,22 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     const MatRef ddp_nfirst{F(ws.ddp), (long long)NC * d * d, (long long)d * d, d, 1, EL_F32, TOK_NONE};   // (n=c, k=b): ddP[c][b]
 
     bool ok = true;
-    auto gemm = [&](float* C, bool tokC, const float* Cin, MatRef A, MatRef Bm, int M, int N, int K, float alpha, int mask) {
+    int cmul = 1, cadd = 0;          // which chunks the following products run on: x * cmul + cadd
+    enum { OUT_C64 = 0, OUT_TOK = 1, OUT_DD = 2, OUT_DD1 = 3, OUT_D64 = 4 };
+    auto gemm = [&](float* C, int tokC, const float* Cin, MatRef A, MatRef Bm, int M, int N, int K, float alpha, int mask) {
         if (!ok) return;
         GemmArgs a;
         a.A = A; a.B = Bm; a.C = C; a.Cin = Cin;
-        if (tokC) { a.c_bh = t_bh; a.c_ch = t_ch; a.crs = d; a.ccs = 1; }
-        else { a.c_bh = c_bh; a.c_ch = c_ch; a.crs = 64; a.ccs = 1; }
+        a.ccs = 1;
+        switch (tokC) {      // layout of C (and Cin)
+            case OUT_TOK:  a.c_bh = t_bh; a.c_ch = t_ch; a.crs = d; break;                                    // tokens x d
+            case OUT_DD:   a.c_bh = (long long)NC * d * d; a.c_ch = (long long)d * d; a.crs = d; break;       // d x d per chunk
+            case OUT_DD1:  a.c_bh = (long long)(NC + 1) * d * d; a.c_ch = (long long)d * d; a.crs = d; break; // ... in an array of NC+1
+            case OUT_D64:  a.c_bh = (long long)NC * d * CHUNK; a.c_ch = (long long)d * CHUNK; a.crs = 64; break;   // d x 64 per chunk
+            default:       a.c_bh = c_bh; a.c_ch = c_ch; a.crs = 64; break;                                   // 64 x 64 per chunk
+        }
         a.M = M; a.N = N; a.K = K; a.alpha = alpha; a.mask = mask; a.NC = NC; a.L = L;
+        a.cmul = cmul; a.cadd = cadd; a.gridx = cmul == 1 ? NC : (NC + cmul - 1) / cmul;
         ok = hip_ok(launch_batched_gemm(a, BH, bf, st), "chunk-transform adjoint product");
     };
     float *dpd = F(ws.dpd), *pd = F(ws.pd), *dsd = F(ws.dsd), *df = F(ws.df), *dy = F(ws.dy), *dn = F(ws.dn);
@@ -268,6 +289,39 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     float *dqf = F(ws.dqf), *dkf = F(ws.dkf), *dwf = F(ws.dwf), *dbf = F(ws.dbf);
     float *dqb = bp.dqb, *dkb = bp.dkb, *dvp = bp.dvp;
     void *fm = fp.fm, *gktm = fp.gktm, *nm = fp.nm, *aim = fp.aim, *ytm = fp.ytm;
+
+    // 5a. adjoint of the second level (Kb2_c = Kb_c R_c^T, R_{c-1} = R_c P_c, P_superblock = R_{first-1}),
+    // position by position inside the super-blocks, all super-blocks at once.  dchain entry c+1 is
+    // the gradient of R_c; entry 4J (gradient of P_superblock J) comes from the far ddP kernel.
+    //     ddP_c  -= R_c^T D_{c-1}
+    //     D_c     = D_{c-1} (I - dP_c)^T + dKb2_c^T Kb_c          dP_c = W_c^T U_c
+    //     dKb_c  += dKb2_c R_c
+    if (NC > SBC) {
+        const long long dd = (long long)d * d, dd_bh = (long long)NC * dd, ch_bh = (long long)(NC + 1) * dd;
+        float* dch = F(ws.dchain);
+        float* t1 = F(ws.t1);
+        float* dk2 = F(ws.dk2);
+        cmul = SBC;
+        for (int cl = 0; cl < SBC && ok; ++cl) {
+            cadd = cl;
+            const MatRef Dprev_kfirst{dch, ch_bh, dd, 1, d, EL_F32, TOK_NONE};          // (n=b, k): D_{c-1}[k][b]
+            const MatRef Dprev_rows{dch, ch_bh, dd, d, 1, EL_F32, TOK_NONE};            // (m=a, k): D_{c-1}[a][k]
+            const MatRef R_kfirst{base + ws.rm, dd_bh, dd, 1, d, EL_OP, TOK_NONE};       // (m=a, k): R_c[k][a]  /  (n=b, k=a): R_c[a][b]
+            gemm(F(ws.ddp), OUT_DD, F(ws.ddp), R_kfirst, Dprev_kfirst, d, d, d, -1.f, MASK_NONE);
+            if (cl + 1 < SBC) {
+                // T1 = D_{c-1} U_c^T  (d x 64),  D_c = D_{c-1} - T1 W_c + dKb2_c^T Kb_c
+                gemm(t1, OUT_D64, nullptr, Dprev_rows, U_rows, d, 64, d, 1.f, MASK_NONE);
+                const MatRef T1_rows{t1, (long long)NC * d * CHUNK, (long long)d * CHUNK, 64, 1, EL_F32, TOK_NONE};
+                gemm(dch + dd, OUT_DD1, dch, T1_rows, user_t(w), d, d, 64, -1.f, MASK_NONE);
+                const MatRef dk2_t{dk2, t_bh, t_ch, 1, d, EL_F32, TOK_NONE};             // (m=a, k=s): dKb2[s][a]
+                const MatRef kb_t{base + ws.kbm, t_bh, t_ch, 1, d, EL_OP, TOK_NONE};     // (n=b, k=s): Kb[s][b]
+                gemm(dch + dd, OUT_DD1, dch + dd, dk2_t, kb_t, d, d, 64, 1.f, MASK_NONE);
+            }
+            const MatRef dk2_n{dk2, t_bh, t_ch, d, 1, EL_F32, TOK_NONE};                 // (m=s, k=a): dKb2[s][a]
+            gemm(dkb, OUT_TOK, dkb, dk2_n, R_kfirst, 64, d, d, 1.f, MASK_NONE);
+        }
+        cmul = 1; cadd = 0;
+    }
 
     // diagonal block: dPd = dO V^T, then P and dSd
     gemm(dpd, false, nullptr, user_n(d_o), user_n(v), 64, 64, d, 1.f, MASK_NONE);

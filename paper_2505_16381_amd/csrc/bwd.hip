@@ -1,8 +1,11 @@
 // Backward of PaTH attention.  The paper gives no backward pass; this is the
 // reverse-mode derivative of the blockwise forward (Sec. 3.2-3.3), organised as
 //
-//   1. prep (forward kernel, extra row-major outputs) and a states-only sweep:
-//      Xs(i,j) = query state of chunk i as used against key chunk j < i.
+//   1. prep and prep2 (forward kernels, extra outputs) and a states-only sweep:
+//      Xs(i,blk) = query state of chunk i as used against key block blk.  Key blocks follow the
+//      forward's two blocking levels: the chunks of i's own super-block one by one ("near", keys
+//      Kb, product dP_j), the super-blocks further left as a whole ("far": one state for the
+//      super-block's SBC chunks, second-level keys Kb2, product dP2 = I - P_superblock).
 //   2. bwd_delta:    delta_t = dO_t . o_t.
 //   3. bwd_adjoint2: per query chunk i, left-to-right over key chunks j:
 //        dS = scale * P o (dO V_j^T - delta),   P = exp(scale * Xs Kb_j^T - lse)
@@ -10,8 +13,9 @@
 //      g(i,i-1) is the gradient of the boundary-adjusted queries Qb_i.
 //   4. bwd_keyside2 / bwd_ddp: per key chunk j, over query chunks i > j (no atomics):
 //        dV_j += P^T dO_i,  dKb_j += dS^T Xs(i,j),  ddP_j -= Xs(i,j)^T g(i,j-1).
-//   5. chunk transform adjoint (Qb, Kb, dP, Sd -> q, k, w, beta): a short
-//      sequence of batched 64x64xd products (batched_gemm) and elementwise steps.
+//   5. adjoint of the second level (dKb2, ddP2 -> dKb, ddP) and of the chunk transform
+//      (Qb, Kb, dP, Sd -> q, k, w, beta): short sequences of batched products (batched_gemm)
+//      and elementwise steps, driven from the host code.
 //
 // Steps 3 and 4 follow the forward's scheme: activations stay in registers in
 // transposed form, streamed operands are fragment-order tiles (written by prep, the
@@ -119,7 +123,8 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
     const bool active = cq < NC;
     const int jmax = ((tile * 2 + 1 < NC) ? tile * 2 + 1 : NC - 1) - 1;     // last key chunk any wave needs
-    const size_t Lp = (size_t)NC * CHUNK, npairs = (size_t)NC * (NC - 1) / 2;
+    const int jsb = (tile * 2 / SBC) * SBC;                                // first chunk of the tile's own super-block
+    const size_t Lp = (size_t)NC * CHUNK, nslots = num_block_slots(NC);
     const float sl2 = p.scale * 1.44269504088896340736f;
     const int tq = cq * CHUNK + 32 * qb + l32;                             // this lane's query
 
@@ -140,24 +145,34 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     Frag idf[SPB];
     identity_frags<T>(idf, l32, h);
 
+    // Step j handles key chunk j: far (j < jsb: second-level keys, state and product of its
+    // super-block) or near (chunk-level keys, state and product of the chunk).
+    const int nsb = (NC + SBC - 1) / SBC;
     auto issue = [&](int j) {
         Frag* buf = sbase + (size_t)(j & (NBUF - 1)) * STF;
         const size_t bhc = (size_t)bh * NC + j;
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * CHUNK * D), buf, KVF, tid, wv);
+        const bool far = j < jsb;
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2 : p.kt) + bhc * CHUNK * D), buf, KVF, tid, wv);
         async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), buf + KVF, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.ktT) + bhc * CHUNK * D), buf + 2 * KVF, KVF, tid, wv);
-        if (j > 0) async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D), buf + 3 * KVF, DPF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2T : p.ktT) + bhc * CHUNK * D), buf + 2 * KVF, KVF, tid, wv);
+        if (j > 0) {
+            if (!far)
+                async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D), buf + 3 * KVF, DPF, tid, wv);
+            else if (j % SBC == 0)
+                async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt2) + ((size_t)bh * nsb + j / SBC) * (size_t)D * D), buf + 3 * KVF, DPF, tid, wv);
+        }
     };
-    // the wave's own state fragments of pair (cq, j): fetched one step ahead
+    auto block_start = [&](int j) { return j >= jsb || j % SBC == 0; };
+    // the wave's own state fragments of the block that starts at chunk j: fetched one step ahead
     auto load_x = [&](int j, Frag* x) {
-        const size_t slot = ((size_t)bh * npairs + pair_slot(cq, j)) * (size_t)CHUNK * D;
+        const size_t slot = ((size_t)bh * nslots + block_slot(cq, j, NC)) * (size_t)CHUNK * D;
         const Frag* xg = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot);
 #pragma unroll
         for (int s = 0; s < DS; ++s) x[s] = xg[((size_t)qb * DS + s) * 64 + lane];
     };
-    Frag Xnext[DS];
+    Frag Xnext[DS], Xb[DS];
 #pragma unroll
-    for (int s = 0; s < DS; ++s) Xnext[s] = Tr<T>::zero();
+    for (int s = 0; s < DS; ++s) { Xnext[s] = Tr<T>::zero(); Xb[s] = Tr<T>::zero(); }
     if (active && cq > 0) load_x(0, Xnext);
     if (jmax >= 0 && NBUF == 2) issue(0);
 
@@ -176,10 +191,13 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
         const Frag* sKT = sK + 2 * KVF;
         const Frag* sDP = sK + 3 * KVF;
 
-        Frag Xb[DS];
+        const bool first = block_start(j);          // first chunk of its block: new state, product applied to g
+        if (first) {
 #pragma unroll
-        for (int s = 0; s < DS; ++s) Xb[s] = Xnext[s];
-        if (j + 1 < cq) load_x(j + 1, Xnext);
+            for (int s = 0; s < DS; ++s) Xb[s] = Xnext[s];
+        }
+        const bool next_starts = j + 1 < cq && block_start(j + 1);
+        if (next_starts) load_x(j + 1, Xnext);
 
         Frag dSb[QS];
 #pragma unroll
@@ -201,15 +219,15 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
         for (int b = 0; b < DB; ++b) {
 #pragma unroll
             for (int s = 0; s < QS; ++s) Gm[b] = Tr<T>::mma(sKT[(b * QS + s) * 64 + lane], dSb[s], Gm[b]);
-            if (j > 0) {
+            if (j > 0 && first) {
 #pragma unroll
                 for (int s = 0; s < DS; ++s) Gm[b] = Tr<T>::mma(sDP[(b * DS + s) * 64 + lane], Gb[s], Gm[b]);
             }
         }
 #pragma unroll
         for (int b = 0; b < DB; ++b) pack_block<T>(Gm[b], Gb + b * SPB);
-        if (j + 1 < cq) {      // g(cq, j) as tile gT (rows b, contraction q) of pair (cq, j+1)
-            const size_t slot2 = ((size_t)bh * npairs + pair_slot(cq, j + 1)) * (size_t)CHUNK * D;
+        if (next_starts) {     // g after this block, as tile gT (rows b, contraction q) of the pair (cq, next block)
+            const size_t slot2 = ((size_t)bh * nslots + block_slot(cq, j + 1, NC)) * (size_t)CHUNK * D;
             Frag* gt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.gs) + slot2);
 #pragma unroll
             for (int b = 0; b < DB; ++b) {
@@ -238,7 +256,10 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
 
 // ---------------------------------------------------------------------------------------
 // Key-side reduction of dV and dKb.  One workgroup per key chunk j; wave w owns the 32 keys of
-// half (w & 1) (= the MFMA columns) and the 32-query half (w >> 1) of every query chunk i > j:
+// half (w & 1) (= the MFMA columns) and the 32-query half (w >> 1) of every query chunk i > j
+// of the kernel's range -- near (FAR = false): the chunks i > j of j's own super-block, keys Kb,
+// results dKb and dV; far (FAR = true): all chunks of the super-blocks to the right, keys Kb2,
+// results dKb2 and dV added to the near part (the near kernel runs first):
 //     S  = Xs Kb_j^T              A = xs tile,   B = Kb fragments (resident)
 //     dP = dO V_j^T               A = doq tile,  B = V fragments (resident)
 //     dV^T  += dO^T P             A = doT tile,  B = P   (registers)
@@ -255,7 +276,7 @@ template <typename TIO, int D> struct Key2Cfg {
     static constexpr size_t smem_bytes = tile_bytes > red_bytes ? tile_bytes : red_bytes;
 };
 
-template <typename TIO, int D>
+template <typename TIO, int D, bool FAR>
 __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     using C = Key2Cfg<TIO, D>;
     using T = typename C::T;
@@ -267,18 +288,36 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     Frag* sbase = reinterpret_cast<Frag*>(smem);
 
-    const int j = blockIdx.x, bh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
-    const int kh = wv & 1, qh = wv >> 1;
+    // Workgroup numbering (1-D grid): workgroup n runs on XCD n % 8.  XCD x takes the heads
+    // bh = x (mod 8), and the workgroups of one super-block get consecutive numbers on it:
+    // they stream the same far states and dO tiles at the same time, out of that XCD's L2.
+    // Super-blocks with the most query chunks to their right come first.
+    // Near: one key chunk per workgroup, wave w = key half (w & 1) x query half (w >> 1).
+    // Far: TWO key chunks per workgroup (they share every staged tile), wave w = key half (w & 1)
+    // of chunk j + (w >> 1), both query halves in turn.
+    constexpr int CPW = FAR ? 2 : 1, NPOS = SBC / CPW;
     const int L = p.L, NC = p.NC;
-    const size_t Lp = (size_t)NC * CHUNK, npairs = (size_t)NC * (NC - 1) / 2;
+    const int nsb_g = (NC + SBC - 1) / SBC;
+    const int xcd = blockIdx.x & 7, kk = blockIdx.x >> 3;
+    const int j = (kk / NPOS % nsb_g) * SBC + (kk % NPOS) * CPW;       // first key chunk of the workgroup
+    const int bh = (kk / (NPOS * nsb_g)) * 8 + xcd;
+    if (bh >= p.B * p.H || j >= NC) return;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int kh = wv & 1;
+    const int jw = FAR ? j + (wv >> 1) : j;                            // this wave's key chunk
+    const bool wactive = jw < NC;
+    const size_t Lp = (size_t)NC * CHUNK, nslots = num_block_slots(NC);
     const float sl2 = p.scale * 1.44269504088896340736f;
+    const int sb_end = (j / SBC + 1) * SBC;                       // first chunk right of j's super-block
+    const int i0 = FAR ? sb_end : j + 1;
+    const int i1 = FAR ? NC : (sb_end < NC ? sb_end : NC);
 
     Frag Kb[DS];
     FragV Vb[DS];
     {
-        const Frag* kg = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + ((size_t)bh * NC + j) * CHUNK * D);
-        const FragV* vg = reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.vk) + ((size_t)bh * NC + j) * CHUNK * D);
+        const int jl = wactive ? jw : j;
+        const Frag* kg = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(FAR ? p.kt2 : p.kt) + ((size_t)bh * NC + jl) * CHUNK * D);
+        const FragV* vg = reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.vk) + ((size_t)bh * NC + jl) * CHUNK * D);
 #pragma unroll
         for (int s = 0; s < DS; ++s) { Kb[s] = kg[((size_t)kh * DS + s) * 64 + lane]; Vb[s] = vg[((size_t)kh * DS + s) * 64 + lane]; }
     }
@@ -289,7 +328,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     // all operands of query chunk i, asynchronously, into stage buffer (i & (NBUF-1))
     auto issue = [&](int i) {
         Frag* buf = sbase + (size_t)(i & (NBUF - 1)) * STF;
-        const size_t slot = ((size_t)bh * npairs + pair_slot(i, j)) * (size_t)CHUNK * D;
+        const size_t slot = ((size_t)bh * nslots + block_slot(i, j, NC)) * (size_t)CHUNK * D;
         const size_t bhi = ((size_t)bh * NC + i) * CHUNK * D;
         async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot), buf, KVF, tid, wv);
         async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf + KVF, KVF, tid, wv);
@@ -302,11 +341,11 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
         }
     };
 
-    if (j + 1 < NC && NBUF == 2) issue(j + 1);
-    for (int i = j + 1; i < NC; ++i) {
+    if (i0 < i1 && NBUF == 2) issue(i0);
+    for (int i = i0; i < i1; ++i) {
         if (NBUF == 2) {
             wait_async_and_sync();                 // chunk i has landed; everyone is done with chunk i-1
-            if (i + 1 < NC) issue(i + 1);
+            if (i + 1 < i1) issue(i + 1);
         } else {
             __syncthreads();
             issue(i);
@@ -319,32 +358,54 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
         const float* lse2 = reinterpret_cast<const float*>(sX + 4 * KVF);
         const float* dl = lse2 + CHUNK;
 
-        f32x16 S = zero16(), dP = zero16();                    // rows q (half qh), lane s
 #pragma unroll
-        for (int s = 0; s < DS; ++s) {
-            S = Tr<T>::mma(sX[(qh * DS + s) * 64 + lane], Kb[s], S);
-            dP = Tr<TIO>::mma(sDQ[(qh * DS + s) * 64 + lane], Vb[s], dP);
-        }
-        f32x16 Pm;
+        for (int qq = 0; qq < CPW; ++qq) {
+            const int qh = FAR ? qq : (wv >> 1);
+            f32x16 S = zero16(), dP = zero16();                    // rows q (half qh), lane s
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj) {
-            const int q = 32 * qh + acc_row(jj, h);
-            const float P = (i * CHUNK + q < L) ? __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -lse2[q])) : 0.f;
-            Pm[jj] = P;
-            S[jj] = P * (dP[jj] - dl[q]) * p.scale;
+            for (int s = 0; s < DS; ++s) {
+                S = Tr<T>::mma(sX[(qh * DS + s) * 64 + lane], Kb[s], S);
+                dP = Tr<TIO>::mma(sDQ[(qh * DS + s) * 64 + lane], Vb[s], dP);
+            }
+            f32x16 Pm;
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const int q = 32 * qh + acc_row(jj, h);
+                const float P = (i * CHUNK + q < L) ? __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -lse2[q])) : 0.f;
+                Pm[jj] = P;
+                S[jj] = P * (dP[jj] - dl[q]) * p.scale;
+            }
+            FragV Pb[SPB];
+            Frag dSb[SPB];
+            pack_block<TIO>(Pm, Pb);
+            pack_block<T>(S, dSb);
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int s = 0; s < SPB; ++s) {
+                    dVt[b] = Tr<TIO>::mma(sDT[(b * QS + qh * SPB + s) * 64 + lane], Pb[s], dVt[b]);
+                    dKt[b] = Tr<T>::mma(sXT[(b * QS + qh * SPB + s) * 64 + lane], dSb[s], dKt[b]);
+                }
         }
-        FragV Pb[SPB];
-        Frag dSb[SPB];
-        pack_block<TIO>(Pm, Pb);
-        pack_block<T>(S, dSb);
+    }
+    if (FAR) {
+        // each wave holds the complete sums of its 32 keys: write row-major fp32 [s][c] from
+        // registers (rows c, lane s); dV is added to the near part
+        if (!wactive) return;
+        const size_t row = ((size_t)bh * Lp + jw * CHUNK + 32 * kh + l32) * D + 4 * h;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
-            for (int s = 0; s < SPB; ++s) {
-                dVt[b] = Tr<TIO>::mma(sDT[(b * QS + qh * SPB + s) * 64 + lane], Pb[s], dVt[b]);
-                dKt[b] = Tr<T>::mma(sXT[(b * QS + qh * SPB + s) * 64 + lane], dSb[s], dKt[b]);
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v4 = *reinterpret_cast<const f32x4*>(p.dvp + row + 32 * b + 8 * g), k4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) { v4[r] += dVt[b][4 * g + r]; k4[r] = dKt[b][4 * g + r]; }
+                *reinterpret_cast<f32x4*>(p.dvp + row + 32 * b + 8 * g) = v4;
+                *reinterpret_cast<f32x4*>(p.dk2 + row + 32 * b + 8 * g) = k4;
             }
+        return;
     }
+    const int qh = wv >> 1;
     // sum the two query halves, write row-major fp32 [s][c] from registers (rows c, lane s)
     __syncthreads();
     float* red = reinterpret_cast<float*>(smem);
@@ -377,9 +438,13 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------------
-// ddP_j[a][b] = - sum_{i>j} sum_q Xs(i,j)[q][a] g(i,j-1)[q][b]: one workgroup per key chunk, a plain
-// product over the stacked query axis; both operands are read as fragments straight from global
-// memory (tiles xsT and gT, contraction q).
+// ddP_blk[a][b] = - sum_i sum_q Xs(i,blk)[q][a] g(i, block before blk)[q][b]: one workgroup per key
+// block, a plain product over the stacked query axis of the tiles xsT and gT (contraction q),
+// staged through LDS.  Near (FAR = false): block = chunk j, queries = the chunks i > j of j's
+// super-block, result ddP_j.  Far (FAR = true): block = super-block J, queries = all chunks
+// right of it; the result is stored with the opposite sign -- the gradient with respect to
+// P_superblock = I - dP2 -- where the adjoint of the second level starts its chain: entry 4J of
+// the per-head array dchain (entry c+1 belongs to chunk c; entry 0 is zero).
 template <typename TIO, int D> struct DdpCfg {
     typedef typename Compute<TIO>::type T;
     static constexpr int KV_FRAGS = CHUNK * D / Tr<T>::FE;
@@ -387,7 +452,7 @@ template <typename TIO, int D> struct DdpCfg {
     static constexpr size_t smem_bytes = (size_t)NBUF * 2 * KV_FRAGS * 16;     // NBUF x (xsT | gT)
 };
 
-template <typename TIO, int D>
+template <typename TIO, int D, bool FAR>
 __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
     using C = DdpCfg<TIO, D>;
     using T = typename Compute<TIO>::type;
@@ -398,21 +463,25 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
     const int j = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
     const int NC = p.NC;
-    const size_t npairs = (size_t)NC * (NC - 1) / 2;
+    const size_t nslots = num_block_slots(NC);
+    const int cj = FAR ? j * SBC : j;                             // a key chunk of the block
+    const int sb_end = (cj / SBC + 1) * SBC;
+    const int i0 = FAR ? sb_end : j + 1;
+    const int i1 = FAR ? NC : (sb_end < NC ? sb_end : NC);
     f32x16 acc[NOWN];
 #pragma unroll
     for (int o = 0; o < NOWN; ++o) acc[o] = zero16();
     if (j >= 1) {
         auto issue = [&](int i) {
             Frag* buf = sbase + (size_t)(i & 1) * 2 * KVF;
-            const size_t slot = ((size_t)bh * npairs + pair_slot(i, j)) * (size_t)CHUNK * D;
+            const size_t slot = ((size_t)bh * nslots + block_slot(i, cj, NC)) * (size_t)CHUNK * D;
             async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf, KVF, tid, wv);
             async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.gs) + slot), buf + KVF, KVF, tid, wv);
         };
-        if (j + 1 < NC) issue(j + 1);
-        for (int i = j + 1; i < NC; ++i) {
+        if (i0 < i1) issue(i0);
+        for (int i = i0; i < i1; ++i) {
             wait_async_and_sync();                 // pair (i, j) has landed; everyone is done with pair (i-1, j)
-            if (i + 1 < NC) issue(i + 1);
+            if (i + 1 < i1) issue(i + 1);
             const Frag* xt = sbase + (size_t)(i & 1) * 2 * KVF;
             const Frag* gt = xt + KVF;
 #pragma unroll
@@ -428,8 +497,11 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
     for (int o = 0; o < NOWN; ++o) {
         const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
 #pragma unroll
-        for (int jj = 0; jj < 16; ++jj)
-            p.ddp[(((size_t)bh * NC + j) * D + 32 * ab + acc_row(jj, h)) * D + 32 * bb + l32] = -acc[o][jj];
+        for (int jj = 0; jj < 16; ++jj) {
+            const size_t el = (size_t)(32 * ab + acc_row(jj, h)) * D + 32 * bb + l32;
+            if (FAR) p.dchain[((size_t)bh * (NC + 1) + (size_t)j * SBC) * D * D + el] = acc[o][jj];
+            else p.ddp[((size_t)bh * NC + j) * D * D + el] = -acc[o][jj];
+        }
     }
 }
 
@@ -494,7 +566,8 @@ __global__ __launch_bounds__(256) void batched_gemm_kernel(GemmArgs a) {
     const int ld = a.K + FE;
     T* As = reinterpret_cast<T*>(smem);
     T* Bs = As + a.M * ld;
-    const int chunk = blockIdx.x, bh = blockIdx.y;
+    const int chunk = blockIdx.x * a.cmul + a.cadd, bh = blockIdx.y;
+    if (chunk >= a.NC) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
     stage_mat<TIO>(a.A, As, ld, a.M, a.K, bh, chunk, a.L, tid);
     stage_mat<TIO>(a.B, Bs, ld, a.N, a.K, bh, chunk, a.L, tid);
@@ -594,12 +667,21 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     const int ntiles = (p.NC + 1) / 2;
     hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D>), dim3((unsigned)(ntiles * p.B * p.H)), dim3(256), adj_bytes, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = set_smem(&bwd_keyside2_kernel<TIO, D>, key_bytes)) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D>), grid, dim3(256), key_bytes, st, p);
+    if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, false>, key_bytes)) != hipSuccess) return e;
+    if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, true>, key_bytes)) != hipSuccess) return e;
+    const int BH = p.B * p.H, nsb = (p.NC + SBC - 1) / SBC;
+    const dim3 grid_key((unsigned)(8 * ((BH + 7) / 8) * nsb * SBC)), grid_key_far((unsigned)(8 * ((BH + 7) / 8) * nsb * (SBC / 2)));
+    hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, false>), grid_key, dim3(256), key_bytes, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, true>), grid_key_far, dim3(256), key_bytes, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const size_t ddp_bytes = DdpCfg<TIO, D>::smem_bytes;
-    if ((e = set_smem(&bwd_ddp_kernel<TIO, D>, ddp_bytes)) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D>), grid, dim3(256), ddp_bytes, st, p);
+    if ((e = set_smem(&bwd_ddp_kernel<TIO, D, false>, ddp_bytes)) != hipSuccess) return e;
+    if ((e = set_smem(&bwd_ddp_kernel<TIO, D, true>, ddp_bytes)) != hipSuccess) return e;
+    hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D, false>), grid, dim3(256), ddp_bytes, st, p);
+    if ((e = hipGetLastError()) != hipSuccess) return e;
+    const dim3 grid_sb((p.NC + SBC - 1) / SBC, p.B * p.H);
+    hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D, true>), grid_sb, dim3(256), ddp_bytes, st, p);
     return hipGetLastError();
 }
 
@@ -611,7 +693,7 @@ hipError_t launch_bwd_scan(const BwdParams& p, int d, int is_bf16, hipStream_t s
 hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream_t st) {
     const size_t es = is_bf16 ? 2 : 4, fe = is_bf16 ? 8 : 4;
     const size_t bytes = (size_t)(a.M + a.N) * (a.K + fe) * es;
-    dim3 grid(a.NC, BH);
+    dim3 grid(a.gridx, BH);
     hipError_t e;
     static bool attr_set[2] = {false, false};
     if (!attr_set[is_bf16 ? 1 : 0]) {

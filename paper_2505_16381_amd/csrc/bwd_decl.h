@@ -8,13 +8,16 @@ struct BwdParams {
     const void *q, *k, *v, *w, *beta, *o, *dO;
     const float* lse;
     const void *kt, *vk, *ktT, *dpt;   // per-chunk fragment tiles from the chunk transform
-    const void *xs, *xsT;              // per-pair query-state tiles from the states sweep
+    const void *kt2, *kt2T, *dpt2;     // second-level tiles: keys per chunk, -(I - P_superblock) per super-block
+    const void *xs, *xsT;              // per-(chunk, key block) query-state tiles from the states sweep
     void *doq, *doT;                   // per-chunk dO tiles (I/O type)
     void* gs;                          // per-pair adjoint-state tiles gT (rows b, contraction q): g(i,j-1) at slot (i,j)
     float *delta;             // [BH][Lp]
     float *lse2p;             // [BH][Lp]: lse * log2(e), zero past L
     float *dqb, *dkb, *dvp;   // [BH][Lp][d] fp32: dQb, dKb, dV (off-diagonal part)
     float *ddp;               // [BH][NC][d][d] fp32: ddP[a][b]
+    float *dk2;               // [BH][Lp][d] fp32: dKb2 (gradient of the second-level keys)
+    float *dchain;            // [BH][NC+1][d][d] fp32: chain of the second level's adjoint, entry c+1 for chunk c
     int B, H, L, NC;
     float scale;
 };
@@ -40,6 +43,7 @@ struct GemmArgs {
     float alpha;
     int mask;
     int NC, L;
+    int cmul, cadd, gridx;  // workgroup x handles chunk x * cmul + cadd (skipped if >= NC); gridx workgroups per head
 };
 
 struct DiagArgs {

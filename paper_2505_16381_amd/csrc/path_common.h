@@ -225,18 +225,34 @@ struct FwdParams {
     float scale;
     // Backward only (NULL in the forward), all in fragment order:
     //   per chunk:  ktT (rows c, contraction s) = Kb[s][c];  vk (rows s, contraction c) = V[s][c] (I/O type);
-    //   per pair (query chunk i, key chunk j < i), slot pair_slot(i,j):
-    //               xs  (rows q, contraction c) and xsT (rows c, contraction q): the query state of
-    //               chunk i as used against key chunk j
-    void *ktT, *vk, *xs, *xsT;
+    //               kt2T: the same arrangement of the second-level keys Kb2;
+    //   per super-block: dpt2 (rows a, contraction b) = -(I - P_superblock)[a][b];
+    //   per pair (query chunk i, key block), slot block_slot(i, c): xs (rows q, contraction c) and
+    //               xsT (rows c, contraction q): the query state of chunk i as used against the block.
+    void *ktT, *vk, *xs, *xsT, *kt2T, *dpt2;
     // Backward only: per-chunk matrices of the transform, row-major 64x64 (operand type) --
     // fm = F[t][t'], gktm[s][t'] = strictLower(W K^T)[t'][s], nm = N, aim = A^{-1},
-    // ytm[s][t] = Y[t][s]; utm [d][64]: utm[c][t] = U[t][c]; fp32: gm = W W^T, sdm[t][s] = Sd.
-    void *fm, *gktm, *nm, *aim, *ytm, *utm;
+    // ytm[s][t] = Y[t][s]; utm [d][64]: utm[c][t] = U[t][c]; fp32: gm = W W^T, sdm[t][s] = Sd;
+    // kbm [Lp][d]: boundary-adjusted keys Kb (rows past L zero); rm [d][d] per chunk: R_c of
+    // the second level (operand type).
+    void *fm, *gktm, *nm, *aim, *ytm, *utm, *kbm, *rm;
     float *gm, *sdm;
 };
 
-// slot of the (query chunk i, key chunk j < i) pair in the per-head state arrays
-__host__ __device__ __forceinline__ size_t pair_slot(int i, int j) { return (size_t)i * (i - 1) / 2 + j; }
+// Key blocks of the backward, for query chunk i (own super-block I = i / SBC): the chunks
+// SBC*I <= j < i one by one ("near"), and the super-blocks J < I as a whole ("far": the state is
+// the one at the super-block's right edge, the keys are the second-level keys).  Per head the
+// state arrays hold the near slots [0, NC*(SBC-1)) first, then the far slots.
+__host__ __device__ __forceinline__ size_t far_base(int i) {
+    const size_t I = (size_t)(i / SBC);
+    return (size_t)SBC * (I * (I - 1) / 2) + (size_t)(i % SBC) * I;
+}
+__host__ __device__ __forceinline__ size_t num_block_slots(int NC) { return (size_t)NC * (SBC - 1) + far_base(NC); }
+// slot of (query chunk i, block holding key chunk c < i)
+__host__ __device__ __forceinline__ size_t block_slot(int i, int c, int NC) {
+    const int jsb = (i / SBC) * SBC;
+    if (c >= jsb) return (size_t)i * (SBC - 1) + (c - jsb);
+    return (size_t)NC * (SBC - 1) + far_base(i) + (size_t)(c / SBC);
+}
 
 }  // namespace path

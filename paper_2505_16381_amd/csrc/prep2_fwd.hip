@@ -51,8 +51,33 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
         const Frag* k1 = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * (size_t)CHUNK * D);
         const Frag* dpn = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dp) + bhc * (size_t)D * D);    // (rows b, contr a) = -dP[a][b]
         Frag* k2 = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2) + bhc * (size_t)CHUNK * D);
+        Frag* k2T = p.kt2T ? reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2T) + bhc * (size_t)CHUNK * D) : nullptr;
+        if (p.rm) {      // backward only: R_c = I - E_c, row-major [a][b]
+            typedef typename Tr<T>::Vec4 TVec4;
+            T* rdst = reinterpret_cast<T*>(p.rm) + bhc * (size_t)D * D;
+#pragma unroll
+            for (int o = 0; o < NE; ++o) {
+                const int blk = wv + 4 * o, bb = blk / DB, ab = blk % DB;
+                const int a = 32 * ab + l32;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    TVec4 o4;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        const int b = 32 * bb + 8 * g + 4 * h + r;
+                        const float e = (c == clast) ? 0.f : Fm[o][4 * g + r];
+                        o4[r] = (T)((a == b ? 1.f : 0.f) - e);
+                    }
+                    *reinterpret_cast<TVec4*>(rdst + (size_t)a * D + 32 * bb + 8 * g + 4 * h) = o4;
+                }
+            }
+        }
         if (c == clast) {
             for (int idx = tid; idx < CHUNK * D / FE; idx += 256) k2[idx] = k1[idx];
+            if (k2T) {
+                const Frag* k1T = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.ktT) + bhc * (size_t)CHUNK * D);
+                for (int idx = tid; idx < CHUNK * D / FE; idx += 256) k2T[idx] = k1T[idx];
+            }
         } else {
             // Kb2^T[cc][s] = Kb^T[cc][s] - sum_b E[cc][b] Kb[s][b]   (registers rows cc, lane s)
 #pragma unroll
@@ -70,6 +95,13 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
                 }
 #pragma unroll
                 for (int s2 = 0; s2 < SPB; ++s2) k2[((size_t)sb2 * DS + cb * SPB + s2) * 64 + lane] = fr[s2];
+                if (k2T) {     // backward only: the arrangement (rows cc, contraction s)
+                    const f32x16 tr = transpose32<T>(fr, idf);      // rows s, lane cc
+                    Frag ft[SPB];
+                    pack_block<T>(tr, ft);
+#pragma unroll
+                    for (int s2 = 0; s2 < SPB; ++s2) k2T[((size_t)cb * (CHUNK / KW) + sb2 * SPB + s2) * 64 + lane] = ft[s2];
+                }
             }
         }
         // E^T <- E^T + dP^T - dP^T E^T   (registers rows b, lane a)
@@ -114,6 +146,16 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
         const int blk = wv + 4 * o, bb = blk / DB, ab = blk % DB;
         Frag fin[SPB];
         pack_block<T>(Fm[o], fin);                              // tile piece (rows a, contraction b)
+        if (p.dpt2) {      // backward only: -(I - P_superblock) in the arrangement (rows a, contraction b)
+            Frag* dt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dpt2) + ((size_t)bh * gridDim.x + sb) * (size_t)D * D);
+#pragma unroll
+            for (int s = 0; s < SPB; ++s) {
+                Frag ng;
+#pragma unroll
+                for (int e = 0; e < FE; ++e) ng[e] = (T)(-(float)fin[s][e]);
+                dt[((size_t)ab * DS + bb * SPB + s) * 64 + lane] = ng;
+            }
+        }
         f32x16 tr = transpose32<T>(fin, idf);                   // rows a, lane b
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) tr[jj] = -tr[jj];

@@ -346,6 +346,17 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             pack_block<T>(acc, fr);
 #pragma unroll
             for (int s2 = 0; s2 < SPB; ++s2) kdst[((size_t)sb * (D / KW) + cb * SPB + s2) * 64 + lane] = fr[s2];
+            if (p.kbm) {       // backward only: the same keys row-major [token][c]
+                typedef typename Tr<T>::Vec4 TVec4;
+                T* kb = reinterpret_cast<T*>(p.kbm) + (bhc * CHUNK + s) * (size_t)D + 32 * cb + 4 * h;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    TVec4 o4;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) o4[r] = (T)acc[4 * g + r];
+                    *reinterpret_cast<TVec4*>(kb + 8 * g) = o4;
+                }
+            }
         }
 #pragma unroll
         for (int i = 0; i < NB / 4; ++i) {

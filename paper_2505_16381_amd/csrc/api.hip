@@ -296,7 +296,10 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     //     ddP_c  -= R_c^T D_{c-1}
     //     D_c     = D_{c-1} (I - dP_c)^T + dKb2_c^T Kb_c          dP_c = W_c^T U_c
     //     dKb_c  += dKb2_c R_c
-    if (NC > SBC) {
+    if (NC > SBC && bf) {         // fused kernel (2-byte operand types)
+        SbChainArgs sa{base + ws.rm, base + ws.kbm, base + ws.utm, w, F(ws.dk2), F(ws.dchain), F(ws.ddp), dkb, L, NC};
+        ok = hip_ok(launch_bwd_sb_chain(sa, BH, d, st), "second-level adjoint");
+    } else if (NC > SBC) {        // the same chain as a sequence of batched products (fp32 operands)
         const long long dd = (long long)d * d, dd_bh = (long long)NC * dd, ch_bh = (long long)(NC + 1) * dd;
         float* dch = F(ws.dchain);
         float* t1 = F(ws.t1);

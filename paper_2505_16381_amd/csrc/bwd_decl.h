@@ -46,6 +46,19 @@ struct GemmArgs {
     int cmul, cadd, gridx;  // workgroup x handles chunk x * cmul + cadd (skipped if >= NC); gridx workgroups per head
 };
 
+// Adjoint of the second blocking level, one workgroup per (super-block, head).
+struct SbChainArgs {
+    const void* rm;      // [BH][NC][d][d] operand type: R_c row-major
+    const void* kbm;     // [BH][Lp][d] operand type: Kb
+    const void* utm;     // [BH][NC][d][64] operand type: utm[c][t] = U[t][c]
+    const void* w;       // [BH][L][d] I/O type
+    const float* dk2;    // [BH][Lp][d]
+    const float* dchain; // [BH][NC+1][d][d]: entry 4J = gradient of P_superblock J
+    float* ddp;          // [BH][NC][d][d]   (updated)
+    float* dkb;          // [BH][Lp][d]      (updated)
+    int L, NC;
+};
+
 struct DiagArgs {
     const float *sdm, *dpd, *delta, *lse;
     float *pd, *dsd;
@@ -66,6 +79,7 @@ struct OutArgs {
 
 hipError_t launch_bwd_scan(const BwdParams& p, int d, int is_bf16, hipStream_t st);
 hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream_t st);
+hipError_t launch_bwd_sb_chain(const SbChainArgs& a, int BH, int d, hipStream_t st);    // 2-byte operand types only
 hipError_t launch_bwd_diag(const DiagArgs& a, int BH, hipStream_t st);
 hipError_t launch_bwd_beta(const BetaArgs& a, int BH, int is_bf16, hipStream_t st);
 hipError_t launch_bwd_store(const OutArgs& a, int BH, int is_bf16, hipStream_t st);

@@ -362,30 +362,53 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
         for (int qq = 0; qq < CPW; ++qq) {
             const int qh = FAR ? qq : (wv >> 1);
             f32x16 S = zero16(), dP = zero16();                    // rows q (half qh), lane s
+            // operand fragments are fetched in batches ahead of the products that use them
 #pragma unroll
-            for (int s = 0; s < DS; ++s) {
-                S = Tr<T>::mma(sX[(qh * DS + s) * 64 + lane], Kb[s], S);
-                dP = Tr<TIO>::mma(sDQ[(qh * DS + s) * 64 + lane], Vb[s], dP);
+            for (int s0 = 0; s0 < DS; s0 += 4) {
+                Frag xa[4];
+                FragV da[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { xa[u] = sX[(qh * DS + s0 + u) * 64 + lane]; da[u] = sDQ[(qh * DS + s0 + u) * 64 + lane]; }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    S = Tr<T>::mma(xa[u], Kb[s0 + u], S);
+                    dP = Tr<TIO>::mma(da[u], Vb[s0 + u], dP);
+                }
+            }
+            // Rows past L need no mask: their state, dO and delta are zero and lse2p is zero, so
+            // P = 1 meets dO = 0 in dV and dS = P (0 - 0) = 0.
+            f32x4 ls[4], dls[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                ls[g] = *reinterpret_cast<const f32x4*>(lse2 + 32 * qh + 8 * g + 4 * h);
+                dls[g] = *reinterpret_cast<const f32x4*>(dl + 32 * qh + 8 * g + 4 * h);
             }
             f32x16 Pm;
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj) {
-                const int q = 32 * qh + acc_row(jj, h);
-                const float P = (i * CHUNK + q < L) ? __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -lse2[q])) : 0.f;
+                const float P = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -ls[jj >> 2][jj & 3]));
                 Pm[jj] = P;
-                S[jj] = P * (dP[jj] - dl[q]) * p.scale;
+                S[jj] = P * (dP[jj] - dls[jj >> 2][jj & 3]) * p.scale;
             }
             FragV Pb[SPB];
             Frag dSb[SPB];
             pack_block<TIO>(Pm, Pb);
             pack_block<T>(S, dSb);
 #pragma unroll
-            for (int b = 0; b < DB; ++b)
+            for (int b = 0; b < DB; b += 2) {
+                FragV ta[2 * SPB];
+                Frag tb[2 * SPB];
 #pragma unroll
-                for (int s = 0; s < SPB; ++s) {
-                    dVt[b] = Tr<TIO>::mma(sDT[(b * QS + qh * SPB + s) * 64 + lane], Pb[s], dVt[b]);
-                    dKt[b] = Tr<T>::mma(sXT[(b * QS + qh * SPB + s) * 64 + lane], dSb[s], dKt[b]);
+                for (int u = 0; u < 2 * SPB; ++u) {
+                    ta[u] = sDT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
+                    tb[u] = sXT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
                 }
+#pragma unroll
+                for (int u = 0; u < 2 * SPB; ++u) {
+                    dVt[b + u / SPB] = Tr<TIO>::mma(ta[u], Pb[u % SPB], dVt[b + u / SPB]);
+                    dKt[b + u / SPB] = Tr<T>::mma(tb[u], dSb[u % SPB], dKt[b + u / SPB]);
+                }
+            }
         }
     }
     if (FAR) {

@@ -26,7 +26,8 @@ template <typename TIO, int D> struct Prep2Cfg {
     static constexpr size_t smem_bytes = (size_t)D * D * sizeof(T);      // operand copy of E (fragment order)
 };
 
-template <typename TIO, int D>
+// BWD: also write the backward-only outputs (compile-time, so the forward carries none of that code).
+template <typename TIO, int D, bool BWD>
 __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
     using T = typename Compute<TIO>::type;
     using Frag = typename Tr<T>::Frag;
@@ -51,8 +52,8 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
         const Frag* k1 = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * (size_t)CHUNK * D);
         const Frag* dpn = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dp) + bhc * (size_t)D * D);    // (rows b, contr a) = -dP[a][b]
         Frag* k2 = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2) + bhc * (size_t)CHUNK * D);
-        Frag* k2T = p.kt2T ? reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2T) + bhc * (size_t)CHUNK * D) : nullptr;
-        if (p.rm) {      // backward only: R_c = I - E_c, row-major [a][b]
+        Frag* k2T = (BWD && p.kt2T) ? reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2T) + bhc * (size_t)CHUNK * D) : nullptr;
+        if (BWD && p.rm) {      // backward only: R_c = I - E_c, row-major [a][b]
             typedef typename Tr<T>::Vec4 TVec4;
             T* rdst = reinterpret_cast<T*>(p.rm) + bhc * (size_t)D * D;
 #pragma unroll
@@ -146,7 +147,7 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
         const int blk = wv + 4 * o, bb = blk / DB, ab = blk % DB;
         Frag fin[SPB];
         pack_block<T>(Fm[o], fin);                              // tile piece (rows a, contraction b)
-        if (p.dpt2) {      // backward only: -(I - P_superblock) in the arrangement (rows a, contraction b)
+        if (BWD && p.dpt2) {      // backward only: -(I - P_superblock) in the arrangement (rows a, contraction b)
             Frag* dt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dpt2) + ((size_t)bh * gridDim.x + sb) * (size_t)D * D);
 #pragma unroll
             for (int s = 0; s < SPB; ++s) {
@@ -166,20 +167,24 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
     }
 }
 
-template <typename TIO, int D>
-hipError_t launch_prep2_fwd_t(const FwdParams& p, hipStream_t stream) {
+template <typename TIO, int D, bool BWD>
+hipError_t launch_prep2_fwd_b(const FwdParams& p, hipStream_t stream) {
     using C = Prep2Cfg<TIO, D>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep2_fwd_kernel<TIO, D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep2_fwd_kernel<TIO, D, BWD>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid((p.NC + SBC - 1) / SBC, p.B * p.H);
     const size_t bytes = C::smem_bytes;
-    hipLaunchKernelGGL((prep2_fwd_kernel<TIO, D>), grid, dim3(256), bytes, stream, p);
+    hipLaunchKernelGGL((prep2_fwd_kernel<TIO, D, BWD>), grid, dim3(256), bytes, stream, p);
     return hipGetLastError();
+}
+template <typename TIO, int D>
+hipError_t launch_prep2_fwd_t(const FwdParams& p, hipStream_t stream) {
+    return p.rm ? launch_prep2_fwd_b<TIO, D, true>(p, stream) : launch_prep2_fwd_b<TIO, D, false>(p, stream);
 }
 
 hipError_t launch_prep2_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {

@@ -53,7 +53,9 @@ template <typename TIO, int D> struct PrepCfg {
     static constexpr size_t smem_bytes = off_xf_bytes + (size_t)CHUNK * LDA * 4;
 };
 
-template <typename TIO, int D>
+// BWD: also write the backward-only outputs (all of them; their pointers are set).  A compile-time
+// switch, so that the forward's instantiation carries none of that code.
+template <typename TIO, int D, bool BWD>
 __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     using C = PrepCfg<TIO, D>;
     using T = typename C::T;
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         for (int j = 0; j < 16; ++j) {
             const int t = 32 * bi + acc_row(j, h);
             Af[t * LDA + s] = (s < t) ? bs[t] * acc[j] : 0.f;
-            if (p.gm) p.gm[bhc * 4096 + t * 64 + s] = acc[j];
+            if (BWD && p.gm) p.gm[bhc * 4096 + t * 64 + s] = acc[j];
         }
     }
     // F block: rows t (Q), cols t' (W); keep t' <= t.
@@ -240,7 +242,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         const int t = idx >> 6, c = idx & 63;
         const float x = Xf[t * LDA + c];
         Nt[t * LDC + c] = (T)(x * bs[c]);
-        if (p.aim) reinterpret_cast<T*>(p.aim)[bhc * 4096 + idx] = (T)x;
+        if (BWD && p.aim) reinterpret_cast<T*>(p.aim)[bhc * 4096 + idx] = (T)x;
     }
     __syncthreads();
 
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     __syncthreads();
 
     // ---- phase 4: outputs -----------------------------------------------------------
-    if (p.fm) {   // backward: keep the chunk's matrices (row-major, operand type)
+    if (BWD && p.fm) {   // backward: keep the chunk's matrices (row-major, operand type)
         T* fm = reinterpret_cast<T*>(p.fm) + bhc * 4096;
         T* gk = reinterpret_cast<T*>(p.gktm) + bhc * 4096;
         T* nm = reinterpret_cast<T*>(p.nm) + bhc * 4096;
@@ -303,7 +305,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) v4[r] = accS[4 * g + r] - corr[4 * g + r];
             *reinterpret_cast<f32x4*>(dst + (g * 64 + lane) * 4) = v4;
-            if (p.sdm) *reinterpret_cast<f32x4*>(p.sdm + bhc * 4096 + (32 * bj + l32) * 64 + 32 * bi + 8 * g + 4 * h) = v4;
+            if (BWD && p.sdm) *reinterpret_cast<f32x4*>(p.sdm + bhc * 4096 + (32 * bj + l32) * 64 + 32 * bi + 8 * g + 4 * h) = v4;
         }
     }
     // (b) -dP tile (rows = output column b of dP, contraction = a): acc rows a, cols b.
@@ -346,7 +348,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             pack_block<T>(acc, fr);
 #pragma unroll
             for (int s2 = 0; s2 < SPB; ++s2) kdst[((size_t)sb * (D / KW) + cb * SPB + s2) * 64 + lane] = fr[s2];
-            if (p.kbm) {       // backward only: the same keys row-major [token][c]
+            if (BWD && p.kbm) {       // backward only: the same keys row-major [token][c]
                 typedef typename Tr<T>::Vec4 TVec4;
                 T* kb = reinterpret_cast<T*>(p.kbm) + (bhc * CHUNK + s) * (size_t)D + 32 * cb + 4 * h;
 #pragma unroll
@@ -395,7 +397,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
 #pragma unroll
             for (int s2 = 0; s2 < SPB; ++s2) vdst[(((size_t)sb * (D / 32) + cb) * SPB + s2) * 64 + lane] = fr[s2];   // [key half][d block][slab]
         }
-        if (p.dpt) {
+        if (BWD && p.dpt) {
             // -dP in the transposed arrangement (rows c, contraction b) = -dP[c][b]: accumulate with rows b,
             // lane c.  Read by the backward's adjoint scan.
             Frag* pdst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dpt) + bhc * (size_t)D * D);
@@ -413,7 +415,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
                 for (int s2 = 0; s2 < SPB; ++s2) pdst[((size_t)cb * (D / KW) + bb * SPB + s2) * 64 + lane] = fr[s2];
             }
         }
-        if (p.ktT) {
+        if (BWD && p.ktT) {
             // ---- backward-only tiles ------------------------------------------------------------
             constexpr int QS = CHUNK / KW;
             // ktT (rows c, contraction s) = Kb[s][c]: accumulate with rows s, lane c
@@ -455,20 +457,24 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     }
 }
 
-template <typename T, int D>
-hipError_t launch_prep_fwd_t(const FwdParams& p, hipStream_t stream) {
+template <typename T, int D, bool BWD>
+hipError_t launch_prep_fwd_b(const FwdParams& p, hipStream_t stream) {
     using C = PrepCfg<T, D>;
     static_assert(sizeof(typename C::T) == sizeof(T), "tile sizes assume equal operand and I/O width");
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep_fwd_kernel<T, D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep_fwd_kernel<T, D, BWD>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.NC, p.B * p.H);
-    hipLaunchKernelGGL((prep_fwd_kernel<T, D>), grid, dim3(256), C::smem_bytes, stream, p);
+    hipLaunchKernelGGL((prep_fwd_kernel<T, D, BWD>), grid, dim3(256), C::smem_bytes, stream, p);
     return hipGetLastError();
+}
+template <typename T, int D>
+hipError_t launch_prep_fwd_t(const FwdParams& p, hipStream_t stream) {
+    return p.fm ? launch_prep_fwd_b<T, D, true>(p, stream) : launch_prep_fwd_b<T, D, false>(p, stream);
 }
 
 hipError_t launch_prep_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {

@@ -21,6 +21,8 @@
 // transposed form, streamed operands are fragment-order tiles (written by prep, the
 // states sweep and bwd_dotile), and the transposes that a change of contraction axis
 // needs are taken through the matrix unit (product with an identity operand).
+#include <type_traits>
+
 #include "path_common.h"
 #include "bwd_decl.h"
 
@@ -203,10 +205,18 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb) {
             f32x16 S = zero16(), dP = zero16();
+            // operand fragments are fetched in batches ahead of the products that use them
 #pragma unroll
-            for (int s = 0; s < DS; ++s) {
-                S = Tr<T>::mma(sK[(kb * DS + s) * 64 + lane], Xb[s], S);
-                dP = Tr<TIO>::mma(sV[(kb * DS + s) * 64 + lane], dOb[s], dP);
+            for (int s0 = 0; s0 < DS; s0 += 4) {
+                Frag ka[4];
+                FragV va[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { ka[u] = sK[(kb * DS + s0 + u) * 64 + lane]; va[u] = sV[(kb * DS + s0 + u) * 64 + lane]; }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    S = Tr<T>::mma(ka[u], Xb[s0 + u], S);
+                    dP = Tr<TIO>::mma(va[u], dOb[s0 + u], dP);
+                }
             }
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj) {
@@ -216,13 +226,25 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
             pack_block<T>(S, dSb + kb * SPB);
         }
 #pragma unroll
-        for (int b = 0; b < DB; ++b) {
+        for (int b = 0; b < DB; b += 2) {
+            Frag ta[2 * QS];
 #pragma unroll
-            for (int s = 0; s < QS; ++s) Gm[b] = Tr<T>::mma(sKT[(b * QS + s) * 64 + lane], dSb[s], Gm[b]);
-            if (j > 0 && first) {
+            for (int u = 0; u < 2 * QS; ++u) ta[u] = sKT[((b + u / QS) * QS + u % QS) * 64 + lane];
 #pragma unroll
-                for (int s = 0; s < DS; ++s) Gm[b] = Tr<T>::mma(sDP[(b * DS + s) * 64 + lane], Gb[s], Gm[b]);
-            }
+            for (int u = 0; u < 2 * QS; ++u) Gm[b + u / QS] = Tr<T>::mma(ta[u], dSb[u % QS], Gm[b + u / QS]);
+        }
+        if (j > 0 && first) {
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int s0 = 0; s0 < DS; s0 += 8) {
+                    constexpr int NB8 = DS < 8 ? DS : 8;
+                    Frag pa[NB8];
+#pragma unroll
+                    for (int u = 0; u < NB8; ++u) pa[u] = sDP[(b * DS + s0 + u) * 64 + lane];
+#pragma unroll
+                    for (int u = 0; u < NB8; ++u) Gm[b] = Tr<T>::mma(pa[u], Gb[s0 + u], Gm[b]);
+                }
         }
 #pragma unroll
         for (int b = 0; b < DB; ++b) pack_block<T>(Gm[b], Gb + b * SPB);
@@ -510,9 +532,11 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
 #pragma unroll
             for (int o = 0; o < NOWN; ++o) {
                 const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
+                Frag fa[QS], fb[QS];
 #pragma unroll
-                for (int s = 0; s < QS; ++s)
-                    acc[o] = Tr<T>::mma(xt[(ab * QS + s) * 64 + lane], gt[(bb * QS + s) * 64 + lane], acc[o]);
+                for (int s = 0; s < QS; ++s) { fa[s] = xt[(ab * QS + s) * 64 + lane]; fb[s] = gt[(bb * QS + s) * 64 + lane]; }
+#pragma unroll
+                for (int s = 0; s < QS; ++s) acc[o] = Tr<T>::mma(fa[s], fb[s], acc[o]);
             }
         }
     }
@@ -602,7 +626,13 @@ __global__ __launch_bounds__(256) void batched_gemm_kernel(GemmArgs a) {
         const T* ap = As + (32 * mb + l32) * ld + FE * h;
         const T* bp = Bs + (32 * cb + l32) * ld + FE * h;
         f32x16 acc = zero16();
-        for (int k0 = 0; k0 < a.K; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
+        for (int k0 = 0; k0 < a.K; k0 += 4 * KW) {        // K is a multiple of 64
+            typename Tr<T>::Frag fa[4], fb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { fa[u] = ld_frag<T>(ap + k0 + u * KW); fb[u] = ld_frag<T>(bp + k0 + u * KW); }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = Tr<T>::mma(fa[u], fb[u], acc);
+        }
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
             const int m = 32 * mb + acc_row(jj, h), n = 32 * cb + l32;
@@ -650,12 +680,23 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
     const size_t Lp = (size_t)NC * CHUNK;
 
     // 32x32 block (mb, nb) of A B^T, operands in LDS with pitch ld, K contraction indices
-    auto block = [&](const T* As, const T* Bs, int ld, int mb, int nb, int K, f32x16 acc) {
+    // (compile-time); fragments are fetched four slabs at a time ahead of their products
+    auto block = [&](const T* As, const T* Bs, int ld, int mb, int nb, auto kc, f32x16 acc) {
+        constexpr int K = decltype(kc)::value;
         const T* ap = As + (32 * mb + l32) * ld + FE * h;
         const T* bp = Bs + (32 * nb + l32) * ld + FE * h;
-        for (int k0 = 0; k0 < K; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
+#pragma unroll
+        for (int k0 = 0; k0 < K; k0 += 4 * KW) {
+            typename Tr<T>::Frag fa[4], fb[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) { fa[u] = ld_frag<T>(ap + k0 + u * KW); fb[u] = ld_frag<T>(bp + k0 + u * KW); }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) acc = Tr<T>::mma(fa[u], fb[u], acc);
+        }
         return acc;
     };
+    constexpr std::integral_constant<int, D> KD{};
+    constexpr std::integral_constant<int, CHUNK> KC{};
 
     // D: block o of this wave = (rows a-block ab, lane b-block bb), blk = wv + 4*o
     f32x16 Dacc[NOWN];
@@ -695,7 +736,7 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
 #pragma unroll
             for (int o = 0; o < NOWN; ++o) {
                 const int blk = wv + 4 * o, xb = blk / DB, bb = blk % DB;
-                const f32x16 acc = block(B0, B1, LD, xb, bb, D, zero16());
+                const f32x16 acc = block(B0, B1, LD, xb, bb, KD, zero16());
 #pragma unroll
                 for (int jj = 0; jj < 16; ++jj) dst[(size_t)(32 * xb + acc_row(jj, h)) * D + 32 * bb + l32] -= acc[jj];
             }
@@ -705,7 +746,7 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
             float* dst = a.dkb + (bhc * CHUNK) * (size_t)D;
             for (int blk = wv; blk < 2 * DB; blk += 4) {
                 const int sb = blk / DB, bb = blk % DB;
-                const f32x16 acc = block(B2, B0, LD, sb, bb, D, zero16());
+                const f32x16 acc = block(B2, B0, LD, sb, bb, KD, zero16());
 #pragma unroll
                 for (int jj = 0; jj < 16; ++jj) dst[(size_t)(32 * sb + acc_row(jj, h)) * D + 32 * bb + l32] += acc[jj];
             }
@@ -728,7 +769,7 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
 #pragma unroll
         for (int i = 0; i < 2 * DB / 4; ++i) {
             const int blk = wv + 4 * i, ab = blk >> 1, tb = blk & 1;
-            t1[i] = block(B1, B3, LD, ab, tb, D, zero16());          // rows a, lane t
+            t1[i] = block(B1, B3, LD, ab, tb, KD, zero16());          // rows a, lane t
         }
         __syncthreads();                                             // B1, B3 are free
 #pragma unroll
@@ -749,8 +790,8 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) {
             const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
-            Dacc[o] = block(B0, B2, LDC, ab, bb, CHUNK, Dacc[o]);    // - T1 W
-            Dacc[o] = block(B3, B1, LDC, ab, bb, CHUNK, Dacc[o]);    // + dKb2^T Kb
+            Dacc[o] = block(B0, B2, LDC, ab, bb, KC, Dacc[o]);    // - T1 W
+            Dacc[o] = block(B3, B1, LDC, ab, bb, KC, Dacc[o]);    // + dKb2^T Kb
         }
     }
 }

@@ -106,7 +106,13 @@ __global__ __launch_bounds__(256) void bwd_states_kernel(FwdParams p) {
 #pragma unroll
             for (int b = 0; b < DB; ++b)
 #pragma unroll
-                for (int s = 0; s < DS; ++s) Xm[b] = Tr<T>::mma(tp[(b * DS + s) * 64 + lane], Xb[s], Xm[b]);
+                for (int s0 = 0; s0 < DS; s0 += 4) {
+                    Frag pa[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) pa[u] = tp[(b * DS + s0 + u) * 64 + lane];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) Xm[b] = Tr<T>::mma(pa[u], Xb[s0 + u], Xm[b]);
+                }
 #pragma unroll
             for (int b = 0; b < DB; ++b) pack_block<T>(Xm[b], Xb + b * SPB);
         }

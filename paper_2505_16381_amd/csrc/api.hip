@@ -267,7 +267,6 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
 
     bool ok = true;
     int cmul = 1, cadd = 0;          // which chunks the following products run on: x * cmul + cadd
-    enum { OUT_C64 = 0, OUT_TOK = 1, OUT_DD = 2, OUT_DD1 = 3, OUT_D64 = 4 };
     auto gemm = [&](float* C, int tokC, const float* Cin, MatRef A, MatRef Bm, int M, int N, int K, float alpha, int mask) {
         if (!ok) return;
         GemmArgs a;
@@ -326,41 +325,55 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
         cmul = 1; cadd = 0;
     }
 
-    // diagonal block: dPd = dO V^T, then P and dSd
-    gemm(dpd, false, nullptr, user_n(d_o), user_n(v), 64, 64, d, 1.f, MASK_NONE);
-    if (ok) {
-        DiagArgs da{fp.sdm, dpd, bp.delta, lse, pd, dsd, L, NC, scale};
-        ok = hip_ok(launch_bwd_diag(da, BH, st), "diagonal block adjoint");
-    }
-    gemm(dvp, true, dvp, chunk_t(pd, EL_F32), user_t(d_o), 64, d, 64, 1.f, MASK_NONE);          // dV += P^T dO
-    gemm(dqf, true, dqb, chunk_n(dsd, EL_F32), user_t(k), 64, d, 64, 1.f, MASK_NONE);           // dQ = dQb + dSd K
-    gemm(dkf, true, dkb, chunk_t(dsd, EL_F32), user_t(q), 64, d, 64, 1.f, MASK_NONE);           // dK = dKb + dSd^T Q
-    gemm(df, false, nullptr, chunk_n(dsd, EL_F32), chunk_t(ytm, EL_OP), 64, 64, 64, -1.f, MASK_TRIL);   // dF = -dSd Y^T
-    gemm(df, false, df, tokws_n(dqb), U_rows, 64, 64, d, -1.f, MASK_TRIL);                              //      - dQb U^T
-    gemm(dy, false, nullptr, chunk_t(fm, EL_OP), chunk_t(dsd, EL_F32), 64, 64, 64, -1.f, MASK_NONE);    // dY = -F^T dSd
-    gemm(dy, false, dy, user_n(w), tokws_n(dkb), 64, 64, d, -1.f, MASK_NONE);                            //      - W dKb^T
-    gemm(du, true, nullptr, chunk_t(fm, EL_OP), tokws_t(dqb), 64, d, 64, -1.f, MASK_NONE);              // dU = -F^T dQb
-    gemm(du, true, du, user_n(w), ddp_kfirst, 64, d, d, 1.f, MASK_NONE);                                 //      + W ddP
-    gemm(dn, false, nullptr, chunk_n(dy, EL_F32), chunk_t(gktm, EL_OP), 64, 64, 64, 1.f, MASK_NONE);    // dN = dY Gk^T
-    gemm(dn, false, dn, tokws_n(du), user_n(w), 64, 64, d, 1.f, MASK_NONE);                              //      + dU W^T
-    gemm(dgk, false, nullptr, chunk_t(nm, EL_OP), chunk_t(dy, EL_F32), 64, 64, 64, 1.f, MASK_SLOWER);   // dGk = sl(N^T dY)
-    gemm(rr, false, nullptr, chunk_t(aim, EL_OP), chunk_t(dn, EL_F32), 64, 64, 64, 1.f, MASK_NONE);     // R = A^-T dN
-    gemm(mm, false, nullptr, chunk_n(rr, EL_F32), chunk_n(nm, EL_OP), 64, 64, 64, -1.f, MASK_SLOWER);   // M = sl(-R N^T)
-    if (ok) {
-        BetaArgs ba{rr, mm, fp.gm, beta, dgs, dbf, L, NC};
-        ok = hip_ok(launch_bwd_beta(ba, BH, bf, st), "beta adjoint");
-    }
-    gemm(dwf, true, nullptr, chunk_t(ytm, EL_OP), tokws_t(dkb), 64, d, 64, -1.f, MASK_NONE);            // dW = -Y dKb
-    gemm(dwf, true, dwf, U_rows, ddp_nfirst, 64, d, d, 1.f, MASK_NONE);                                  //    + U ddP^T
-    gemm(dwf, true, dwf, chunk_t(df, EL_F32), user_t(q), 64, d, 64, 1.f, MASK_NONE);                     //    + dF^T Q
-    gemm(dwf, true, dwf, chunk_n(dgk, EL_F32), user_t(k), 64, d, 64, 1.f, MASK_NONE);                    //    + dGk K
-    gemm(dwf, true, dwf, chunk_t(nm, EL_OP), tokws_t(du), 64, d, 64, 1.f, MASK_NONE);                    //    + N^T dU
-    gemm(dwf, true, dwf, chunk_n(dgs, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE);                    //    + (dG+dG^T) W
-    gemm(dqf, true, dqf, chunk_n(df, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE);                     // dQ += dF W
-    gemm(dkf, true, dkf, chunk_t(dgk, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE);                    // dK += dGk^T W
-    if (ok) {
-        OutArgs oa{dqf, dkf, dvp, dwf, dbf, dq, dk, dv, dw, dbeta, L, NC, d};
-        ok = hip_ok(launch_bwd_store(oa, BH, bf, st), "gradient store");
-    }
+    // 5b. adjoint of the chunk transform: one fused kernel runs this list per (chunk, head).
+    // Chains of products that add into the same result are consecutive.
+    if (!ok) return PATH_ERR_HIP;
+    ChunkProgram pr = {};
+    pr.L = L; pr.NC = NC;
+    bool chain_open = false;
+    // one product: C (+)= alpha A B^T; `first` opens a chain (from Cin or zero), `last` masks and writes C
+    auto prod = [&](float* C, int out, const float* Cin, MatRef A, MatRef Bm, int M, int N, int K, float alpha, int mask,
+                    bool first, bool last) {
+        ChunkOp& o = pr.ops[pr.n++];
+        o.kind = OP_PRODUCT; o.A = A; o.B = Bm; o.C = C; o.Cin = Cin;
+        if (out == OUT_TOK) { o.c_bh = t_bh; o.c_ch = t_ch; o.crs = d; }
+        else { o.c_bh = c_bh; o.c_ch = c_ch; o.crs = 64; }
+        o.M = (short)M; o.N = (short)N; o.K = (short)K; o.alpha = alpha; o.mask = (unsigned char)mask;
+        o.first = first; o.last = last;
+        chain_open = !last;
+    };
+    auto special = [&](int kind) { pr.ops[pr.n++].kind = (unsigned char)kind; };
+    pr.diag = DiagArgs{fp.sdm, dpd, bp.delta, lse, pd, dsd, L, NC, scale};
+    pr.beta = BetaArgs{rr, mm, fp.gm, beta, dgs, dbf, L, NC};
+    pr.out = OutArgs{dqf, dkf, dvp, dwf, dbf, dq, dk, dv, dw, dbeta, L, NC, d};
+
+    prod(dpd, OUT_C64, nullptr, user_n(d_o), user_n(v), 64, 64, d, 1.f, MASK_NONE, true, true);              // dPd = dO V^T
+    special(OP_DIAG);                                                                                          // P, dSd
+    prod(dvp, OUT_TOK, dvp, chunk_t(pd, EL_F32), user_t(d_o), 64, d, 64, 1.f, MASK_NONE, true, true);         // dV += P^T dO
+    prod(dqf, OUT_TOK, dqb, chunk_n(dsd, EL_F32), user_t(k), 64, d, 64, 1.f, MASK_NONE, true, true);          // dQ = dQb + dSd K
+    prod(dkf, OUT_TOK, dkb, chunk_t(dsd, EL_F32), user_t(q), 64, d, 64, 1.f, MASK_NONE, true, true);          // dK = dKb + dSd^T Q
+    prod(df, OUT_C64, nullptr, chunk_n(dsd, EL_F32), chunk_t(ytm, EL_OP), 64, 64, 64, -1.f, MASK_TRIL, true, false);   // dF = tril(-dSd Y^T
+    prod(df, OUT_C64, nullptr, tokws_n(dqb), U_rows, 64, 64, d, -1.f, MASK_TRIL, false, true);                         //          - dQb U^T)
+    prod(dy, OUT_C64, nullptr, chunk_t(fm, EL_OP), chunk_t(dsd, EL_F32), 64, 64, 64, -1.f, MASK_NONE, true, false);    // dY = -F^T dSd
+    prod(dy, OUT_C64, nullptr, user_n(w), tokws_n(dkb), 64, 64, d, -1.f, MASK_NONE, false, true);                      //      - W dKb^T
+    prod(du, OUT_TOK, nullptr, chunk_t(fm, EL_OP), tokws_t(dqb), 64, d, 64, -1.f, MASK_NONE, true, false);             // dU = -F^T dQb
+    prod(du, OUT_TOK, nullptr, user_n(w), ddp_kfirst, 64, d, d, 1.f, MASK_NONE, false, true);                          //      + W ddP
+    prod(dn, OUT_C64, nullptr, chunk_n(dy, EL_F32), chunk_t(gktm, EL_OP), 64, 64, 64, 1.f, MASK_NONE, true, false);    // dN = dY Gk^T
+    prod(dn, OUT_C64, nullptr, tokws_n(du), user_n(w), 64, 64, d, 1.f, MASK_NONE, false, true);                        //      + dU W^T
+    prod(dgk, OUT_C64, nullptr, chunk_t(nm, EL_OP), chunk_t(dy, EL_F32), 64, 64, 64, 1.f, MASK_SLOWER, true, true);    // dGk = sl(N^T dY)
+    prod(rr, OUT_C64, nullptr, chunk_t(aim, EL_OP), chunk_t(dn, EL_F32), 64, 64, 64, 1.f, MASK_NONE, true, true);      // R = A^-T dN
+    prod(mm, OUT_C64, nullptr, chunk_n(rr, EL_F32), chunk_n(nm, EL_OP), 64, 64, 64, -1.f, MASK_SLOWER, true, true);    // M = sl(-R N^T)
+    special(OP_BETA);                                                                                          // dGs, dbeta
+    prod(dwf, OUT_TOK, nullptr, chunk_t(ytm, EL_OP), tokws_t(dkb), 64, d, 64, -1.f, MASK_NONE, true, false);           // dW = -Y dKb
+    prod(dwf, OUT_TOK, nullptr, U_rows, ddp_nfirst, 64, d, d, 1.f, MASK_NONE, false, false);                           //    + U ddP^T
+    prod(dwf, OUT_TOK, nullptr, chunk_t(df, EL_F32), user_t(q), 64, d, 64, 1.f, MASK_NONE, false, false);              //    + dF^T Q
+    prod(dwf, OUT_TOK, nullptr, chunk_n(dgk, EL_F32), user_t(k), 64, d, 64, 1.f, MASK_NONE, false, false);             //    + dGk K
+    prod(dwf, OUT_TOK, nullptr, chunk_t(nm, EL_OP), tokws_t(du), 64, d, 64, 1.f, MASK_NONE, false, false);             //    + N^T dU
+    prod(dwf, OUT_TOK, nullptr, chunk_n(dgs, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE, false, true);              //    + (dG+dG^T) W
+    prod(dqf, OUT_TOK, dqf, chunk_n(df, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE, true, true);           // dQ += dF W
+    prod(dkf, OUT_TOK, dkf, chunk_t(dgk, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE, true, true);          // dK += dGk^T W
+    special(OP_STORE);                                                                                         // to the I/O dtype
+    if (chain_open || pr.n > MAX_CHUNK_OPS) return PATH_ERR_HIP;
+    ok = hip_ok(launch_chunk_adjoint(pr, BH, bf, st), "chunk-transform adjoint");
     return ok ? PATH_OK : PATH_ERR_HIP;
 }

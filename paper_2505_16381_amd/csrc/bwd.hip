@@ -119,8 +119,13 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
 
     const int BH = p.B * p.H, L = p.L, NC = p.NC;
     const int ntiles = (NC + 1) / 2;
-    const int tile = ntiles - 1 - (int)(blockIdx.x / BH);
-    const int bh = blockIdx.x % BH;
+    // XCD-aware numbering: workgroup n runs on XCD n % 8; that XCD takes heads xcd, xcd+8, ... one
+    // after the other, all tiles of a head together (heaviest first).  They walk the key chunks
+    // from 0 upwards at the same pace, so each tile is fetched once per head into that XCD's L2.
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int bh = (slot / ntiles) * 8 + xcd;
+    const int tile = ntiles - 1 - slot % ntiles;
+    if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
     const bool active = cq < NC;
@@ -561,7 +566,7 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
 // elements per thread along whichever index is contiguous in memory (one 16/32-byte load).
 template <typename TIO, typename E>
 __device__ __forceinline__ void stage_mat_t(const MatRef& r, typename Compute<TIO>::type* dst, int ld, int R, int K,
-                                            long long base, int ntok, int tid) {
+                                            long long base, int ntok, int tid, float mul = 1.f) {
     typedef typename Compute<TIO>::type T;
     const E* src = reinterpret_cast<const E*>(r.p) + base;
     typedef E Vec8 __attribute__((ext_vector_type(8)));
@@ -575,7 +580,7 @@ __device__ __forceinline__ void stage_mat_t(const MatRef& r, typename Compute<TI
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const bool ok = row_ok && (r.tok != TOK_K || k0 + e < ntok);
-                dst[m * ld + k0 + e] = ok ? (T)(float)v[e] : (T)0.f;
+                dst[m * ld + k0 + e] = ok ? (T)((float)v[e] * mul) : (T)0.f;
             }
         }
     } else {                               // row index contiguous (rs == 1)
@@ -588,7 +593,7 @@ __device__ __forceinline__ void stage_mat_t(const MatRef& r, typename Compute<TI
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const bool ok = k_ok && (r.tok != TOK_ROW || m0 + e < ntok);
-                dst[(m0 + e) * ld + k] = ok ? (T)(float)v[e] : (T)0.f;
+                dst[(m0 + e) * ld + k] = ok ? (T)((float)v[e] * mul) : (T)0.f;
             }
         }
     }
@@ -596,13 +601,13 @@ __device__ __forceinline__ void stage_mat_t(const MatRef& r, typename Compute<TI
 
 template <typename TIO>
 __device__ __forceinline__ void stage_mat(const MatRef& r, typename Compute<TIO>::type* dst, int ld, int R, int K,
-                                          int bh, int chunk, int L, int tid) {
+                                          int bh, int chunk, int L, int tid, float mul = 1.f) {
     typedef typename Compute<TIO>::type T;
     const long long base = bh * r.s_bh + chunk * r.s_ch;
     const int ntok = L - chunk * CHUNK;     // tokens of this chunk that exist
-    if (r.type == EL_F32) stage_mat_t<TIO, float>(r, dst, ld, R, K, base, ntok, tid);
-    else if (r.type == EL_OP) stage_mat_t<TIO, T>(r, dst, ld, R, K, base, ntok, tid);
-    else stage_mat_t<TIO, TIO>(r, dst, ld, R, K, base, ntok, tid);
+    if (r.type == EL_F32) stage_mat_t<TIO, float>(r, dst, ld, R, K, base, ntok, tid, mul);
+    else if (r.type == EL_OP) stage_mat_t<TIO, T>(r, dst, ld, R, K, base, ntok, tid, mul);
+    else stage_mat_t<TIO, TIO>(r, dst, ld, R, K, base, ntok, tid, mul);
 }
 
 template <typename TIO>
@@ -797,11 +802,11 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Element-wise steps of the chunk-transform adjoint (device functions of the fused kernel).
 // Diagonal block: P = exp(scale*Sd - lse) on key <= query, dSd = scale * P (dPd - delta).
-__global__ __launch_bounds__(256) void bwd_diag_kernel(DiagArgs a) {
-    const int chunk = blockIdx.x, bh = blockIdx.y;
+__device__ __forceinline__ void chunk_diag(const DiagArgs& a, int chunk, int bh, int tid) {
     const size_t base = ((size_t)bh * a.NC + chunk) * 4096;
-    for (int idx = threadIdx.x; idx < 4096; idx += 256) {
+    for (int idx = tid; idx < 4096; idx += 256) {
         const int t = idx >> 6, s = idx & 63, tg = chunk * CHUNK + t;
         float P = 0.f, ds = 0.f;
         if (s <= t && tg < a.L) {
@@ -815,9 +820,7 @@ __global__ __launch_bounds__(256) void bwd_diag_kernel(DiagArgs a) {
 
 // dbeta_a = R[a][a] + sum_s M[a][s] G[a][s];  dGs = diag(beta) M + (diag(beta) M)^T.
 template <typename TIO>
-__global__ __launch_bounds__(256) void bwd_beta_kernel(BetaArgs a) {
-    __shared__ float bs[CHUNK];
-    const int chunk = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+__device__ __forceinline__ void chunk_beta(const BetaArgs& a, float* bs, int chunk, int bh, int tid) {
     const size_t base = ((size_t)bh * a.NC + chunk) * 4096;
     if (tid < CHUNK) {
         const int tg = chunk * CHUNK + tid;
@@ -837,8 +840,7 @@ __global__ __launch_bounds__(256) void bwd_beta_kernel(BetaArgs a) {
 
 // fp32 [BH][Lp][d] -> I/O type [BH][L][d]; dbeta likewise.
 template <typename TIO>
-__global__ __launch_bounds__(256) void bwd_store_kernel(OutArgs a) {
-    const int chunk = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
+__device__ __forceinline__ void chunk_store(const OutArgs& a, int chunk, int bh, int tid) {
     const size_t Lp = (size_t)a.NC * CHUNK;
     for (int idx = tid; idx < CHUNK * a.d; idx += 256) {
         const int t = idx / a.d, c = idx % a.d, tg = chunk * CHUNK + t;
@@ -851,6 +853,72 @@ __global__ __launch_bounds__(256) void bwd_store_kernel(OutArgs a) {
     }
     if (tid < CHUNK && chunk * CHUNK + tid < a.L)
         reinterpret_cast<TIO*>(a.dbeta)[(size_t)bh * a.L + chunk * CHUNK + tid] = (TIO)a.dbf[(size_t)bh * Lp + chunk * CHUNK + tid];
+}
+
+// The fused adjoint of the chunk transform: one workgroup per (chunk, head) runs the program.
+// Results that later steps read go through global memory (they stay in L2); a chain of
+// products that add into the same result keeps it in accumulator registers.
+template <typename TIO>
+__global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) {
+    typedef typename Compute<TIO>::type T;
+    constexpr int FE = Tr<T>::FE, KW = Tr<T>::KW;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int chunk = blockIdx.x, bh = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    f32x16 acc[2];
+    for (int i = 0; i < pr.n; ++i) {
+        const ChunkOp& op = pr.ops[i];
+        __syncthreads();       // earlier steps' results are visible to the whole workgroup; LDS is free
+        if (op.kind == OP_DIAG) { chunk_diag(pr.diag, chunk, bh, tid); continue; }
+        if (op.kind == OP_BETA) { chunk_beta<TIO>(pr.beta, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
+        if (op.kind == OP_STORE) { chunk_store<TIO>(pr.out, chunk, bh, tid); continue; }
+        // M = 64 for every product of the list; N = 64 or 128.  Results are handled in halves of 64
+        // columns (one 32x32 block per wave and half), the B operand is staged half by half, so a
+        // workgroup needs (64 + 64) x (K + pad) operand elements of LDS and four workgroups fit a CU.
+        const int N = op.N, K = op.K, ld = K + FE;
+        T* As = reinterpret_cast<T*>(smem);
+        T* Bs = As + CHUNK * ld;
+        stage_mat<TIO>(op.A, As, ld, CHUNK, K, bh, chunk, pr.L, tid, op.alpha);
+        const long long cbase = bh * op.c_bh + chunk * op.c_ch;
+        const int mb = wv >> 1;
+#pragma unroll
+        for (int o = 0; o < 2; ++o) {
+            if (64 * o >= N) break;
+            if (o > 0) __syncthreads();                    // the first half's fragments have been read
+            MatRef bhalf = op.B;                           // rows 64*o .. 64*o+63 of B (features, never tokens)
+            bhalf.p = reinterpret_cast<const char*>(op.B.p) + (size_t)(64 * o) * op.B.rs * (op.B.type == EL_F32 ? 4 : sizeof(T));
+            stage_mat<TIO>(bhalf, Bs, ld, 64, K, bh, chunk, pr.L, tid);
+            __syncthreads();
+            const int cb = 2 * o + (wv & 1), cbl = wv & 1;
+            if (op.first) {
+                if (op.Cin) {
+#pragma unroll
+                    for (int jj = 0; jj < 16; ++jj)
+                        acc[o][jj] = op.Cin[cbase + (long long)(32 * mb + acc_row(jj, h)) * op.crs + 32 * cb + l32];
+                } else {
+                    acc[o] = zero16();
+                }
+            }
+            const T* ap = As + (32 * mb + l32) * ld + FE * h;
+            const T* bp = Bs + (32 * cbl + l32) * ld + FE * h;
+            for (int k0 = 0; k0 < K; k0 += 4 * KW) {        // K is a multiple of 64
+                typename Tr<T>::Frag fa[4], fb[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) { fa[u] = ld_frag<T>(ap + k0 + u * KW); fb[u] = ld_frag<T>(bp + k0 + u * KW); }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc[o] = Tr<T>::mma(fa[u], fb[u], acc[o]);
+            }
+            if (op.last) {
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    const int m = 32 * mb + acc_row(jj, h), n = 32 * cb + l32;
+                    float v = acc[o][jj];
+                    if ((op.mask == MASK_TRIL && n > m) || (op.mask == MASK_SLOWER && n >= m)) v = 0.f;
+                    op.C[cbase + (long long)m * op.crs + n] = v;
+                }
+            }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -869,7 +937,7 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     const size_t adj_bytes = Adj2Cfg<TIO, D>::smem_bytes, key_bytes = Key2Cfg<TIO, D>::smem_bytes;
     if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D>, adj_bytes)) != hipSuccess) return e;
     const int ntiles = (p.NC + 1) / 2;
-    hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D>), dim3((unsigned)(ntiles * p.B * p.H)), dim3(256), adj_bytes, st, p);
+    hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D>), dim3((unsigned)(8 * ((p.B * p.H + 7) / 8) * ntiles)), dim3(256), adj_bytes, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, false>, key_bytes)) != hipSuccess) return e;
     if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, true>, key_bytes)) != hipSuccess) return e;
@@ -923,20 +991,19 @@ hipError_t launch_bwd_sb_chain(const SbChainArgs& a, int BH, int d, hipStream_t 
     return d == 64 ? launch_sb_chain_t<bf16_t, 64>(a, BH, st) : launch_sb_chain_t<bf16_t, 128>(a, BH, st);
 }
 
-hipError_t launch_bwd_diag(const DiagArgs& a, int BH, hipStream_t st) {
-    hipLaunchKernelGGL(bwd_diag_kernel, dim3(a.NC, BH), dim3(256), 0, st, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_bwd_beta(const BetaArgs& a, int BH, int is_bf16, hipStream_t st) {
-    if (is_bf16) hipLaunchKernelGGL((bwd_beta_kernel<bf16_t>), dim3(a.NC, BH), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((bwd_beta_kernel<float>), dim3(a.NC, BH), dim3(256), 0, st, a);
-    return hipGetLastError();
-}
-
-hipError_t launch_bwd_store(const OutArgs& a, int BH, int is_bf16, hipStream_t st) {
-    if (is_bf16) hipLaunchKernelGGL((bwd_store_kernel<bf16_t>), dim3(a.NC, BH), dim3(256), 0, st, a);
-    else hipLaunchKernelGGL((bwd_store_kernel<float>), dim3(a.NC, BH), dim3(256), 0, st, a);
+hipError_t launch_chunk_adjoint(const ChunkProgram& pr, int BH, int is_bf16, hipStream_t st) {
+    const size_t es = is_bf16 ? 2 : 4, fe = is_bf16 ? 8 : 4;
+    size_t bytes = 1024;
+    for (int i = 0; i < pr.n; ++i) {
+        if (pr.ops[i].kind != OP_PRODUCT) continue;
+        const size_t b = (size_t)(CHUNK + CHUNK) * (pr.ops[i].K + fe) * es;      // A and half of B
+        if (b > bytes) bytes = b;
+    }
+    hipError_t e = is_bf16 ? set_smem(&chunk_adjoint_kernel<bf16_t>, 160 * 1024) : set_smem(&chunk_adjoint_kernel<float>, 160 * 1024);
+    if (e != hipSuccess) return e;
+    dim3 grid(pr.NC, BH);
+    if (is_bf16) hipLaunchKernelGGL((chunk_adjoint_kernel<bf16_t>), grid, dim3(256), bytes, st, pr);
+    else hipLaunchKernelGGL((chunk_adjoint_kernel<float>), grid, dim3(256), bytes, st, pr);
     return hipGetLastError();
 }
 

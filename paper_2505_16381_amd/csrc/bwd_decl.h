@@ -77,11 +77,35 @@ struct OutArgs {
     int L, NC, d;
 };
 
+// Adjoint of the chunk transform as ONE kernel: every workgroup (chunk, head) runs the same
+// list of steps.  A step is one product of a chain  acc (+)= alpha * A B^T  (the chain's first
+// step starts from Cin or zero, its last step masks and writes C), or one of the element-wise
+// specials between the chains.
+enum { OP_PRODUCT = 0, OP_DIAG = 1, OP_BETA = 2, OP_STORE = 3 };
+enum { OUT_C64 = 0, OUT_TOK = 1, OUT_DD = 2, OUT_DD1 = 3, OUT_D64 = 4 };   // layout of a product's result
+struct ChunkOp {
+    MatRef A, B;
+    float* C;
+    const float* Cin;
+    long long c_bh, c_ch;
+    int crs;
+    short M, N, K;
+    float alpha;
+    unsigned char mask, first, last, kind;
+};
+constexpr int MAX_CHUNK_OPS = 26;
+struct ChunkProgram {
+    ChunkOp ops[MAX_CHUNK_OPS];
+    int n;
+    DiagArgs diag;
+    BetaArgs beta;
+    OutArgs out;
+    int L, NC;
+};
+hipError_t launch_chunk_adjoint(const ChunkProgram& pr, int BH, int is_bf16, hipStream_t st);
+
 hipError_t launch_bwd_scan(const BwdParams& p, int d, int is_bf16, hipStream_t st);
 hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream_t st);
 hipError_t launch_bwd_sb_chain(const SbChainArgs& a, int BH, int d, hipStream_t st);    // 2-byte operand types only
-hipError_t launch_bwd_diag(const DiagArgs& a, int BH, hipStream_t st);
-hipError_t launch_bwd_beta(const BetaArgs& a, int BH, int is_bf16, hipStream_t st);
-hipError_t launch_bwd_store(const OutArgs& a, int BH, int is_bf16, hipStream_t st);
 
 }  // namespace path

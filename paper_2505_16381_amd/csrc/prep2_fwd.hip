@@ -23,7 +23,10 @@ namespace path {
 
 template <typename TIO, int D> struct Prep2Cfg {
     typedef typename Compute<TIO>::type T;
-    static constexpr size_t smem_bytes = (size_t)D * D * sizeof(T);      // operand copy of E (fragment order)
+    static constexpr int KV_FRAGS = CHUNK * D / Tr<T>::FE, DP_FRAGS = D * D / Tr<T>::FE;
+    static constexpr int NBUF = sizeof(T) == 2 ? 2 : 1;      // fp32 tiles: one stage only fits
+    // operand copy of E (fragment order) + NBUF stages of (key tile | -dP tile) of a chunk
+    static constexpr size_t smem_bytes = (size_t)D * D * sizeof(T) + (size_t)NBUF * (KV_FRAGS + DP_FRAGS) * 16;
 };
 
 // BWD: also write the backward-only outputs (compile-time, so the forward carries none of that code).
@@ -47,10 +50,28 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
     identity_frags<T>(idf, l32, h);
     f32x16 Fm[NE];      // E^T: block o = (rows b-block bb, lane a-block ab), blk = wv + 4*o, bb = blk / DB, ab = blk % DB
 
+    // the chunk's key and -dP tiles are copied to LDS (direct-to-LDS), one chunk ahead where two stages fit
+    constexpr int KVF = Prep2Cfg<TIO, D>::KV_FRAGS, DPF = Prep2Cfg<TIO, D>::DP_FRAGS, NBUF = Prep2Cfg<TIO, D>::NBUF;
+    Frag* stage = Es + DPF;
+    auto issue = [&](int c) {
+        const size_t bhc = (size_t)bh * NC + c;
+        Frag* buf = stage + (size_t)(c & (NBUF - 1)) * (KVF + DPF);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * (size_t)CHUNK * D), buf, KVF, tid, wv);
+        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dp) + bhc * (size_t)D * D), buf + KVF, DPF, tid, wv);
+    };
+    if (NBUF == 2) issue(clast);
     for (int c = clast; c >= c0; --c) {
         const size_t bhc = (size_t)bh * NC + c;
-        const Frag* k1 = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * (size_t)CHUNK * D);
-        const Frag* dpn = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dp) + bhc * (size_t)D * D);    // (rows b, contr a) = -dP[a][b]
+        if (NBUF == 2) {
+            wait_async_and_sync();             // chunk c has landed; everyone is done with chunk c+1
+            if (c > c0) issue(c - 1);
+        } else {
+            __syncthreads();
+            issue(c);
+            wait_async_and_sync();
+        }
+        const Frag* k1 = stage + (size_t)(c & (NBUF - 1)) * (KVF + DPF);
+        const Frag* dpn = k1 + KVF;                                                                                  // (rows b, contr a) = -dP[a][b]
         Frag* k2 = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2) + bhc * (size_t)CHUNK * D);
         Frag* k2T = (BWD && p.kt2T) ? reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2T) + bhc * (size_t)CHUNK * D) : nullptr;
         if (BWD && p.rm) {      // backward only: R_c = I - E_c, row-major [a][b]

@@ -95,22 +95,37 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     const TIO* Bg = reinterpret_cast<const TIO*>(p.beta) + (size_t)bh * L + t0;
 
     // ---- phase 0: stage the chunk (zero rows past L) ---------------------------
-    for (int idx = tid; idx < CHUNK * (D / FE); idx += 256) {
-        const int row = idx / (D / FE), cf = idx % (D / FE);
-        Frag wv_ = Tr<T>::zero(), qv = Tr<T>::zero(), kv = Tr<T>::zero();
-        if (row < nvalid) {
-            wv_ = cvt_frag<T, TIO>(ld_frag<TIO>(Wg + (size_t)row * D + cf * FE));
-            if (C::STAGE_QK) {
-                qv = cvt_frag<T, TIO>(ld_frag<TIO>(Qg + (size_t)row * D + cf * FE));
-                kv = cvt_frag<T, TIO>(ld_frag<TIO>(Kg + (size_t)row * D + cf * FE));
+    // All of a thread's loads are issued before the first conversion, so their latencies overlap.
+    {
+        typedef typename Tr<TIO>::Frag FragIO;
+        constexpr int NIT = CHUNK * (D / FE) / 256;
+        FragIO wr[NIT], qr[C::STAGE_QK ? NIT : 1], kr[C::STAGE_QK ? NIT : 1];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int idx = tid + it * 256, row = idx / (D / FE), cf = idx % (D / FE);
+            if (row < nvalid) {
+                wr[it] = ld_frag<TIO>(Wg + (size_t)row * D + cf * FE);
+                if (C::STAGE_QK) {
+                    qr[it] = ld_frag<TIO>(Qg + (size_t)row * D + cf * FE);
+                    kr[it] = ld_frag<TIO>(Kg + (size_t)row * D + cf * FE);
+                }
             }
         }
-        *reinterpret_cast<Frag*>(Ws + row * LDD + cf * FE) = wv_;
 #pragma unroll
-        for (int e = 0; e < FE; ++e) Wt[(cf * FE + e) * LDC + row] = wv_[e];
-        if (C::STAGE_QK) {
-            *reinterpret_cast<Frag*>(sT + C::off_qs + row * LDD + cf * FE) = qv;
-            *reinterpret_cast<Frag*>(sT + C::off_ks + row * LDD + cf * FE) = kv;
+        for (int it = 0; it < NIT; ++it) {
+            const int idx = tid + it * 256, row = idx / (D / FE), cf = idx % (D / FE);
+            Frag wv_ = Tr<T>::zero(), qv = Tr<T>::zero(), kv = Tr<T>::zero();
+            if (row < nvalid) {
+                wv_ = cvt_frag<T, TIO>(wr[it]);
+                if (C::STAGE_QK) { qv = cvt_frag<T, TIO>(qr[it]); kv = cvt_frag<T, TIO>(kr[it]); }
+            }
+            *reinterpret_cast<Frag*>(Ws + row * LDD + cf * FE) = wv_;
+#pragma unroll
+            for (int e = 0; e < FE; ++e) Wt[(cf * FE + e) * LDC + row] = wv_[e];
+            if (C::STAGE_QK) {
+                *reinterpret_cast<Frag*>(sT + C::off_qs + row * LDD + cf * FE) = qv;
+                *reinterpret_cast<Frag*>(sT + C::off_ks + row * LDD + cf * FE) = kv;
+            }
         }
     }
     if (tid < CHUNK) bs[tid] = (tid < nvalid) ? (float)Bg[tid] : 0.f;

@@ -97,3 +97,10 @@ def test_config3_backward_full_shape_sampled_heads(gpu, oracle):
     """Full benchmark shape on the GPU; the oracle (not row-separable) on a sample of heads."""
     x, c = si.make_config(3)
     _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, heads=[0, 37, 127], tag="cfg3")
+
+
+def test_headline_shape_backward_sampled_head(gpu, oracle):
+    """The shape and launch configuration bench.py times (B=4, H=16, L=8192, d=128, bf16):
+    the whole batch runs on the GPU, one head is checked against the oracle."""
+    x, c = si.make_config(2, with_do=True)
+    _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, heads=[41], tag="headline shape")

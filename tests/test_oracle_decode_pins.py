@@ -1,0 +1,88 @@
+"""Pins of the decode oracle (CPU).  The cache formulation (keys refreshed as tokens arrive,
+paper Sec. 3.4) is checked against things it does not share code with: the forward oracle's
+query-side walk (paper Sec. 2.2 definition), closed forms, and special cases."""
+import numpy as np
+
+from oracle import decode_oracle as dec
+from oracle import path_oracle
+from paper_2505_16381_amd import synth_inputs as si
+
+
+def _x(L=37, d=8, seed=11, B=1, H=2):
+    return si.make_inputs(B, H, L, d, "fp32", seed, 0.0)
+
+
+def test_prefilled_cache_reproduces_the_walk_logits_of_the_last_query():
+    # q_l . k_i^(l) * scale must equal the definition's logit s_{l,i}, which the forward oracle
+    # gets by transforming the QUERY leftwards -- a different order of the same product.
+    x = _x()
+    scale = 0.3
+    kc = dec.key_prefill(x["k"], x["w"], x["beta"])
+    last = x["q"].shape[2] - 1
+    got = scale * np.einsum("bhnd,bhd->bhn", kc, x["q"][:, :, last].astype(np.float64))
+    for b in range(x["q"].shape[0]):
+        for h in range(x["q"].shape[1]):
+            S = path_oracle.logits(x["q"][b, h], x["k"][b, h], x["w"][b, h], x["beta"][b, h], scale)   # [L,L], row i = query i
+            assert np.abs(got[b, h] - S[last, :]).max() <= 1e-12
+
+
+def test_decode_steps_equal_forward_rows():
+    # prefill on the first l0 tokens, then decode the rest one by one: every step's output and
+    # log-sum-exp equal the forward oracle's row.
+    x = _x(L=29, d=8, seed=5)
+    scale = 8 ** -0.5
+    o_ref, lse_ref = path_oracle.fwd(x["q"], x["k"], x["v"], x["w"], x["beta"], scale)
+    l0 = 10
+    kc = dec.key_prefill(x["k"][:, :, :l0 - 1], x["w"][:, :, :l0 - 1], x["beta"][:, :, :l0 - 1])
+    vc = x["v"][:, :, :l0 - 1].astype(np.float64)
+    for t in range(l0 - 1, 29):
+        o, lse, kc, vc = dec.decode_step(x["q"][:, :, t], x["k"][:, :, t], x["v"][:, :, t], x["w"][:, :, t],
+                                         x["beta"][:, :, t], kc, vc, scale)
+        assert np.abs(o - o_ref[:, :, t]).max() <= 1e-12
+        assert np.abs(lse - lse_ref[:, :, t]).max() <= 1e-12
+
+
+def test_beta_zero_leaves_the_cache_alone_and_beta_two_reflects():
+    x = _x(L=12, d=6, seed=3)
+    kc = x["k"].astype(np.float64)
+    w = x["w"][:, :, 0].astype(np.float64)
+    w = w / np.linalg.norm(w, axis=-1, keepdims=True)          # unit in fp64, not just in fp32
+    assert np.array_equal(dec.cache_update(kc, w, np.zeros(w.shape[:-1])), kc)
+    # beta = 2 with unit w is a reflection: applying it twice is the identity, norms are kept
+    r1 = dec.cache_update(kc, w, 2 * np.ones(w.shape[:-1]))
+    r2 = dec.cache_update(r1, w, 2 * np.ones(w.shape[:-1]))
+    assert np.abs(r2 - kc).max() <= 1e-12
+    assert np.abs(np.linalg.norm(r1, axis=-1) - np.linalg.norm(kc, axis=-1)).max() <= 1e-12
+
+
+def test_one_update_closed_form_and_transposed_operand_trap():
+    # k' = k - beta (w.k) w, written out for one key; an update with w and k swapped, or with the
+    # outer product transposed, gives a different vector for these numbers.
+    k = np.array([[1.0, 2.0, -1.0]])
+    w = np.array([0.6, 0.0, 0.8])
+    beta = np.array(1.5)
+    got = dec.cache_update(k, w, beta)
+    want = np.array([[1.0 - 1.5 * (-0.2) * 0.6, 2.0, -1.0 - 1.5 * (-0.2) * 0.8]])
+    assert np.abs(got - want).max() <= 1e-15
+    wrong = k - 1.5 * (k @ k.T) * w          # (k.k) instead of (w.k)
+    assert np.abs(wrong - want).max() > 0.1
+
+
+def test_last_key_enters_untouched_and_order_of_transitions_matters():
+    x = _x(L=9, d=5, seed=21)
+    kc = dec.key_prefill(x["k"], x["w"], x["beta"])
+    assert np.array_equal(kc[:, :, -1], x["k"][:, :, -1].astype(np.float64))
+    # k_0^(l) = H_{l-1} ... H_1 k_0 (later transitions applied last): brute force with explicit matrices
+    b, h = 0, 1
+    u = x["k"][b, h, 0].astype(np.float64)
+    for t in range(1, 9):
+        wt = x["w"][b, h, t].astype(np.float64)
+        Ht = np.eye(5) - float(x["beta"][b, h, t]) * np.outer(wt, wt)
+        u = Ht @ u
+    assert np.abs(kc[b, h, 0] - u).max() <= 1e-13
+    # the reversed order is a different vector (the transitions do not commute)
+    u2 = x["k"][b, h, 0].astype(np.float64)
+    for t in range(8, 0, -1):
+        wt = x["w"][b, h, t].astype(np.float64)
+        u2 = (np.eye(5) - float(x["beta"][b, h, t]) * np.outer(wt, wt)) @ u2
+    assert np.abs(u2 - u).max() > 1e-3

@@ -66,6 +66,66 @@ def cpu_baseline(x, cfg, scale, n_rows=3072):
     }
 
 
+def bench_decode(args, torch, pa, si, dev):
+    """One decoding step at the headline head shape over a cache of L tokens (paper Sec. 3.4):
+    every cached key is refreshed in place, then q attends over the cache.  HBM-bound:
+    algorithmic traffic = read K + write K + read V = 3 * L * d * 2 bytes per head."""
+    cfg = dict(si.CONFIGS[args.config])
+    if args.shape:
+        cfg.update(dict(zip(("B", "H", "L", "d"), (int(v) for v in args.shape.split(",")))))
+    B, H, L, d = cfg["B"], cfg["H"], cfg["L"], cfg["d"]
+    g = torch.Generator(device="cuda").manual_seed(20250516)
+    rn = lambda *shape: torch.randn(*shape, device=dev, generator=g)
+    kc = rn(B, H, L + 64, d).to(torch.bfloat16)
+    vc = rn(B, H, L + 64, d).to(torch.bfloat16)
+    q, k, v = (rn(B, H, d).to(torch.bfloat16) for _ in range(3))
+    w = torch.nn.functional.normalize(rn(B, H, d), dim=-1).to(torch.bfloat16)
+    beta = (2 * torch.sigmoid(rn(B, H))).to(torch.bfloat16)
+    ws = torch.empty(pa.path_decode_workspace_bytes(B, H, d), dtype=torch.uint8, device=dev)
+    scale = d ** -0.5
+    step = lambda: pa.path_decode_step(q, k, v, w, beta, kc, vc, L, scale, workspace=ws)   # same position every time
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(args.steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms = e0.elapsed_time(e1) / args.steps
+    bytes_alg = 3.0 * L * d * 2 * B * H
+    # key prefill of the same cache from a prompt's forward workspace (one-off, linear in L)
+    pq, pk, pv = (rn(B, H, L, d).to(torch.bfloat16) for _ in range(3))
+    pw = torch.nn.functional.normalize(rn(B, H, L, d), dim=-1).to(torch.bfloat16)
+    pbeta = (2 * torch.sigmoid(rn(B, H, L))).to(torch.bfloat16)
+    fws = torch.empty(pa.path_attn_workspace_bytes(B, H, L, d, pa.PATH_BF16, False), dtype=torch.uint8, device=dev)
+    pa.path_attn_fwd_prep(pq, pk, pv, pw, pbeta, fws)
+    pa.path_key_prefill(pv, fws, kc, vc)
+    torch.cuda.synchronize()
+    p0, p1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    p0.record()
+    for _ in range(5):
+        pa.path_key_prefill(pv, fws, kc, vc)
+    p1.record()
+    torch.cuda.synchronize()
+    prefill_ms = p0.elapsed_time(p1) / 5
+    out = {
+        "metric": "PaTH decode step: in-place key-cache refresh + attention, tokens/s", "value": B / (wall / args.steps),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 caches, fp32 arithmetic",
+        "data": "synthetic",
+        "config": {"workload": f"decode step over a cache of L={L} tokens, B={B} H={H} d={d}"},
+        "key_prefill_ms": prefill_ms,
+        "roofline": {"kernel": "decode_partial_kernel + decode_combine_kernel", "bound": "hbm", "achieved": bytes_alg / (ms * 1e-3) / 1e9,
+                     "peak": 8000.0, "unit": "GB/s", "frac": bytes_alg / (ms * 1e-3) / 1e9 / 8000.0, "traffic": None,
+                     "note": "algorithmic bytes = read K + write K + read V = 3*L*d*2 per head; HIP-event time of one step"},
+    }
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,6 +135,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fwd-only", action="store_true")
     ap.add_argument("--shape", type=str, default=None, help="override B,H,L,d of the chosen configuration (exploration only)")
+    ap.add_argument("--workload", choices=["train", "decode"], default="train",
+                    help="train (default): the headline forward+backward step; decode: one decoding step "
+                         "(in-place key-cache refresh + attention) over a cache of L tokens, its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (each (batch, head) is independent; "
@@ -89,6 +152,8 @@ def main():
     pa.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.workload == "decode":
+        return bench_decode(args, torch, pa, si, dev)
     over = {}
     if args.shape:
         over = dict(zip(("B", "H", "L", "d"), (int(v) for v in args.shape.split(","))))

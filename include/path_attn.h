@@ -128,6 +128,37 @@ path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const v
                             path_dtype_t dt, void* workspace, size_t workspace_bytes,
                             void* stream);
 
+/*
+ * Decode path (paper Sec. 3.4 "Efficient Inference").  Caches are caller-owned device memory,
+ * kcache and vcache [B,H,Lmax,d] contiguous in the I/O type dt; position i of a head holds
+ * token i.  The key cache holds REFRESHED keys: after t tokens, k_i^(t) = H_t ... H_{i+1} k_i
+ * (the section's first equation applied at every arrival), so that attention of q_t over the
+ * cache is ordinary softmax attention.  With dt = PATH_BF16 every refresh rounds the stored
+ * keys to bf16 again; that rounding is part of the method as the paper runs it.
+ *
+ * path_key_prefill: fills positions [0, L) of both caches after a prompt of L tokens (the
+ * section's key-prefill formula, with suffix products: linear in L).  It reads the forward
+ * workspace of the SAME prompt, i.e. call it after path_attn_fwd / path_attn_fwd_prep on
+ * (q, k, v, w, beta) with that workspace (device, read-only here); v [B,H,L,d] is copied.
+ * Errors: PATH_ERR_SHAPE also for L > Lmax.
+ *
+ * path_decode_step: one arriving token per (batch, head): q, k, v, w [B,H,d], beta [B,H] (dt,
+ * device, read-only).  n = tokens already cached (0 <= n < Lmax).  Refreshes the n cached
+ * keys in place, appends k and v at position n, writes o [B,H,d] (dt) and lse [B,H] (fp32,
+ * natural log) of the attention of q over the n+1 keys.  workspace: device scratch of
+ * path_decode_workspace_bytes(B, H, d) bytes, 256-byte aligned, contents undefined afterwards.
+ * Nothing is allocated; all work is enqueued on `stream`.
+ */
+size_t path_decode_workspace_bytes(int B, int H, int d);
+path_status_t path_key_prefill(const void* v, int B, int H, int L, int d, path_dtype_t dt,
+                               const void* fwd_workspace, size_t fwd_workspace_bytes,
+                               void* kcache, void* vcache, int Lmax, void* stream);
+path_status_t path_decode_step(const void* q, const void* k, const void* v, const void* w,
+                               const void* beta, void* kcache, void* vcache, int n, int Lmax,
+                               void* o, float* lse, int B, int H, int d, float scale,
+                               path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                               void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -59,6 +59,12 @@ def load_library():
     lib.path_attn_fwd_sweep.argtypes = [vp, vp, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_attn_bwd.restype = ci
     lib.path_attn_bwd.argtypes = [vp] * 13 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_decode_workspace_bytes.restype = sz
+    lib.path_decode_workspace_bytes.argtypes = [ci, ci, ci]
+    lib.path_key_prefill.restype = ci
+    lib.path_key_prefill.argtypes = [vp, ci, ci, ci, ci, ci, vp, sz, vp, vp, ci, vp]
+    lib.path_decode_step.restype = ci
+    lib.path_decode_step.argtypes = [vp] * 7 + [ci, ci, vp, vp, ci, ci, ci, cf, ci, vp, sz, vp]
     _lib = lib
     return lib
 
@@ -180,3 +186,30 @@ def path_attn_bwd(q, k, v, w, beta, o, lse, d_o, scale=None, causal=True,
                              B, H, L, d, int(bool(causal)), float(scale), dt,
                              _ptr(workspace), workspace.numel(), _stream_handle(stream)))
     return dq, dk, dv, dw, dbeta
+
+
+def path_decode_workspace_bytes(B, H, d) -> int:
+    return int(load_library().path_decode_workspace_bytes(B, H, d))
+
+
+def path_key_prefill(v, fwd_workspace, kcache, vcache, stream=None):
+    """Fills positions [0, L) of the caches [B,H,Lmax,d] after a prompt; ``fwd_workspace`` is the
+    workspace path_attn_fwd / path_attn_fwd_prep used on that prompt."""
+    B, H, L, d = v.shape
+    _check(load_library().path_key_prefill(_ptr(v), B, H, L, d, _dt_of(v), _ptr(fwd_workspace), fwd_workspace.numel(),
+                                           _ptr(kcache), _ptr(vcache), kcache.shape[2], _stream_handle(stream)))
+
+
+def path_decode_step(q, k, v, w, beta, kcache, vcache, n, scale, workspace=None, stream=None):
+    """One arriving token per (batch, head): q,k,v,w [B,H,d], beta [B,H]; n tokens already cached.
+    Returns (o [B,H,d], lse [B,H]); the caches are updated in place."""
+    import torch
+    B, H, d = q.shape
+    if workspace is None:
+        workspace = torch.empty(path_decode_workspace_bytes(B, H, d), dtype=torch.uint8, device=q.device)
+    o = torch.empty_like(q)
+    lse = torch.empty((B, H), dtype=torch.float32, device=q.device)
+    _check(load_library().path_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(kcache), _ptr(vcache),
+                                           int(n), kcache.shape[2], _ptr(o), _ptr(lse), B, H, d, float(scale), _dt_of(q),
+                                           _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return o, lse

@@ -12,6 +12,7 @@ hipError_t launch_attn_fwd2(const FwdParams& p, int d, int is_bf16, hipStream_t 
 hipError_t launch_attn_states(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 }  // namespace path
 #include "bwd_decl.h"
+#include "decode_decl.h"
 namespace path {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -167,8 +168,9 @@ extern "C" path_status_t path_attn_fwd_prep(const void* q, const void* k, const 
     clear_inherited_error();
     if (!hip_ok(launch_prep_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "chunk transform"))
         return PATH_ERR_HIP;
-    if (p.NC > SBC &&            // the second level is only read when there is a super-block to the left
-        !hip_ok(launch_prep2_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "second-level transform"))
+    // (the sweep reads the second level only when there is a super-block to the left; the key
+    // prefill of the decode path reads it always)
+    if (!hip_ok(launch_prep2_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "second-level transform"))
         return PATH_ERR_HIP;
     return PATH_OK;
 }
@@ -376,4 +378,51 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     if (chain_open || pr.n > MAX_CHUNK_OPS) return PATH_ERR_HIP;
     ok = hip_ok(launch_chunk_adjoint(pr, BH, bf, st), "chunk-transform adjoint");
     return ok ? PATH_OK : PATH_ERR_HIP;
+}
+
+extern "C" size_t path_decode_workspace_bytes(int B, int H, int d) {
+    if (B < 1 || H < 1 || (d != 64 && d != 128)) return 0;
+    return align256((size_t)B * H * DECODE_MAX_SPLITS * (d + 2) * 4);
+}
+
+extern "C" path_status_t path_key_prefill(const void* v, int B, int H, int L, int d, path_dtype_t dt,
+                                          const void* fws, size_t fws_bytes,
+                                          void* kcache, void* vcache, int Lmax, void* stream) {
+    if (!v || !fws || !kcache || !vcache) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (!shape_ok(B, H, L, d) || L > Lmax) return PATH_ERR_SHAPE;
+    const size_t es = dt == PATH_BF16 ? 2 : 4;
+    const FwdWorkspace ws = fwd_workspace(B, H, L, d, es);
+    if (fws_bytes < ws.total || (reinterpret_cast<uintptr_t>(fws) & 255)) return PATH_ERR_WORKSPACE;
+    if (misaligned(v) || misaligned(kcache) || misaligned(vcache)) return PATH_ERR_ALIGN;
+    const unsigned char* base = static_cast<const unsigned char*>(fws);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    clear_inherited_error();
+    PrefillArgs a{base + ws.kt2, base + ws.dp2, kcache, L, (L + CHUNK - 1) / CHUNK, Lmax};
+    if (!hip_ok(launch_key_prefill(a, B * H, d, dt == PATH_BF16, st), "key prefill")) return PATH_ERR_HIP;
+    // values: rows [0, L) of every head, unchanged
+    if (!hip_ok(hipMemcpy2DAsync(vcache, (size_t)Lmax * d * es, v, (size_t)L * d * es, (size_t)L * d * es, (size_t)B * H,
+                                 hipMemcpyDeviceToDevice, st), "value cache copy"))
+        return PATH_ERR_HIP;
+    return PATH_OK;
+}
+
+extern "C" path_status_t path_decode_step(const void* q, const void* k, const void* v, const void* w,
+                                          const void* beta, void* kcache, void* vcache, int n, int Lmax,
+                                          void* o, float* lse, int B, int H, int d, float scale,
+                                          path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                                          void* stream) {
+    if (!q || !k || !v || !w || !beta || !kcache || !vcache || !o || !lse || !workspace) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (B < 1 || H < 1 || (d != 64 && d != 128) || (long long)B * H > 65535 || n < 0 || n >= Lmax) return PATH_ERR_SHAPE;
+    if (!(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
+    if (workspace_bytes < path_decode_workspace_bytes(B, H, d) || (reinterpret_cast<uintptr_t>(workspace) & 255))
+        return PATH_ERR_WORKSPACE;
+    const void* al[] = {q, k, v, w, kcache, vcache, o};
+    for (const void* ptr : al) if (misaligned(ptr)) return PATH_ERR_ALIGN;
+    clear_inherited_error();
+    DecodeArgs a{q, k, v, w, beta, kcache, vcache, o, lse, static_cast<float*>(workspace), n, Lmax, scale};
+    if (!hip_ok(launch_decode_step(a, B * H, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "decode step"))
+        return PATH_ERR_HIP;
+    return PATH_OK;
 }

@@ -119,7 +119,8 @@ path_status_t path_attn_fwd_sweep(void* o, float* lse, int B, int H, int L, int 
  *        d_o [B,H,L,d] (dt)                                  -- device, read-only
  *   out: dq, dk, dv, dw [B,H,L,d] (dt), dbeta [B,H,L] (dt)   -- device
  * dw is the gradient with respect to the w passed in (no projection onto the
- * unit sphere).  No atomics are used: results are bit-reproducible.
+ * unit sphere).  Results are bit-reproducible: every sum is taken in a fixed order (the one
+ * place that uses the hardware's floating-point add to memory adds exactly one term per element).
  */
 path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const void* w,
                             const void* beta, const void* o, const float* lse, const void* d_o,

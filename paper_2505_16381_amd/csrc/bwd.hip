@@ -564,36 +564,70 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
 // matrix can be used), converted to the operand type while being staged in LDS.
 // Stage R x K elements of one operand into LDS (row-major, pitch ld, operand type), eight
 // elements per thread along whichever index is contiguous in memory (one 16/32-byte load).
-template <typename TIO, typename E>
+// NB: how many 8-element vectors a thread loads before it converts and stores any of them.
+// 1 keeps the register count low (kernels that rely on several workgroups per CU); 4 overlaps
+// the load latencies (kernels with one workgroup per CU and registers to spare).
+template <typename TIO, typename E, int NB = 1>
 __device__ __forceinline__ void stage_mat_t(const MatRef& r, typename Compute<TIO>::type* dst, int ld, int R, int K,
                                             long long base, int ntok, int tid, float mul = 1.f) {
     typedef typename Compute<TIO>::type T;
     const E* src = reinterpret_cast<const E*>(r.p) + base;
     typedef E Vec8 __attribute__((ext_vector_type(8)));
-    if (r.ks == 1) {                       // contraction index contiguous
-        const int kg = K / 8;
-        for (int idx = tid; idx < R * kg; idx += 256) {
-            const int m = idx / kg, k0 = (idx % kg) * 8;
-            Vec8 v;
-            const bool row_ok = r.tok != TOK_ROW || m < ntok;
-            if (row_ok) v = *reinterpret_cast<const Vec8*>(src + (long long)m * r.rs + k0);
+    if (NB == 1) {
+        if (r.ks == 1) {                       // contraction index contiguous
+            const int kg = K / 8;
+            for (int idx = tid; idx < R * kg; idx += 256) {
+                const int m = idx / kg, k0 = (idx % kg) * 8;
+                Vec8 v;
+                const bool row_ok = r.tok != TOK_ROW || m < ntok;
+                if (row_ok) v = *reinterpret_cast<const Vec8*>(src + (long long)m * r.rs + k0);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const bool ok = row_ok && (r.tok != TOK_K || k0 + e < ntok);
-                dst[m * ld + k0 + e] = ok ? (T)((float)v[e] * mul) : (T)0.f;
+                for (int e = 0; e < 8; ++e) {
+                    const bool ok = row_ok && (r.tok != TOK_K || k0 + e < ntok);
+                    dst[m * ld + k0 + e] = ok ? (T)((float)v[e] * mul) : (T)0.f;
+                }
+            }
+        } else {                               // row index contiguous (rs == 1)
+            const int mg = R / 8;
+            for (int idx = tid; idx < K * mg; idx += 256) {
+                const int k = idx / mg, m0 = (idx % mg) * 8;
+                Vec8 v;
+                const bool k_ok = r.tok != TOK_K || k < ntok;
+                if (k_ok) v = *reinterpret_cast<const Vec8*>(src + (long long)k * r.ks + m0);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool ok = k_ok && (r.tok != TOK_ROW || m0 + e < ntok);
+                    dst[(m0 + e) * ld + k] = ok ? (T)((float)v[e] * mul) : (T)0.f;
+                }
             }
         }
-    } else {                               // row index contiguous (rs == 1)
-        const int mg = R / 8;
-        for (int idx = tid; idx < K * mg; idx += 256) {
-            const int k = idx / mg, m0 = (idx % mg) * 8;
-            Vec8 v;
-            const bool k_ok = r.tok != TOK_K || k < ntok;
-            if (k_ok) v = *reinterpret_cast<const Vec8*>(src + (long long)k * r.ks + m0);
+        return;
+    }
+    // A thread moves vectors of 8 elements along whichever index is contiguous in memory
+    // (vectors per line: K/8 or R/8, a power of two).
+    const bool kcontig = r.ks == 1;
+    const int vlen = (kcontig ? K : R) / 8, sh = __ffs(vlen) - 1, nvec = R * K / 8;
+    const long long lstride = kcontig ? r.rs : r.ks;
+    for (int i0 = tid; i0 < nvec; i0 += 256 * NB) {
+        Vec8 v[NB];
+        bool ok_line[NB];
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int idx = i0 + u * 256, line = idx >> sh, pos = (idx & (vlen - 1)) * 8;
+            ok_line[u] = idx < nvec && (kcontig ? (r.tok != TOK_ROW || line < ntok) : (r.tok != TOK_K || line < ntok));
+            if (ok_line[u]) v[u] = *reinterpret_cast<const Vec8*>(src + line * lstride + pos);
+        }
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            const int idx = i0 + u * 256, line = idx >> sh, pos = (idx & (vlen - 1)) * 8;
+            if (idx >= nvec) break;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const bool ok = k_ok && (r.tok != TOK_ROW || m0 + e < ntok);
-                dst[(m0 + e) * ld + k] = ok ? (T)((float)v[e] * mul) : (T)0.f;
+                // the index that runs along the vector is a token when it is k (kcontig, TOK_K) or a row (TOK_ROW)
+                const bool ok = ok_line[u] && ((kcontig ? r.tok != TOK_K : r.tok != TOK_ROW) || pos + e < ntok);
+                const T val = ok ? (T)((float)v[u][e] * mul) : (T)0.f;
+                if (kcontig) dst[line * ld + pos + e] = val;
+                else dst[(pos + e) * ld + line] = val;
             }
         }
     }
@@ -721,8 +755,8 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
         const MatRef Rt{a.rm, 0, 0, 1, D, EL_OP, TOK_NONE};          // (row x, k): R[k][x]
         const MatRef K2r{a.dk2, 0, 0, D, 1, EL_F32, TOK_NONE};       // (row s, k=a): dKb2[s][a]
         __syncthreads();                                             // previous iteration's reads are done
-        stage_mat_t<TIO, T>(Rt, B0, LD, D, D, (long long)(bhc * D * D), ntok, tid);
-        stage_mat_t<TIO, float>(K2r, B2, LD, CHUNK, D, (long long)(bhc * CHUNK * D), ntok, tid);
+        stage_mat_t<TIO, T, 4>(Rt, B0, LD, D, D, (long long)(bhc * D * D), ntok, tid);
+        stage_mat_t<TIO, float, 4>(K2r, B2, LD, CHUNK, D, (long long)(bhc * CHUNK * D), ntok, tid);
 #pragma unroll
         for (int o = 0; o < NOWN; ++o) {                             // B1[b][k] = D[k][b]
             const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
@@ -743,7 +777,9 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
                 const int blk = wv + 4 * o, xb = blk / DB, bb = blk % DB;
                 const f32x16 acc = block(B0, B1, LD, xb, bb, KD, zero16());
 #pragma unroll
-                for (int jj = 0; jj < 16; ++jj) dst[(size_t)(32 * xb + acc_row(jj, h)) * D + 32 * bb + l32] -= acc[jj];
+                // one addend per element and launch: the hardware add (no return value, so the wave
+                // does not wait for the old value) is as reproducible as a read-modify-write
+                for (int jj = 0; jj < 16; ++jj) unsafeAtomicAdd(dst + (size_t)(32 * xb + acc_row(jj, h)) * D + 32 * bb + l32, -acc[jj]);
             }
         }
         // dKb_c[s][b] += sum_a dKb2[s][a] R[a][b]
@@ -753,7 +789,7 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
                 const int sb = blk / DB, bb = blk % DB;
                 const f32x16 acc = block(B2, B0, LD, sb, bb, KD, zero16());
 #pragma unroll
-                for (int jj = 0; jj < 16; ++jj) dst[(size_t)(32 * sb + acc_row(jj, h)) * D + 32 * bb + l32] += acc[jj];
+                for (int jj = 0; jj < 16; ++jj) unsafeAtomicAdd(dst + (size_t)(32 * sb + acc_row(jj, h)) * D + 32 * bb + l32, acc[jj]);
             }
         }
         if (c == clast) break;
@@ -767,7 +803,7 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
         }
         {
             const MatRef Ur{a.utm, 0, 0, 1, CHUNK, EL_OP, TOK_NONE};     // (row t, k): utm[k][t]
-            stage_mat_t<TIO, T>(Ur, B3, LD, CHUNK, D, (long long)(bhc * D * CHUNK), ntok, tid);
+            stage_mat_t<TIO, T, 4>(Ur, B3, LD, CHUNK, D, (long long)(bhc * D * CHUNK), ntok, tid);
         }
         __syncthreads();
         f32x16 t1[2 * DB / 4];
@@ -787,9 +823,9 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
             const MatRef Wt{a.w, 0, 0, 1, D, EL_IO, TOK_K};             // (row b, k=t): W[t][b]
             const MatRef K2t{a.dk2, 0, 0, 1, D, EL_F32, TOK_NONE};      // (row a, k=s): dKb2[s][a]
             const MatRef Kbt{a.kbm, 0, 0, 1, D, EL_OP, TOK_NONE};       // (row b, k=s): Kb[s][b]
-            stage_mat_t<TIO, TIO>(Wt, B2, LDC, D, CHUNK, (long long)(((size_t)bh * L + (size_t)c * CHUNK) * D), ntok, tid);
-            stage_mat_t<TIO, float>(K2t, B3, LDC, D, CHUNK, (long long)(bhc * CHUNK * D), ntok, tid);
-            stage_mat_t<TIO, T>(Kbt, B1, LDC, D, CHUNK, (long long)(bhc * CHUNK * D), ntok, tid);
+            stage_mat_t<TIO, TIO, 4>(Wt, B2, LDC, D, CHUNK, (long long)(((size_t)bh * L + (size_t)c * CHUNK) * D), ntok, tid);
+            stage_mat_t<TIO, float, 4>(K2t, B3, LDC, D, CHUNK, (long long)(bhc * CHUNK * D), ntok, tid);
+            stage_mat_t<TIO, T, 4>(Kbt, B1, LDC, D, CHUNK, (long long)(bhc * CHUNK * D), ntok, tid);
         }
         __syncthreads();
 #pragma unroll

@@ -155,14 +155,21 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     // Step j handles key chunk j: far (j < jsb: second-level keys, state and product of its
     // super-block) or near (chunk-level keys, state and product of the chunk).
     const int nsb = (NC + SBC - 1) / SBC;
-    auto issue = [&](int j) {
+    // The four tiles of chunk j are requested in four parts (part = -1: all at once).  With two
+    // stage buffers the parts of the NEXT chunk are spread over the current chunk's work: the
+    // direct-to-LDS path takes about 32 B/clk per CU, and a wave that issues a whole stage at
+    // once sits in the issue queue for that long.
+    auto issue = [&](int j, int part) {
         Frag* buf = sbase + (size_t)(j & (NBUF - 1)) * STF;
         const size_t bhc = (size_t)bh * NC + j;
         const bool far = j < jsb;
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2 : p.kt) + bhc * CHUNK * D), buf, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), buf + KVF, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2T : p.ktT) + bhc * CHUNK * D), buf + 2 * KVF, KVF, tid, wv);
-        if (j > 0) {
+        if (part < 0 || part == 0)
+            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2 : p.kt) + bhc * CHUNK * D), buf, KVF, tid, wv);
+        if (part < 0 || part == 1)
+            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), buf + KVF, KVF, tid, wv);
+        if (part < 0 || part == 2)
+            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2T : p.ktT) + bhc * CHUNK * D), buf + 2 * KVF, KVF, tid, wv);
+        if ((part < 0 || part == 3) && j > 0) {
             if (!far)
                 async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D), buf + 3 * KVF, DPF, tid, wv);
             else if (j % SBC == 0)
@@ -181,18 +188,22 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
 #pragma unroll
     for (int s = 0; s < DS; ++s) { Xnext[s] = Tr<T>::zero(); Xb[s] = Tr<T>::zero(); }
     if (active && cq > 0) load_x(0, Xnext);
-    if (jmax >= 0 && NBUF == 2) issue(0);
+    if (jmax >= 0 && NBUF == 2) issue(0, -1);
 
     for (int j = 0; j <= jmax; ++j) {
+        const bool spread = NBUF == 2 && j + 1 <= jmax;     // request chunk j+1 while working on chunk j
         if (NBUF == 2) {
             wait_async_and_sync();                 // chunk j has landed; everyone is done with chunk j-1
-            if (j + 1 <= jmax) issue(j + 1);
+            if (spread) issue(j + 1, 0);
         } else {
             __syncthreads();
-            issue(j);
+            issue(j, -1);
             wait_async_and_sync();
         }
-        if (!active || j >= cq) continue;
+        if (!active || j >= cq) {
+            if (spread) { issue(j + 1, 1); issue(j + 1, 2); issue(j + 1, 3); }
+            continue;
+        }
         const Frag* sK = sbase + (size_t)(j & (NBUF - 1)) * STF;
         const FragV* sV = reinterpret_cast<const FragV*>(sK + KVF);
         const Frag* sKT = sK + 2 * KVF;
@@ -229,7 +240,9 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
                 S[jj] = P * (dP[jj] - dl) * p.scale;
             }
             pack_block<T>(S, dSb + kb * SPB);
+            if (spread) issue(j + 1, 1 + kb);
         }
+        if (spread) issue(j + 1, 3);
 #pragma unroll
         for (int b = 0; b < DB; b += 2) {
             Frag ta[2 * QS];
@@ -353,29 +366,36 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     for (int b = 0; b < DB; ++b) { dVt[b] = zero16(); dKt[b] = zero16(); }
 
     // all operands of query chunk i, asynchronously, into stage buffer (i & (NBUF-1))
-    auto issue = [&](int i) {
+    // part = -1: everything; 0..3: one tile each (the requests for the next chunk are spread over
+    // the current chunk's work, see the adjoint scan)
+    auto issue = [&](int i, int part) {
         Frag* buf = sbase + (size_t)(i & (NBUF - 1)) * STF;
         const size_t slot = ((size_t)bh * nslots + block_slot(i, j, NC)) * (size_t)CHUNK * D;
         const size_t bhi = ((size_t)bh * NC + i) * CHUNK * D;
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot), buf, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf + KVF, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doq) + bhi), buf + 2 * KVF, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doT) + bhi), buf + 3 * KVF, KVF, tid, wv);
-        if (tid < 32) {     // 64 floats of lse2 (lanes 0-15) and of delta (lanes 16-31): 16 bytes per lane
+        if (part < 0 || part == 0)
+            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot), buf, KVF, tid, wv);
+        if (part < 0 || part == 2)
+            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf + KVF, KVF, tid, wv);
+        if (part < 0 || part == 1)
+            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doq) + bhi), buf + 2 * KVF, KVF, tid, wv);
+        if (part < 0 || part == 3)
+            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doT) + bhi), buf + 3 * KVF, KVF, tid, wv);
+        if ((part < 0 || part == 0) && tid < 32) {     // 64 floats of lse2 (lanes 0-15) and of delta (lanes 16-31): 16 bytes per lane
             const float* src = (tid < 16 ? p.lse2p : p.delta) + (size_t)bh * Lp + (size_t)i * CHUNK + 4 * (tid & 15);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(buf + 4 * KVF), 16, 0, 0);
         }
     };
 
-    if (i0 < i1 && NBUF == 2) issue(i0);
+    if (i0 < i1 && NBUF == 2) issue(i0, -1);
     for (int i = i0; i < i1; ++i) {
+        const bool spread = NBUF == 2 && i + 1 < i1 && FAR;       // far: two rounds of work per chunk to spread over
         if (NBUF == 2) {
             wait_async_and_sync();                 // chunk i has landed; everyone is done with chunk i-1
-            if (i + 1 < i1) issue(i + 1);
+            if (i + 1 < i1) issue(i + 1, spread ? 0 : -1);
         } else {
             __syncthreads();
-            issue(i);
+            issue(i, -1);
             wait_async_and_sync();
         }
         const Frag* sX = sbase + (size_t)(i & (NBUF - 1)) * STF;
@@ -402,6 +422,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                     dP = Tr<TIO>::mma(da[u], Vb[s0 + u], dP);
                 }
             }
+            if (spread) issue(i + 1, qq == 0 ? 1 : 3);
             // Rows past L need no mask: their state, dO and delta are zero and lse2p is zero, so
             // P = 1 meets dO = 0 in dV and dS = P (0 - 0) = 0.
             f32x4 ls[4], dls[4];
@@ -436,6 +457,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                     dKt[b + u / SPB] = Tr<T>::mma(tb[u], dSb[u % SPB], dKt[b + u / SPB]);
                 }
             }
+            if (spread && qq == 0) issue(i + 1, 2);
         }
     }
     if (FAR) {

@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 METRIC = "PaTH attn fwd+bwd TFLOP/s and % bf16 MFMA peak at B=4,H=16,L=8192,d=128"
 PEAK_TFLOPS = 2500.0      # MI355X dense bf16/fp16 MFMA
-SWEEP_HBM_BYTES = 1.95e9  # measured HBM traffic of one sweep launch at the headline shape (see profiles/)
+SWEEP_HBM_BYTES = 1.96e9  # measured HBM traffic of one sweep launch at the headline shape (see profiles/)
 CHUNK = 64
 
 
@@ -228,7 +228,7 @@ def main():
                      "traffic": SWEEP_HBM_BYTES if (args.config == 2 and not args.shape) else None,
                      "note": "achieved = attention-equivalent flops of the launch / HIP-event time of the sweep kernel; "
                              "traffic = HBM bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE "
-                             "(profiles/fwd_headline_L8192_d128_hbm_traffic.txt), vs 1.2e9 algorithmic"},
+                             "(profiles/fwd_bwd_headline_L8192_d128_hbm_traffic.txt), vs 1.2e9 algorithmic"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, cfg, scale)

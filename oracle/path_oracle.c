@@ -28,7 +28,14 @@
  * the function) and pinned by finite differences of path_oracle_fwd and by an
  * independent autograd model in the tests.
  *
- * Layout: q,k,v,w,o,dO and gradients [B,H,L,d] contiguous; beta, lse, dbeta
+ * PaTH-FoX (the paper's "Extension: PaTH-FoX" paragraph in Sec. 2.2): with forget gates
+ * f_s in (0,1) the attention weight gets the extra factor prod_{s=j+1..i} f_s, i.e. the
+ * logit gets + sum_{s=j+1..i} log f_s (outside `scale`: the paper adds it to the finished
+ * logit).  Every function takes `logf` ([B,H,L], the LOG of the gates, NULL = no gates); the
+ * walk adds the running sum as it moves left.  Backward: with zbar_ij = p_ij (dO_i.v_j -
+ * delta_i) the gradient of the total logit, dlogf_s = sum_{j < s <= i} zbar_ij.
+ *
+ * Layout: q,k,v,w,o,dO and gradients [B,H,L,d] contiguous; beta, lse, dbeta, logf, dlogf
  * [B,H,L].  Everything is double.
  */
 #include <math.h>
@@ -58,15 +65,17 @@ static double dot(const double *a, const double *b, int d)
  * if `states` is non-NULL, states[j*d .. j*d+d) receives the walk vector u
  * as it stood when the logit against k_j was taken (u^{(i)} = q_i). */
 static void walk_row(const double *q_i, const double *K, const double *W,
-                     const double *beta, int i, int d, double scale,
+                     const double *beta, const double *logf, int i, int d, double scale,
                      double *s, double *u, double *states)
 {
+    double bias = 0.0;      /* sum_{s=j+1..i} log f_s: empty for j = i */
     memcpy(u, q_i, sizeof(double) * (size_t)d);
     for (int j = i; j >= 0; --j) {
         const double *kj = K + (size_t)j * d;
         const double *wj = W + (size_t)j * d;
         if (states) memcpy(states + (size_t)j * d, u, sizeof(double) * (size_t)d);
-        s[j] = scale * dot(u, kj, d);
+        s[j] = scale * dot(u, kj, d) + bias;
+        if (logf) bias += logf[j];
         /* u <- H_j u = u - beta_j (w_j . u) w_j   (Sec. 2.2) */
         double a = beta[j] * dot(wj, u, d);
         for (int c = 0; c < d; ++c) u[c] -= a * wj[c];
@@ -90,7 +99,7 @@ static double softmax_row(const double *s, int n, double *p)
  * lse_rows is [B,H,n_rows].  Rows are independent, so a sample of rows is
  * exact for those rows. */
 void path_oracle_fwd_rows(const double *q, const double *k, const double *v,
-                          const double *w, const double *beta,
+                          const double *w, const double *beta, const double *logf,
                           const int *rows, int n_rows,
                           double *o_rows, double *lse_rows,
                           int B, int H, int L, int d, double scale)
@@ -110,7 +119,8 @@ void path_oracle_fwd_rows(const double *q, const double *k, const double *v,
             const double *Q = q + bh * L * d, *K = k + bh * L * d;
             const double *V = v + bh * L * d, *W = w + bh * L * d;
             const double *Bt = beta + bh * L;
-            walk_row(Q + (size_t)i * d, K, W, Bt, i, d, scale, s, u, NULL);
+            const double *Lf = logf ? logf + bh * L : NULL;
+            walk_row(Q + (size_t)i * d, K, W, Bt, Lf, i, d, scale, s, u, NULL);
             double lse = softmax_row(s, i + 1, p);
             double *oi = o_rows + (bh * n_rows + r) * d;
             for (int c = 0; c < d; ++c) oi[c] = 0.0;
@@ -126,13 +136,13 @@ void path_oracle_fwd_rows(const double *q, const double *k, const double *v,
 
 /* Full forward: every row. */
 void path_oracle_fwd(const double *q, const double *k, const double *v,
-                     const double *w, const double *beta,
+                     const double *w, const double *beta, const double *logf,
                      double *o, double *lse,
                      int B, int H, int L, int d, double scale)
 {
     int *rows = (int *)malloc(sizeof(int) * (size_t)L);
     for (int i = 0; i < L; ++i) rows[i] = i;
-    path_oracle_fwd_rows(q, k, v, w, beta, rows, L, o, lse, B, H, L, d, scale);
+    path_oracle_fwd_rows(q, k, v, w, beta, logf, rows, L, o, lse, B, H, L, d, scale);
     free(rows);
 }
 
@@ -144,7 +154,7 @@ void path_oracle_logits(const double *q, const double *k, const double *w,
     double *s = (double *)malloc(sizeof(double) * (size_t)L);
     double *u = (double *)malloc(sizeof(double) * (size_t)d);
     for (int i = 0; i < L; ++i) {
-        walk_row(q + (size_t)i * d, k, w, beta, i, d, scale, s, u, NULL);
+        walk_row(q + (size_t)i * d, k, w, beta, NULL, i, d, scale, s, u, NULL);
         for (int j = 0; j < L; ++j) S[(size_t)i * L + j] = (j <= i) ? s[j] : 0.0;
     }
     free(s); free(u);
@@ -159,7 +169,7 @@ void path_oracle_walk_norms(const double *q, const double *k, const double *w,
     double *s = (double *)malloc(sizeof(double) * (size_t)L);
     double *u = (double *)malloc(sizeof(double) * (size_t)d);
     double *st = (double *)malloc(sizeof(double) * (size_t)L * d);
-    walk_row(q + (size_t)i * d, k, w, beta, i, d, 1.0, s, u, st);
+    walk_row(q + (size_t)i * d, k, w, beta, NULL, i, d, 1.0, s, u, st);
     for (int j = 0; j < L; ++j)
         norms[j] = (j <= i) ? sqrt(dot(st + (size_t)j * d, st + (size_t)j * d, d)) : 0.0;
     free(s); free(u); free(st);
@@ -182,10 +192,12 @@ void path_oracle_walk_norms(const double *q, const double *k, const double *w,
  *       ubar^{(t)} = ubar^{(t-1)} - beta_t a w_t + g_it k_t
  *   dq_i = ubar^{(i)}
  * H_0 never enters a logit that is used, so dw_0 = dbeta_0 = 0.
+ * With gates (logf != NULL) the logits carry the running sum of log f and, with
+ * zbar_ij = g_ij / scale, dlogf_s = sum_i sum_{j<s<=i} zbar_ij (dlogf_0 = 0).
  */
 void path_oracle_bwd(const double *q, const double *k, const double *v,
-                     const double *w, const double *beta, const double *dO,
-                     double *dq, double *dk, double *dv, double *dw, double *dbeta,
+                     const double *w, const double *beta, const double *logf, const double *dO,
+                     double *dq, double *dk, double *dv, double *dw, double *dbeta, double *dlogf,
                      int B, int H, int L, int d, double scale)
 {
     const long BH = (long)B * H;
@@ -195,12 +207,15 @@ void path_oracle_bwd(const double *q, const double *k, const double *v,
     memset(dv, 0, sizeof(double) * BH * Ld);
     memset(dw, 0, sizeof(double) * BH * Ld);
     memset(dbeta, 0, sizeof(double) * BH * (size_t)L);
+    if (dlogf) memset(dlogf, 0, sizeof(double) * BH * (size_t)L);
 
     for (long bh = 0; bh < BH; ++bh) {
         const double *Q = q + bh * Ld, *K = k + bh * Ld, *V = v + bh * Ld;
         const double *W = w + bh * Ld, *Bt = beta + bh * L, *DO = dO + bh * Ld;
         double *DQ = dq + bh * Ld, *DK = dk + bh * Ld, *DV = dv + bh * Ld;
         double *DW = dw + bh * Ld, *DB = dbeta + bh * L;
+        const double *Lf = logf ? logf + bh * L : NULL;
+        double *DLF = (logf && dlogf) ? dlogf + bh * L : NULL;
 #pragma omp parallel
         {
             double *s = (double *)malloc(sizeof(double) * (size_t)L);
@@ -214,10 +229,11 @@ void path_oracle_bwd(const double *q, const double *k, const double *v,
             double *tv = (double *)calloc(Ld, sizeof(double));
             double *tw = (double *)calloc(Ld, sizeof(double));
             double *tb = (double *)calloc((size_t)L, sizeof(double));
+            double *tf = (double *)calloc((size_t)L, sizeof(double));
 #pragma omp for schedule(dynamic, 4)
             for (int ii = 0; ii < L; ++ii) {
                 int i = L - 1 - ii; /* longest rows first */
-                walk_row(Q + (size_t)i * d, K, W, Bt, i, d, scale, s, u, st);
+                walk_row(Q + (size_t)i * d, K, W, Bt, Lf, i, d, scale, s, u, st);
                 softmax_row(s, i + 1, p);
                 const double *doi = DO + (size_t)i * d;
                 for (int c = 0; c < d; ++c) oi[c] = 0.0;
@@ -244,14 +260,22 @@ void path_oracle_bwd(const double *q, const double *k, const double *v,
                     }
                 }
                 memcpy(DQ + (size_t)i * d, ub, sizeof(double) * (size_t)d);
+                if (DLF) {      /* gate s sits on the path of every pair (i, j) with j < s <= i */
+                    double csum = 0.0;
+                    for (int sgate = 1; sgate <= i; ++sgate) {
+                        csum += g[sgate - 1] / scale;
+                        tf[sgate] += csum;
+                    }
+                }
             }
 #pragma omp critical
             {
                 for (size_t x = 0; x < Ld; ++x) { DK[x] += tk[x]; DV[x] += tv[x]; DW[x] += tw[x]; }
                 for (int t = 0; t < L; ++t) DB[t] += tb[t];
+                if (DLF) for (int t = 0; t < L; ++t) DLF[t] += tf[t];
             }
             free(s); free(p); free(g); free(u); free(ub); free(oi);
-            free(st); free(tk); free(tv); free(tw); free(tb);
+            free(st); free(tk); free(tv); free(tw); free(tb); free(tf);
         }
     }
 }

@@ -51,13 +51,17 @@ def _f64(a):
     return np.ascontiguousarray(a, dtype=np.float64)
 
 
-def fwd(q, k, v, w, beta, scale, rows=None):
+def fwd(q, k, v, w, beta, scale, rows=None, logf=None):
     """o, lse for all rows (``rows=None``) or for the token indices ``rows``.
 
-    q,k,v,w: [B,H,L,d]; beta: [B,H,L].  Returns o [B,H,R,d], lse [B,H,R].
+    q,k,v,w: [B,H,L,d]; beta: [B,H,L]; logf (PaTH-FoX, optional): [B,H,L], the log of the
+    forget gates.  Returns o [B,H,R,d], lse [B,H,R].
     """
     lib = _load()
     q, k, v, w, beta = map(_f64, (q, k, v, w, beta))
+    if logf is not None:
+        logf = _f64(logf)
+        assert logf.shape == beta.shape
     B, H, L, d = q.shape
     assert k.shape == q.shape and v.shape == q.shape and w.shape == q.shape
     assert beta.shape == (B, H, L)
@@ -69,7 +73,7 @@ def fwd(q, k, v, w, beta, scale, rows=None):
     o = np.empty((B, H, R, d), dtype=np.float64)
     lse = np.empty((B, H, R), dtype=np.float64)
     if R:
-        lib.path_oracle_fwd_rows(_p(q), _p(k), _p(v), _p(w), _p(beta), _p(rows),
+        lib.path_oracle_fwd_rows(_p(q), _p(k), _p(v), _p(w), _p(beta), _p(logf) if logf is not None else None, _p(rows),
                                  ctypes.c_int(R), _p(o), _p(lse),
                                  ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(L),
                                  ctypes.c_int(d), ctypes.c_double(scale))
@@ -98,14 +102,20 @@ def walk_norms(q, k, w, beta, i):
     return n[: i + 1]
 
 
-def bwd(q, k, v, w, beta, dO, scale):
-    """Gradients of sum(dO * o) w.r.t. q, k, v, w, beta (same shapes)."""
+def bwd(q, k, v, w, beta, dO, scale, logf=None):
+    """Gradients of sum(dO * o) w.r.t. q, k, v, w, beta (same shapes) -- and, with gates
+    (PaTH-FoX, ``logf`` [B,H,L]), w.r.t. logf as a sixth result."""
     lib = _load()
     q, k, v, w, beta, dO = map(_f64, (q, k, v, w, beta, dO))
     B, H, L, d = q.shape
     outs = [np.empty_like(q) for _ in range(4)] + [np.empty((B, H, L), dtype=np.float64)]
-    lib.path_oracle_bwd(_p(q), _p(k), _p(v), _p(w), _p(beta), _p(dO),
-                        *[_p(x) for x in outs],
+    dlogf = None
+    if logf is not None:
+        logf = _f64(logf)
+        assert logf.shape == beta.shape
+        dlogf = np.empty((B, H, L), dtype=np.float64)
+    lib.path_oracle_bwd(_p(q), _p(k), _p(v), _p(w), _p(beta), _p(logf) if logf is not None else None, _p(dO),
+                        *[_p(x) for x in outs], _p(dlogf) if dlogf is not None else None,
                         ctypes.c_int(B), ctypes.c_int(H), ctypes.c_int(L),
                         ctypes.c_int(d), ctypes.c_double(scale))
-    return tuple(outs)
+    return tuple(outs) + ((dlogf,) if dlogf is not None else ())

@@ -130,6 +130,19 @@ path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const v
                             void* stream);
 
 /*
+ * PaTH-FoX (paper Sec. 2.2, "Extension: PaTH-FoX"): the attention weight of key j for query i
+ * gets the extra factor prod_{s=j+1..i} f_s of data-dependent forget gates f_s in (0,1), i.e.
+ * the logit becomes  scale * q_i^T H_i ... H_{j+1} k_j + sum_{s=j+1..i} log f_s.
+ * log_f [B,H,L] (dt, device, read-only) holds the LOG of the gates (<= 0); everything else as
+ * in path_attn_fwd, same workspace size.  lse is the log-sum-exp of the full logits.
+ */
+path_status_t path_attn_fox_fwd(const void* q, const void* k, const void* v, const void* w,
+                                const void* beta, const void* log_f, void* o, float* lse,
+                                int B, int H, int L, int d, int causal, float scale,
+                                path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                                void* stream);
+
+/*
  * Decode path (paper Sec. 3.4 "Efficient Inference").  Caches are caller-owned device memory,
  * kcache and vcache [B,H,Lmax,d] contiguous in the I/O type dt; position i of a head holds
  * token i.  The key cache holds REFRESHED keys: after t tokens, k_i^(t) = H_t ... H_{i+1} k_i

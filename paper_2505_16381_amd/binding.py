@@ -59,6 +59,8 @@ def load_library():
     lib.path_attn_fwd_sweep.argtypes = [vp, vp, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_attn_bwd.restype = ci
     lib.path_attn_bwd.argtypes = [vp] * 13 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_fox_fwd.restype = ci
+    lib.path_attn_fox_fwd.argtypes = [vp] * 8 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_decode_workspace_bytes.restype = sz
     lib.path_decode_workspace_bytes.argtypes = [ci, ci, ci]
     lib.path_key_prefill.restype = ci
@@ -212,4 +214,18 @@ def path_decode_step(q, k, v, w, beta, kcache, vcache, n, scale, workspace=None,
     _check(load_library().path_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(kcache), _ptr(vcache),
                                            int(n), kcache.shape[2], _ptr(o), _ptr(lse), B, H, d, float(scale), _dt_of(q),
                                            _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return o, lse
+
+
+def path_attn_fox_fwd(q, k, v, w, beta, log_f, scale=None, workspace=None, stream=None):
+    """PaTH-FoX forward: as path_attn_fwd with log_f [B,H,L], the log of the forget gates."""
+    import torch
+    B, H, L, d = q.shape
+    scale = float(d ** -0.5 if scale is None else scale)
+    dt = _dt_of(q)
+    o = torch.empty_like(q)
+    lse = torch.empty((B, H, L), dtype=torch.float32, device=q.device)
+    workspace = _workspace(path_attn_workspace_bytes(B, H, L, d, dt, False), q, workspace)
+    _check(load_library().path_attn_fox_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(log_f), _ptr(o), _ptr(lse),
+                                            B, H, L, d, 1, scale, dt, _ptr(workspace), workspace.numel(), _stream_handle(stream)))
     return o, lse

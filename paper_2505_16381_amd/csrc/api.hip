@@ -13,6 +13,7 @@ hipError_t launch_attn_states(const FwdParams& p, int d, int is_bf16, hipStream_
 }  // namespace path
 #include "bwd_decl.h"
 #include "decode_decl.h"
+#include "fox_decl.h"
 namespace path {
 
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -37,6 +38,7 @@ static FwdWorkspace fwd_workspace(int B, int H, int L, int d, size_t es) {
     const size_t NSB = (NC + SBC - 1) / SBC;
     w.kt2 = off;    off = align256(off + BH * Lp * d * es);
     w.dp2 = off;    off = align256(off + BH * NSB * d * d * es);
+    w.cum = off;    off = align256(off + BH * Lp * 4);          // PaTH-FoX: cumulative log2 gates
     w.total = off;
     return w;
 }
@@ -152,8 +154,16 @@ static path_status_t fwd_setup(FwdParams& p, int B, int H, int L, int d, path_dt
     p.sd = reinterpret_cast<float*>(base + ws.sd);
     p.kt2 = base + ws.kt2; p.dp2 = base + ws.dp2;
     p.dpt = nullptr;                                         // transposed -dP tile: backward only
+    p.cum = nullptr;                                         // set by the PaTH-FoX entry points
     p.B = B; p.H = H; p.L = L; p.NC = (L + CHUNK - 1) / CHUNK;
     return PATH_OK;
+}
+
+// PaTH-FoX: cum[t] = log2(e) * sum_{s<=t} log f_s per head, fp32, padded to whole chunks.
+static hipError_t launch_gate_sums(const void* log_f, float* cum, int B, int H, int L, path_dtype_t dt, hipStream_t st) {
+    const int Lp = ((L + CHUNK - 1) / CHUNK) * CHUNK;
+    ScanArgs a{log_f, cum, L, Lp, L, Lp, 1, 1.44269504088896340736f};
+    return launch_fox_scan(a, B * H, dt == PATH_BF16 ? 1 : 0, 0, st);
 }
 
 extern "C" path_status_t path_attn_fwd_prep(const void* q, const void* k, const void* v, const void* w,
@@ -203,6 +213,29 @@ extern "C" path_status_t path_attn_fwd(const void* q, const void* k, const void*
     path_status_t st = path_attn_fwd_prep(q, k, v, w, beta, B, H, L, d, dt, workspace, workspace_bytes, stream);
     if (st != PATH_OK) return st;
     return path_attn_fwd_sweep(o, lse, B, H, L, d, scale, dt, workspace, workspace_bytes, stream);
+}
+
+extern "C" path_status_t path_attn_fox_fwd(const void* q, const void* k, const void* v, const void* w,
+                                           const void* beta, const void* log_f, void* o, float* lse, int B, int H,
+                                           int L, int d, int causal, float scale, path_dtype_t dt, void* workspace,
+                                           size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !w || !beta || !log_f || !o || !lse || !workspace) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
+    if (!causal || !(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
+    if (misaligned(o)) return PATH_ERR_ALIGN;
+    path_status_t st = path_attn_fwd_prep(q, k, v, w, beta, B, H, L, d, dt, workspace, workspace_bytes, stream);
+    if (st != PATH_OK) return st;
+    FwdParams p = {};
+    st = fwd_setup(p, B, H, L, d, dt, workspace, workspace_bytes);
+    if (st != PATH_OK) return st;
+    const FwdWorkspace ws = fwd_workspace(B, H, L, d, dt == PATH_BF16 ? 2 : 4);
+    float* cum = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.cum);
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    if (!hip_ok(launch_gate_sums(log_f, cum, B, H, L, dt, hs), "gate sums")) return PATH_ERR_HIP;
+    p.o = o; p.lse = lse; p.scale = scale; p.cum = cum;
+    if (!hip_ok(launch_attn_fwd2(p, d, dt == PATH_BF16, hs), "forward sweep (PaTH-FoX)")) return PATH_ERR_HIP;
+    return PATH_OK;
 }
 
 extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const void* w,

@@ -31,7 +31,7 @@ template <typename TIO, int D> struct Fwd2Cfg {
     static constexpr int FE = Tr<T>::FE;
     static constexpr int HALF_FRAGS = 32 * D / FE;      // fragments of 32 keys of a key tile / V^T tile
     static constexpr int DP_FRAGS = D * D / FE;         // fragments per -dP tile
-    static constexpr size_t smem_bytes = (size_t)(4 * HALF_FRAGS + DP_FRAGS) * 16;   // 2 stages x (K|V) + dP
+    static constexpr size_t smem_bytes = (size_t)(4 * HALF_FRAGS + DP_FRAGS) * 16 + 256;   // 2 stages x (K|V) + dP + 2 x 32 gate sums
 };
 
 // Linear copy of nfrag 16-byte fragments global -> LDS, asynchronous (direct-to-LDS):
@@ -48,7 +48,10 @@ __device__ __forceinline__ void wait_tiles_and_sync() {
     __syncthreads();
 }
 
-template <typename TIO, int D>
+// FOX (PaTH-FoX, paper Sec. 2.2 extension): the logit of key j gets - c_j (c = cumulative log of the
+// forget gates, here in base-2 units); the query's own + c_i cancels in the softmax and is added
+// to the log-sum-exp at the end.
+template <typename TIO, int D, bool FOX>
 __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p) {
     using C = Fwd2Cfg<TIO, D>;
     using T = typename C::T;
@@ -63,6 +66,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     Frag* sKV = reinterpret_cast<Frag*>(smem);                  // [2 stages][K half | V half]
     Frag* sP = sKV + 4 * HF;                                    // -dP tile
+    float* sC = reinterpret_cast<float*>(sP + DPF);             // FOX: [2 stages][32] gate sums of the stage's keys
 
     const int BH = p.B * p.H, L = p.L, NC = p.NC;
     const int ntiles = (NC + 1) / 2;
@@ -116,6 +120,9 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
         const T* kg = (j >= jsb ? ktg : kt2g) + (size_t)j * CHUNK * D;
         async_tile(reinterpret_cast<const Frag*>(kg) + kb * HF, buf, HF, tid, wv);
         async_tile(reinterpret_cast<const Frag*>(vtg + (size_t)j * CHUNK * D) + kb * HF, buf + HF, HF, tid, wv);
+        if (FOX && tid < 8)      // 32 floats, 16 bytes per lane
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.cum + (size_t)bh * NC * CHUNK + (size_t)j * CHUNK + 32 * kb + 4 * tid),
+                                             (__attribute__((address_space(3))) void*)(sC + (u & 1) * 32), 16, 0, 0);
     };
     // the product applied after chunk j (if any): loaded while the chunk's first half is
     // processed (sP is free then: the previous update ended before this stage's barrier)
@@ -165,12 +172,22 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
         {
             f32x16 E;
             float rs = 0.f;
+            if (FOX) {            // T = logit in base-2 units minus the key's gate sum; then as below with scale 1
+                const float* ck = sC + (u & 1) * 32 + 4 * h;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    const f32x4 c4 = *reinterpret_cast<const f32x4*>(ck + 8 * g);
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) S[4 * g + r] = __builtin_fmaf(S[4 * g + r], sl2, -c4[r]);
+                }
+            }
+            const float sl = FOX ? 1.f : sl2;
             bool slow = j == cq && kb == 0;             // first block of this wave: no reference yet
             if (!slow) {
                 const float mneg = -m_run;
 #pragma unroll
                 for (int jj = 0; jj < 16; ++jj) {
-                    E[jj] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, mneg));
+                    E[jj] = __builtin_amdgcn_exp2f(FOX ? S[jj] + mneg : __builtin_fmaf(S[jj], sl2, mneg));
                     rs += E[jj];
                 }
                 slow = __builtin_amdgcn_ballot_w64(!(rs < 65536.f)) != 0;
@@ -179,7 +196,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
                 float mloc = fmaxf(S[0], S[1]);
 #pragma unroll
                 for (int jj = 2; jj < 16; jj += 2) mloc = fmaxf(mloc, fmaxf(S[jj], S[jj + 1]));
-                mloc = fmaxf(mloc, __shfl_xor(mloc, 32)) * sl2;
+                mloc = fmaxf(mloc, __shfl_xor(mloc, 32)) * sl;
                 const float m_new = fmaxf(m_run, mloc);     // finite: the first block holds the diagonal
                 const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);
                 m_run = m_new;
@@ -191,7 +208,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
                 rs = 0.f;
 #pragma unroll
                 for (int jj = 0; jj < 16; ++jj) {
-                    E[jj] = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -m_new));
+                    E[jj] = __builtin_amdgcn_exp2f(FOX ? S[jj] - m_new : __builtin_fmaf(S[jj], sl2, -m_new));
                     rs += E[jj];
                 }
             }
@@ -246,16 +263,17 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
                 for (int r = 0; r < 4; ++r) v4[r] = (TIO)(O[b][4 * g + r] * inv);
                 *reinterpret_cast<Vec4*>(orow + 32 * b + 8 * g) = v4;
             }
-        if (h == 0) p.lse[(size_t)bh * L + tq] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+        const float ci = FOX ? p.cum[(size_t)bh * NC * CHUNK + tq] : 0.f;
+        if (h == 0) p.lse[(size_t)bh * L + tq] = (m_run + __builtin_amdgcn_logf(l_tot) + ci) * 0.69314718055994530942f;
     }
 }
 
-template <typename TIO, int D>
-hipError_t launch_attn_fwd2_t(const FwdParams& p, hipStream_t stream) {
+template <typename TIO, int D, bool FOX>
+hipError_t launch_attn_fwd2_f(const FwdParams& p, hipStream_t stream) {
     using C = Fwd2Cfg<TIO, D>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd2_kernel<TIO, D>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd2_kernel<TIO, D, FOX>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -264,8 +282,12 @@ hipError_t launch_attn_fwd2_t(const FwdParams& p, hipStream_t stream) {
     const int BH = p.B * p.H;
     dim3 grid((unsigned)(((BH + 7) / 8) * 8 * ntiles));
     const size_t bytes = C::smem_bytes;
-    hipLaunchKernelGGL((attn_fwd2_kernel<TIO, D>), grid, dim3(FWD2_THREADS), bytes, stream, p);
+    hipLaunchKernelGGL((attn_fwd2_kernel<TIO, D, FOX>), grid, dim3(FWD2_THREADS), bytes, stream, p);
     return hipGetLastError();
+}
+template <typename TIO, int D>
+hipError_t launch_attn_fwd2_t(const FwdParams& p, hipStream_t stream) {
+    return p.cum ? launch_attn_fwd2_f<TIO, D, true>(p, stream) : launch_attn_fwd2_f<TIO, D, false>(p, stream);
 }
 
 hipError_t launch_attn_fwd2(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {

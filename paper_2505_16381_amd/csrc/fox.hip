@@ -1,0 +1,50 @@
+// PaTH-FoX helper (paper Sec. 2.2, "Extension: PaTH-FoX"): the gate product prod_{s=j+1..i} f_s
+// enters the logit as c_i - c_j with c_t = sum_{s<=t} log f_s.  One kernel does both scans that
+// the forward and the backward need, per head, in fp32:
+//   forward:  cum[t]   = scale_out * sum_{s<=t} x[s]      (inclusive; x = log f, scale_out = log2 e)
+//   backward: dlogf[s] = sum_{t<s} y[t]                   (exclusive; y = column sums of the logit gradient)
+// One workgroup per head; a thread owns a contiguous run of the row.
+#include "path_common.h"
+#include "fox_decl.h"
+
+namespace path {
+
+template <typename TIN, typename TOUT>
+__global__ __launch_bounds__(256) void fox_scan_kernel(ScanArgs a) {
+    __shared__ float part[256];
+    const int bh = blockIdx.x, tid = threadIdx.x;
+    const int per = (a.n_out + 255) / 256;
+    const int t0 = tid * per, t1 = (t0 + per < a.n_out) ? t0 + per : a.n_out;
+    const TIN* x = reinterpret_cast<const TIN*>(a.in) + (size_t)bh * a.in_stride;
+    TOUT* y = reinterpret_cast<TOUT*>(a.out) + (size_t)bh * a.out_stride;
+    float s = 0.f;
+    for (int t = t0; t < t1; ++t) s += (t < a.n_in) ? (float)x[t] : 0.f;
+    part[tid] = s;
+    __syncthreads();
+    // exclusive scan of the 256 partial sums (Hillis-Steele on a copy)
+    float run = s;
+    for (int off = 1; off < 256; off <<= 1) {
+        const float other = (tid >= off) ? part[tid - off] : 0.f;
+        __syncthreads();
+        run += other;
+        part[tid] = run;
+        __syncthreads();
+    }
+    float acc = run - s;                       // sum of everything before this thread's run
+    for (int t = t0; t < t1; ++t) {
+        const float v = (t < a.n_in) ? (float)x[t] : 0.f;
+        if (a.inclusive) { acc += v; y[t] = (TOUT)(acc * a.scale_out); }
+        else { y[t] = (TOUT)(acc * a.scale_out); acc += v; }
+    }
+}
+
+hipError_t launch_fox_scan(const ScanArgs& a, int BH, int in_type, int out_type, hipStream_t st) {
+    // types: 0 = float, 1 = bf16
+    if (in_type == 0 && out_type == 0) hipLaunchKernelGGL((fox_scan_kernel<float, float>), dim3(BH), dim3(256), 0, st, a);
+    else if (in_type == 1 && out_type == 0) hipLaunchKernelGGL((fox_scan_kernel<bf16_t, float>), dim3(BH), dim3(256), 0, st, a);
+    else if (in_type == 0 && out_type == 1) hipLaunchKernelGGL((fox_scan_kernel<float, bf16_t>), dim3(BH), dim3(256), 0, st, a);
+    else hipLaunchKernelGGL((fox_scan_kernel<bf16_t, bf16_t>), dim3(BH), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace path

@@ -1,0 +1,16 @@
+// Scan kernel of the PaTH-FoX extension.
+#pragma once
+#include "path_common.h"
+
+namespace path {
+
+struct ScanArgs {
+    const void* in;      // [BH][in_stride], first n_in entries of a row are read (the rest count as zero)
+    void* out;           // [BH][out_stride], first n_out entries of a row are written
+    int in_stride, out_stride, n_in, n_out;
+    int inclusive;
+    float scale_out;
+};
+hipError_t launch_fox_scan(const ScanArgs& a, int BH, int in_type, int out_type, hipStream_t st);   // types: 0 float, 1 bf16
+
+}  // namespace path

@@ -210,7 +210,7 @@ __device__ __forceinline__ f32x16 transpose32(const typename Tr<T>::Frag* a, con
 
 // Workspace carve-up shared by host launch code and kernels (byte offsets, 256-aligned).
 struct FwdWorkspace {
-    size_t kt, vt, dp, xinit, sd, kt2, dp2, total;
+    size_t kt, vt, dp, xinit, sd, kt2, dp2, cum, total;
 };
 
 struct FwdParams {
@@ -221,6 +221,7 @@ struct FwdParams {
     void *kt2, *dp2;      // second level: keys carried to their super-block's right edge; -(I - P_superblock)
     void *dpt;            // backward only: -dP per chunk in the transposed arrangement (rows a, contraction b) = -dP[a][b]
     float *xinit, *sd;    // accumulator-order fp32 tiles
+    const float* cum;     // PaTH-FoX only (else NULL): [BH][64*NC] cumulative log2 of the forget gates, log2(e) * sum_{s<=t} log f_s
     int B, H, L, NC;      // NC = number of 64-token chunks = ceil(L/64)
     float scale;
     // Backward only (NULL in the forward), all in fragment order:

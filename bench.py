@@ -126,6 +126,58 @@ def bench_decode(args, torch, pa, si, dev):
     print(json.dumps(out))
 
 
+def bench_fox(args, torch, pa, si, dev):
+    """PaTH-FoX (forget gates on the logits, paper Sec. 2.2 extension) forward + backward at the
+    chosen configuration's shape; same FLOP convention as the headline line."""
+    cfg = dict(si.CONFIGS[args.config])
+    if args.shape:
+        cfg.update(dict(zip(("B", "H", "L", "d"), (int(v) for v in args.shape.split(",")))))
+    B, H, L, d = cfg["B"], cfg["H"], cfg["L"], cfg["d"]
+    g = torch.Generator(device="cuda").manual_seed(20250516)
+    rn = lambda *shape: torch.randn(*shape, device=dev, generator=g)
+    q, k, v, dO = (rn(B, H, L, d).to(torch.bfloat16) for _ in range(4))
+    w = torch.nn.functional.normalize(rn(B, H, L, d), dim=-1).to(torch.bfloat16)
+    beta = (2 * torch.sigmoid(rn(B, H, L))).to(torch.bfloat16)
+    logf = torch.nn.functional.logsigmoid(rn(B, H, L) + 2.0).to(torch.bfloat16)
+    ws_f = torch.empty(pa.path_attn_workspace_bytes(B, H, L, d, pa.PATH_BF16, False), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(pa.path_attn_workspace_bytes(B, H, L, d, pa.PATH_BF16, True), dtype=torch.uint8, device=dev)
+    scale = d ** -0.5
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    marks = []
+
+    def step(record):
+        e0, e1, e2 = (ev(), ev(), ev()) if record else (None,) * 3
+        if record: e0.record()
+        o, lse = pa.path_attn_fox_fwd(q, k, v, w, beta, logf, scale=scale, workspace=ws_f)
+        if record: e1.record()
+        pa.path_attn_fox_bwd(q, k, v, w, beta, logf, o, lse, dO, scale=scale, workspace=ws_b)
+        if record:
+            e2.record()
+            marks.append((e0, e1, e2))
+
+    for _ in range(args.warmup):
+        step(False)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(True)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    fwd_ms = sum(a.elapsed_time(b) for a, b, _ in marks) / len(marks)
+    bwd_ms = sum(b.elapsed_time(c) for _, b, c in marks) / len(marks)
+    fl = attn_flops(B, H, L, d)
+    value = 3.5 * fl / (ms_step * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "PaTH-FoX attn fwd+bwd TFLOP/s (attention-equivalent)", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 I/O, fp16+bf16 MFMA operands, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": f"PaTH-FoX forward+backward, B={B} H={H} L={L} d={d} causal"},
+        "fwd": {"ms": fwd_ms, "attn_equiv_tflops": fl / (fwd_ms * 1e-3) / 1e12},
+        "bwd": {"ms": bwd_ms, "attn_equiv_tflops": 2.5 * fl / (bwd_ms * 1e-3) / 1e12},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -135,7 +187,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fwd-only", action="store_true")
     ap.add_argument("--shape", type=str, default=None, help="override B,H,L,d of the chosen configuration (exploration only)")
-    ap.add_argument("--workload", choices=["train", "decode"], default="train",
+    ap.add_argument("--workload", choices=["train", "decode", "fox"], default="train",
                     help="train (default): the headline forward+backward step; decode: one decoding step "
                          "(in-place key-cache refresh + attention) over a cache of L tokens, its own JSON line")
     args = ap.parse_args()
@@ -154,6 +206,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.workload == "decode":
         return bench_decode(args, torch, pa, si, dev)
+    if args.workload == "fox":
+        return bench_fox(args, torch, pa, si, dev)
     over = {}
     if args.shape:
         over = dict(zip(("B", "H", "L", "d"), (int(v) for v in args.shape.split(","))))

@@ -142,6 +142,15 @@ path_status_t path_attn_fox_fwd(const void* q, const void* k, const void* v, con
                                 path_dtype_t dt, void* workspace, size_t workspace_bytes,
                                 void* stream);
 
+/* Backward of path_attn_fox_fwd: as path_attn_bwd, plus dlog_f [B,H,L] (dt), the gradient with
+ * respect to log_f (entry 0 of every head is exactly 0: the first gate lies on no path).
+ * Same workspace size as path_attn_bwd. */
+path_status_t path_attn_fox_bwd(const void* q, const void* k, const void* v, const void* w,
+                                const void* beta, const void* log_f, const void* o, const float* lse,
+                                const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                void* dlog_f, int B, int H, int L, int d, int causal, float scale,
+                                path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+
 /*
  * Decode path (paper Sec. 3.4 "Efficient Inference").  Caches are caller-owned device memory,
  * kcache and vcache [B,H,Lmax,d] contiguous in the I/O type dt; position i of a head holds

@@ -61,6 +61,8 @@ def load_library():
     lib.path_attn_bwd.argtypes = [vp] * 13 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_attn_fox_fwd.restype = ci
     lib.path_attn_fox_fwd.argtypes = [vp] * 8 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_fox_bwd.restype = ci
+    lib.path_attn_fox_bwd.argtypes = [vp] * 15 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_decode_workspace_bytes.restype = sz
     lib.path_decode_workspace_bytes.argtypes = [ci, ci, ci]
     lib.path_key_prefill.restype = ci
@@ -229,3 +231,17 @@ def path_attn_fox_fwd(q, k, v, w, beta, log_f, scale=None, workspace=None, strea
     _check(load_library().path_attn_fox_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(log_f), _ptr(o), _ptr(lse),
                                             B, H, L, d, 1, scale, dt, _ptr(workspace), workspace.numel(), _stream_handle(stream)))
     return o, lse
+
+
+def path_attn_fox_bwd(q, k, v, w, beta, log_f, o, lse, d_o, scale=None, workspace=None, stream=None):
+    """PaTH-FoX backward: returns (dq, dk, dv, dw, dbeta, dlog_f)."""
+    import torch
+    B, H, L, d = q.shape
+    scale = float(d ** -0.5 if scale is None else scale)
+    dt = _dt_of(q)
+    outs = [torch.empty_like(q) for _ in range(4)] + [torch.empty_like(beta), torch.empty_like(log_f)]
+    workspace = _workspace(path_attn_workspace_bytes(B, H, L, d, dt, True), q, workspace)
+    _check(load_library().path_attn_fox_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(log_f), _ptr(o), _ptr(lse), _ptr(d_o),
+                                            *[_ptr(x) for x in outs], B, H, L, d, 1, scale, dt,
+                                            _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return tuple(outs)

@@ -47,6 +47,7 @@ struct BwdWorkspace {
     FwdWorkspace f;
     size_t ktT, vk, dpt, doq, doT, xs, xsT, gs, fm, gktm, nm, aim, ytm, utm, gm, sdm, delta, lse2p, dqb, dkb, dvp, ddp;
     size_t kt2T, dpt2, kbm, rm, dk2, dchain, t1;       // second level and its adjoint
+    size_t dcol, drow;                                 // PaTH-FoX: column and row sums of the logit gradient
     size_t dpd, pd, dsd, df, dy, dn, dgk, rr, mm, dgs, du, dqf, dkf, dwf, dbf, total;
 };
 
@@ -67,6 +68,8 @@ static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
     take(w.dk2, BH * Lp * d * 4);
     take(w.dchain, BH * (NC + 1) * d * d * 4);
     take(w.t1, BH * NC * d * CHUNK * 4);
+    take(w.dcol, BH * Lp * 4);
+    take(w.drow, BH * Lp * 4);
     for (size_t* f : {&w.fm, &w.gktm, &w.nm, &w.aim, &w.ytm}) take(*f, BH * NC * 4096 * es);
     take(w.utm, BH * NC * d * CHUNK * es);
     take(w.gm, BH * NC * 4096 * 4);
@@ -162,7 +165,7 @@ static path_status_t fwd_setup(FwdParams& p, int B, int H, int L, int d, path_dt
 // PaTH-FoX: cum[t] = log2(e) * sum_{s<=t} log f_s per head, fp32, padded to whole chunks.
 static hipError_t launch_gate_sums(const void* log_f, float* cum, int B, int H, int L, path_dtype_t dt, hipStream_t st) {
     const int Lp = ((L + CHUNK - 1) / CHUNK) * CHUNK;
-    ScanArgs a{log_f, cum, L, Lp, L, Lp, 1, 1.44269504088896340736f};
+    ScanArgs a{log_f, nullptr, cum, L, Lp, L, Lp, 1, 1.44269504088896340736f};
     return launch_fox_scan(a, B * H, dt == PATH_BF16 ? 1 : 0, 0, st);
 }
 
@@ -238,13 +241,15 @@ extern "C" path_status_t path_attn_fox_fwd(const void* q, const void* k, const v
     return PATH_OK;
 }
 
-extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const void* w,
-                                       const void* beta, const void* o, const float* lse, const void* d_o,
-                                       void* dq, void* dk, void* dv, void* dw, void* dbeta, int B, int H,
-                                       int L, int d, int causal, float scale, path_dtype_t dt,
-                                       void* workspace, size_t workspace_bytes, void* stream) {
+// Backward of plain PaTH (log_f == NULL) and of PaTH-FoX (log_f, dlog_f given).
+static path_status_t bwd_impl(const void* q, const void* k, const void* v, const void* w,
+                              const void* beta, const void* log_f, const void* o, const float* lse, const void* d_o,
+                              void* dq, void* dk, void* dv, void* dw, void* dbeta, void* dlog_f, int B, int H,
+                              int L, int d, int causal, float scale, path_dtype_t dt,
+                              void* workspace, size_t workspace_bytes, void* stream) {
     if (!q || !k || !v || !w || !beta || !o || !lse || !d_o || !dq || !dk || !dv || !dw || !dbeta || !workspace)
         return PATH_ERR_NULL;
+    if ((log_f == nullptr) != (dlog_f == nullptr)) return PATH_ERR_NULL;
     if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
     if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
     if (!causal || !(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
@@ -272,6 +277,11 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     fp.fm = base + ws.fm; fp.gktm = base + ws.gktm; fp.nm = base + ws.nm; fp.aim = base + ws.aim;
     fp.ytm = base + ws.ytm; fp.utm = base + ws.utm; fp.gm = F(ws.gm); fp.sdm = F(ws.sdm);
     clear_inherited_error();
+    float* cum = nullptr;
+    if (log_f) {
+        cum = F(ws.f.cum);
+        if (!hip_ok(launch_gate_sums(log_f, cum, B, H, L, dt, st), "gate sums (backward)")) return PATH_ERR_HIP;
+    }
     if (!hip_ok(launch_prep_fwd(fp, d, bf, st), "chunk transform (backward)")) return PATH_ERR_HIP;
     if (!hip_ok(launch_prep2_fwd(fp, d, bf, st), "second-level transform (backward)")) return PATH_ERR_HIP;
     if (NC > 1 && !hip_ok(launch_attn_states(fp, d, bf, st), "query states")) return PATH_ERR_HIP;
@@ -284,6 +294,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     bp.doq = base + ws.doq; bp.doT = base + ws.doT; bp.gs = base + ws.gs;
     bp.delta = F(ws.delta); bp.lse2p = F(ws.lse2p); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
     bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale;
+    bp.cum = cum; bp.dcol = cum ? F(ws.dcol) : nullptr; bp.drow = cum ? F(ws.drow) : nullptr;
     if (!hip_ok(launch_bwd_scan(bp, d, bf, st), "backward pair kernels")) return PATH_ERR_HIP;
 
     // 5. adjoint of the chunk transform
@@ -378,7 +389,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
         chain_open = !last;
     };
     auto special = [&](int kind) { pr.ops[pr.n++].kind = (unsigned char)kind; };
-    pr.diag = DiagArgs{fp.sdm, dpd, bp.delta, lse, pd, dsd, L, NC, scale};
+    pr.diag = DiagArgs{fp.sdm, dpd, bp.delta, lse, pd, dsd, L, NC, scale, bp.cum, bp.dcol, bp.drow};
     pr.beta = BetaArgs{rr, mm, fp.gm, beta, dgs, dbf, L, NC};
     pr.out = OutArgs{dqf, dkf, dvp, dwf, dbf, dq, dk, dv, dw, dbeta, L, NC, d};
 
@@ -410,6 +421,13 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
     special(OP_STORE);                                                                                         // to the I/O dtype
     if (chain_open || pr.n > MAX_CHUNK_OPS) return PATH_ERR_HIP;
     ok = hip_ok(launch_chunk_adjoint(pr, BH, bf, st), "chunk-transform adjoint");
+    if (ok && log_f) {
+        // dlog f_s = sum over the pairs j < s <= i of the logit gradient = (column sums left of s) - (row sums
+        // above s).  The row sums vanish in exact arithmetic; subtracting them as computed removes the error that
+        // delta = dO . o (o rounded to the I/O type) puts into every row, which the prefix sum would pile up.
+        ScanArgs sa{bp.dcol, bp.drow, dlog_f, (int)Lp, L, L, L, 0, 1.f};
+        ok = hip_ok(launch_fox_scan(sa, BH, 0, bf ? 1 : 0, st), "gate gradient");
+    }
     return ok ? PATH_OK : PATH_ERR_HIP;
 }
 
@@ -458,4 +476,23 @@ extern "C" path_status_t path_decode_step(const void* q, const void* k, const vo
     if (!hip_ok(launch_decode_step(a, B * H, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "decode step"))
         return PATH_ERR_HIP;
     return PATH_OK;
+}
+
+extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const void* w,
+                                       const void* beta, const void* o, const float* lse, const void* d_o,
+                                       void* dq, void* dk, void* dv, void* dw, void* dbeta, int B, int H,
+                                       int L, int d, int causal, float scale, path_dtype_t dt,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+    return bwd_impl(q, k, v, w, beta, nullptr, o, lse, d_o, dq, dk, dv, dw, dbeta, nullptr, B, H, L, d, causal, scale, dt,
+                    workspace, workspace_bytes, stream);
+}
+
+extern "C" path_status_t path_attn_fox_bwd(const void* q, const void* k, const void* v, const void* w,
+                                           const void* beta, const void* log_f, const void* o, const float* lse,
+                                           const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                           void* dlog_f, int B, int H, int L, int d, int causal, float scale,
+                                           path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!log_f || !dlog_f) return PATH_ERR_NULL;
+    return bwd_impl(q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
+                    workspace, workspace_bytes, stream);
 }

@@ -45,7 +45,9 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(BwdParams p) {
     s += __shfl_xor(s, 2);
     if (part == 0) {
         p.delta[(size_t)bh * p.NC * CHUNK + tg] = s;
-        p.lse2p[(size_t)bh * p.NC * CHUNK + tg] = (tg < p.L) ? p.lse[(size_t)bh * p.L + tg] * 1.44269504088896340736f : 0.f;
+        // log-sum-exp in base-2 units; with gates (PaTH-FoX) minus the query's own gate sum, so that
+        // P = exp2(scale2 * s - c_key - lse2p)
+        p.lse2p[(size_t)bh * p.NC * CHUNK + tg] = (tg < p.L) ? p.lse[(size_t)bh * p.L + tg] * 1.44269504088896340736f - (p.cum ? p.cum[(size_t)bh * p.NC * CHUNK + tg] : 0.f) : 3.0e38f;      // rows past L: P = exp2(-huge) = 0
     }
 }
 
@@ -104,7 +106,7 @@ template <typename TIO, int D> struct Adj2Cfg {
     static constexpr size_t smem_bytes = (size_t)NBUF * STAGE_FRAGS * 16;
 };
 
-template <typename TIO, int D>
+template <typename TIO, int D, bool FOX>
 __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     using C = Adj2Cfg<TIO, D>;
     using T = typename C::T;
@@ -138,11 +140,12 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     // resident: dO fragments of the wave's 32 queries, lse and delta of the lane's query
     FragV dOb[DS];
     float lse2 = 0.f, dl = 0.f;
+    float drow = 0.f;       // PaTH-FoX: this query's row sum of the logit gradient (off-diagonal part)
     if (active) {
         const FragV* dq = reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.doq) + ((size_t)bh * NC + cq) * CHUNK * D);
 #pragma unroll
         for (int s = 0; s < DS; ++s) dOb[s] = dq[((size_t)qb * DS + s) * 64 + lane];
-        if (tq < L) lse2 = p.lse[(size_t)bh * L + tq] * 1.44269504088896340736f;
+        if (tq < L) lse2 = p.lse2p[(size_t)bh * Lp + tq];       // base-2 units (PaTH-FoX: minus the query's gate sum)
         dl = p.delta[(size_t)bh * Lp + tq];
     }
     f32x16 Gm[DB];
@@ -234,10 +237,19 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
                     dP = Tr<TIO>::mma(va[u], dOb[s0 + u], dP);
                 }
             }
+            f32x4 ck4[4];
+            if (FOX) {      // gate sums of the 16 keys this lane holds (rows 8g + 4h + r of the 32-key block)
+                const float* ck = p.cum + (size_t)bh * Lp + (size_t)j * CHUNK + 32 * kb + 4 * h;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) ck4[g] = *reinterpret_cast<const f32x4*>(ck + 8 * g);
+            }
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj) {
-                const float P = (tq < L) ? __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -lse2)) : 0.f;
-                S[jj] = P * (dP[jj] - dl) * p.scale;
+                const float arg = __builtin_fmaf(S[jj], sl2, -lse2) - (FOX ? ck4[jj >> 2][jj & 3] : 0.f);
+                const float P = (tq < L) ? __builtin_amdgcn_exp2f(arg) : 0.f;
+                const float dz = P * (dP[jj] - dl);
+                if (FOX) drow += dz;
+                S[jj] = dz * p.scale;
             }
             pack_block<T>(S, dSb + kb * SPB);
             if (spread) issue(j + 1, 1 + kb);
@@ -279,6 +291,10 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
             }
         }
     }
+    if (FOX && active) {    // the two half-waves hold different keys of the same query
+        drow += __shfl_xor(drow, 32);
+        if (h == 0) p.drow[(size_t)bh * Lp + tq] = drow;
+    }
     // dQb of the wave's queries: row-major fp32 [q][c] from registers (rows c, lane q)
     if (active) {
         float* dst = p.dqb + ((size_t)bh * Lp + tq) * D + 4 * h;
@@ -312,11 +328,11 @@ template <typename TIO, int D> struct Key2Cfg {
     static constexpr int NBUF = (sizeof(T) == 2) ? 2 : 1;                     // fp32 tiles are too big to double-buffer
     static constexpr int STAGE_FRAGS = 4 * KV_FRAGS + 32;                     // xs | xsT | doq | doT | lse2 | delta
     static constexpr size_t tile_bytes = (size_t)NBUF * STAGE_FRAGS * 16;
-    static constexpr size_t red_bytes = (size_t)2 * 2 * (D / 32) * 1024 * 4;   // dV, dKb of the two upper waves
+    static constexpr size_t red_bytes = (size_t)2 * 2 * (D / 32) * 1024 * 4 + 256;   // dV, dKb (and FOX column sums) of the two upper waves
     static constexpr size_t smem_bytes = tile_bytes > red_bytes ? tile_bytes : red_bytes;
 };
 
-template <typename TIO, int D, bool FAR>
+template <typename TIO, int D, bool FAR, bool FOX>
 __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     using C = Key2Cfg<TIO, D>;
     using T = typename C::T;
@@ -364,6 +380,10 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     f32x16 dVt[DB], dKt[DB];
 #pragma unroll
     for (int b = 0; b < DB; ++b) { dVt[b] = zero16(); dKt[b] = zero16(); }
+    // PaTH-FoX: this lane's key has gate sum ckj; dcol collects the column sum of the logit gradient
+    const int key_tok = (wactive ? jw : j) * CHUNK + 32 * kh + l32;
+    const float ckj = FOX ? p.cum[(size_t)bh * Lp + key_tok] : 0.f;
+    float dcol = 0.f;
 
     // all operands of query chunk i, asynchronously, into stage buffer (i & (NBUF-1))
     // part = -1: everything; 0..3: one tile each (the requests for the next chunk are spread over
@@ -423,8 +443,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 }
             }
             if (spread) issue(i + 1, qq == 0 ? 1 : 3);
-            // Rows past L need no mask: their state, dO and delta are zero and lse2p is zero, so
-            // P = 1 meets dO = 0 in dV and dS = P (0 - 0) = 0.
+            // Rows past L need no mask: their padded lse2p is huge, so P = exp2(-huge) = 0.
             f32x4 ls[4], dls[4];
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
@@ -434,9 +453,11 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
             f32x16 Pm;
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj) {
-                const float P = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -ls[jj >> 2][jj & 3]));
+                const float P = __builtin_amdgcn_exp2f(__builtin_fmaf(S[jj], sl2, -ls[jj >> 2][jj & 3]) - ckj);
                 Pm[jj] = P;
-                S[jj] = P * (dP[jj] - dls[jj >> 2][jj & 3]) * p.scale;
+                const float dz = P * (dP[jj] - dls[jj >> 2][jj & 3]);
+                if (FOX) dcol += dz;
+                S[jj] = dz * p.scale;
             }
             FragV Pb[SPB];
             Frag dSb[SPB];
@@ -464,6 +485,10 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
         // each wave holds the complete sums of its 32 keys: write row-major fp32 [s][c] from
         // registers (rows c, lane s); dV is added to the near part
         if (!wactive) return;
+        if (FOX) {           // the two half-waves hold different query rows of the same keys
+            dcol += __shfl_xor(dcol, 32);
+            if (h == 0) p.dcol[(size_t)bh * Lp + key_tok] += dcol;      // added to the near part
+        }
         const size_t row = ((size_t)bh * Lp + jw * CHUNK + 32 * kh + l32) * D + 4 * h;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
@@ -481,6 +506,8 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     // sum the two query halves, write row-major fp32 [s][c] from registers (rows c, lane s)
     __syncthreads();
     float* red = reinterpret_cast<float*>(smem);
+    float* redc = red + 2 * 2 * DB * 1024;       // FOX: column sums of the upper waves
+    if (FOX) dcol += __shfl_xor(dcol, 32);
     if (qh == 1) {
 #pragma unroll
         for (int b = 0; b < DB; ++b)
@@ -489,8 +516,10 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 red[((kh * 2 + 0) * DB + b) * 1024 + jj * 64 + lane] = dVt[b][jj];
                 red[((kh * 2 + 1) * DB + b) * 1024 + jj * 64 + lane] = dKt[b][jj];
             }
+        if (FOX && h == 0) redc[kh * 32 + l32] = dcol;
     }
     __syncthreads();
+    if (FOX && qh == 0 && h == 0) p.dcol[(size_t)bh * Lp + key_tok] = dcol + redc[kh * 32 + l32];
     if (qh == 0) {
         const size_t row = ((size_t)bh * Lp + j * CHUNK + 32 * kh + l32) * D + 4 * h;
 #pragma unroll
@@ -862,17 +891,36 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
 // ---------------------------------------------------------------------------------------
 // Element-wise steps of the chunk-transform adjoint (device functions of the fused kernel).
 // Diagonal block: P = exp(scale*Sd - lse) on key <= query, dSd = scale * P (dPd - delta).
-__device__ __forceinline__ void chunk_diag(const DiagArgs& a, int chunk, int bh, int tid) {
+template <bool FOX>
+__device__ __forceinline__ void chunk_diag(const DiagArgs& a, float* colsum, int chunk, int bh, int tid) {
     const size_t base = ((size_t)bh * a.NC + chunk) * 4096;
+    if (FOX) {
+        if (tid < 2 * CHUNK) colsum[tid] = 0.f;
+        __syncthreads();
+    }
     for (int idx = tid; idx < 4096; idx += 256) {
         const int t = idx >> 6, s = idx & 63, tg = chunk * CHUNK + t;
         float P = 0.f, ds = 0.f;
         if (s <= t && tg < a.L) {
-            P = __expf(a.scale * a.sdm[base + idx] - a.lse[(size_t)bh * a.L + tg]);
-            ds = a.scale * P * (a.dpd[base + idx] - a.delta[(size_t)bh * a.NC * CHUNK + tg]);
+            float z = a.scale * a.sdm[base + idx] - a.lse[(size_t)bh * a.L + tg];
+            if (FOX) {     // PaTH-FoX: + c_t - c_s (the gate sums are kept in base-2 units)
+                const float* c = a.cum + (size_t)bh * a.NC * CHUNK + (size_t)chunk * CHUNK;
+                z += (c[t] - c[s]) * 0.69314718055994530942f;
+            }
+            P = __expf(z);
+            const float dz = P * (a.dpd[base + idx] - a.delta[(size_t)bh * a.NC * CHUNK + tg]);
+            ds = a.scale * dz;
+            if (FOX) { atomicAdd(colsum + s, dz); atomicAdd(colsum + CHUNK + t, dz); }      // LDS: column and row sums of the block
         }
         a.pd[base + idx] = P;
         a.dsd[base + idx] = ds;
+    }
+    if (FOX) {
+        __syncthreads();
+        if (tid < CHUNK) {
+            a.dcol[(size_t)bh * a.NC * CHUNK + (size_t)chunk * CHUNK + tid] += colsum[tid];
+            a.drow[(size_t)bh * a.NC * CHUNK + (size_t)chunk * CHUNK + tid] += colsum[CHUNK + tid];
+        }
     }
 }
 
@@ -916,7 +964,8 @@ __device__ __forceinline__ void chunk_store(const OutArgs& a, int chunk, int bh,
 // The fused adjoint of the chunk transform: one workgroup per (chunk, head) runs the program.
 // Results that later steps read go through global memory (they stay in L2); a chain of
 // products that add into the same result keeps it in accumulator registers.
-template <typename TIO>
+// FOX: the diagonal-block step also applies the gate sums and collects row/column sums (PaTH-FoX).
+template <typename TIO, bool FOX>
 __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) {
     typedef typename Compute<TIO>::type T;
     constexpr int FE = Tr<T>::FE, KW = Tr<T>::KW;
@@ -927,7 +976,7 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
     for (int i = 0; i < pr.n; ++i) {
         const ChunkOp& op = pr.ops[i];
         __syncthreads();       // earlier steps' results are visible to the whole workgroup; LDS is free
-        if (op.kind == OP_DIAG) { chunk_diag(pr.diag, chunk, bh, tid); continue; }
+        if (op.kind == OP_DIAG) { chunk_diag<FOX>(pr.diag, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
         if (op.kind == OP_BETA) { chunk_beta<TIO>(pr.beta, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
         if (op.kind == OP_STORE) { chunk_store<TIO>(pr.out, chunk, bh, tid); continue; }
         // M = 64 for every product of the list; N = 64 or 128.  Results are handled in halves of 64
@@ -993,18 +1042,31 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D>), grid, dim3(256), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const size_t adj_bytes = Adj2Cfg<TIO, D>::smem_bytes, key_bytes = Key2Cfg<TIO, D>::smem_bytes;
-    if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D>, adj_bytes)) != hipSuccess) return e;
     const int ntiles = (p.NC + 1) / 2;
-    hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D>), dim3((unsigned)(8 * ((p.B * p.H + 7) / 8) * ntiles)), dim3(256), adj_bytes, st, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, false>, key_bytes)) != hipSuccess) return e;
-    if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, true>, key_bytes)) != hipSuccess) return e;
     const int BH = p.B * p.H, nsb = (p.NC + SBC - 1) / SBC;
+    const dim3 grid_adj((unsigned)(8 * ((BH + 7) / 8) * ntiles));
     const dim3 grid_key((unsigned)(8 * ((BH + 7) / 8) * nsb * SBC)), grid_key_far((unsigned)(8 * ((BH + 7) / 8) * nsb * (SBC / 2)));
-    hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, false>), grid_key, dim3(256), key_bytes, st, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, true>), grid_key_far, dim3(256), key_bytes, st, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    if (p.cum) {       // PaTH-FoX instantiations
+        if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D, true>, adj_bytes)) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D, true>), grid_adj, dim3(256), adj_bytes, st, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, false, true>, key_bytes)) != hipSuccess) return e;
+        if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, true, true>, key_bytes)) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, false, true>), grid_key, dim3(256), key_bytes, st, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, true, true>), grid_key_far, dim3(256), key_bytes, st, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    } else {
+        if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D, false>, adj_bytes)) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D, false>), grid_adj, dim3(256), adj_bytes, st, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, false, false>, key_bytes)) != hipSuccess) return e;
+        if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, true, false>, key_bytes)) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, false, false>), grid_key, dim3(256), key_bytes, st, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, true, false>), grid_key_far, dim3(256), key_bytes, st, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     const size_t ddp_bytes = DdpCfg<TIO, D>::smem_bytes;
     if ((e = set_smem(&bwd_ddp_kernel<TIO, D, false>, ddp_bytes)) != hipSuccess) return e;
     if ((e = set_smem(&bwd_ddp_kernel<TIO, D, true>, ddp_bytes)) != hipSuccess) return e;
@@ -1057,11 +1119,17 @@ hipError_t launch_chunk_adjoint(const ChunkProgram& pr, int BH, int is_bf16, hip
         const size_t b = (size_t)(CHUNK + CHUNK) * (pr.ops[i].K + fe) * es;      // A and half of B
         if (b > bytes) bytes = b;
     }
-    hipError_t e = is_bf16 ? set_smem(&chunk_adjoint_kernel<bf16_t>, 160 * 1024) : set_smem(&chunk_adjoint_kernel<float>, 160 * 1024);
-    if (e != hipSuccess) return e;
+    const bool fox = pr.diag.cum != nullptr;
+    hipError_t e;
     dim3 grid(pr.NC, BH);
-    if (is_bf16) hipLaunchKernelGGL((chunk_adjoint_kernel<bf16_t>), grid, dim3(256), bytes, st, pr);
-    else hipLaunchKernelGGL((chunk_adjoint_kernel<float>), grid, dim3(256), bytes, st, pr);
+#define LAUNCH_CHUNK_ADJ(TT, FF)                                                                  \
+    do {                                                                                          \
+        if ((e = set_smem(&chunk_adjoint_kernel<TT, FF>, 160 * 1024)) != hipSuccess) return e;    \
+        hipLaunchKernelGGL((chunk_adjoint_kernel<TT, FF>), grid, dim3(256), bytes, st, pr);       \
+    } while (0)
+    if (is_bf16) { if (fox) LAUNCH_CHUNK_ADJ(bf16_t, true); else LAUNCH_CHUNK_ADJ(bf16_t, false); }
+    else { if (fox) LAUNCH_CHUNK_ADJ(float, true); else LAUNCH_CHUNK_ADJ(float, false); }
+#undef LAUNCH_CHUNK_ADJ
     return hipGetLastError();
 }
 

@@ -18,6 +18,9 @@ struct BwdParams {
     float *ddp;               // [BH][NC][d][d] fp32: ddP[a][b]
     float *dk2;               // [BH][Lp][d] fp32: dKb2 (gradient of the second-level keys)
     float *dchain;            // [BH][NC+1][d][d] fp32: chain of the second level's adjoint, entry c+1 for chunk c
+    const float* cum;         // PaTH-FoX only (else NULL): [BH][Lp] cumulative log2 gates
+    float* dcol;              // PaTH-FoX only: [BH][Lp] column sums of the logit gradient
+    float* drow;              // PaTH-FoX only: [BH][Lp] row sums of the logit gradient (zero in exact arithmetic)
     int B, H, L, NC;
     float scale;
 };
@@ -64,6 +67,9 @@ struct DiagArgs {
     float *pd, *dsd;
     int L, NC;
     float scale;
+    const float* cum;     // PaTH-FoX only (else NULL)
+    float* dcol;          // PaTH-FoX only: the diagonal block's column sums are ADDED here
+    float* drow;          // PaTH-FoX only: ... and its row sums here
 };
 struct BetaArgs {
     const float *r, *m, *g;

@@ -2,7 +2,7 @@
 // enters the logit as c_i - c_j with c_t = sum_{s<=t} log f_s.  One kernel does both scans that
 // the forward and the backward need, per head, in fp32:
 //   forward:  cum[t]   = scale_out * sum_{s<=t} x[s]      (inclusive; x = log f, scale_out = log2 e)
-//   backward: dlogf[s] = sum_{t<s} y[t]                   (exclusive; y = column sums of the logit gradient)
+//   backward: dlogf[s] = sum_{t<s} (y[t] - r[t])          (exclusive; y = column sums, r = row sums of the logit gradient)
 // One workgroup per head; a thread owns a contiguous run of the row.
 #include "path_common.h"
 #include "fox_decl.h"
@@ -17,8 +17,10 @@ __global__ __launch_bounds__(256) void fox_scan_kernel(ScanArgs a) {
     const int t0 = tid * per, t1 = (t0 + per < a.n_out) ? t0 + per : a.n_out;
     const TIN* x = reinterpret_cast<const TIN*>(a.in) + (size_t)bh * a.in_stride;
     TOUT* y = reinterpret_cast<TOUT*>(a.out) + (size_t)bh * a.out_stride;
+    const float* mi = a.minus ? a.minus + (size_t)bh * a.in_stride : nullptr;
+    auto val = [&](int t) { return (t < a.n_in) ? (float)x[t] - (mi ? mi[t] : 0.f) : 0.f; };
     float s = 0.f;
-    for (int t = t0; t < t1; ++t) s += (t < a.n_in) ? (float)x[t] : 0.f;
+    for (int t = t0; t < t1; ++t) s += val(t);
     part[tid] = s;
     __syncthreads();
     // exclusive scan of the 256 partial sums (Hillis-Steele on a copy)
@@ -32,7 +34,7 @@ __global__ __launch_bounds__(256) void fox_scan_kernel(ScanArgs a) {
     }
     float acc = run - s;                       // sum of everything before this thread's run
     for (int t = t0; t < t1; ++t) {
-        const float v = (t < a.n_in) ? (float)x[t] : 0.f;
+        const float v = val(t);
         if (a.inclusive) { acc += v; y[t] = (TOUT)(acc * a.scale_out); }
         else { y[t] = (TOUT)(acc * a.scale_out); acc += v; }
     }

@@ -6,6 +6,7 @@ namespace path {
 
 struct ScanArgs {
     const void* in;      // [BH][in_stride], first n_in entries of a row are read (the rest count as zero)
+    const float* minus;  // optional (float input only): subtracted from `in` element by element before the scan
     void* out;           // [BH][out_stride], first n_out entries of a row are written
     int in_stride, out_stride, n_in, n_out;
     int inclusive;

@@ -57,3 +57,29 @@ def test_unit_gates_reproduce_plain_path_bit_for_bit_in_o(gpu):
     o1, l1 = pa.path_attn_fox_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], zero, scale=0.125)
     o0, l0 = pa.path_attn_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], scale=0.125)
     assert float((o1.float() - o0.float()).abs().max()) <= 2e-2 and float((l1 - l0).abs().max()) <= 1e-5
+
+
+NAMES = ("dq", "dk", "dv", "dw", "dbeta", "dlogf")
+
+
+@pytest.mark.parametrize("dtype,L,d", [("fp32", 64, 64), ("fp32", 200, 128), ("fp32", 1100, 64), ("bf16", 300, 64),
+                                       ("bf16", 1030, 128)])
+def test_fox_backward_matches_the_oracle(gpu, oracle, dtype, L, d):
+    torch, pa = gpu
+    x = _inputs(1, 2, L, d, dtype, 1400 + L + d)
+    dv = _dev(gpu, x, dtype)
+    scale = d ** -0.5
+    o, lse = pa.path_attn_fox_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], dv["logf"], scale=scale)
+    got = pa.path_attn_fox_bwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], dv["logf"], o, lse, dv["dO"], scale=scale)
+    torch.cuda.synchronize()
+    ref = oracle.bwd(x["q"], x["k"], x["v"], x["w"], x["beta"], x["dO"], scale, logf=x["logf"])
+    msg, worst = [], 0.0
+    for n, g, r in zip(NAMES, got, ref):
+        g = g.float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(g).all(), n
+        e = np.abs(g - r).max() / max(np.abs(r).max(), 1e-2)
+        msg.append(f"{n}={e:.2e}")
+        worst = max(worst, e)
+    print(f"[fox bwd {dtype} L={L} d={d}] rel err " + " ".join(msg), flush=True)
+    assert worst <= (1e-4 if dtype == "fp32" else 2e-2), msg
+    assert float(got[5][:, :, 0].abs().max()) == 0.0

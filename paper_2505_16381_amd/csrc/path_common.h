@@ -40,7 +40,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int CHUNK = 64;      // tokens per chunk (UT transform block)
-constexpr int SBC = 4;         // chunks per super-block (second blocking level of the forward sweep)
+constexpr int SBC = 16;         // chunks per super-block (second blocking level of the forward sweep)
 
 __device__ __forceinline__ int acc_row(int j, int h) { return 8 * (j >> 2) + 4 * h + (j & 3); }
 

@@ -65,10 +65,12 @@ def test_bwd_bf16_small(gpu, oracle, L, d):
     _check(gpu, oracle, x, "bf16", d ** -0.5, tag=f"bwd bf16 L={L} d={d}")
 
 
-@pytest.mark.parametrize("dtype,L,d", [("fp32", 1100, 64), ("bf16", 1100, 128), ("fp32", 1024, 128), ("bf16", 580, 64)])
+@pytest.mark.parametrize("dtype,L,d", [("fp32", 1100, 64), ("bf16", 1100, 128), ("fp32", 1024, 128), ("bf16", 580, 64),
+                                       ("fp32", 2200, 64), ("bf16", 3100, 128)])
 def test_bwd_several_superblocks(gpu, oracle, dtype, L, d):
-    """Long enough that the second blocking level (super-blocks of 4 chunks, far key blocks with
-    their own products) and its adjoint carry most pairs; ragged and exact lengths."""
+    """Long enough that the second blocking level (super-blocks of 16 chunks = 1024 tokens, far key
+    blocks with their own products) and its adjoint carry pairs; from two super-blocks (no far
+    product applied yet) to four, ragged and exact lengths."""
     x = si.make_inputs(1, 2, L, d, dtype, 650 + L + d, 0.0, with_do=True)
     _check(gpu, oracle, x, dtype, d ** -0.5, tag=f"bwd superblocks L={L} d={d}")
 

@@ -105,6 +105,14 @@ def test_fp32_ragged_lengths(gpu, oracle, L, d):
     _check(gpu, oracle, x, "fp32", d ** -0.5, tag=f"fp32 L={L} d={d}")
 
 
+@pytest.mark.parametrize("dtype,L,d", [("fp32", 2200, 64), ("fp32", 3300, 128), ("bf16", 2500, 64), ("bf16", 4100, 128)])
+def test_several_superblocks(gpu, oracle, dtype, L, d):
+    """Three to five super-blocks (16 chunks = 1024 tokens each), ragged: near chunks, far
+    super-blocks and the far product all take part."""
+    x = si.make_inputs(1, 2, L, d, dtype, 250 + L + d)
+    _check(gpu, oracle, x, dtype, d ** -0.5, tag=f"superblocks {dtype} L={L} d={d}")
+
+
 @pytest.mark.parametrize("L", [1, 77, 512, 1000])
 @pytest.mark.parametrize("d", [64, 128])
 def test_bf16_small(gpu, oracle, L, d):

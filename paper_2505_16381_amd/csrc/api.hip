@@ -378,6 +378,9 @@ static path_status_t bwd_impl(const void* q, const void* k, const void* v, const
     pr.L = L; pr.NC = NC;
     bool chain_open = false;
     // one product: C (+)= alpha A B^T; `first` opens a chain (from Cin or zero), `last` masks and writes C
+    // results that are only read as matrix operands (marked OP) are stored in the operand type: half the bytes
+    // for 2-byte operands, and the same values the staging would produce from a float copy
+    bool as_op = false;
     auto prod = [&](float* C, int out, const float* Cin, MatRef A, MatRef Bm, int M, int N, int K, float alpha, int mask,
                     bool first, bool last) {
         ChunkOp& o = pr.ops[pr.n++];
@@ -385,7 +388,7 @@ static path_status_t bwd_impl(const void* q, const void* k, const void* v, const
         if (out == OUT_TOK) { o.c_bh = t_bh; o.c_ch = t_ch; o.crs = d; }
         else { o.c_bh = c_bh; o.c_ch = c_ch; o.crs = 64; }
         o.M = (short)M; o.N = (short)N; o.K = (short)K; o.alpha = alpha; o.mask = (unsigned char)mask;
-        o.first = first; o.last = last;
+        o.first = first; o.last = last; o.c_op = as_op;
         chain_open = !last;
     };
     auto special = [&](int kind) { pr.ops[pr.n++].kind = (unsigned char)kind; };
@@ -395,29 +398,31 @@ static path_status_t bwd_impl(const void* q, const void* k, const void* v, const
 
     prod(dpd, OUT_C64, nullptr, user_n(d_o), user_n(v), 64, 64, d, 1.f, MASK_NONE, true, true);              // dPd = dO V^T
     special(OP_DIAG);                                                                                          // P, dSd
-    prod(dvp, OUT_TOK, dvp, chunk_t(pd, EL_F32), user_t(d_o), 64, d, 64, 1.f, MASK_NONE, true, true);         // dV += P^T dO
-    prod(dqf, OUT_TOK, dqb, chunk_n(dsd, EL_F32), user_t(k), 64, d, 64, 1.f, MASK_NONE, true, true);          // dQ = dQb + dSd K
-    prod(dkf, OUT_TOK, dkb, chunk_t(dsd, EL_F32), user_t(q), 64, d, 64, 1.f, MASK_NONE, true, true);          // dK = dKb + dSd^T Q
-    prod(df, OUT_C64, nullptr, chunk_n(dsd, EL_F32), chunk_t(ytm, EL_OP), 64, 64, 64, -1.f, MASK_TRIL, true, false);   // dF = tril(-dSd Y^T
+    prod(dvp, OUT_TOK, dvp, chunk_t(pd, EL_OP), user_t(d_o), 64, d, 64, 1.f, MASK_NONE, true, true);         // dV += P^T dO
+    prod(dqf, OUT_TOK, dqb, chunk_n(dsd, EL_OP), user_t(k), 64, d, 64, 1.f, MASK_NONE, true, true);          // dQ = dQb + dSd K
+    prod(dkf, OUT_TOK, dkb, chunk_t(dsd, EL_OP), user_t(q), 64, d, 64, 1.f, MASK_NONE, true, true);          // dK = dKb + dSd^T Q
+    as_op = true;
+    prod(df, OUT_C64, nullptr, chunk_n(dsd, EL_OP), chunk_t(ytm, EL_OP), 64, 64, 64, -1.f, MASK_TRIL, true, false);   // dF = tril(-dSd Y^T
     prod(df, OUT_C64, nullptr, tokws_n(dqb), U_rows, 64, 64, d, -1.f, MASK_TRIL, false, true);                         //          - dQb U^T)
-    prod(dy, OUT_C64, nullptr, chunk_t(fm, EL_OP), chunk_t(dsd, EL_F32), 64, 64, 64, -1.f, MASK_NONE, true, false);    // dY = -F^T dSd
+    prod(dy, OUT_C64, nullptr, chunk_t(fm, EL_OP), chunk_t(dsd, EL_OP), 64, 64, 64, -1.f, MASK_NONE, true, false);    // dY = -F^T dSd
     prod(dy, OUT_C64, nullptr, user_n(w), tokws_n(dkb), 64, 64, d, -1.f, MASK_NONE, false, true);                      //      - W dKb^T
     prod(du, OUT_TOK, nullptr, chunk_t(fm, EL_OP), tokws_t(dqb), 64, d, 64, -1.f, MASK_NONE, true, false);             // dU = -F^T dQb
     prod(du, OUT_TOK, nullptr, user_n(w), ddp_kfirst, 64, d, d, 1.f, MASK_NONE, false, true);                          //      + W ddP
-    prod(dn, OUT_C64, nullptr, chunk_n(dy, EL_F32), chunk_t(gktm, EL_OP), 64, 64, 64, 1.f, MASK_NONE, true, false);    // dN = dY Gk^T
-    prod(dn, OUT_C64, nullptr, tokws_n(du), user_n(w), 64, 64, d, 1.f, MASK_NONE, false, true);                        //      + dU W^T
-    prod(dgk, OUT_C64, nullptr, chunk_t(nm, EL_OP), chunk_t(dy, EL_F32), 64, 64, 64, 1.f, MASK_SLOWER, true, true);    // dGk = sl(N^T dY)
-    prod(rr, OUT_C64, nullptr, chunk_t(aim, EL_OP), chunk_t(dn, EL_F32), 64, 64, 64, 1.f, MASK_NONE, true, true);      // R = A^-T dN
+    prod(dn, OUT_C64, nullptr, chunk_n(dy, EL_OP), chunk_t(gktm, EL_OP), 64, 64, 64, 1.f, MASK_NONE, true, false);    // dN = dY Gk^T
+    prod(dn, OUT_C64, nullptr, MatRef{du, t_bh, t_ch, d, 1, EL_OP, TOK_NONE}, user_n(w), 64, 64, d, 1.f, MASK_NONE, false, true);                        //      + dU W^T
+    prod(dgk, OUT_C64, nullptr, chunk_t(nm, EL_OP), chunk_t(dy, EL_OP), 64, 64, 64, 1.f, MASK_SLOWER, true, true);    // dGk = sl(N^T dY)
+    as_op = false;      // R and M are also read element-wise (dbeta)
+    prod(rr, OUT_C64, nullptr, chunk_t(aim, EL_OP), chunk_t(dn, EL_OP), 64, 64, 64, 1.f, MASK_NONE, true, true);      // R = A^-T dN
     prod(mm, OUT_C64, nullptr, chunk_n(rr, EL_F32), chunk_n(nm, EL_OP), 64, 64, 64, -1.f, MASK_SLOWER, true, true);    // M = sl(-R N^T)
     special(OP_BETA);                                                                                          // dGs, dbeta
     prod(dwf, OUT_TOK, nullptr, chunk_t(ytm, EL_OP), tokws_t(dkb), 64, d, 64, -1.f, MASK_NONE, true, false);           // dW = -Y dKb
     prod(dwf, OUT_TOK, nullptr, U_rows, ddp_nfirst, 64, d, d, 1.f, MASK_NONE, false, false);                           //    + U ddP^T
-    prod(dwf, OUT_TOK, nullptr, chunk_t(df, EL_F32), user_t(q), 64, d, 64, 1.f, MASK_NONE, false, false);              //    + dF^T Q
-    prod(dwf, OUT_TOK, nullptr, chunk_n(dgk, EL_F32), user_t(k), 64, d, 64, 1.f, MASK_NONE, false, false);             //    + dGk K
-    prod(dwf, OUT_TOK, nullptr, chunk_t(nm, EL_OP), tokws_t(du), 64, d, 64, 1.f, MASK_NONE, false, false);             //    + N^T dU
-    prod(dwf, OUT_TOK, nullptr, chunk_n(dgs, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE, false, true);              //    + (dG+dG^T) W
-    prod(dqf, OUT_TOK, dqf, chunk_n(df, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE, true, true);           // dQ += dF W
-    prod(dkf, OUT_TOK, dkf, chunk_t(dgk, EL_F32), user_t(w), 64, d, 64, 1.f, MASK_NONE, true, true);          // dK += dGk^T W
+    prod(dwf, OUT_TOK, nullptr, chunk_t(df, EL_OP), user_t(q), 64, d, 64, 1.f, MASK_NONE, false, false);              //    + dF^T Q
+    prod(dwf, OUT_TOK, nullptr, chunk_n(dgk, EL_OP), user_t(k), 64, d, 64, 1.f, MASK_NONE, false, false);             //    + dGk K
+    prod(dwf, OUT_TOK, nullptr, chunk_t(nm, EL_OP), MatRef{du, t_bh, t_ch, 1, d, EL_OP, TOK_NONE}, 64, d, 64, 1.f, MASK_NONE, false, false);             //    + N^T dU
+    prod(dwf, OUT_TOK, nullptr, chunk_n(dgs, EL_OP), user_t(w), 64, d, 64, 1.f, MASK_NONE, false, true);              //    + (dG+dG^T) W
+    prod(dqf, OUT_TOK, dqf, chunk_n(df, EL_OP), user_t(w), 64, d, 64, 1.f, MASK_NONE, true, true);           // dQ += dF W
+    prod(dkf, OUT_TOK, dkf, chunk_t(dgk, EL_OP), user_t(w), 64, d, 64, 1.f, MASK_NONE, true, true);          // dK += dGk^T W
     special(OP_STORE);                                                                                         // to the I/O dtype
     if (chain_open || pr.n > MAX_CHUNK_OPS) return PATH_ERR_HIP;
     ok = hip_ok(launch_chunk_adjoint(pr, BH, bf, st), "chunk-transform adjoint");

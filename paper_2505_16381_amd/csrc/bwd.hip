@@ -684,15 +684,15 @@ __device__ __forceinline__ void stage_mat_t(const MatRef& r, typename Compute<TI
     }
 }
 
-template <typename TIO>
+template <typename TIO, int NB = 1>
 __device__ __forceinline__ void stage_mat(const MatRef& r, typename Compute<TIO>::type* dst, int ld, int R, int K,
                                           int bh, int chunk, int L, int tid, float mul = 1.f) {
     typedef typename Compute<TIO>::type T;
     const long long base = bh * r.s_bh + chunk * r.s_ch;
     const int ntok = L - chunk * CHUNK;     // tokens of this chunk that exist
-    if (r.type == EL_F32) stage_mat_t<TIO, float>(r, dst, ld, R, K, base, ntok, tid, mul);
-    else if (r.type == EL_OP) stage_mat_t<TIO, T>(r, dst, ld, R, K, base, ntok, tid, mul);
-    else stage_mat_t<TIO, TIO>(r, dst, ld, R, K, base, ntok, tid, mul);
+    if (r.type == EL_F32) stage_mat_t<TIO, float, NB>(r, dst, ld, R, K, base, ntok, tid, mul);
+    else if (r.type == EL_OP) stage_mat_t<TIO, T, NB>(r, dst, ld, R, K, base, ntok, tid, mul);
+    else stage_mat_t<TIO, TIO, NB>(r, dst, ld, R, K, base, ntok, tid, mul);
 }
 
 template <typename TIO>
@@ -891,8 +891,9 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
 // ---------------------------------------------------------------------------------------
 // Element-wise steps of the chunk-transform adjoint (device functions of the fused kernel).
 // Diagonal block: P = exp(scale*Sd - lse) on key <= query, dSd = scale * P (dPd - delta).
-template <bool FOX>
+template <typename TIO, bool FOX>
 __device__ __forceinline__ void chunk_diag(const DiagArgs& a, float* colsum, int chunk, int bh, int tid) {
+    typedef typename Compute<TIO>::type T;
     const size_t base = ((size_t)bh * a.NC + chunk) * 4096;
     if (FOX) {
         if (tid < 2 * CHUNK) colsum[tid] = 0.f;
@@ -912,8 +913,8 @@ __device__ __forceinline__ void chunk_diag(const DiagArgs& a, float* colsum, int
             ds = a.scale * dz;
             if (FOX) { atomicAdd(colsum + s, dz); atomicAdd(colsum + CHUNK + t, dz); }      // LDS: column and row sums of the block
         }
-        a.pd[base + idx] = P;
-        a.dsd[base + idx] = ds;
+        reinterpret_cast<T*>(a.pd)[base + idx] = (T)P;
+        reinterpret_cast<T*>(a.dsd)[base + idx] = (T)ds;
     }
     if (FOX) {
         __syncthreads();
@@ -935,7 +936,7 @@ __device__ __forceinline__ void chunk_beta(const BetaArgs& a, float* bs, int chu
     __syncthreads();
     for (int idx = tid; idx < 4096; idx += 256) {
         const int r = idx >> 6, c = idx & 63;
-        a.dgs[base + idx] = bs[r] * a.m[base + idx] + bs[c] * a.m[base + c * 64 + r];
+        reinterpret_cast<typename Compute<TIO>::type*>(a.dgs)[base + idx] = (typename Compute<TIO>::type)(bs[r] * a.m[base + idx] + bs[c] * a.m[base + c * 64 + r]);
     }
     if (tid < CHUNK) {
         float s = a.r[base + tid * 64 + tid];
@@ -964,6 +965,9 @@ __device__ __forceinline__ void chunk_store(const OutArgs& a, int chunk, int bh,
 // The fused adjoint of the chunk transform: one workgroup per (chunk, head) runs the program.
 // Results that later steps read go through global memory (they stay in L2); a chain of
 // products that add into the same result keeps it in accumulator registers.
+#ifndef CHUNK_NB
+#define CHUNK_NB 1
+#endif
 // FOX: the diagonal-block step also applies the gate sums and collects row/column sums (PaTH-FoX).
 template <typename TIO, bool FOX>
 __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) {
@@ -976,7 +980,7 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
     for (int i = 0; i < pr.n; ++i) {
         const ChunkOp& op = pr.ops[i];
         __syncthreads();       // earlier steps' results are visible to the whole workgroup; LDS is free
-        if (op.kind == OP_DIAG) { chunk_diag<FOX>(pr.diag, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
+        if (op.kind == OP_DIAG) { chunk_diag<TIO, FOX>(pr.diag, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
         if (op.kind == OP_BETA) { chunk_beta<TIO>(pr.beta, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
         if (op.kind == OP_STORE) { chunk_store<TIO>(pr.out, chunk, bh, tid); continue; }
         // M = 64 for every product of the list; N = 64 or 128.  Results are handled in halves of 64
@@ -985,7 +989,7 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
         const int N = op.N, K = op.K, ld = K + FE;
         T* As = reinterpret_cast<T*>(smem);
         T* Bs = As + CHUNK * ld;
-        stage_mat<TIO>(op.A, As, ld, CHUNK, K, bh, chunk, pr.L, tid, op.alpha);
+        stage_mat<TIO, CHUNK_NB>(op.A, As, ld, CHUNK, K, bh, chunk, pr.L, tid, op.alpha);
         const long long cbase = bh * op.c_bh + chunk * op.c_ch;
         const int mb = wv >> 1;
 #pragma unroll
@@ -994,7 +998,7 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
             if (o > 0) __syncthreads();                    // the first half's fragments have been read
             MatRef bhalf = op.B;                           // rows 64*o .. 64*o+63 of B (features, never tokens)
             bhalf.p = reinterpret_cast<const char*>(op.B.p) + (size_t)(64 * o) * op.B.rs * (op.B.type == EL_F32 ? 4 : sizeof(T));
-            stage_mat<TIO>(bhalf, Bs, ld, 64, K, bh, chunk, pr.L, tid);
+            stage_mat<TIO, CHUNK_NB>(bhalf, Bs, ld, 64, K, bh, chunk, pr.L, tid);
             __syncthreads();
             const int cb = 2 * o + (wv & 1), cbl = wv & 1;
             if (op.first) {
@@ -1021,7 +1025,8 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
                     const int m = 32 * mb + acc_row(jj, h), n = 32 * cb + l32;
                     float v = acc[o][jj];
                     if ((op.mask == MASK_TRIL && n > m) || (op.mask == MASK_SLOWER && n >= m)) v = 0.f;
-                    op.C[cbase + (long long)m * op.crs + n] = v;
+                    if (op.c_op) reinterpret_cast<T*>(op.C)[cbase + (long long)m * op.crs + n] = (T)v;
+                    else op.C[cbase + (long long)m * op.crs + n] = v;
                 }
             }
         }

@@ -64,7 +64,7 @@ struct SbChainArgs {
 
 struct DiagArgs {
     const float *sdm, *dpd, *delta, *lse;
-    float *pd, *dsd;
+    void *pd, *dsd;       // operand type (read only as matrix operands)
     int L, NC;
     float scale;
     const float* cum;     // PaTH-FoX only (else NULL)
@@ -74,7 +74,8 @@ struct DiagArgs {
 struct BetaArgs {
     const float *r, *m, *g;
     const void* beta;
-    float *dgs, *dbf;
+    void* dgs;            // operand type
+    float* dbf;
     int L, NC;
 };
 struct OutArgs {
@@ -98,6 +99,7 @@ struct ChunkOp {
     short M, N, K;
     float alpha;
     unsigned char mask, first, last, kind;
+    unsigned char c_op;      // the result is stored in the operand type (it is only read as an operand), not as float
 };
 constexpr int MAX_CHUNK_OPS = 26;
 struct ChunkProgram {

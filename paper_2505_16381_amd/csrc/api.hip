@@ -374,6 +374,17 @@ static path_status_t bwd_impl(const void* q, const void* k, const void* v, const
     // 5b. adjoint of the chunk transform: one fused kernel runs this list per (chunk, head).
     // Chains of products that add into the same result are consecutive.
     if (!ok) return PATH_ERR_HIP;
+    if (bf) {      // 2-byte operand types: the hand-fused kernel
+        ChunkFusedArgs ca{q, k, v, w, beta, d_o, lse, bp.delta, fp.sdm, fp.gm, fp.fm, fp.gktm, fp.nm, fp.aim, fp.ytm,
+                          base + ws.utm, bp.dqb, bp.dkb, bp.dvp, F(ws.ddp), dq, dk, dv, dw, dbeta, bp.cum, bp.dcol, bp.drow,
+                          L, NC, scale};
+        ok = hip_ok(launch_chunk_fused(ca, BH, d, st), "chunk-transform adjoint");
+        if (ok && log_f) {
+            ScanArgs sa{bp.dcol, bp.drow, dlog_f, (int)Lp, L, L, L, 0, 1.f};
+            ok = hip_ok(launch_fox_scan(sa, BH, 0, 1, st), "gate gradient");
+        }
+        return ok ? PATH_OK : PATH_ERR_HIP;
+    }
     ChunkProgram pr = {};
     pr.L = L; pr.NC = NC;
     bool chain_open = false;

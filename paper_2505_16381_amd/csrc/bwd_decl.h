@@ -112,6 +112,23 @@ struct ChunkProgram {
 };
 hipError_t launch_chunk_adjoint(const ChunkProgram& pr, int BH, int is_bf16, hipStream_t st);
 
+// The same steps as one hand-fused kernel (2-byte operand types): every input is a plain pointer.
+struct ChunkFusedArgs {
+    const void *q, *k, *v, *w, *beta, *d_o;      // I/O type, [BH][L][d] / [BH][L]
+    const float *lse, *delta;                    // [BH][L], [BH][Lp]
+    const float *sdm, *gm;                       // [BH][NC][64][64]: raw diagonal logits, G
+    const void *fm, *gktm, *nm, *aim, *ytm;      // operand type, [BH][NC][64][64]
+    const void* utm;                             // operand type, [BH][NC][d][64]
+    const float *dqb, *dkb, *dvp;                // [BH][Lp][d]
+    const float* ddp;                            // [BH][NC][d][d]
+    void *dq, *dk, *dv, *dw, *dbeta;             // I/O type
+    const float* cum;                            // PaTH-FoX only (else NULL)
+    float *dcol, *drow;
+    int L, NC;
+    float scale;
+};
+hipError_t launch_chunk_fused(const ChunkFusedArgs& a, int BH, int d, hipStream_t st);
+
 hipError_t launch_bwd_scan(const BwdParams& p, int d, int is_bf16, hipStream_t st);
 hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream_t st);
 hipError_t launch_bwd_sb_chain(const SbChainArgs& a, int BH, int d, hipStream_t st);    // 2-byte operand types only

@@ -1,0 +1,418 @@
+// Adjoint of the chunk transform (the UT transform of Sec. 3.2 and the diagonal block of
+// Sec. 3.3), fused: one workgroup per (chunk, head) for 2-byte operand types.  The paper gives
+// no backward; with the chunk's matrices (rows = the 64 tokens of the chunk)
+//
+//   F   strictly-lower part of the boundary-adjusted query transform,  Y = solved W-side block,
+//   N, Gk, A^-1 from the UT transform,  U = T^-1-transformed W (dP = W^T U),  Sd the raw diagonal logits,
+//
+// the gradients that arrive are dQb, dKb (boundary-adjusted queries / keys), ddP (chunk product),
+// dV' (off-diagonal part of dV), and the steps are
+//
+//   dPd = dO V^T;  P = exp(scale Sd - lse) (key <= query);  dSd = scale P o (dPd - delta)
+//   dV  = dV' + P^T dO
+//   dF  = tril(-dSd Y^T - dQb U^T)            dY = -F^T dSd - W dKb^T
+//   dU  = -F^T dQb + W ddP                     dN = dY Gk^T + dU W^T
+//   dGk = sl(N^T dY)     R = A^-T dN     M = sl(-R N^T)     dGs = diag(beta) M + (diag(beta) M)^T
+//   dbeta_a = R_aa + sum_s M_as G_as
+//   dQ  = dQb + dSd K + dF W
+//   dK  = dKb + dSd^T Q + dGk^T W
+//   dW  = -Y dKb + U ddP^T + dF^T Q + dGk K + N^T dU + dGs W
+//
+// (sl = strictly lower part).  Every matrix is staged ONCE into LDS in the layout it has in
+// memory (converted to the operand type); a product whose contraction runs along the rows of a
+// stored matrix gathers its 16-byte fragments with 2-byte LDS reads instead of keeping a
+// transposed copy.  dK and dW accumulate in registers across the whole kernel; the 64 x 64
+// intermediates never leave LDS.  Per chunk the kernel reads about 0.46 MB and writes the four
+// gradients, against about 1.5 MB for the same steps run as separate staged products.
+#include "path_common.h"
+#include "bwd_decl.h"
+
+namespace path {
+namespace {
+
+constexpr int CA_NT = 512;       // threads per workgroup (8 waves)
+
+template <typename TIO, int D> struct CaCfg {
+    typedef typename Compute<TIO>::type T;
+    static_assert(sizeof(T) == 2, "fused chunk adjoint: 2-byte operand types only");
+    static constexpr int LDD = D + 8;          // pitch of a [..][D] tile (elements)
+    static constexpr int LDC = CHUNK + 8;      // pitch of a [..][64] tile
+    static constexpr int BIG = (64 * LDD > D * LDC ? 64 * LDD : D * LDC) * 2;   // bytes of a 64 x D or D x 64 tile
+    static constexpr int SMALL = 64 * LDC * 2;
+    static constexpr int LDM = 65;             // pitch of the fp32 copy of M
+    // byte offsets: W | X0 X3 (adjacent: ddP spans both) | X1 | X2 | Y0..Y4 | misc
+    static constexpr int XW = 0, X0 = BIG, X3 = 2 * BIG, X1 = 3 * BIG, X2 = 4 * BIG;
+    static constexpr int Y0 = 5 * BIG, Y1 = Y0 + SMALL, Y2 = Y1 + SMALL, Y3 = Y2 + SMALL, Y4 = Y3 + SMALL;
+    static constexpr int MISC = Y4 + SMALL;
+    static constexpr int TOTAL = MISC + 2048;
+    static_assert(D * LDD * 2 <= 2 * BIG, "ddP tile must fit X0+X3");
+    static_assert(64 * LDM * 4 <= 2 * BIG, "fp32 M must fit X0+X3");
+    static_assert(TOTAL <= 160 * 1024, "LDS budget");
+};
+
+// ROWS x COLS elements of type S from global memory (row-major, `stride` elements between rows), 8 per
+// thread and step, held in registers between load() and store(); rows >= nvalid are zero.
+template <typename S, int ROWS, int COLS> struct GTile {
+    static constexpr int NV = ROWS * COLS / 8 / CA_NT;
+    static_assert(NV >= 1 && NV * 8 * CA_NT == ROWS * COLS, "tile must be a multiple of the workgroup's reach");
+    typedef S Vec8 __attribute__((ext_vector_type(8)));
+    Vec8 v[NV];
+    __device__ __forceinline__ void load(const S* src, int stride, int nvalid, int tid) {
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int idx = tid + u * CA_NT, r = idx / (COLS / 8), c = (idx % (COLS / 8)) * 8;
+            if (r < nvalid) v[u] = *reinterpret_cast<const Vec8*>(src + (size_t)r * stride + c);
+            else
+#pragma unroll
+                for (int e = 0; e < 8; ++e) v[u][e] = (S)0.f;
+        }
+    }
+    template <typename T, bool NEG> __device__ __forceinline__ void store(T* dst, int ld, int tid) const {
+        typedef T TVec8 __attribute__((ext_vector_type(8)));
+#pragma unroll
+        for (int u = 0; u < NV; ++u) {
+            const int idx = tid + u * CA_NT, r = idx / (COLS / 8), c = (idx % (COLS / 8)) * 8;
+            TVec8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (T)(NEG ? -(float)v[u][e] : (float)v[u][e]);
+            *reinterpret_cast<TVec8*>(dst + r * ld + c) = o;
+        }
+    }
+};
+
+// acc[m][n] += sum_k A(m,k) B(n,k) for one 32x32 block (rows ar0.., columns br0..).
+// TA == false: A is stored [m][k] (16-byte fragment reads); TA == true: A is stored [k][m] (gathered).  Same for B.
+template <typename T, int K, bool TA, bool TB>
+__device__ __forceinline__ void mm(f32x16& acc, const T* A, int lda, int ar0, const T* B, int ldb, int br0, int l32, int h) {
+    constexpr int NS = K / 16;
+    typename Tr<T>::Frag fa[NS], fb[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+        const int k = 16 * s + 8 * h;
+        if (TA) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) fa[s][e] = A[(k + e) * lda + ar0 + l32];
+        } else {
+            fa[s] = ld_frag<T>(A + (ar0 + l32) * lda + k);
+        }
+        if (TB) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) fb[s][e] = B[(k + e) * ldb + br0 + l32];
+        } else {
+            fb[s] = ld_frag<T>(B + (br0 + l32) * ldb + k);
+        }
+    }
+#pragma unroll
+    for (int s = 0; s < NS; ++s) acc = Tr<T>::mma(fa[s], fb[s], acc);
+}
+
+// One 32x32 accumulator block -> LDS, stored [m][n] in the operand type.
+template <typename T>
+__device__ __forceinline__ void st_block(T* dst, int ld, int r0, int c0, const f32x16& acc, int l32, int h) {
+#pragma unroll
+    for (int jj = 0; jj < 16; ++jj) dst[(r0 + acc_row(jj, h)) * ld + c0 + l32] = (T)acc[jj];
+}
+
+template <typename TIO, int D, bool FOX>
+__global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
+    using C = CaCfg<TIO, D>;
+    typedef typename C::T T;
+    constexpr int LDD = C::LDD, LDC = C::LDC, LDM = C::LDM;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    T* XW = reinterpret_cast<T*>(smem + C::XW);
+    T* X0 = reinterpret_cast<T*>(smem + C::X0);
+    T* X1 = reinterpret_cast<T*>(smem + C::X1);
+    T* X2 = reinterpret_cast<T*>(smem + C::X2);
+    T* X3 = reinterpret_cast<T*>(smem + C::X3);
+    T* Y0 = reinterpret_cast<T*>(smem + C::Y0);
+    T* Y1 = reinterpret_cast<T*>(smem + C::Y1);
+    T* Y2 = reinterpret_cast<T*>(smem + C::Y2);
+    T* Y3 = reinterpret_cast<T*>(smem + C::Y3);
+    T* Y4 = reinterpret_cast<T*>(smem + C::Y4);
+    float* Mf = reinterpret_cast<float*>(smem + C::X0);      // fp32 M, after ddP is dead
+    float* misc = reinterpret_cast<float*>(smem + C::MISC);
+    float *lse_s = misc, *delta_s = misc + 64, *beta_s = misc + 128, *rdiag = misc + 192, *colsum = misc + 256, *cum_s = misc + 384;
+
+    const int chunk = blockIdx.x, bh = blockIdx.y;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int L = a.L, NC = a.NC;
+    const int ntok = (L - chunk * CHUNK < CHUNK) ? L - chunk * CHUNK : CHUNK;
+    const size_t Lp = (size_t)NC * CHUNK;
+    const size_t ubase = ((size_t)bh * L + (size_t)chunk * CHUNK) * D;       // user [L][d] tensors
+    const size_t pbase = ((size_t)bh * Lp + (size_t)chunk * CHUNK) * D;      // padded [Lp][d] workspace tensors
+    const size_t cbase = ((size_t)bh * NC + chunk) * 4096;                   // 64 x 64 per chunk
+    const size_t tpad = (size_t)bh * Lp + (size_t)chunk * CHUNK;             // per-token, padded
+    const TIO* qg = reinterpret_cast<const TIO*>(a.q) + ubase;
+    const TIO* kg = reinterpret_cast<const TIO*>(a.k) + ubase;
+    const TIO* vg = reinterpret_cast<const TIO*>(a.v) + ubase;
+    const TIO* wg = reinterpret_cast<const TIO*>(a.w) + ubase;
+    const TIO* dog = reinterpret_cast<const TIO*>(a.d_o) + ubase;
+    const T* utmg = reinterpret_cast<const T*>(a.utm) + ((size_t)bh * NC + chunk) * D * CHUNK;
+    const float* ddpg = a.ddp + ((size_t)bh * NC + chunk) * D * D;
+
+    // wave -> 32x32 block of a 64 x D result (all 8 waves for D = 128) and of a 64 x 64 result (waves 0..3)
+    constexpr int NBD = D / 32;
+    const bool actD = wv < 2 * NBD, act6 = wv < 4;
+    const int mbD = wv / NBD, cbD = wv % NBD, mb6 = (wv >> 1) & 1, cb6 = wv & 1;
+
+    auto cin = [&](const float* g, f32x16& acc) {       // accumulator block (mbD, cbD) from a padded fp32 [64][D] tensor
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) acc[jj] = g[(size_t)(32 * mbD + acc_row(jj, h)) * D + 32 * cbD + l32];
+    };
+    auto out_user = [&](void* base, const f32x16& acc) {   // ... to a user gradient, rows of existing tokens only
+        TIO* g = reinterpret_cast<TIO*>(base) + ubase;
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const int t = 32 * mbD + acc_row(jj, h);
+            if (t < ntok) g[(size_t)t * D + 32 * cbD + l32] = (TIO)acc[jj];
+        }
+    };
+
+    // ---- stage W, dO, V; per-token scalars ---------------------------------------------------
+    GTile<TIO, 64, D> tW, tdO, tV;
+    tW.load(wg, D, ntok, tid);
+    tdO.load(dog, D, ntok, tid);
+    tV.load(vg, D, ntok, tid);
+    if (tid < CHUNK) {
+        const bool ok = tid < ntok;
+        lse_s[tid] = ok ? a.lse[(size_t)bh * L + chunk * CHUNK + tid] : 0.f;
+        delta_s[tid] = a.delta[tpad + tid];
+        beta_s[tid] = ok ? (float)reinterpret_cast<const TIO*>(a.beta)[(size_t)bh * L + chunk * CHUNK + tid] : 0.f;
+        if (FOX) { cum_s[tid] = a.cum[tpad + tid]; colsum[tid] = 0.f; colsum[CHUNK + tid] = 0.f; }
+    }
+    float sd[16];                                   // raw diagonal logits of this wave's block
+    if (act6) {
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) sd[jj] = a.sdm[cbase + (size_t)(32 * mb6 + acc_row(jj, h)) * 64 + 32 * cb6 + l32];
+    }
+    tW.template store<T, false>(XW, LDD, tid);
+    tdO.template store<T, false>(X0, LDD, tid);
+    tV.template store<T, false>(X1, LDD, tid);
+    f32x16 accV, accK, accQ, accW = zero16();
+    if (actD) cin(a.dvp + pbase, accV);
+    GTile<TIO, 64, D> tQ;
+    tQ.load(qg, D, ntok, tid);
+    __syncthreads();
+
+    // ---- dPd = dO V^T; P, dSd (diagonal block) -> Y0 = P, Y1 = dSd, both [query][key] ----------
+    if (act6) {
+        f32x16 acc = zero16();
+        mm<T, D, false, false>(acc, X0, LDD, 32 * mb6, X1, LDD, 32 * cb6, l32, h);
+        const int s = 32 * cb6 + l32;
+        float csum = 0.f;
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const int t = 32 * mb6 + acc_row(jj, h);
+            float P = 0.f, ds = 0.f;
+            if (s <= t && t < ntok) {
+                float z = a.scale * sd[jj] - lse_s[t];
+                if (FOX) z += (cum_s[t] - cum_s[s]) * 0.69314718055994530942f;     // gate sums are kept in base-2 units
+                P = __expf(z);
+                const float dz = P * (acc[jj] - delta_s[t]);
+                ds = a.scale * dz;
+                if (FOX) { csum += dz; atomicAdd(colsum + CHUNK + t, dz); }
+            }
+            Y0[t * LDC + s] = (T)P;
+            Y1[t * LDC + s] = (T)ds;
+        }
+        if (FOX) atomicAdd(colsum + s, csum);
+    }
+    GTile<T, 64, 64> tY;
+    tY.load(reinterpret_cast<const T*>(a.ytm) + cbase, 64, 64, tid);
+    GTile<float, 64, D> tdQb;
+    tdQb.load(a.dqb + pbase, D, 64, tid);
+    GTile<T, D, 64> tU;
+    tU.load(utmg, 64, D, tid);
+    __syncthreads();
+    if (FOX && tid < CHUNK) {        // the diagonal block's column and row sums of the logit gradient
+        a.dcol[tpad + tid] += colsum[tid];
+        a.drow[tpad + tid] += colsum[CHUNK + tid];
+    }
+
+    // ---- dV = dV' + P^T dO ---------------------------------------------------------------------
+    if (actD) {
+        mm<T, 64, true, true>(accV, Y0, LDC, 32 * mbD, X0, LDD, 32 * cbD, l32, h);
+        out_user(a.dv, accV);
+        cin(a.dkb + pbase, accK);
+    }
+    __syncthreads();                 // dO (X0), V (X1), P (Y0) are free
+    tQ.template store<T, false>(X0, LDD, tid);
+    tY.template store<T, true>(Y0, LDC, tid);          // -Y^T as stored ([r][s])
+    tdQb.template store<T, true>(X1, LDD, tid);        // -dQb
+    tU.template store<T, false>(X2, LDC, tid);         // U as stored: [feature][token]
+    GTile<float, 64, D> tdKb;
+    tdKb.load(a.dkb + pbase, D, 64, tid);
+    __syncthreads();
+
+    // ---- dK = dKb + dSd^T Q (kept open);  dF = tril(-dSd Y^T - dQb U^T) -> Y2 --------------------
+    if (actD) mm<T, 64, true, true>(accK, Y1, LDC, 32 * mbD, X0, LDD, 32 * cbD, l32, h);
+    if (act6) {
+        f32x16 acc = zero16();
+        mm<T, 64, false, true>(acc, Y1, LDC, 32 * mb6, Y0, LDC, 32 * cb6, l32, h);
+        mm<T, D, false, true>(acc, X1, LDD, 32 * mb6, X2, LDC, 32 * cb6, l32, h);
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj)
+            if (32 * cb6 + l32 > 32 * mb6 + acc_row(jj, h)) acc[jj] = 0.f;
+        st_block<T>(Y2, LDC, 32 * mb6, 32 * cb6, acc, l32, h);
+    }
+    tdKb.template store<T, false>(X3, LDD, tid);
+    if (actD) cin(a.dqb + pbase, accQ);
+    GTile<TIO, 64, D> tK;
+    tK.load(kg, D, ntok, tid);
+    GTile<T, 64, 64> tF;
+    tF.load(reinterpret_cast<const T*>(a.fm) + cbase, 64, 64, tid);
+    __syncthreads();
+
+    // ---- dW = dF^T Q - Y dKb (kept open) ----------------------------------------------------------
+    if (actD) {
+        mm<T, 64, true, true>(accW, Y2, LDC, 32 * mbD, X0, LDD, 32 * cbD, l32, h);
+        mm<T, 64, true, true>(accW, Y0, LDC, 32 * mbD, X3, LDD, 32 * cbD, l32, h);
+    }
+    __syncthreads();                 // Q (X0) and Y (Y0) are free
+    tK.template store<T, false>(X0, LDD, tid);
+    tF.template store<T, false>(Y3, LDC, tid);
+    GTile<float, D, D> tDD;
+    tDD.load(ddpg, D, D, tid);
+    __syncthreads();
+
+    // ---- dQ = dQb + dSd K + dF W;  dY = -(F^T dSd + W dKb^T) -> Y4 ---------------------------------
+    if (actD) {
+        mm<T, 64, false, true>(accQ, Y1, LDC, 32 * mbD, X0, LDD, 32 * cbD, l32, h);
+        mm<T, 64, false, true>(accQ, Y2, LDC, 32 * mbD, XW, LDD, 32 * cbD, l32, h);
+        out_user(a.dq, accQ);
+    }
+    if (act6) {
+        f32x16 acc = zero16();
+        mm<T, 64, true, true>(acc, Y3, LDC, 32 * mb6, Y1, LDC, 32 * cb6, l32, h);
+        mm<T, D, false, false>(acc, XW, LDD, 32 * mb6, X3, LDD, 32 * cb6, l32, h);
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) acc[jj] = -acc[jj];
+        st_block<T>(Y4, LDC, 32 * mb6, 32 * cb6, acc, l32, h);
+    }
+    GTile<T, 64, 64> tN, tG;
+    tN.load(reinterpret_cast<const T*>(a.nm) + cbase, 64, 64, tid);
+    tG.load(reinterpret_cast<const T*>(a.gktm) + cbase, 64, 64, tid);
+    __syncthreads();                 // K (X0), dKb (X3), dSd (Y1), dF (Y2) are free
+    tDD.template store<T, false>(X0, LDD, tid);        // ddP [a][b], spans X0 and X3
+    tN.template store<T, false>(Y0, LDC, tid);
+    tG.template store<T, false>(Y1, LDC, tid);
+    __syncthreads();
+
+    // ---- dU = -F^T dQb + W ddP;  dW += U ddP^T ---------------------------------------------------
+    f32x16 accU = zero16();
+    if (actD) {
+        mm<T, 64, true, true>(accU, Y3, LDC, 32 * mbD, X1, LDD, 32 * cbD, l32, h);
+        mm<T, D, false, true>(accU, XW, LDD, 32 * mbD, X0, LDD, 32 * cbD, l32, h);
+        mm<T, D, true, false>(accW, X2, LDC, 32 * mbD, X0, LDD, 32 * cbD, l32, h);
+    }
+    GTile<T, 64, 64> tA;
+    tA.load(reinterpret_cast<const T*>(a.aim) + cbase, 64, 64, tid);
+    tK.load(kg, D, ntok, tid);       // K once more, for dGk K at the end
+    __syncthreads();                 // every wave is done with dQb (X1), U (X2)
+    if (actD) st_block<T>(X1, LDD, 32 * mbD, 32 * cbD, accU, l32, h);       // dU [token][feature]
+    tK.template store<T, false>(X2, LDD, tid);
+    __syncthreads();
+
+    // ---- dW += N^T dU;  dN = dY Gk^T + dU W^T -> Y3 ------------------------------------------------
+    if (actD) mm<T, 64, true, true>(accW, Y0, LDC, 32 * mbD, X1, LDD, 32 * cbD, l32, h);
+    if (act6) {
+        f32x16 acc = zero16();
+        mm<T, 64, false, true>(acc, Y4, LDC, 32 * mb6, Y1, LDC, 32 * cb6, l32, h);
+        mm<T, D, false, false>(acc, X1, LDD, 32 * mb6, XW, LDD, 32 * cb6, l32, h);
+        st_block<T>(Y3, LDC, 32 * mb6, 32 * cb6, acc, l32, h);
+    }
+    float gv[8];                     // G of the rows this wave reduces for dbeta (row wv + 8 i, column lane)
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = wv + 8 * i;
+        gv[i] = (lane < r) ? a.gm[cbase + (size_t)r * 64 + lane] : 0.f;
+    }
+    __syncthreads();                 // dN visible; Gk (Y1) is free
+
+    // ---- dGk = sl(N^T dY) -> Y1 ----------------------------------------------------------------------
+    if (act6) {
+        f32x16 acc = zero16();
+        mm<T, 64, true, true>(acc, Y0, LDC, 32 * mb6, Y4, LDC, 32 * cb6, l32, h);
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj)
+            if (32 * cb6 + l32 >= 32 * mb6 + acc_row(jj, h)) acc[jj] = 0.f;
+        st_block<T>(Y1, LDC, 32 * mb6, 32 * cb6, acc, l32, h);
+    }
+    __syncthreads();                 // dY (Y4) is free
+    tA.template store<T, false>(Y4, LDC, tid);
+    __syncthreads();
+
+    // ---- R = A^-T dN -> Y2 (operand) and its diagonal (fp32) ----------------------------------------
+    if (act6) {
+        f32x16 acc = zero16();
+        mm<T, 64, true, true>(acc, Y4, LDC, 32 * mb6, Y3, LDC, 32 * cb6, l32, h);
+        st_block<T>(Y2, LDC, 32 * mb6, 32 * cb6, acc, l32, h);
+        if (mb6 == cb6) {
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj)
+                if (acc_row(jj, h) == l32) rdiag[32 * mb6 + l32] = acc[jj];
+        }
+    }
+    __syncthreads();
+
+    // ---- M = sl(-R N^T) -> fp32 in LDS ---------------------------------------------------------------
+    if (act6) {
+        f32x16 acc = zero16();
+        mm<T, 64, false, false>(acc, Y2, LDC, 32 * mb6, Y0, LDC, 32 * cb6, l32, h);
+#pragma unroll
+        for (int jj = 0; jj < 16; ++jj) {
+            const int m = 32 * mb6 + acc_row(jj, h), n = 32 * cb6 + l32;
+            Mf[m * LDM + n] = (n >= m) ? 0.f : -acc[jj];
+        }
+    }
+    __syncthreads();
+
+    // ---- dGs = diag(beta) M + (diag(beta) M)^T -> Y3;  dbeta ------------------------------------------
+    for (int idx = tid; idx < 4096; idx += CA_NT) {
+        const int r = idx >> 6, c = idx & 63;
+        Y3[r * LDC + c] = (T)(beta_s[r] * Mf[r * LDM + c] + beta_s[c] * Mf[c * LDM + r]);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int r = wv + 8 * i;
+        float s = Mf[r * LDM + lane] * gv[i];           // M is zero on and above the diagonal, gv outside lane < r
+#pragma unroll
+        for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
+        if (lane == 0 && r < ntok)
+            reinterpret_cast<TIO*>(a.dbeta)[(size_t)bh * L + chunk * CHUNK + r] = (TIO)(s + rdiag[r]);
+    }
+    __syncthreads();
+
+    // ---- dK += dGk^T W;  dW += dGs W + dGk K ------------------------------------------------------------
+    if (actD) {
+        mm<T, 64, true, true>(accK, Y1, LDC, 32 * mbD, XW, LDD, 32 * cbD, l32, h);
+        out_user(a.dk, accK);
+        mm<T, 64, false, true>(accW, Y3, LDC, 32 * mbD, XW, LDD, 32 * cbD, l32, h);
+        mm<T, 64, false, true>(accW, Y1, LDC, 32 * mbD, X2, LDD, 32 * cbD, l32, h);
+        out_user(a.dw, accW);
+    }
+}
+
+template <typename TIO, int D, bool FOX>
+hipError_t launch_t(const ChunkFusedArgs& a, int BH, hipStream_t st) {
+    using C = CaCfg<TIO, D>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_fused_kernel<TIO, D, FOX>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::TOTAL);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((chunk_fused_kernel<TIO, D, FOX>), dim3(a.NC, BH), dim3(CA_NT), (size_t)C::TOTAL, st, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_chunk_fused(const ChunkFusedArgs& a, int BH, int d, hipStream_t st) {
+    const bool fox = a.cum != nullptr;
+    if (d == 64) return fox ? launch_t<bf16_t, 64, true>(a, BH, st) : launch_t<bf16_t, 64, false>(a, BH, st);
+    return fox ? launch_t<bf16_t, 128, true>(a, BH, st) : launch_t<bf16_t, 128, false>(a, BH, st);
+}
+
+}  // namespace path

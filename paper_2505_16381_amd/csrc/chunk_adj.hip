@@ -84,26 +84,29 @@ template <typename S, int ROWS, int COLS> struct GTile {
 // TA == false: A is stored [m][k] (16-byte fragment reads); TA == true: A is stored [k][m] (gathered).  Same for B.
 template <typename T, int K, bool TA, bool TB>
 __device__ __forceinline__ void mm(f32x16& acc, const T* A, int lda, int ar0, const T* B, int ldb, int br0, int l32, int h) {
-    constexpr int NS = K / 16;
-    typename Tr<T>::Frag fa[NS], fb[NS];
+    // four slabs (64 contraction indices) at a time: their fragments are fetched ahead of the four products
 #pragma unroll
-    for (int s = 0; s < NS; ++s) {
-        const int k = 16 * s + 8 * h;
-        if (TA) {
+    for (int k0 = 0; k0 < K; k0 += 64) {
+        typename Tr<T>::Frag fa[4], fb[4];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) fa[s][e] = A[(k + e) * lda + ar0 + l32];
-        } else {
-            fa[s] = ld_frag<T>(A + (ar0 + l32) * lda + k);
+        for (int s = 0; s < 4; ++s) {
+            const int k = k0 + 16 * s + 8 * h;
+            if (TA) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) fa[s][e] = A[(k + e) * lda + ar0 + l32];
+            } else {
+                fa[s] = ld_frag<T>(A + (ar0 + l32) * lda + k);
+            }
+            if (TB) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) fb[s][e] = B[(k + e) * ldb + br0 + l32];
+            } else {
+                fb[s] = ld_frag<T>(B + (br0 + l32) * ldb + k);
+            }
         }
-        if (TB) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) fb[s][e] = B[(k + e) * ldb + br0 + l32];
-        } else {
-            fb[s] = ld_frag<T>(B + (br0 + l32) * ldb + k);
-        }
+        for (int s = 0; s < 4; ++s) acc = Tr<T>::mma(fa[s], fb[s], acc);
     }
-#pragma unroll
-    for (int s = 0; s < NS; ++s) acc = Tr<T>::mma(fa[s], fb[s], acc);
 }
 
 // One 32x32 accumulator block -> LDS, stored [m][n] in the operand type.
@@ -406,6 +409,7 @@ hipError_t launch_t(const ChunkFusedArgs& a, int BH, hipStream_t st) {
     hipLaunchKernelGGL((chunk_fused_kernel<TIO, D, FOX>), dim3(a.NC, BH), dim3(CA_NT), (size_t)C::TOTAL, st, a);
     return hipGetLastError();
 }
+
 
 }  // namespace
 

@@ -425,10 +425,10 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
         const float* lse2 = reinterpret_cast<const float*>(sX + 4 * KVF);
         const float* dl = lse2 + CHUNK;
 
-#pragma unroll
-        for (int qq = 0; qq < CPW; ++qq) {
-            const int qh = FAR ? qq : (wv >> 1);
-            f32x16 S = zero16(), dP = zero16();                    // rows q (half qh), lane s
+        // The three parts of the work on a 32-query half: logits and dP (16 products), the element-wise
+        // part, and the updates of dV^T and dKb^T (32 products).
+        auto sdp = [&](int qh, f32x16& S, f32x16& dP) {
+            S = zero16(); dP = zero16();                           // rows q (half qh), lane s
             // operand fragments are fetched in batches ahead of the products that use them
 #pragma unroll
             for (int s0 = 0; s0 < DS; s0 += 4) {
@@ -442,7 +442,8 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                     dP = Tr<TIO>::mma(da[u], Vb[s0 + u], dP);
                 }
             }
-            if (spread) issue(i + 1, qq == 0 ? 1 : 3);
+        };
+        auto soft = [&](int qh, f32x16& S, const f32x16& dP, FragV* Pb, Frag* dSb) {
             // Rows past L need no mask: their padded lse2p is huge, so P = exp2(-huge) = 0.
             f32x4 ls[4], dls[4];
 #pragma unroll
@@ -459,10 +460,10 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 if (FOX) dcol += dz;
                 S[jj] = dz * p.scale;
             }
-            FragV Pb[SPB];
-            Frag dSb[SPB];
             pack_block<TIO>(Pm, Pb);
             pack_block<T>(S, dSb);
+        };
+        auto upd = [&](int qh, const FragV* Pb, const Frag* dSb) {
 #pragma unroll
             for (int b = 0; b < DB; b += 2) {
                 FragV ta[2 * SPB];
@@ -478,7 +479,123 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                     dKt[b + u / SPB] = Tr<T>::mma(tb[u], dSb[u % SPB], dKt[b + u / SPB]);
                 }
             }
-            if (spread && qq == 0) issue(i + 1, 2);
+        };
+        if (FAR && sizeof(T) == 2) {
+            // Both query halves, software-pipelined by hand: the element-wise part of one half is
+            // interleaved, element by element, with the products of the other (one wave per SIMD:
+            // nothing else hides it).  The scheduling barriers keep the compiler from undoing the order.
+            f32x16 S0 = zero16(), dP0 = zero16(), S1 = zero16(), dP1 = zero16(), Pm;
+            FragV Pb0[SPB], Pb1[SPB];
+            Frag dSb0[SPB], dSb1[SPB];
+            f32x4 ls0[4], dls0[4], ls1[4], dls1[4];
+            // Rows past L need no mask: their padded lse2p is huge, so P = exp2(-huge) = 0.
+            // The empty asm statements pin the element's arithmetic between the two products around it
+            // (they are ordered with the scheduling barriers; plain arithmetic alone is not).
+            auto elem = [&](int jj, f32x16& S, const f32x16& dP, const f32x4* ls, const f32x4* dls) {
+                float sv = S[jj], dv = dP[jj];
+                asm volatile("" : "+v"(sv), "+v"(dv));
+                const float P = __builtin_amdgcn_exp2f(__builtin_fmaf(sv, sl2, -ls[jj >> 2][jj & 3]) - ckj);
+                const float dz = P * (dv - dls[jj >> 2][jj & 3]);
+                if (FOX) dcol += dz;
+                float ds = dz * p.scale, pv = P;
+                asm volatile("" : "+v"(ds), "+v"(pv));
+                Pm[jj] = pv;
+                S[jj] = ds;
+            };
+            Frag xa0[DS], xa1[DS], tb0[DB * SPB], tb1[DB * SPB];
+            FragV da0[DS], da1[DS], ta0[DB * SPB], ta1[DB * SPB];
+#pragma unroll
+            for (int u = 0; u < DS; ++u) { xa0[u] = sX[u * 64 + lane]; da0[u] = sDQ[u * 64 + lane]; }
+            __builtin_amdgcn_sched_barrier(0);
+            // logits and dP of half 0
+#pragma unroll
+            for (int u = 0; u < DS; ++u) {
+                S0 = Tr<T>::mma(xa0[u], Kb[u], S0);
+                dP0 = Tr<TIO>::mma(da0[u], Vb[u], dP0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            if (spread) issue(i + 1, 1);
+            // logits and dP of half 1  ||  element-wise part of half 0
+#pragma unroll
+            for (int u = 0; u < DS; ++u) { xa1[u] = sX[(DS + u) * 64 + lane]; da1[u] = sDQ[(DS + u) * 64 + lane]; }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                ls0[g] = *reinterpret_cast<const f32x4*>(lse2 + 8 * g + 4 * h);
+                dls0[g] = *reinterpret_cast<const f32x4*>(dl + 8 * g + 4 * h);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < DS; ++u) {
+                S1 = Tr<T>::mma(xa1[u], Kb[u], S1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (2 * u < 16) elem(2 * u, S0, dP0, ls0, dls0);
+                __builtin_amdgcn_sched_barrier(0);
+                dP1 = Tr<TIO>::mma(da1[u], Vb[u], dP1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (2 * u + 1 < 16) elem(2 * u + 1, S0, dP0, ls0, dls0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (DS < 8) {
+#pragma unroll
+                for (int jj = 2 * DS; jj < 16; ++jj) elem(jj, S0, dP0, ls0, dls0);
+            }
+            pack_block<TIO>(Pm, Pb0);
+            pack_block<T>(S0, dSb0);
+            if (spread) issue(i + 1, 3);
+            // dV^T, dKb^T of half 0  ||  element-wise part of half 1
+#pragma unroll
+            for (int u = 0; u < DB * SPB; ++u) {
+                ta0[u] = sDT[((u / SPB) * QS + u % SPB) * 64 + lane];
+                tb0[u] = sXT[((u / SPB) * QS + u % SPB) * 64 + lane];
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                ls1[g] = *reinterpret_cast<const f32x4*>(lse2 + 32 + 8 * g + 4 * h);
+                dls1[g] = *reinterpret_cast<const f32x4*>(dl + 32 + 8 * g + 4 * h);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < DB * SPB; ++u) {
+                dVt[u / SPB] = Tr<TIO>::mma(ta0[u], Pb0[u % SPB], dVt[u / SPB]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (2 * u < 16) elem(2 * u, S1, dP1, ls1, dls1);
+                __builtin_amdgcn_sched_barrier(0);
+                dKt[u / SPB] = Tr<T>::mma(tb0[u], dSb0[u % SPB], dKt[u / SPB]);
+                __builtin_amdgcn_sched_barrier(0);
+                if (2 * u + 1 < 16) elem(2 * u + 1, S1, dP1, ls1, dls1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (DB * SPB < 8) {
+#pragma unroll
+                for (int jj = 2 * DB * SPB; jj < 16; ++jj) elem(jj, S1, dP1, ls1, dls1);
+            }
+            pack_block<TIO>(Pm, Pb1);
+            pack_block<T>(S1, dSb1);
+            if (spread) issue(i + 1, 2);
+            // dV^T, dKb^T of half 1
+#pragma unroll
+            for (int u = 0; u < DB * SPB; ++u) {
+                ta1[u] = sDT[((u / SPB) * QS + SPB + u % SPB) * 64 + lane];
+                tb1[u] = sXT[((u / SPB) * QS + SPB + u % SPB) * 64 + lane];
+            }
+#pragma unroll
+            for (int u = 0; u < DB * SPB; ++u) {
+                dVt[u / SPB] = Tr<TIO>::mma(ta1[u], Pb1[u % SPB], dVt[u / SPB]);
+                dKt[u / SPB] = Tr<T>::mma(tb1[u], dSb1[u % SPB], dKt[u / SPB]);
+            }
+        } else {
+#pragma unroll
+            for (int qq = 0; qq < CPW; ++qq) {
+                const int qh = FAR ? qq : (wv >> 1);
+                f32x16 S, dP;
+                FragV Pb[SPB];
+                Frag dSb[SPB];
+                sdp(qh, S, dP);
+                if (FAR && spread) issue(i + 1, qq == 0 ? 1 : 3);
+                soft(qh, S, dP, Pb, dSb);
+                upd(qh, Pb, dSb);
+                if (FAR && spread && qq == 0) issue(i + 1, 2);
+            }
         }
     }
     if (FAR) {

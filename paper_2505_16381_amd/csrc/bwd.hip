@@ -221,47 +221,125 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
         if (next_starts) load_x(j + 1, Xnext);
 
         Frag dSb[QS];
+        if (sizeof(T) == 2) {
+            // The two key halves, software-pipelined by hand: the element-wise part of one half is
+            // interleaved, element by element, with the products that follow it (one wave per SIMD:
+            // nothing else hides it).  The scheduling barriers and the empty asm statements keep the
+            // compiler from undoing the order.
+            f32x16 S0 = zero16(), dP0 = zero16(), S1 = zero16(), dP1 = zero16();
+            f32x4 ck0[4], ck1[4];
+            if (FOX) {      // gate sums of the 16 keys this lane holds (rows 8g + 4h + r of each 32-key block)
+                const float* ck = p.cum + (size_t)bh * Lp + (size_t)j * CHUNK + 4 * h;
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
-            f32x16 S = zero16(), dP = zero16();
-            // operand fragments are fetched in batches ahead of the products that use them
-#pragma unroll
-            for (int s0 = 0; s0 < DS; s0 += 4) {
-                Frag ka[4];
-                FragV va[4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) { ka[u] = sK[(kb * DS + s0 + u) * 64 + lane]; va[u] = sV[(kb * DS + s0 + u) * 64 + lane]; }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    S = Tr<T>::mma(ka[u], Xb[s0 + u], S);
-                    dP = Tr<TIO>::mma(va[u], dOb[s0 + u], dP);
-                }
+                for (int g = 0; g < 4; ++g) { ck0[g] = *reinterpret_cast<const f32x4*>(ck + 8 * g); ck1[g] = *reinterpret_cast<const f32x4*>(ck + 32 + 8 * g); }
             }
-            f32x4 ck4[4];
-            if (FOX) {      // gate sums of the 16 keys this lane holds (rows 8g + 4h + r of the 32-key block)
-                const float* ck = p.cum + (size_t)bh * Lp + (size_t)j * CHUNK + 32 * kb + 4 * h;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) ck4[g] = *reinterpret_cast<const f32x4*>(ck + 8 * g);
-            }
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) {
-                const float arg = __builtin_fmaf(S[jj], sl2, -lse2) - (FOX ? ck4[jj >> 2][jj & 3] : 0.f);
+            auto elem = [&](int jj, f32x16& S, const f32x16& dP, const f32x4* ck) {
+                float sv = S[jj], dv = dP[jj];
+                asm volatile("" : "+v"(sv), "+v"(dv));
+                const float arg = __builtin_fmaf(sv, sl2, -lse2) - (FOX ? ck[jj >> 2][jj & 3] : 0.f);
                 const float P = (tq < L) ? __builtin_amdgcn_exp2f(arg) : 0.f;
-                const float dz = P * (dP[jj] - dl);
+                const float dz = P * (dv - dl);
                 if (FOX) drow += dz;
-                S[jj] = dz * p.scale;
+                float ds = dz * p.scale;
+                asm volatile("" : "+v"(ds));
+                S[jj] = ds;
+            };
+            Frag ka[DS], ta[DB * SPB];
+            FragV va[DS];
+#pragma unroll
+            for (int u = 0; u < DS; ++u) { ka[u] = sK[u * 64 + lane]; va[u] = sV[u * 64 + lane]; }
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int u = 0; u < DS; ++u) {
+                S0 = Tr<T>::mma(ka[u], Xb[u], S0);
+                dP0 = Tr<TIO>::mma(va[u], dOb[u], dP0);
             }
-            pack_block<T>(S, dSb + kb * SPB);
-            if (spread) issue(j + 1, 1 + kb);
-        }
-        if (spread) issue(j + 1, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            if (spread) issue(j + 1, 1);
+            // logits and dP of key half 1  ||  element-wise part of half 0
 #pragma unroll
-        for (int b = 0; b < DB; b += 2) {
-            Frag ta[2 * QS];
+            for (int u = 0; u < DS; ++u) { ka[u] = sK[(DS + u) * 64 + lane]; va[u] = sV[(DS + u) * 64 + lane]; }
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int u = 0; u < 2 * QS; ++u) ta[u] = sKT[((b + u / QS) * QS + u % QS) * 64 + lane];
+            for (int u = 0; u < DS; ++u) {
+                S1 = Tr<T>::mma(ka[u], Xb[u], S1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (2 * u < 16) elem(2 * u, S0, dP0, ck0);
+                __builtin_amdgcn_sched_barrier(0);
+                dP1 = Tr<TIO>::mma(va[u], dOb[u], dP1);
+                __builtin_amdgcn_sched_barrier(0);
+                if (2 * u + 1 < 16) elem(2 * u + 1, S0, dP0, ck0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            if (DS < 8) {
 #pragma unroll
-            for (int u = 0; u < 2 * QS; ++u) Gm[b + u / QS] = Tr<T>::mma(ta[u], dSb[u % QS], Gm[b + u / QS]);
+                for (int jj = 2 * DS; jj < 16; ++jj) elem(jj, S0, dP0, ck0);
+            }
+            pack_block<T>(S0, dSb);
+            if (spread) issue(j + 1, 2);
+            // g^T += Kb^T dS^T, keys of half 0  ||  element-wise part of half 1
+#pragma unroll
+            for (int u = 0; u < DB * SPB; ++u) ta[u] = sKT[((u / SPB) * QS + u % SPB) * 64 + lane];
+            __builtin_amdgcn_sched_barrier(0);
+            constexpr int EPM = 16 / (DB * SPB);       // elements per product
+#pragma unroll
+            for (int u = 0; u < DB * SPB; ++u) {
+                Gm[u / SPB] = Tr<T>::mma(ta[u], dSb[u % SPB], Gm[u / SPB]);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int e = 0; e < EPM; ++e) elem(EPM * u + e, S1, dP1, ck1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            pack_block<T>(S1, dSb + SPB);
+            if (spread) issue(j + 1, 3);
+            // ... keys of half 1
+#pragma unroll
+            for (int u = 0; u < DB * SPB; ++u) ta[u] = sKT[((u / SPB) * QS + SPB + u % SPB) * 64 + lane];
+#pragma unroll
+            for (int u = 0; u < DB * SPB; ++u) Gm[u / SPB] = Tr<T>::mma(ta[u], dSb[SPB + u % SPB], Gm[u / SPB]);
+        } else {
+    #pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                f32x16 S = zero16(), dP = zero16();
+                // operand fragments are fetched in batches ahead of the products that use them
+    #pragma unroll
+                for (int s0 = 0; s0 < DS; s0 += 4) {
+                    Frag ka[4];
+                    FragV va[4];
+    #pragma unroll
+                    for (int u = 0; u < 4; ++u) { ka[u] = sK[(kb * DS + s0 + u) * 64 + lane]; va[u] = sV[(kb * DS + s0 + u) * 64 + lane]; }
+    #pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        S = Tr<T>::mma(ka[u], Xb[s0 + u], S);
+                        dP = Tr<TIO>::mma(va[u], dOb[s0 + u], dP);
+                    }
+                }
+                f32x4 ck4[4];
+                if (FOX) {      // gate sums of the 16 keys this lane holds (rows 8g + 4h + r of the 32-key block)
+                    const float* ck = p.cum + (size_t)bh * Lp + (size_t)j * CHUNK + 32 * kb + 4 * h;
+    #pragma unroll
+                    for (int g = 0; g < 4; ++g) ck4[g] = *reinterpret_cast<const f32x4*>(ck + 8 * g);
+                }
+    #pragma unroll
+                for (int jj = 0; jj < 16; ++jj) {
+                    const float arg = __builtin_fmaf(S[jj], sl2, -lse2) - (FOX ? ck4[jj >> 2][jj & 3] : 0.f);
+                    const float P = (tq < L) ? __builtin_amdgcn_exp2f(arg) : 0.f;
+                    const float dz = P * (dP[jj] - dl);
+                    if (FOX) drow += dz;
+                    S[jj] = dz * p.scale;
+                }
+                pack_block<T>(S, dSb + kb * SPB);
+                if (spread) issue(j + 1, 1 + kb);
+            }
+            if (spread) issue(j + 1, 3);
+    #pragma unroll
+            for (int b = 0; b < DB; b += 2) {
+                Frag ta[2 * QS];
+    #pragma unroll
+                for (int u = 0; u < 2 * QS; ++u) ta[u] = sKT[((b + u / QS) * QS + u % QS) * 64 + lane];
+    #pragma unroll
+                for (int u = 0; u < 2 * QS; ++u) Gm[b + u / QS] = Tr<T>::mma(ta[u], dSb[u % QS], Gm[b + u / QS]);
+            }
         }
         if (j > 0 && first) {
 #pragma unroll

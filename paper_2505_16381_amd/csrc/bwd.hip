@@ -354,9 +354,10 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
                     for (int u = 0; u < NB8; ++u) Gm[b] = Tr<T>::mma(pa[u], Gb[s0 + u], Gm[b]);
                 }
         }
+        if (next_starts) {     // g after this block: operand copy for the next block's product, and
+                               // tile gT (rows b, contraction q) of the pair (cq, next block)
 #pragma unroll
-        for (int b = 0; b < DB; ++b) pack_block<T>(Gm[b], Gb + b * SPB);
-        if (next_starts) {     // g after this block, as tile gT (rows b, contraction q) of the pair (cq, next block)
+            for (int b = 0; b < DB; ++b) pack_block<T>(Gm[b], Gb + b * SPB);
             const size_t slot2 = ((size_t)bh * nslots + block_slot(cq, j + 1, NC)) * (size_t)CHUNK * D;
             Frag* gt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.gs) + slot2);
 #pragma unroll

@@ -148,9 +148,9 @@ def bench_fox(args, torch, pa, si, dev):
     def step(record):
         e0, e1, e2 = (ev(), ev(), ev()) if record else (None,) * 3
         if record: e0.record()
-        o, lse = pa.path_attn_fox_fwd(q, k, v, w, beta, logf, scale=scale, workspace=ws_f)
+        o, lse = pa.path_attn_train_fwd(q, k, v, w, beta, ws_b, log_f=logf, scale=scale)      # the training pair, with gates
         if record: e1.record()
-        pa.path_attn_fox_bwd(q, k, v, w, beta, logf, o, lse, dO, scale=scale, workspace=ws_b)
+        pa.path_attn_train_bwd(q, k, v, w, beta, o, lse, dO, ws_b, log_f=logf, scale=scale)
         if record:
             e2.record()
             marks.append((e0, e1, e2))
@@ -172,7 +172,7 @@ def bench_fox(args, torch, pa, si, dev):
         "metric": "PaTH-FoX attn fwd+bwd TFLOP/s (attention-equivalent)", "value": value, "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16 I/O, fp16+bf16 MFMA operands, fp32 accumulate", "data": "synthetic",
-        "config": {"workload": f"PaTH-FoX forward+backward, B={B} H={H} L={L} d={d} causal"},
+        "config": {"workload": f"PaTH-FoX forward+backward (training pair, shared workspace), B={B} H={H} L={L} d={d} causal"},
         "fwd": {"ms": fwd_ms, "attn_equiv_tflops": fl / (fwd_ms * 1e-3) / 1e12},
         "bwd": {"ms": bwd_ms, "attn_equiv_tflops": 2.5 * fl / (bwd_ms * 1e-3) / 1e12},
     }))
@@ -230,15 +230,23 @@ def main():
     ev = lambda: torch.cuda.Event(enable_timing=True)
     marks = []
 
+    # One training step = the training pair: forward and backward share the backward-sized workspace, so the
+    # chunk transform runs once per step (forward-only runs use the plain forward and its smaller workspace).
     def step(record):
         e0, e1, e2, e3 = (ev(), ev(), ev(), ev()) if record else (None,) * 4
         if record: e0.record()
-        pa.path_attn_fwd_prep(t["q"], t["k"], t["v"], t["w"], t["beta"], ws_f)
+        if do_bwd:
+            pa.path_attn_train_fwd_prep(t["q"], t["k"], t["v"], t["w"], t["beta"], ws_b)
+        else:
+            pa.path_attn_fwd_prep(t["q"], t["k"], t["v"], t["w"], t["beta"], ws_f)
         if record: e1.record()
-        pa.path_attn_fwd_sweep(o, lse, scale, ws_f)
+        if do_bwd:
+            pa.path_attn_train_fwd_sweep(o, lse, scale, ws_b)
+        else:
+            pa.path_attn_fwd_sweep(o, lse, scale, ws_f)
         if record: e2.record()
         if do_bwd:
-            pa.path_attn_bwd(t["q"], t["k"], t["v"], t["w"], t["beta"], o, lse, t["dO"], scale=scale, workspace=ws_b)
+            pa.path_attn_train_bwd(t["q"], t["k"], t["v"], t["w"], t["beta"], o, lse, t["dO"], ws_b, scale=scale)
         if record:
             e3.record()
             marks.append((e0, e1, e2, e3))
@@ -257,6 +265,20 @@ def main():
     sweep_ms = sum(b.elapsed_time(c) for _, b, c, _ in marks) / len(marks)
     bwd_ms = sum(c.elapsed_time(e) for _, _, c, e in marks) / len(marks) if do_bwd else None
 
+    # for the record, outside the timed region: the stand-alone calls (each runs the transform itself)
+    alone = None
+    if do_bwd:
+        a0, a1, a2 = ev(), ev(), ev()
+        for i in range(3):
+            if i == 1: a0.record()
+            pa.path_attn_fwd(t["q"], t["k"], t["v"], t["w"], t["beta"], scale=scale, o=o, lse=lse, workspace=ws_f)
+        a1.record()
+        for i in range(2):
+            pa.path_attn_bwd(t["q"], t["k"], t["v"], t["w"], t["beta"], o, lse, t["dO"], scale=scale, workspace=ws_b)
+        a2.record()
+        torch.cuda.synchronize()
+        alone = {"path_attn_fwd_ms": a0.elapsed_time(a1) / 2, "path_attn_bwd_ms": a1.elapsed_time(a2) / 2}
+
     fl_f = attn_flops(B, H, L, d)
     fl_step = fl_f * (3.5 if do_bwd else 1.0)
     value = fl_step / (ms_step * 1e-3) / 1e12
@@ -270,13 +292,14 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: B={B} H={H} L={L} d={d} causal, "
                                f"{'forward+backward' if do_bwd else 'forward only (no backward at this shape yet)'}",
-                   "passes": "fwd+bwd" if do_bwd else "fwd"},
+                   "passes": "fwd+bwd (training pair: path_attn_train_fwd + path_attn_train_bwd, shared workspace)" if do_bwd else "fwd"},
         "pct_of_mfma_peak": 100.0 * value / PEAK_TFLOPS,
         "tokens_per_s": B * L / (ms_step * 1e-3),
         "fwd": {"ms": prep_ms + sweep_ms, "prep_ms": prep_ms, "sweep_ms": sweep_ms,
                 "attn_equiv_tflops": fwd_tflops, "pct_of_mfma_peak": 100.0 * fwd_tflops / PEAK_TFLOPS,
                 "path_inclusive_tflops": (fl_f + path_extra_flops(B, H, L, d)) / ((prep_ms + sweep_ms) * 1e-3) / 1e12},
         "bwd": ({"ms": bwd_ms, "attn_equiv_tflops": 2.5 * fl_f / (bwd_ms * 1e-3) / 1e12} if do_bwd else None),
+        "standalone_calls": alone,
         "roofline": {"kernel": "attn_fwd_kernel (sweep)", "bound": "mfma", "achieved": sweep_tflops,
                      "peak": PEAK_TFLOPS, "unit": "TFLOP/s", "frac": sweep_tflops / PEAK_TFLOPS,
                      "traffic": SWEEP_HBM_BYTES if (args.config == 2 and not args.shape) else None,

@@ -152,6 +152,35 @@ path_status_t path_attn_fox_bwd(const void* q, const void* k, const void* v, con
                                 path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * Training pair: forward and backward of one step that share a workspace, so that the chunk
+ * transform (paper Sec. 3.2) runs once per step instead of once in each.  path_attn_train_fwd
+ * computes o and lse exactly as path_attn_fwd (log_f == NULL) or path_attn_fox_fwd (log_f given)
+ * do, but in a workspace of the BACKWARD's size (path_attn_workspace_bytes(..., for_backward = 1)),
+ * where it leaves the transformed operands; path_attn_train_bwd then computes the gradients exactly
+ * as path_attn_bwd / path_attn_fox_bwd do (dlog_f given iff log_f is), provided that the workspace
+ * has not been written since path_attn_train_fwd returned and that q, k, v, w, beta, log_f are the
+ * same tensors with the same contents.  The price is that the workspace stays alive between the
+ * two calls.  Arguments, layouts and error codes as for the calls they stand in for.
+ */
+path_status_t path_attn_train_fwd(const void* q, const void* k, const void* v, const void* w,
+                                  const void* beta, const void* log_f, void* o, float* lse,
+                                  int B, int H, int L, int d, int causal, float scale,
+                                  path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+/* path_attn_train_fwd as two launches, for callers that time or overlap the stages: it is exactly
+ * path_attn_train_fwd_prep followed by path_attn_train_fwd_sweep on the same stream and workspace
+ * (with_gates != 0 iff log_f was given to the first). */
+path_status_t path_attn_train_fwd_prep(const void* q, const void* k, const void* v, const void* w,
+                                       const void* beta, const void* log_f, int B, int H, int L, int d,
+                                       path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+path_status_t path_attn_train_fwd_sweep(void* o, float* lse, int with_gates, int B, int H, int L, int d, float scale,
+                                        path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+path_status_t path_attn_train_bwd(const void* q, const void* k, const void* v, const void* w,
+                                  const void* beta, const void* log_f, const void* o, const float* lse,
+                                  const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                  void* dlog_f, int B, int H, int L, int d, int causal, float scale,
+                                  path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Decode path (paper Sec. 3.4 "Efficient Inference").  Caches are caller-owned device memory,
  * kcache and vcache [B,H,Lmax,d] contiguous in the I/O type dt; position i of a head holds
  * token i.  The key cache holds REFRESHED keys: after t tokens, k_i^(t) = H_t ... H_{i+1} k_i

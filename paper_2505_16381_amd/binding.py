@@ -63,6 +63,14 @@ def load_library():
     lib.path_attn_fox_fwd.argtypes = [vp] * 8 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_attn_fox_bwd.restype = ci
     lib.path_attn_fox_bwd.argtypes = [vp] * 15 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_train_fwd.restype = ci
+    lib.path_attn_train_fwd.argtypes = [vp] * 8 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_train_fwd_prep.restype = ci
+    lib.path_attn_train_fwd_prep.argtypes = [vp] * 6 + [ci, ci, ci, ci, ci, vp, sz, vp]
+    lib.path_attn_train_fwd_sweep.restype = ci
+    lib.path_attn_train_fwd_sweep.argtypes = [vp, vp, ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_train_bwd.restype = ci
+    lib.path_attn_train_bwd.argtypes = [vp] * 15 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_decode_workspace_bytes.restype = sz
     lib.path_decode_workspace_bytes.argtypes = [ci, ci, ci]
     lib.path_key_prefill.restype = ci
@@ -245,3 +253,48 @@ def path_attn_fox_bwd(q, k, v, w, beta, log_f, o, lse, d_o, scale=None, workspac
                                             *[_ptr(x) for x in outs], B, H, L, d, 1, scale, dt,
                                             _ptr(workspace), workspace.numel(), _stream_handle(stream)))
     return tuple(outs)
+
+
+def path_attn_train_fwd(q, k, v, w, beta, workspace, log_f=None, scale=None, stream=None):
+    """Forward of the training pair: o, lse as path_attn_fwd (or path_attn_fox_fwd with log_f); `workspace`
+    (backward-sized, path_attn_workspace_bytes(..., True)) keeps what path_attn_train_bwd starts from."""
+    import torch
+    B, H, L, d = q.shape
+    scale = float(d ** -0.5 if scale is None else scale)
+    dt = _dt_of(q)
+    o = torch.empty_like(q)
+    lse = torch.empty((B, H, L), dtype=torch.float32, device=q.device)
+    _check(load_library().path_attn_train_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(log_f) if log_f is not None else None,
+                                              _ptr(o), _ptr(lse), B, H, L, d, 1, scale, dt,
+                                              _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return o, lse
+
+
+def path_attn_train_bwd(q, k, v, w, beta, o, lse, d_o, workspace, log_f=None, scale=None, stream=None):
+    """Backward of the training pair on the workspace path_attn_train_fwd left: (dq, dk, dv, dw, dbeta[, dlog_f])."""
+    import torch
+    B, H, L, d = q.shape
+    scale = float(d ** -0.5 if scale is None else scale)
+    dt = _dt_of(q)
+    outs = [torch.empty_like(q) for _ in range(4)] + [torch.empty_like(beta)]
+    dlog_f = torch.empty_like(log_f) if log_f is not None else None
+    _check(load_library().path_attn_train_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(log_f) if log_f is not None else None,
+                                              _ptr(o), _ptr(lse), _ptr(d_o), *[_ptr(x) for x in outs],
+                                              _ptr(dlog_f) if dlog_f is not None else None, B, H, L, d, 1, scale, dt,
+                                              _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return tuple(outs) + ((dlog_f,) if dlog_f is not None else ())
+
+
+def path_attn_train_fwd_prep(q, k, v, w, beta, workspace, log_f=None, stream=None):
+    """First stage of path_attn_train_fwd: the transforms, into the backward-sized workspace."""
+    B, H, L, d = q.shape
+    _check(load_library().path_attn_train_fwd_prep(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta),
+                                                   _ptr(log_f) if log_f is not None else None, B, H, L, d, _dt_of(q),
+                                                   _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+
+
+def path_attn_train_fwd_sweep(o, lse, scale, workspace, with_gates=False, stream=None):
+    """Second stage of path_attn_train_fwd: the sweep, on the workspace the first stage filled."""
+    B, H, L, d = o.shape
+    _check(load_library().path_attn_train_fwd_sweep(_ptr(o), _ptr(lse), int(bool(with_gates)), B, H, L, d, float(scale), _dt_of(o),
+                                                    _ptr(workspace), workspace.numel(), _stream_handle(stream)))

@@ -67,7 +67,10 @@ static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
     take(w.rm, BH * NC * d * d * es);
     take(w.dk2, BH * Lp * d * 4);
     take(w.dchain, BH * (NC + 1) * d * d * 4);
-    take(w.t1, BH * NC * d * CHUNK * 4);
+    // (regions only the fp32-operand path uses -- the second level's chain and the chunk-transform adjoint as
+    //  staged products -- have size zero for 2-byte operands, whose fused kernels keep these in LDS)
+    const size_t staged = es == 4 ? 1 : 0;
+    take(w.t1, staged * BH * NC * d * CHUNK * 4);
     take(w.dcol, BH * Lp * 4);
     take(w.drow, BH * Lp * 4);
     for (size_t* f : {&w.fm, &w.gktm, &w.nm, &w.aim, &w.ytm}) take(*f, BH * NC * 4096 * es);
@@ -78,9 +81,9 @@ static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
     take(w.lse2p, BH * Lp * 4);
     for (size_t* f : {&w.dqb, &w.dkb, &w.dvp}) take(*f, BH * Lp * d * 4);
     take(w.ddp, BH * NC * d * d * 4);
-    for (size_t* f : {&w.dpd, &w.pd, &w.dsd, &w.df, &w.dy, &w.dn, &w.dgk, &w.rr, &w.mm, &w.dgs}) take(*f, BH * NC * 4096 * 4);
-    for (size_t* f : {&w.du, &w.dqf, &w.dkf, &w.dwf}) take(*f, BH * Lp * d * 4);
-    take(w.dbf, BH * Lp * 4);
+    for (size_t* f : {&w.dpd, &w.pd, &w.dsd, &w.df, &w.dy, &w.dn, &w.dgk, &w.rr, &w.mm, &w.dgs}) take(*f, staged * BH * NC * 4096 * 4);
+    for (size_t* f : {&w.du, &w.dqf, &w.dkf, &w.dwf}) take(*f, staged * BH * Lp * d * 4);
+    take(w.dbf, staged * BH * Lp * 4);
     w.total = off;
     return w;
 }
@@ -241,20 +244,32 @@ extern "C" path_status_t path_attn_fox_fwd(const void* q, const void* k, const v
     return PATH_OK;
 }
 
-// Backward of plain PaTH (log_f == NULL) and of PaTH-FoX (log_f, dlog_f given).
-static path_status_t bwd_impl(const void* q, const void* k, const void* v, const void* w,
+// Backward of plain PaTH (log_f == NULL) and of PaTH-FoX (log_f, dlog_f given), and the forward of the
+// training pair, which runs the backward's instantiations of the two transforms so that the backward
+// can start from what they left in the workspace.
+enum BwdMode { BWD_FULL = 0,        // transforms + backward (path_attn_bwd)
+               BWD_FWD_ONLY = 1,    // transforms + forward sweep, everything the backward needs stays in the workspace
+               BWD_RESUME = 2,      // backward without the transforms (the workspace is as BWD_FWD_ONLY left it)
+               BWD_FWD_PREP = 3,    // the two halves of BWD_FWD_ONLY as separate calls: transforms ...
+               BWD_FWD_SWEEP = 4 }; // ... and the forward sweep
+static path_status_t bwd_impl(BwdMode mode, const void* q, const void* k, const void* v, const void* w,
                               const void* beta, const void* log_f, const void* o, const float* lse, const void* d_o,
                               void* dq, void* dk, void* dv, void* dw, void* dbeta, void* dlog_f, int B, int H,
                               int L, int d, int causal, float scale, path_dtype_t dt,
                               void* workspace, size_t workspace_bytes, void* stream) {
-    if (!q || !k || !v || !w || !beta || !o || !lse || !d_o || !dq || !dk || !dv || !dw || !dbeta || !workspace)
-        return PATH_ERR_NULL;
-    if ((log_f == nullptr) != (dlog_f == nullptr)) return PATH_ERR_NULL;
+    if (!workspace) return PATH_ERR_NULL;
+    if (mode != BWD_FWD_SWEEP && (!q || !k || !v || !w || !beta)) return PATH_ERR_NULL;
+    if (mode != BWD_FWD_PREP && (!o || !lse)) return PATH_ERR_NULL;
+    const bool fwd_mode = mode == BWD_FWD_ONLY || mode == BWD_FWD_PREP || mode == BWD_FWD_SWEEP;
+    if (!fwd_mode) {
+        if (!d_o || !dq || !dk || !dv || !dw || !dbeta) return PATH_ERR_NULL;
+        if ((log_f == nullptr) != (dlog_f == nullptr)) return PATH_ERR_NULL;
+    }
     if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
     if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
     if (!causal || !(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
     const void* al[] = {q, k, v, w, o, d_o, dq, dk, dv, dw};
-    for (const void* ptr : al) if (misaligned(ptr)) return PATH_ERR_ALIGN;
+    for (const void* ptr : al) if (misaligned(ptr)) return PATH_ERR_ALIGN;      // (NULL is aligned)
     const int bf = dt == PATH_BF16;
     const size_t es = bf ? 2 : 4;
     const BwdWorkspace ws = bwd_workspace(B, H, L, d, es);
@@ -277,13 +292,18 @@ static path_status_t bwd_impl(const void* q, const void* k, const void* v, const
     fp.fm = base + ws.fm; fp.gktm = base + ws.gktm; fp.nm = base + ws.nm; fp.aim = base + ws.aim;
     fp.ytm = base + ws.ytm; fp.utm = base + ws.utm; fp.gm = F(ws.gm); fp.sdm = F(ws.sdm);
     clear_inherited_error();
-    float* cum = nullptr;
-    if (log_f) {
-        cum = F(ws.f.cum);
-        if (!hip_ok(launch_gate_sums(log_f, cum, B, H, L, dt, st), "gate sums (backward)")) return PATH_ERR_HIP;
+    float* cum = log_f ? F(ws.f.cum) : nullptr;
+    if (mode != BWD_RESUME && mode != BWD_FWD_SWEEP) {
+        if (log_f && !hip_ok(launch_gate_sums(log_f, cum, B, H, L, dt, st), "gate sums (backward)")) return PATH_ERR_HIP;
+        if (!hip_ok(launch_prep_fwd(fp, d, bf, st), "chunk transform (backward)")) return PATH_ERR_HIP;
+        if (!hip_ok(launch_prep2_fwd(fp, d, bf, st), "second-level transform (backward)")) return PATH_ERR_HIP;
     }
-    if (!hip_ok(launch_prep_fwd(fp, d, bf, st), "chunk transform (backward)")) return PATH_ERR_HIP;
-    if (!hip_ok(launch_prep2_fwd(fp, d, bf, st), "second-level transform (backward)")) return PATH_ERR_HIP;
+    if (mode == BWD_FWD_PREP) return PATH_OK;
+    if (fwd_mode) {
+        fp.o = const_cast<void*>(o); fp.lse = const_cast<float*>(lse); fp.cum = cum;
+        if (!hip_ok(launch_attn_fwd2(fp, d, bf, st), "forward sweep (training pair)")) return PATH_ERR_HIP;
+        return PATH_OK;
+    }
     if (NC > 1 && !hip_ok(launch_attn_states(fp, d, bf, st), "query states")) return PATH_ERR_HIP;
 
     // 2.-4. delta, adjoint scan over key chunks, key-side reductions
@@ -499,7 +519,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
                                        void* dq, void* dk, void* dv, void* dw, void* dbeta, int B, int H,
                                        int L, int d, int causal, float scale, path_dtype_t dt,
                                        void* workspace, size_t workspace_bytes, void* stream) {
-    return bwd_impl(q, k, v, w, beta, nullptr, o, lse, d_o, dq, dk, dv, dw, dbeta, nullptr, B, H, L, d, causal, scale, dt,
+    return bwd_impl(BWD_FULL, q, k, v, w, beta, nullptr, o, lse, d_o, dq, dk, dv, dw, dbeta, nullptr, B, H, L, d, causal, scale, dt,
                     workspace, workspace_bytes, stream);
 }
 
@@ -509,6 +529,37 @@ extern "C" path_status_t path_attn_fox_bwd(const void* q, const void* k, const v
                                            void* dlog_f, int B, int H, int L, int d, int causal, float scale,
                                            path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
     if (!log_f || !dlog_f) return PATH_ERR_NULL;
-    return bwd_impl(q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
+    return bwd_impl(BWD_FULL, q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
+                    workspace, workspace_bytes, stream);
+}
+
+extern "C" path_status_t path_attn_train_fwd(const void* q, const void* k, const void* v, const void* w,
+                                             const void* beta, const void* log_f, void* o, float* lse,
+                                             int B, int H, int L, int d, int causal, float scale,
+                                             path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
+    return bwd_impl(BWD_FWD_ONLY, q, k, v, w, beta, log_f, o, lse, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                    B, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
+}
+
+extern "C" path_status_t path_attn_train_fwd_prep(const void* q, const void* k, const void* v, const void* w,
+                                                  const void* beta, const void* log_f, int B, int H, int L, int d,
+                                                  path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
+    return bwd_impl(BWD_FWD_PREP, q, k, v, w, beta, log_f, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+                    nullptr, B, H, L, d, 1, 1.f, dt, workspace, workspace_bytes, stream);
+}
+
+extern "C" path_status_t path_attn_train_fwd_sweep(void* o, float* lse, int with_gates, int B, int H, int L, int d, float scale,
+                                                   path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
+    // (log_f itself is not read here: the gate sums are in the workspace; any non-NULL value selects them)
+    return bwd_impl(BWD_FWD_SWEEP, nullptr, nullptr, nullptr, nullptr, nullptr, with_gates ? workspace : nullptr, o, lse, nullptr,
+                    nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, B, H, L, d, 1, scale, dt, workspace, workspace_bytes, stream);
+}
+
+extern "C" path_status_t path_attn_train_bwd(const void* q, const void* k, const void* v, const void* w,
+                                             const void* beta, const void* log_f, const void* o, const float* lse,
+                                             const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                             void* dlog_f, int B, int H, int L, int d, int causal, float scale,
+                                             path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
+    return bwd_impl(BWD_RESUME, q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
                     workspace, workspace_bytes, stream);
 }

@@ -145,7 +145,10 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
         const FragV* dq = reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.doq) + ((size_t)bh * NC + cq) * CHUNK * D);
 #pragma unroll
         for (int s = 0; s < DS; ++s) dOb[s] = dq[((size_t)qb * DS + s) * 64 + lane];
-        if (tq < L) lse2 = p.lse2p[(size_t)bh * Lp + tq];       // base-2 units (PaTH-FoX: minus the query's gate sum)
+        // base-2 units (PaTH-FoX: minus the query's gate sum); rows past L hold a huge value, so that their
+        // P = exp2(-huge) = 0 without a mask.  log2(scale) is folded in: the exponential then yields scale * P,
+        // which is all the logit gradient dS = scale * P o (dP - delta) needs.
+        lse2 = p.lse2p[(size_t)bh * Lp + tq] - __builtin_log2f(p.scale);
         dl = p.delta[(size_t)bh * Lp + tq];
     }
     f32x16 Gm[DB];
@@ -237,10 +240,8 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
                 float sv = S[jj], dv = dP[jj];
                 asm volatile("" : "+v"(sv), "+v"(dv));
                 const float arg = __builtin_fmaf(sv, sl2, -lse2) - (FOX ? ck[jj >> 2][jj & 3] : 0.f);
-                const float P = (tq < L) ? __builtin_amdgcn_exp2f(arg) : 0.f;
-                const float dz = P * (dv - dl);
-                if (FOX) drow += dz;
-                float ds = dz * p.scale;
+                float ds = __builtin_amdgcn_exp2f(arg) * (dv - dl);      // scale * P * (dP - delta)
+                if (FOX) drow += ds;
                 asm volatile("" : "+v"(ds));
                 S[jj] = ds;
             };
@@ -323,10 +324,9 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     #pragma unroll
                 for (int jj = 0; jj < 16; ++jj) {
                     const float arg = __builtin_fmaf(S[jj], sl2, -lse2) - (FOX ? ck4[jj >> 2][jj & 3] : 0.f);
-                    const float P = (tq < L) ? __builtin_amdgcn_exp2f(arg) : 0.f;
-                    const float dz = P * (dP[jj] - dl);
-                    if (FOX) drow += dz;
-                    S[jj] = dz * p.scale;
+                    const float ds = __builtin_amdgcn_exp2f(arg) * (dP[jj] - dl);      // scale * P * (dP - delta)
+                    if (FOX) drow += ds;
+                    S[jj] = ds;
                 }
                 pack_block<T>(S, dSb + kb * SPB);
                 if (spread) issue(j + 1, 1 + kb);
@@ -372,7 +372,7 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     }
     if (FOX && active) {    // the two half-waves hold different keys of the same query
         drow += __shfl_xor(drow, 32);
-        if (h == 0) p.drow[(size_t)bh * Lp + tq] = drow;
+        if (h == 0) p.drow[(size_t)bh * Lp + tq] = drow / p.scale;      // the sums above carry the factor scale
     }
     // dQb of the wave's queries: row-major fp32 [q][c] from registers (rows c, lane q)
     if (active) {
@@ -537,7 +537,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 Pm[jj] = P;
                 const float dz = P * (dP[jj] - dls[jj >> 2][jj & 3]);
                 if (FOX) dcol += dz;
-                S[jj] = dz * p.scale;
+                S[jj] = dz;                 // the factor scale of dS is applied to the finished dKb sums
             }
             pack_block<TIO>(Pm, Pb);
             pack_block<T>(S, dSb);
@@ -576,7 +576,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 const float P = __builtin_amdgcn_exp2f(__builtin_fmaf(sv, sl2, -ls[jj >> 2][jj & 3]) - ckj);
                 const float dz = P * (dv - dls[jj >> 2][jj & 3]);
                 if (FOX) dcol += dz;
-                float ds = dz * p.scale, pv = P;
+                float ds = dz, pv = P;      // the factor scale of dS is applied to the finished dKb sums
                 asm volatile("" : "+v"(ds), "+v"(pv));
                 Pm[jj] = pv;
                 S[jj] = ds;
@@ -692,7 +692,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
             for (int g = 0; g < 4; ++g) {
                 f32x4 v4 = *reinterpret_cast<const f32x4*>(p.dvp + row + 32 * b + 8 * g), k4;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) { v4[r] += dVt[b][4 * g + r]; k4[r] = dKt[b][4 * g + r]; }
+                for (int r = 0; r < 4; ++r) { v4[r] += dVt[b][4 * g + r]; k4[r] = p.scale * dKt[b][4 * g + r]; }
                 *reinterpret_cast<f32x4*>(p.dvp + row + 32 * b + 8 * g) = v4;
                 *reinterpret_cast<f32x4*>(p.dk2 + row + 32 * b + 8 * g) = k4;
             }
@@ -726,7 +726,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
 #pragma unroll
                 for (int r = 0; r < 4; ++r) {
                     v4[r] = dVt[b][4 * g + r] + red[((kh * 2 + 0) * DB + b) * 1024 + (4 * g + r) * 64 + lane];
-                    k4[r] = dKt[b][4 * g + r] + red[((kh * 2 + 1) * DB + b) * 1024 + (4 * g + r) * 64 + lane];
+                    k4[r] = p.scale * (dKt[b][4 * g + r] + red[((kh * 2 + 1) * DB + b) * 1024 + (4 * g + r) * 64 + lane]);
                 }
                 *reinterpret_cast<f32x4*>(p.dvp + row + 32 * b + 8 * g) = v4;
                 *reinterpret_cast<f32x4*>(p.dkb + row + 32 * b + 8 * g) = k4;

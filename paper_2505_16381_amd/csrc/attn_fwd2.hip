@@ -34,15 +34,6 @@ template <typename TIO, int D> struct Fwd2Cfg {
     static constexpr size_t smem_bytes = (size_t)(4 * HALF_FRAGS + DP_FRAGS) * 16 + 256;   // 2 stages x (K|V) + dP + 2 x 32 gate sums
 };
 
-// Linear copy of nfrag 16-byte fragments global -> LDS, asynchronous (direct-to-LDS):
-// wave wv moves fragments [i*256 + 64*wv, +64) of every 256-fragment group.
-template <typename Frag>
-__device__ __forceinline__ void async_tile(const Frag* g, Frag* s, int nfrag, int tid, int wv) {
-    for (int i = 0; i < nfrag; i += FWD2_THREADS)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + i + tid),
-                                         (__attribute__((address_space(3))) void*)(s + i + 64 * wv), 16, 0, 0);
-}
-
 __device__ __forceinline__ void wait_tiles_and_sync() {
     __builtin_amdgcn_s_waitcnt(0x0000);   // vmcnt(0) expcnt(0) lgkmcnt(0): this wave's tile loads have landed
     __syncthreads();
@@ -75,7 +66,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
     const int bh = (slot / ntiles) * 8 + xcd;
     const int tile = ntiles - 1 - slot % ntiles;
     if (bh >= BH) return;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
 
     const int cq = tile * 2 + (wv >> 1);            // this wave's chunk
     const int qb = wv & 1;                          // ... and which 32-query half of it
@@ -118,8 +109,8 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
         const int j = jtop - (u >> 1), kb = u & 1;
         Frag* buf = sKV + (size_t)(u & 1) * 2 * HF;
         const T* kg = (j >= jsb ? ktg : kt2g) + (size_t)j * CHUNK * D;
-        async_tile(reinterpret_cast<const Frag*>(kg) + kb * HF, buf, HF, tid, wv);
-        async_tile(reinterpret_cast<const Frag*>(vtg + (size_t)j * CHUNK * D) + kb * HF, buf + HF, HF, tid, wv);
+        async_copy_tile<FWD2_THREADS, HF>(reinterpret_cast<const Frag*>(kg) + kb * HF, buf, tid, wv);
+        async_copy_tile<FWD2_THREADS, HF>(reinterpret_cast<const Frag*>(vtg + (size_t)j * CHUNK * D) + kb * HF, buf + HF, tid, wv);
         if (FOX && tid < 8)      // 32 floats, 16 bytes per lane
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(p.cum + (size_t)bh * NC * CHUNK + (size_t)j * CHUNK + 32 * kb + 4 * tid),
                                              (__attribute__((address_space(3))) void*)(sC + (u & 1) * 32), 16, 0, 0);
@@ -128,9 +119,9 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
     // processed (sP is free then: the previous update ended before this stage's barrier)
     auto issue_dp = [&](int j) {
         if (j >= jsb) {
-            if (j < jtop && j > 0) async_tile(reinterpret_cast<const Frag*>(dpg + (size_t)j * D * D), sP, DPF, tid, wv);
+            if (j < jtop && j > 0) async_copy_tile<FWD2_THREADS, DPF>(reinterpret_cast<const Frag*>(dpg + (size_t)j * D * D), sP, tid, wv);
         } else if (j % SBC == 0 && j > 0) {
-            async_tile(reinterpret_cast<const Frag*>(dp2g + (size_t)(j / SBC) * D * D), sP, DPF, tid, wv);
+            async_copy_tile<FWD2_THREADS, DPF>(reinterpret_cast<const Frag*>(dp2g + (size_t)(j / SBC) * D * D), sP, tid, wv);
         }
     };
 

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     const int bh = (slot / ntiles) * 8 + xcd;
     const int tile = ntiles - 1 - slot % ntiles;
     if (bh >= BH) return;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
     const bool active = cq < NC;
     const int jmax = ((tile * 2 + 1 < NC) ? tile * 2 + 1 : NC - 1) - 1;     // last key chunk any wave needs
@@ -170,16 +170,16 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
         const size_t bhc = (size_t)bh * NC + j;
         const bool far = j < jsb;
         if (part < 0 || part == 0)
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2 : p.kt) + bhc * CHUNK * D), buf, KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2 : p.kt) + bhc * CHUNK * D), buf, tid, wv);
         if (part < 0 || part == 1)
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), buf + KVF, KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), buf + KVF, tid, wv);
         if (part < 0 || part == 2)
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2T : p.ktT) + bhc * CHUNK * D), buf + 2 * KVF, KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2T : p.ktT) + bhc * CHUNK * D), buf + 2 * KVF, tid, wv);
         if ((part < 0 || part == 3) && j > 0) {
             if (!far)
-                async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D), buf + 3 * KVF, DPF, tid, wv);
+                async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D), buf + 3 * KVF, tid, wv);
             else if (j % SBC == 0)
-                async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt2) + ((size_t)bh * nsb + j / SBC) * (size_t)D * D), buf + 3 * KVF, DPF, tid, wv);
+                async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dpt2) + ((size_t)bh * nsb + j / SBC) * (size_t)D * D), buf + 3 * KVF, tid, wv);
         }
     };
     auto block_start = [&](int j) { return j >= jsb || j % SBC == 0; };
@@ -437,7 +437,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     const int j = (kk / NPOS % nsb_g) * SBC + (kk % NPOS) * CPW;       // first key chunk of the workgroup
     const int bh = (kk / (NPOS * nsb_g)) * 8 + xcd;
     if (bh >= p.B * p.H || j >= NC) return;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int kh = wv & 1;
     const int jw = FAR ? j + (wv >> 1) : j;                            // this wave's key chunk
     const bool wactive = jw < NC;
@@ -472,13 +472,13 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
         const size_t slot = ((size_t)bh * nslots + block_slot(i, j, NC)) * (size_t)CHUNK * D;
         const size_t bhi = ((size_t)bh * NC + i) * CHUNK * D;
         if (part < 0 || part == 0)
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot), buf, KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot), buf, tid, wv);
         if (part < 0 || part == 2)
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf + KVF, KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf + KVF, tid, wv);
         if (part < 0 || part == 1)
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doq) + bhi), buf + 2 * KVF, KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doq) + bhi), buf + 2 * KVF, tid, wv);
         if (part < 0 || part == 3)
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doT) + bhi), buf + 3 * KVF, KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doT) + bhi), buf + 3 * KVF, tid, wv);
         if ((part < 0 || part == 0) && tid < 32) {     // 64 floats of lse2 (lanes 0-15) and of delta (lanes 16-31): 16 bytes per lane
             const float* src = (tid < 16 ? p.lse2p : p.delta) + (size_t)bh * Lp + (size_t)i * CHUNK + 4 * (tid & 15);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
@@ -772,8 +772,8 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
         auto issue = [&](int i) {
             Frag* buf = sbase + (size_t)(i & 1) * 2 * KVF;
             const size_t slot = ((size_t)bh * nslots + block_slot(i, cj, NC)) * (size_t)CHUNK * D;
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf, KVF, tid, wv);
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.gs) + slot), buf + KVF, KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.gs) + slot), buf + KVF, tid, wv);
         };
         if (i0 < i1) issue(i0);
         for (int i = i0; i < i1; ++i) {

@@ -56,9 +56,9 @@ __global__ __launch_bounds__(256) void key_prefill_kernel(PrefillArgs a) {
         for (int c = c0; c < c1; ++c) {
             const size_t bhc = (size_t)bh * NC + c;
             __syncthreads();                       // sK is free (and, first time round, Es is written)
-            async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(a.kt2) + bhc * (size_t)CHUNK * D), sK, KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(a.kt2) + bhc * (size_t)CHUNK * D), sK, tid, wv);
             if (c == c0 && J > 0)
-                async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(a.dp2) + ((size_t)bh * nsb + J) * (size_t)D * D), sDP, DPF, tid, wv);
+                async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(a.dp2) + ((size_t)bh * nsb + J) * (size_t)D * D), sDP, tid, wv);
             wait_async_and_sync();
             // K^(l)^T[cc][s] = Kb2^T[cc][s] - sum_b E[cc][b] Kb2[s][b]   (registers rows cc, lane s)
 #pragma unroll

@@ -174,13 +174,25 @@ __device__ __forceinline__ f32x16 gemm_rows(const T* ap, const T* bp, f32x16 acc
     return acc;
 }
 
-// Linear copy of nfrag 16-byte fragments global -> LDS, asynchronous (direct-to-LDS): in a
-// workgroup of NT threads wave wv moves fragments [i*NT + 64*wv, +64) of every NT-fragment group.
-template <int NT, typename Frag>
-__device__ __forceinline__ void async_copy_tile(const Frag* g, Frag* s, int nfrag, int tid, int wv) {
-    for (int i = 0; i < nfrag; i += NT)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(g + i + tid),
-                                         (__attribute__((address_space(3))) void*)(s + i + 64 * wv), 16, 0, 0);
+// Linear copy of NFRAG 16-byte fragments global -> LDS, asynchronous (direct-to-LDS), by a workgroup of
+// NT threads.  One instruction moves 64 consecutive fragments (lane = fragment); wave wv takes the
+// groups wv*NPT .. wv*NPT + NPT-1 (NPT = NFRAG / NT), which are 1 KB apart, so that one
+// global address and one LDS base per four groups do: the instruction's immediate offset (added to both
+// sides, at most 4095) covers the rest.
+template <int NT, int NFRAG, typename Frag>
+__device__ __forceinline__ void async_copy_tile(const Frag* g, Frag* s, int tid, int wv) {
+    static_assert(sizeof(Frag) == 16 && NFRAG % NT == 0, "whole groups of fragments");
+    constexpr int NPT = NFRAG / NT;
+    const int lane = tid & 63;
+#pragma unroll
+    for (int i0 = 0; i0 < NPT; i0 += 4) {
+        const char* ga = reinterpret_cast<const char*>(g) + (unsigned)(((wv * NPT + i0) * 64 + lane) * 16);
+        Frag* sa = s + (wv * NPT + i0) * 64;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ga, (__attribute__((address_space(3))) void*)sa, 16, 0, 0);
+        if (i0 + 1 < NPT) __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ga, (__attribute__((address_space(3))) void*)sa, 16, 1024, 0);
+        if (i0 + 2 < NPT) __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ga, (__attribute__((address_space(3))) void*)sa, 16, 2048, 0);
+        if (i0 + 3 < NPT) __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)ga, (__attribute__((address_space(3))) void*)sa, 16, 3072, 0);
+    }
 }
 __device__ __forceinline__ void wait_async_and_sync() {
     __builtin_amdgcn_s_waitcnt(0x0000);   // vmcnt(0) expcnt(0) lgkmcnt(0): this wave's copies have landed

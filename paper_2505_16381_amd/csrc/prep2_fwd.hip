@@ -56,8 +56,8 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
     auto issue = [&](int c) {
         const size_t bhc = (size_t)bh * NC + c;
         Frag* buf = stage + (size_t)(c & (NBUF - 1)) * (KVF + DPF);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * (size_t)CHUNK * D), buf, KVF, tid, wv);
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dp) + bhc * (size_t)D * D), buf + KVF, DPF, tid, wv);
+        async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.kt) + bhc * (size_t)CHUNK * D), buf, tid, wv);
+        async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.dp) + bhc * (size_t)D * D), buf + KVF, tid, wv);
     };
     if (NBUF == 2) issue(clast);
     for (int c = clast; c >= c0; --c) {

@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void bwd_states_kernel(FwdParams p) {
             if (J == 0) return;
             src = dp2g + (size_t)J * D * D;
         }
-        async_copy_tile<256>(reinterpret_cast<const Frag*>(src), sP + (size_t)(k & 1) * DPF, DPF, tid, wv);
+        async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(src), sP + (size_t)(k & 1) * DPF, tid, wv);
     };
 
     if (nsteps > 0) issue(0);

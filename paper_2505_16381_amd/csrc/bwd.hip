@@ -59,7 +59,7 @@ __global__ __launch_bounds__(256) void bwd_dotile_kernel(BwdParams p) {
     using FragV = typename Tr<TIO>::Frag;
     constexpr int KW = Tr<TIO>::KW, SPB = 32 / KW, DB = D / 32, QS = CHUNK / KW;
     const int i = blockIdx.x, bh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int L = p.L, NC = p.NC;
     const TIO* dO = reinterpret_cast<const TIO*>(p.dO) + ((size_t)bh * L + (size_t)i * CHUNK) * D;
     const int nvalid = (L - i * CHUNK < CHUNK) ? L - i * CHUNK : CHUNK;
@@ -758,7 +758,7 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     Frag* sbase = reinterpret_cast<Frag*>(smem);
     const int j = blockIdx.x, bh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int NC = p.NC;
     const size_t nslots = num_block_slots(NC);
     const int cj = FAR ? j * SBC : j;                             // a key chunk of the block
@@ -901,7 +901,7 @@ __global__ __launch_bounds__(256) void batched_gemm_kernel(GemmArgs a) {
     T* Bs = As + a.M * ld;
     const int chunk = blockIdx.x * a.cmul + a.cadd, bh = blockIdx.y;
     if (chunk >= a.NC) return;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     stage_mat<TIO>(a.A, As, ld, a.M, a.K, bh, chunk, a.L, tid);
     stage_mat<TIO>(a.B, Bs, ld, a.N, a.K, bh, chunk, a.L, tid);
     __syncthreads();
@@ -960,7 +960,7 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
     T* B3 = B2 + D * LD;                     // U rows [t][k]; later dKb2^T [a][s] (pitch LDC)
 
     const int J = blockIdx.x, bh = blockIdx.y, NC = a.NC, L = a.L;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int c0 = J * SBC;
     const int clast = (c0 + SBC - 1 < NC) ? c0 + SBC - 1 : NC - 1;
     const size_t Lp = (size_t)NC * CHUNK;
@@ -1171,7 +1171,7 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
     constexpr int FE = Tr<T>::FE, KW = Tr<T>::KW;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int chunk = blockIdx.x, bh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     f32x16 acc[2];
     for (int i = 0; i < pr.n; ++i) {
         const ChunkOp& op = pr.ops[i];

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
     Frag* Es = reinterpret_cast<Frag*>(smem);      // tile (rows a, contraction b) of E
 
     const int sb = blockIdx.x, bh = blockIdx.y;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int NC = p.NC;
     const int c0 = sb * SBC;
     const int clast = (c0 + SBC - 1 < NC) ? c0 + SBC - 1 : NC - 1;

@@ -33,7 +33,7 @@ __global__ __launch_bounds__(256) void bwd_states_kernel(FwdParams p) {
     const int ntiles = (NC + 1) / 2;
     const int tile = ntiles - 1 - (int)(blockIdx.x / BH);      // heaviest (right-most) tiles first
     const int bh = blockIdx.x % BH;
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
     const bool active = cq < NC;
     const int ctop = (tile * 2 + 1 < NC) ? tile * 2 + 1 : NC - 1;     // right-most chunk of the tile

@@ -18,8 +18,9 @@
  *    never allocates, frees or synchronises; all kernels are enqueued on
  *    `stream` (a hipStream_t passed as void*, NULL = the null stream).
  *  - Layout: q, k, v, w, o, d_o, dq, dk, dv, dw are contiguous [B, H, L, d];
- *    beta, dbeta, lse are contiguous [B, H, L].  w and beta are per token and
- *    per head.  No grouped-query sharing.
+ *    beta, dbeta, lse are contiguous [B, H, L] (the *_layout and *_varlen entry
+ *    points also take [B, L, H, d] and packed sequences).  w and beta are per
+ *    token and per head.  No grouped-query sharing.
  *  - dtype `dt` is the storage type of q,k,v,w,beta,o and of all gradients
  *    (PATH_F32: float, PATH_BF16: bfloat16).  lse is always float.
  *    PATH_BF16 contracts on bf16 MFMA with fp32 accumulation; PATH_F32
@@ -49,6 +50,12 @@ extern "C" {
 #endif
 
 typedef enum { PATH_F32 = 0, PATH_BF16 = 1 } path_dtype_t;
+
+/* Layout of the caller's tensors, for the entry points that take one (the others use PATH_LAYOUT_BHLD):
+ *   PATH_LAYOUT_BHLD: q, k, v, w, o and gradients [B,H,L,d]; beta, lse, log_f and gradients [B,H,L]
+ *   PATH_LAYOUT_BLHD: ...                          [B,L,H,d]; ...                             [B,L,H]
+ * (both contiguous, d innermost). */
+typedef enum { PATH_LAYOUT_BHLD = 0, PATH_LAYOUT_BLHD = 1 } path_layout_t;
 
 typedef enum {
     PATH_OK = 0,
@@ -179,6 +186,44 @@ path_status_t path_attn_train_bwd(const void* q, const void* k, const void* v, c
                                   const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
                                   void* dlog_f, int B, int H, int L, int d, int causal, float scale,
                                   path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * The forward and backward on either layout.  log_f == NULL: plain PaTH (as path_attn_fwd / path_attn_bwd);
+ * log_f given: PaTH-FoX (as path_attn_fox_fwd / path_attn_fox_bwd; dlog_f is required iff log_f is).
+ * Same workspace sizes, argument rules and error codes; an unknown layout returns PATH_ERR_UNSUPPORTED.
+ * The kernels read and write the caller's tensors in place through their strides: nothing is transposed
+ * or copied.
+ */
+path_status_t path_attn_fwd_layout(const void* q, const void* k, const void* v, const void* w,
+                                   const void* beta, const void* log_f, void* o, float* lse,
+                                   int B, int H, int L, int d, path_layout_t layout, int causal, float scale,
+                                   path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+path_status_t path_attn_bwd_layout(const void* q, const void* k, const void* v, const void* w,
+                                   const void* beta, const void* log_f, const void* o, const float* lse,
+                                   const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                   void* dlog_f, int B, int H, int L, int d, path_layout_t layout, int causal,
+                                   float scale, path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Variable-length batches: nseq sequences packed along the token axis, q, k, v, w, o and gradients
+ * [T,H,d], beta, lse, log_f and gradients [T,H] (T = cu_seqlens[nseq]); sequence s owns the tokens
+ * cu_seqlens[s] .. cu_seqlens[s+1]-1 and attends only to itself.  cu_seqlens is a HOST array of nseq+1
+ * ints (cu_seqlens[0] = 0, strictly increasing; else PATH_ERR_SHAPE); it is read before the call returns.
+ * Each sequence is one problem of its own length in the [1,L_s,H,d] layout; the sequences are enqueued one
+ * after the other on `stream` and share the workspace, which must hold
+ * path_attn_varlen_workspace_bytes(...) bytes (that of the longest sequence).  log_f / dlog_f as above.
+ */
+size_t path_attn_varlen_workspace_bytes(const int* cu_seqlens, int nseq, int H, int d, path_dtype_t dt,
+                                        int for_backward);
+path_status_t path_attn_varlen_fwd(const void* q, const void* k, const void* v, const void* w,
+                                   const void* beta, const void* log_f, void* o, float* lse,
+                                   const int* cu_seqlens, int nseq, int H, int d, int causal, float scale,
+                                   path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+path_status_t path_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* w,
+                                   const void* beta, const void* log_f, const void* o, const float* lse,
+                                   const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                   void* dlog_f, const int* cu_seqlens, int nseq, int H, int d, int causal,
+                                   float scale, path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Decode path (paper Sec. 3.4 "Efficient Inference").  Caches are caller-owned device memory,

@@ -12,6 +12,8 @@ import os
 
 PATH_F32 = 0
 PATH_BF16 = 1
+PATH_LAYOUT_BHLD = 0      # q, k, v, w, o [B,H,L,d]; beta, lse [B,H,L]
+PATH_LAYOUT_BLHD = 1      # ...           [B,L,H,d]; ...       [B,L,H]
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_HERE, "libpath_attn.so")
@@ -71,6 +73,16 @@ def load_library():
     lib.path_attn_train_fwd_sweep.argtypes = [vp, vp, ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_attn_train_bwd.restype = ci
     lib.path_attn_train_bwd.argtypes = [vp] * 15 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_fwd_layout.restype = ci
+    lib.path_attn_fwd_layout.argtypes = [vp] * 8 + [ci, ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_bwd_layout.restype = ci
+    lib.path_attn_bwd_layout.argtypes = [vp] * 15 + [ci, ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_varlen_workspace_bytes.restype = sz
+    lib.path_attn_varlen_workspace_bytes.argtypes = [ctypes.POINTER(ci), ci, ci, ci, ci, ci]
+    lib.path_attn_varlen_fwd.restype = ci
+    lib.path_attn_varlen_fwd.argtypes = [vp] * 8 + [ctypes.POINTER(ci), ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_varlen_bwd.restype = ci
+    lib.path_attn_varlen_bwd.argtypes = [vp] * 15 + [ctypes.POINTER(ci), ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_decode_workspace_bytes.restype = sz
     lib.path_decode_workspace_bytes.argtypes = [ci, ci, ci]
     lib.path_key_prefill.restype = ci
@@ -298,3 +310,87 @@ def path_attn_train_fwd_sweep(o, lse, scale, workspace, with_gates=False, stream
     B, H, L, d = o.shape
     _check(load_library().path_attn_train_fwd_sweep(_ptr(o), _ptr(lse), int(bool(with_gates)), B, H, L, d, float(scale), _dt_of(o),
                                                     _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+
+
+def _opt(x):
+    return _ptr(x) if x is not None else None
+
+
+def _dims(q, layout):
+    if layout == PATH_LAYOUT_BLHD:
+        B, L, H, d = q.shape
+    else:
+        B, H, L, d = q.shape
+    return B, H, L, d
+
+
+def path_attn_fwd_layout(q, k, v, w, beta, layout, log_f=None, scale=None, workspace=None, stream=None):
+    """Forward on [B,H,L,d] (PATH_LAYOUT_BHLD) or [B,L,H,d] (PATH_LAYOUT_BLHD) tensors; with log_f: PaTH-FoX.
+    Returns (o, lse) in the same layout."""
+    import torch
+    B, H, L, d = _dims(q, layout)
+    scale = float(d ** -0.5 if scale is None else scale)
+    dt = _dt_of(q)
+    o = torch.empty_like(q)
+    lse = torch.empty(beta.shape, dtype=torch.float32, device=q.device)
+    workspace = _workspace(path_attn_workspace_bytes(B, H, L, d, dt, False), q, workspace)
+    _check(load_library().path_attn_fwd_layout(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _opt(log_f), _ptr(o), _ptr(lse),
+                                               B, H, L, d, int(layout), 1, scale, dt, _ptr(workspace), workspace.numel(),
+                                               _stream_handle(stream)))
+    return o, lse
+
+
+def path_attn_bwd_layout(q, k, v, w, beta, o, lse, d_o, layout, log_f=None, scale=None, workspace=None, stream=None):
+    """Backward on either layout: (dq, dk, dv, dw, dbeta[, dlog_f]) in the layout of the inputs."""
+    import torch
+    B, H, L, d = _dims(q, layout)
+    scale = float(d ** -0.5 if scale is None else scale)
+    dt = _dt_of(q)
+    outs = [torch.empty_like(q) for _ in range(4)] + [torch.empty_like(beta)]
+    dlog_f = torch.empty_like(log_f) if log_f is not None else None
+    workspace = _workspace(path_attn_workspace_bytes(B, H, L, d, dt, True), q, workspace)
+    _check(load_library().path_attn_bwd_layout(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _opt(log_f), _ptr(o), _ptr(lse), _ptr(d_o),
+                                               *[_ptr(x) for x in outs], _opt(dlog_f), B, H, L, d, int(layout), 1, scale, dt,
+                                               _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return tuple(outs) + ((dlog_f,) if dlog_f is not None else ())
+
+
+def _cu(cu_seqlens):
+    cu = [int(x) for x in cu_seqlens]
+    return (ctypes.c_int * len(cu))(*cu), len(cu) - 1
+
+
+def path_attn_varlen_workspace_bytes(cu_seqlens, H, d, dt, for_backward=False) -> int:
+    arr, n = _cu(cu_seqlens)
+    return int(load_library().path_attn_varlen_workspace_bytes(arr, n, H, d, dt, int(bool(for_backward))))
+
+
+def path_attn_varlen_fwd(q, k, v, w, beta, cu_seqlens, log_f=None, scale=None, workspace=None, stream=None):
+    """Forward on packed sequences: q, k, v, w [T,H,d], beta [T,H]; cu_seqlens = host list of nseq+1 offsets."""
+    import torch
+    T, H, d = q.shape
+    scale = float(d ** -0.5 if scale is None else scale)
+    dt = _dt_of(q)
+    arr, n = _cu(cu_seqlens)
+    o = torch.empty_like(q)
+    lse = torch.empty((T, H), dtype=torch.float32, device=q.device)
+    workspace = _workspace(path_attn_varlen_workspace_bytes(cu_seqlens, H, d, dt, False), q, workspace)
+    _check(load_library().path_attn_varlen_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _opt(log_f), _ptr(o), _ptr(lse),
+                                               arr, n, H, d, 1, scale, dt, _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return o, lse
+
+
+def path_attn_varlen_bwd(q, k, v, w, beta, o, lse, d_o, cu_seqlens, log_f=None, scale=None, workspace=None, stream=None):
+    """Backward on packed sequences: (dq, dk, dv, dw, dbeta[, dlog_f])."""
+    import torch
+    T, H, d = q.shape
+    scale = float(d ** -0.5 if scale is None else scale)
+    dt = _dt_of(q)
+    arr, n = _cu(cu_seqlens)
+    outs = [torch.empty_like(q) for _ in range(4)] + [torch.empty_like(beta)]
+    dlog_f = torch.empty_like(log_f) if log_f is not None else None
+    workspace = _workspace(path_attn_varlen_workspace_bytes(cu_seqlens, H, d, dt, True), q, workspace)
+    _check(load_library().path_attn_varlen_bwd(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _opt(log_f), _ptr(o), _ptr(lse), _ptr(d_o),
+                                               *[_ptr(x) for x in outs], _opt(dlog_f), arr, n, H, d, 1, scale, dt,
+                                               _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return tuple(outs) + ((dlog_f,) if dlog_f is not None else ())

@@ -2,6 +2,8 @@
 // kernel launches on the caller's stream.  No allocation, no synchronisation.
 #include <cstdio>
 #include "../../include/path_attn.h"
+#include <type_traits>
+
 #include "path_common.h"
 
 namespace path {
@@ -147,7 +149,22 @@ extern "C" path_status_t path_attn_fwd_workspace_layout(int B, int H, int L, int
 
 static bool misaligned(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15) != 0; }
 
-static path_status_t fwd_setup(FwdParams& p, int B, int H, int L, int d, path_dtype_t dt, void* workspace,
+// Strides of the caller's tensors for one of the two layouts of the ABI.
+static bool layout_ok(int layout) { return layout == PATH_LAYOUT_BHLD || layout == PATH_LAYOUT_BLHD; }
+static UserLayout layout_of(int layout, int H, int L, int d) {
+    UserLayout u;
+    u.H = H;
+    if (layout == PATH_LAYOUT_BLHD) {
+        u.vb = (long long)L * H * d; u.vh = d; u.vt = (long long)H * d;
+        u.sb = (long long)L * H; u.sh = 1; u.st = H;
+    } else {
+        u.vb = (long long)H * L * d; u.vh = (long long)L * d; u.vt = d;
+        u.sb = (long long)H * L; u.sh = L; u.st = 1;
+    }
+    return u;
+}
+
+static path_status_t fwd_setup(FwdParams& p, const UserLayout& ul, int B, int H, int L, int d, path_dtype_t dt, void* workspace,
                                size_t workspace_bytes) {
     if (!workspace) return PATH_ERR_NULL;
     if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
@@ -162,86 +179,81 @@ static path_status_t fwd_setup(FwdParams& p, int B, int H, int L, int d, path_dt
     p.dpt = nullptr;                                         // transposed -dP tile: backward only
     p.cum = nullptr;                                         // set by the PaTH-FoX entry points
     p.B = B; p.H = H; p.L = L; p.NC = (L + CHUNK - 1) / CHUNK;
+    p.ul = ul;
     return PATH_OK;
 }
 
 // PaTH-FoX: cum[t] = log2(e) * sum_{s<=t} log f_s per head, fp32, padded to whole chunks.
-static hipError_t launch_gate_sums(const void* log_f, float* cum, int B, int H, int L, path_dtype_t dt, hipStream_t st) {
+static hipError_t launch_gate_sums(const void* log_f, const UserLayout& ul, float* cum, int B, int H, int L, path_dtype_t dt, hipStream_t st) {
     const int Lp = ((L + CHUNK - 1) / CHUNK) * CHUNK;
-    ScanArgs a{log_f, nullptr, cum, L, Lp, L, Lp, 1, 1.44269504088896340736f};
+    ScanArgs a{log_f, nullptr, cum, L, Lp, L, Lp, 1, 1.44269504088896340736f, 1, 0, ul};
     return launch_fox_scan(a, B * H, dt == PATH_BF16 ? 1 : 0, 0, st);
+}
+
+// Forward of plain PaTH (log_f == NULL) and of PaTH-FoX: stage 0 = everything, 1 = the two transforms
+// (and the gate sums), 2 = the sweep (with_gates tells whether gate sums are in the workspace).
+static path_status_t fwd_impl(int stage, const UserLayout& ul, const void* q, const void* k, const void* v, const void* w,
+                              const void* beta, const void* log_f, int with_gates, void* o, float* lse, int B, int H, int L,
+                              int d, int causal, float scale, path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                              void* stream) {
+    if (stage != 2 && (!q || !k || !v || !w || !beta)) return PATH_ERR_NULL;
+    if (stage != 1 && (!o || !lse)) return PATH_ERR_NULL;
+    if (!workspace) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
+    if (!causal || (stage != 1 && !(scale > 0.f))) return PATH_ERR_UNSUPPORTED;     // the online softmax tracks max(s) * scale
+    FwdParams p = {};
+    const path_status_t st = fwd_setup(p, ul, B, H, L, d, dt, workspace, workspace_bytes);
+    if (st != PATH_OK) return st;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(w) || misaligned(o)) return PATH_ERR_ALIGN;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const FwdWorkspace ws = fwd_workspace(B, H, L, d, dt == PATH_BF16 ? 2 : 4);
+    float* cum = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.cum);
+    clear_inherited_error();
+    if (stage != 2) {
+        p.q = q; p.k = k; p.v = v; p.w = w; p.beta = beta;
+        if (!hip_ok(launch_prep_fwd(p, d, dt == PATH_BF16, hs), "chunk transform")) return PATH_ERR_HIP;
+        // (the sweep reads the second level only when there is a super-block to the left; the key
+        // prefill of the decode path reads it always)
+        if (!hip_ok(launch_prep2_fwd(p, d, dt == PATH_BF16, hs), "second-level transform")) return PATH_ERR_HIP;
+        if (log_f && !hip_ok(launch_gate_sums(log_f, ul, cum, B, H, L, dt, hs), "gate sums")) return PATH_ERR_HIP;
+    }
+    if (stage != 1) {
+        p.o = o; p.lse = lse; p.scale = scale; p.cum = (log_f || with_gates) ? cum : nullptr;
+        if (!hip_ok(launch_attn_fwd2(p, d, dt == PATH_BF16, hs), "forward sweep")) return PATH_ERR_HIP;
+    }
+    return PATH_OK;
 }
 
 extern "C" path_status_t path_attn_fwd_prep(const void* q, const void* k, const void* v, const void* w,
                                             const void* beta, int B, int H, int L, int d, path_dtype_t dt,
                                             void* workspace, size_t workspace_bytes, void* stream) {
-    if (!q || !k || !v || !w || !beta) return PATH_ERR_NULL;
-    FwdParams p = {};
-    const path_status_t st = fwd_setup(p, B, H, L, d, dt, workspace, workspace_bytes);
-    if (st != PATH_OK) return st;
-    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(w)) return PATH_ERR_ALIGN;
-    p.q = q; p.k = k; p.v = v; p.w = w; p.beta = beta;
-    clear_inherited_error();
-    if (!hip_ok(launch_prep_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "chunk transform"))
-        return PATH_ERR_HIP;
-    // (the sweep reads the second level only when there is a super-block to the left; the key
-    // prefill of the decode path reads it always)
-    if (!hip_ok(launch_prep2_fwd(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "second-level transform"))
-        return PATH_ERR_HIP;
-    return PATH_OK;
+    return fwd_impl(1, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, nullptr, 0, nullptr, nullptr, B, H, L, d, 1, 1.f, dt,
+                    workspace, workspace_bytes, stream);
 }
 
 extern "C" path_status_t path_attn_fwd_sweep(void* o, float* lse, int B, int H, int L, int d, float scale,
                                              path_dtype_t dt, void* workspace, size_t workspace_bytes,
                                              void* stream) {
-    if (!o || !lse) return PATH_ERR_NULL;
-    if (!(scale > 0.f)) return PATH_ERR_UNSUPPORTED;     // the online softmax tracks max(s) * scale
-    FwdParams p = {};
-    const path_status_t st = fwd_setup(p, B, H, L, d, dt, workspace, workspace_bytes);
-    if (st != PATH_OK) return st;
-    if (misaligned(o)) return PATH_ERR_ALIGN;
-    p.o = o; p.lse = lse; p.scale = scale;
-    clear_inherited_error();
-    if (!hip_ok(launch_attn_fwd2(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "forward sweep"))
-        return PATH_ERR_HIP;
-    return PATH_OK;
+    return fwd_impl(2, layout_of(PATH_LAYOUT_BHLD, H, L, d), nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, 0, o, lse, B, H, L, d, 1,
+                    scale, dt, workspace, workspace_bytes, stream);
 }
 
 extern "C" path_status_t path_attn_fwd(const void* q, const void* k, const void* v, const void* w,
                                        const void* beta, void* o, float* lse, int B, int H, int L, int d,
                                        int causal, float scale, path_dtype_t dt, void* workspace,
                                        size_t workspace_bytes, void* stream) {
-    if (!q || !k || !v || !w || !beta || !o || !lse || !workspace) return PATH_ERR_NULL;
-    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
-    if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
-    if (!causal || !(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
-    if (misaligned(o)) return PATH_ERR_ALIGN;
-    path_status_t st = path_attn_fwd_prep(q, k, v, w, beta, B, H, L, d, dt, workspace, workspace_bytes, stream);
-    if (st != PATH_OK) return st;
-    return path_attn_fwd_sweep(o, lse, B, H, L, d, scale, dt, workspace, workspace_bytes, stream);
+    return fwd_impl(0, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, nullptr, 0, o, lse, B, H, L, d, causal, scale, dt,
+                    workspace, workspace_bytes, stream);
 }
 
 extern "C" path_status_t path_attn_fox_fwd(const void* q, const void* k, const void* v, const void* w,
                                            const void* beta, const void* log_f, void* o, float* lse, int B, int H,
                                            int L, int d, int causal, float scale, path_dtype_t dt, void* workspace,
                                            size_t workspace_bytes, void* stream) {
-    if (!q || !k || !v || !w || !beta || !log_f || !o || !lse || !workspace) return PATH_ERR_NULL;
-    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
-    if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
-    if (!causal || !(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
-    if (misaligned(o)) return PATH_ERR_ALIGN;
-    path_status_t st = path_attn_fwd_prep(q, k, v, w, beta, B, H, L, d, dt, workspace, workspace_bytes, stream);
-    if (st != PATH_OK) return st;
-    FwdParams p = {};
-    st = fwd_setup(p, B, H, L, d, dt, workspace, workspace_bytes);
-    if (st != PATH_OK) return st;
-    const FwdWorkspace ws = fwd_workspace(B, H, L, d, dt == PATH_BF16 ? 2 : 4);
-    float* cum = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + ws.cum);
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    if (!hip_ok(launch_gate_sums(log_f, cum, B, H, L, dt, hs), "gate sums")) return PATH_ERR_HIP;
-    p.o = o; p.lse = lse; p.scale = scale; p.cum = cum;
-    if (!hip_ok(launch_attn_fwd2(p, d, dt == PATH_BF16, hs), "forward sweep (PaTH-FoX)")) return PATH_ERR_HIP;
-    return PATH_OK;
+    if (!log_f) return PATH_ERR_NULL;
+    return fwd_impl(0, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, 1, o, lse, B, H, L, d, causal, scale, dt,
+                    workspace, workspace_bytes, stream);
 }
 
 // Backward of plain PaTH (log_f == NULL) and of PaTH-FoX (log_f, dlog_f given), and the forward of the
@@ -252,7 +264,7 @@ enum BwdMode { BWD_FULL = 0,        // transforms + backward (path_attn_bwd)
                BWD_RESUME = 2,      // backward without the transforms (the workspace is as BWD_FWD_ONLY left it)
                BWD_FWD_PREP = 3,    // the two halves of BWD_FWD_ONLY as separate calls: transforms ...
                BWD_FWD_SWEEP = 4 }; // ... and the forward sweep
-static path_status_t bwd_impl(BwdMode mode, const void* q, const void* k, const void* v, const void* w,
+static path_status_t bwd_impl(BwdMode mode, const UserLayout& ul, const void* q, const void* k, const void* v, const void* w,
                               const void* beta, const void* log_f, const void* o, const float* lse, const void* d_o,
                               void* dq, void* dk, void* dv, void* dw, void* dbeta, void* dlog_f, int B, int H,
                               int L, int d, int causal, float scale, path_dtype_t dt,
@@ -287,14 +299,14 @@ static path_status_t bwd_impl(BwdMode mode, const void* q, const void* k, const 
     fp.xinit = F(ws.f.xinit); fp.sd = F(ws.f.sd);
     fp.kt2 = base + ws.f.kt2; fp.dp2 = base + ws.f.dp2;
     fp.kt2T = base + ws.kt2T; fp.dpt2 = base + ws.dpt2; fp.kbm = base + ws.kbm; fp.rm = base + ws.rm;
-    fp.B = B; fp.H = H; fp.L = L; fp.NC = NC; fp.scale = scale;
+    fp.B = B; fp.H = H; fp.L = L; fp.NC = NC; fp.scale = scale; fp.ul = ul;
     fp.ktT = base + ws.ktT; fp.vk = base + ws.vk; fp.dpt = base + ws.dpt; fp.xs = base + ws.xs; fp.xsT = base + ws.xsT;
     fp.fm = base + ws.fm; fp.gktm = base + ws.gktm; fp.nm = base + ws.nm; fp.aim = base + ws.aim;
     fp.ytm = base + ws.ytm; fp.utm = base + ws.utm; fp.gm = F(ws.gm); fp.sdm = F(ws.sdm);
     clear_inherited_error();
     float* cum = log_f ? F(ws.f.cum) : nullptr;
     if (mode != BWD_RESUME && mode != BWD_FWD_SWEEP) {
-        if (log_f && !hip_ok(launch_gate_sums(log_f, cum, B, H, L, dt, st), "gate sums (backward)")) return PATH_ERR_HIP;
+        if (log_f && !hip_ok(launch_gate_sums(log_f, ul, cum, B, H, L, dt, st), "gate sums (backward)")) return PATH_ERR_HIP;
         if (!hip_ok(launch_prep_fwd(fp, d, bf, st), "chunk transform (backward)")) return PATH_ERR_HIP;
         if (!hip_ok(launch_prep2_fwd(fp, d, bf, st), "second-level transform (backward)")) return PATH_ERR_HIP;
     }
@@ -313,20 +325,20 @@ static path_status_t bwd_impl(BwdMode mode, const void* q, const void* k, const 
     bp.kt2 = fp.kt2; bp.kt2T = fp.kt2T; bp.dpt2 = fp.dpt2; bp.dk2 = F(ws.dk2); bp.dchain = F(ws.dchain);
     bp.doq = base + ws.doq; bp.doT = base + ws.doT; bp.gs = base + ws.gs;
     bp.delta = F(ws.delta); bp.lse2p = F(ws.lse2p); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
-    bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale;
+    bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale; bp.ul = ul;
     bp.cum = cum; bp.dcol = cum ? F(ws.dcol) : nullptr; bp.drow = cum ? F(ws.drow) : nullptr;
     if (!hip_ok(launch_bwd_scan(bp, d, bf, st), "backward pair kernels")) return PATH_ERR_HIP;
 
     // 5. adjoint of the chunk transform
     const long long c_bh = (long long)NC * 4096, c_ch = 4096;          // 64x64 per chunk
     const long long t_bh = Lp * d, t_ch = (long long)CHUNK * d;        // padded token-major [Lp][d]
-    const long long u_bh = (long long)L * d;                           // user token-major [L][d]
     auto chunk_n = [&](const void* p, int type) { return MatRef{p, c_bh, c_ch, 64, 1, type, TOK_NONE}; };   // [r][k]
     auto chunk_t = [&](const void* p, int type) { return MatRef{p, c_bh, c_ch, 1, 64, type, TOK_NONE}; };   // [k][r]
     auto tokws_n = [&](const void* p) { return MatRef{p, t_bh, t_ch, d, 1, EL_F32, TOK_NONE}; };            // rows = tokens
     auto tokws_t = [&](const void* p) { return MatRef{p, t_bh, t_ch, 1, d, EL_F32, TOK_NONE}; };            // k = tokens
-    auto user_n = [&](const void* p) { return MatRef{p, u_bh, t_ch, d, 1, EL_IO, TOK_ROW}; };
-    auto user_t = [&](const void* p) { return MatRef{p, u_bh, t_ch, 1, d, EL_IO, TOK_K}; };
+    const int uts = (int)ul.vt;                                         // token stride of the caller's tensors
+    auto user_n = [&](const void* p) { return MatRef{p, 0, 0, uts, 1, EL_IO, TOK_ROW, 1}; };
+    auto user_t = [&](const void* p) { return MatRef{p, 0, 0, 1, uts, EL_IO, TOK_K, 1}; };
     const MatRef U_rows{base + ws.utm, (long long)NC * d * CHUNK, (long long)d * CHUNK, 1, 64, EL_OP, TOK_NONE};  // U[t'][c]
     const MatRef ddp_kfirst{F(ws.ddp), (long long)NC * d * d, (long long)d * d, 1, d, EL_F32, TOK_NONE};   // (n=c, k=a): ddP[a][c]
     const MatRef ddp_nfirst{F(ws.ddp), (long long)NC * d * d, (long long)d * d, d, 1, EL_F32, TOK_NONE};   // (n=c, k=b): ddP[c][b]
@@ -346,7 +358,7 @@ static path_status_t bwd_impl(BwdMode mode, const void* q, const void* k, const 
             default:       a.c_bh = c_bh; a.c_ch = c_ch; a.crs = 64; break;                                   // 64 x 64 per chunk
         }
         a.M = M; a.N = N; a.K = K; a.alpha = alpha; a.mask = mask; a.NC = NC; a.L = L;
-        a.cmul = cmul; a.cadd = cadd; a.gridx = cmul == 1 ? NC : (NC + cmul - 1) / cmul;
+        a.cmul = cmul; a.cadd = cadd; a.gridx = cmul == 1 ? NC : (NC + cmul - 1) / cmul; a.ul = ul;
         ok = hip_ok(launch_batched_gemm(a, BH, bf, st), "chunk-transform adjoint product");
     };
     float *dpd = F(ws.dpd), *pd = F(ws.pd), *dsd = F(ws.dsd), *df = F(ws.df), *dy = F(ws.dy), *dn = F(ws.dn);
@@ -362,7 +374,7 @@ static path_status_t bwd_impl(BwdMode mode, const void* q, const void* k, const 
     //     D_c     = D_{c-1} (I - dP_c)^T + dKb2_c^T Kb_c          dP_c = W_c^T U_c
     //     dKb_c  += dKb2_c R_c
     if (NC > SBC && bf) {         // fused kernel (2-byte operand types)
-        SbChainArgs sa{base + ws.rm, base + ws.kbm, base + ws.utm, w, F(ws.dk2), F(ws.dchain), F(ws.ddp), dkb, L, NC};
+        SbChainArgs sa{base + ws.rm, base + ws.kbm, base + ws.utm, w, F(ws.dk2), F(ws.dchain), F(ws.ddp), dkb, L, NC, ul};
         ok = hip_ok(launch_bwd_sb_chain(sa, BH, d, st), "second-level adjoint");
     } else if (NC > SBC) {        // the same chain as a sequence of batched products (fp32 operands)
         const long long dd = (long long)d * d, dd_bh = (long long)NC * dd, ch_bh = (long long)(NC + 1) * dd;
@@ -395,18 +407,18 @@ static path_status_t bwd_impl(BwdMode mode, const void* q, const void* k, const 
     // Chains of products that add into the same result are consecutive.
     if (!ok) return PATH_ERR_HIP;
     if (bf) {      // 2-byte operand types: the hand-fused kernel
-        ChunkFusedArgs ca{q, k, v, w, beta, d_o, lse, bp.delta, fp.sdm, fp.gm, fp.fm, fp.gktm, fp.nm, fp.aim, fp.ytm,
+        ChunkFusedArgs ca{ul, q, k, v, w, beta, d_o, lse, bp.delta, fp.sdm, fp.gm, fp.fm, fp.gktm, fp.nm, fp.aim, fp.ytm,
                           base + ws.utm, bp.dqb, bp.dkb, bp.dvp, F(ws.ddp), dq, dk, dv, dw, dbeta, bp.cum, bp.dcol, bp.drow,
                           L, NC, scale};
         ok = hip_ok(launch_chunk_fused(ca, BH, d, st), "chunk-transform adjoint");
         if (ok && log_f) {
-            ScanArgs sa{bp.dcol, bp.drow, dlog_f, (int)Lp, L, L, L, 0, 1.f};
+            ScanArgs sa{bp.dcol, bp.drow, dlog_f, (int)Lp, L, L, L, 0, 1.f, 0, 1, ul};
             ok = hip_ok(launch_fox_scan(sa, BH, 0, 1, st), "gate gradient");
         }
         return ok ? PATH_OK : PATH_ERR_HIP;
     }
     ChunkProgram pr = {};
-    pr.L = L; pr.NC = NC;
+    pr.L = L; pr.NC = NC; pr.ul = ul;
     bool chain_open = false;
     // one product: C (+)= alpha A B^T; `first` opens a chain (from Cin or zero), `last` masks and writes C
     // results that are only read as matrix operands (marked OP) are stored in the operand type: half the bytes
@@ -461,7 +473,7 @@ static path_status_t bwd_impl(BwdMode mode, const void* q, const void* k, const 
         // dlog f_s = sum over the pairs j < s <= i of the logit gradient = (column sums left of s) - (row sums
         // above s).  The row sums vanish in exact arithmetic; subtracting them as computed removes the error that
         // delta = dO . o (o rounded to the I/O type) puts into every row, which the prefix sum would pile up.
-        ScanArgs sa{bp.dcol, bp.drow, dlog_f, (int)Lp, L, L, L, 0, 1.f};
+        ScanArgs sa{bp.dcol, bp.drow, dlog_f, (int)Lp, L, L, L, 0, 1.f, 0, 1, ul};
         ok = hip_ok(launch_fox_scan(sa, BH, 0, bf ? 1 : 0, st), "gate gradient");
     }
     return ok ? PATH_OK : PATH_ERR_HIP;
@@ -519,7 +531,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
                                        void* dq, void* dk, void* dv, void* dw, void* dbeta, int B, int H,
                                        int L, int d, int causal, float scale, path_dtype_t dt,
                                        void* workspace, size_t workspace_bytes, void* stream) {
-    return bwd_impl(BWD_FULL, q, k, v, w, beta, nullptr, o, lse, d_o, dq, dk, dv, dw, dbeta, nullptr, B, H, L, d, causal, scale, dt,
+    return bwd_impl(BWD_FULL, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, nullptr, o, lse, d_o, dq, dk, dv, dw, dbeta, nullptr, B, H, L, d, causal, scale, dt,
                     workspace, workspace_bytes, stream);
 }
 
@@ -529,7 +541,7 @@ extern "C" path_status_t path_attn_fox_bwd(const void* q, const void* k, const v
                                            void* dlog_f, int B, int H, int L, int d, int causal, float scale,
                                            path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
     if (!log_f || !dlog_f) return PATH_ERR_NULL;
-    return bwd_impl(BWD_FULL, q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
+    return bwd_impl(BWD_FULL, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
                     workspace, workspace_bytes, stream);
 }
 
@@ -537,21 +549,21 @@ extern "C" path_status_t path_attn_train_fwd(const void* q, const void* k, const
                                              const void* beta, const void* log_f, void* o, float* lse,
                                              int B, int H, int L, int d, int causal, float scale,
                                              path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
-    return bwd_impl(BWD_FWD_ONLY, q, k, v, w, beta, log_f, o, lse, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+    return bwd_impl(BWD_FWD_ONLY, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                     B, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
 }
 
 extern "C" path_status_t path_attn_train_fwd_prep(const void* q, const void* k, const void* v, const void* w,
                                                   const void* beta, const void* log_f, int B, int H, int L, int d,
                                                   path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
-    return bwd_impl(BWD_FWD_PREP, q, k, v, w, beta, log_f, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+    return bwd_impl(BWD_FWD_PREP, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                     nullptr, B, H, L, d, 1, 1.f, dt, workspace, workspace_bytes, stream);
 }
 
 extern "C" path_status_t path_attn_train_fwd_sweep(void* o, float* lse, int with_gates, int B, int H, int L, int d, float scale,
                                                    path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
     // (log_f itself is not read here: the gate sums are in the workspace; any non-NULL value selects them)
-    return bwd_impl(BWD_FWD_SWEEP, nullptr, nullptr, nullptr, nullptr, nullptr, with_gates ? workspace : nullptr, o, lse, nullptr,
+    return bwd_impl(BWD_FWD_SWEEP, layout_of(PATH_LAYOUT_BHLD, H, L, d), nullptr, nullptr, nullptr, nullptr, nullptr, with_gates ? workspace : nullptr, o, lse, nullptr,
                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, B, H, L, d, 1, scale, dt, workspace, workspace_bytes, stream);
 }
 
@@ -560,6 +572,98 @@ extern "C" path_status_t path_attn_train_bwd(const void* q, const void* k, const
                                              const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
                                              void* dlog_f, int B, int H, int L, int d, int causal, float scale,
                                              path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
-    return bwd_impl(BWD_RESUME, q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
+    return bwd_impl(BWD_RESUME, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
                     workspace, workspace_bytes, stream);
+}
+
+// ---- the same computations on [B,L,H,d] tensors, and on packed variable-length batches ------------------
+
+extern "C" path_status_t path_attn_fwd_layout(const void* q, const void* k, const void* v, const void* w,
+                                              const void* beta, const void* log_f, void* o, float* lse,
+                                              int B, int H, int L, int d, path_layout_t layout, int causal, float scale,
+                                              path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!layout_ok(layout)) return PATH_ERR_UNSUPPORTED;
+    return fwd_impl(0, layout_of(layout, H, L, d), q, k, v, w, beta, log_f, log_f != nullptr, o, lse, B, H, L, d, causal, scale, dt,
+                    workspace, workspace_bytes, stream);
+}
+
+extern "C" path_status_t path_attn_bwd_layout(const void* q, const void* k, const void* v, const void* w,
+                                              const void* beta, const void* log_f, const void* o, const float* lse,
+                                              const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                              void* dlog_f, int B, int H, int L, int d, path_layout_t layout, int causal,
+                                              float scale, path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                                              void* stream) {
+    if (!layout_ok(layout)) return PATH_ERR_UNSUPPORTED;
+    return bwd_impl(BWD_FULL, layout_of(layout, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f,
+                    B, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
+}
+
+// Packed sequences [T,H,d]: sequence s is a [1,L_s,H,d] problem whose tensors start at token cu_seqlens[s].
+static bool varlen_ok(const int* cu, int nseq, int* lmax) {
+    if (!cu || nseq < 1 || cu[0] != 0) return false;
+    int m = 0;
+    for (int s = 0; s < nseq; ++s) {
+        const int len = cu[s + 1] - cu[s];
+        if (len < 1) return false;
+        if (len > m) m = len;
+    }
+    *lmax = m;
+    return true;
+}
+template <typename P> static P* at_token(P* base, long long tok, long long per_token, size_t es) {
+    typedef typename std::conditional<std::is_const<P>::value, const unsigned char, unsigned char>::type B;
+    return base ? reinterpret_cast<P*>(reinterpret_cast<B*>(base) + (size_t)(tok * per_token) * es) : nullptr;
+}
+
+extern "C" size_t path_attn_varlen_workspace_bytes(const int* cu_seqlens, int nseq, int H, int d, path_dtype_t dt,
+                                                   int for_backward) {
+    int lmax = 0;
+    if (!varlen_ok(cu_seqlens, nseq, &lmax)) return 0;
+    return path_attn_workspace_bytes(1, H, lmax, d, dt, for_backward);
+}
+
+extern "C" path_status_t path_attn_varlen_fwd(const void* q, const void* k, const void* v, const void* w,
+                                              const void* beta, const void* log_f, void* o, float* lse,
+                                              const int* cu_seqlens, int nseq, int H, int d, int causal, float scale,
+                                              path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    int lmax = 0;
+    if (!varlen_ok(cu_seqlens, nseq, &lmax)) return PATH_ERR_SHAPE;
+    const size_t es = dt == PATH_BF16 ? 2 : 4;
+    for (int s = 0; s < nseq; ++s) {         // one after the other on the stream: they share the workspace
+        const long long t0 = cu_seqlens[s];
+        const int L = cu_seqlens[s + 1] - cu_seqlens[s];
+        const long long hd = (long long)H * d;
+        const path_status_t st = fwd_impl(0, layout_of(PATH_LAYOUT_BLHD, H, L, d), at_token(q, t0, hd, es), at_token(k, t0, hd, es),
+                                          at_token(v, t0, hd, es), at_token(w, t0, hd, es), at_token(beta, t0, H, es),
+                                          at_token(log_f, t0, H, es), log_f != nullptr, at_token(o, t0, hd, es),
+                                          at_token(lse, t0, H, 4), 1, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
+        if (st != PATH_OK) return st;
+    }
+    return PATH_OK;
+}
+
+extern "C" path_status_t path_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* w,
+                                              const void* beta, const void* log_f, const void* o, const float* lse,
+                                              const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                              void* dlog_f, const int* cu_seqlens, int nseq, int H, int d, int causal,
+                                              float scale, path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                                              void* stream) {
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    int lmax = 0;
+    if (!varlen_ok(cu_seqlens, nseq, &lmax)) return PATH_ERR_SHAPE;
+    const size_t es = dt == PATH_BF16 ? 2 : 4;
+    for (int s = 0; s < nseq; ++s) {
+        const long long t0 = cu_seqlens[s];
+        const int L = cu_seqlens[s + 1] - cu_seqlens[s];
+        const long long hd = (long long)H * d;
+        const path_status_t st = bwd_impl(BWD_FULL, layout_of(PATH_LAYOUT_BLHD, H, L, d), at_token(q, t0, hd, es), at_token(k, t0, hd, es),
+                                          at_token(v, t0, hd, es), at_token(w, t0, hd, es), at_token(beta, t0, H, es),
+                                          at_token(log_f, t0, H, es), at_token(o, t0, hd, es), at_token(lse, t0, H, 4),
+                                          at_token(d_o, t0, hd, es), at_token(dq, t0, hd, es), at_token(dk, t0, hd, es),
+                                          at_token(dv, t0, hd, es), at_token(dw, t0, hd, es), at_token(dbeta, t0, H, es),
+                                          at_token(dlog_f, t0, H, es), 1, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
+        if (st != PATH_OK) return st;
+    }
+    return PATH_OK;
 }

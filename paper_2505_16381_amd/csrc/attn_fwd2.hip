@@ -244,7 +244,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
     const float inv = 1.f / l_tot;
     const int tq = cq * CHUNK + 32 * qb + l32;
     if (tq < L) {
-        TIO* orow = reinterpret_cast<TIO*>(p.o) + ((size_t)bh * L + tq) * D + 4 * h;
+        TIO* orow = reinterpret_cast<TIO*>(p.o) + user_vec(p.ul, bh, tq) + 4 * h;
 #pragma unroll
         for (int b = 0; b < DB; ++b)
 #pragma unroll
@@ -255,7 +255,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
                 *reinterpret_cast<Vec4*>(orow + 32 * b + 8 * g) = v4;
             }
         const float ci = FOX ? p.cum[(size_t)bh * NC * CHUNK + tq] : 0.f;
-        if (h == 0) p.lse[(size_t)bh * L + tq] = (m_run + __builtin_amdgcn_logf(l_tot) + ci) * 0.69314718055994530942f;
+        if (h == 0) p.lse[user_scl(p.ul, bh, tq)] = (m_run + __builtin_amdgcn_logf(l_tot) + ci) * 0.69314718055994530942f;
     }
 }
 

@@ -36,8 +36,8 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(BwdParams p) {
     const int tg = chunk * CHUNK + row;
     float s = 0.f;
     if (tg < p.L) {
-        const TIO* a = reinterpret_cast<const TIO*>(p.o) + ((size_t)bh * p.L + tg) * D + part * (D / 4);
-        const TIO* b = reinterpret_cast<const TIO*>(p.dO) + ((size_t)bh * p.L + tg) * D + part * (D / 4);
+        const TIO* a = reinterpret_cast<const TIO*>(p.o) + user_vec(p.ul, bh, tg) + part * (D / 4);
+        const TIO* b = reinterpret_cast<const TIO*>(p.dO) + user_vec(p.ul, bh, tg) + part * (D / 4);
 #pragma unroll
         for (int c = 0; c < D / 4; ++c) s += (float)a[c] * (float)b[c];
     }
@@ -47,21 +47,22 @@ __global__ __launch_bounds__(256) void bwd_delta_kernel(BwdParams p) {
         p.delta[(size_t)bh * p.NC * CHUNK + tg] = s;
         // log-sum-exp in base-2 units; with gates (PaTH-FoX) minus the query's own gate sum, so that
         // P = exp2(scale2 * s - c_key - lse2p)
-        p.lse2p[(size_t)bh * p.NC * CHUNK + tg] = (tg < p.L) ? p.lse[(size_t)bh * p.L + tg] * 1.44269504088896340736f - (p.cum ? p.cum[(size_t)bh * p.NC * CHUNK + tg] : 0.f) : 3.0e38f;      // rows past L: P = exp2(-huge) = 0
+        p.lse2p[(size_t)bh * p.NC * CHUNK + tg] = (tg < p.L) ? p.lse[user_scl(p.ul, bh, tg)] * 1.44269504088896340736f - (p.cum ? p.cum[(size_t)bh * p.NC * CHUNK + tg] : 0.f) : 3.0e38f;      // rows past L: P = exp2(-huge) = 0
     }
 }
 
 // ---------------------------------------------------------------------------------------
 // dO of a query chunk as two fragment-order tiles (I/O type; rows past L are zero):
 //   doq (rows q, contraction c)  and  doT (rows c, contraction q).
-template <typename TIO, int D>
+template <typename TIO, int D, bool STRIDED>
 __global__ __launch_bounds__(256) void bwd_dotile_kernel(BwdParams p) {
     using FragV = typename Tr<TIO>::Frag;
     constexpr int KW = Tr<TIO>::KW, SPB = 32 / KW, DB = D / 32, QS = CHUNK / KW;
     const int i = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int L = p.L, NC = p.NC;
-    const TIO* dO = reinterpret_cast<const TIO*>(p.dO) + ((size_t)bh * L + (size_t)i * CHUNK) * D;
+    const TIO* dO = reinterpret_cast<const TIO*>(p.dO) + user_vec(p.ul, bh, (long long)i * CHUNK);
+    const int TS = STRIDED ? (int)p.ul.vt : D;       // token stride: a compile-time constant unless heads are interleaved
     const int nvalid = (L - i * CHUNK < CHUNK) ? L - i * CHUNK : CHUNK;
     FragV* dq = reinterpret_cast<FragV*>(reinterpret_cast<TIO*>(p.doq) + ((size_t)bh * NC + i) * CHUNK * D);
     FragV* dt = reinterpret_cast<FragV*>(reinterpret_cast<TIO*>(p.doT) + ((size_t)bh * NC + i) * CHUNK * D);
@@ -71,9 +72,9 @@ __global__ __launch_bounds__(256) void bwd_dotile_kernel(BwdParams p) {
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int q1 = 32 * qb + l32, c1 = 32 * cb + acc_row(j, h);      // registers rows c, lane q
-            a[j] = (q1 < nvalid) ? (float)dO[(size_t)q1 * D + c1] : 0.f;
+            a[j] = (q1 < nvalid) ? (float)dO[q1 * TS + c1] : 0.f;
             const int q2 = 32 * qb + acc_row(j, h), c2 = 32 * cb + l32;      // registers rows q, lane c
-            b[j] = (q2 < nvalid) ? (float)dO[(size_t)q2 * D + c2] : 0.f;
+            b[j] = (q2 < nvalid) ? (float)dO[q2 * TS + c2] : 0.f;
         }
         FragV fa[SPB], fb[SPB];
         pack_block<TIO>(a, fa);
@@ -881,10 +882,10 @@ __device__ __forceinline__ void stage_mat_t(const MatRef& r, typename Compute<TI
 }
 
 template <typename TIO, int NB = 1>
-__device__ __forceinline__ void stage_mat(const MatRef& r, typename Compute<TIO>::type* dst, int ld, int R, int K,
+__device__ __forceinline__ void stage_mat(const MatRef& r, const UserLayout& ul, typename Compute<TIO>::type* dst, int ld, int R, int K,
                                           int bh, int chunk, int L, int tid, float mul = 1.f) {
     typedef typename Compute<TIO>::type T;
-    const long long base = bh * r.s_bh + chunk * r.s_ch;
+    const long long base = r.user ? user_vec(ul, bh, (long long)chunk * CHUNK) : bh * r.s_bh + chunk * r.s_ch;
     const int ntok = L - chunk * CHUNK;     // tokens of this chunk that exist
     if (r.type == EL_F32) stage_mat_t<TIO, float, NB>(r, dst, ld, R, K, base, ntok, tid, mul);
     else if (r.type == EL_OP) stage_mat_t<TIO, T, NB>(r, dst, ld, R, K, base, ntok, tid, mul);
@@ -902,8 +903,8 @@ __global__ __launch_bounds__(256) void batched_gemm_kernel(GemmArgs a) {
     const int chunk = blockIdx.x * a.cmul + a.cadd, bh = blockIdx.y;
     if (chunk >= a.NC) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
-    stage_mat<TIO>(a.A, As, ld, a.M, a.K, bh, chunk, a.L, tid);
-    stage_mat<TIO>(a.B, Bs, ld, a.N, a.K, bh, chunk, a.L, tid);
+    stage_mat<TIO>(a.A, a.ul, As, ld, a.M, a.K, bh, chunk, a.L, tid);
+    stage_mat<TIO>(a.B, a.ul, Bs, ld, a.N, a.K, bh, chunk, a.L, tid);
     __syncthreads();
     const int nb = a.N / 32, nblk = (a.M / 32) * nb;
     const long long cbase = bh * a.c_bh + chunk * a.c_ch;
@@ -947,7 +948,7 @@ template <typename TIO, int D> struct SbChainCfg {
     static constexpr size_t smem_bytes = (size_t)4 * D * LD * sizeof(T);
 };
 
-template <typename TIO, int D>
+template <typename TIO, int D, bool STRIDED>
 __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
     using C = SbChainCfg<TIO, D>;
     using T = typename C::T;
@@ -1067,10 +1068,10 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
             for (int jj = 0; jj < 16; ++jj) B0[(32 * ab + acc_row(jj, h)) * LDC + 32 * tb + l32] = (T)(-t1[i][jj]);
         }
         {
-            const MatRef Wt{a.w, 0, 0, 1, D, EL_IO, TOK_K};             // (row b, k=t): W[t][b]
+            const MatRef Wt{a.w, 0, 0, 1, STRIDED ? (int)a.ul.vt : D, EL_IO, TOK_K, 0};    // (row b, k=t): W[t][b], token stride of the caller's layout
             const MatRef K2t{a.dk2, 0, 0, 1, D, EL_F32, TOK_NONE};      // (row a, k=s): dKb2[s][a]
             const MatRef Kbt{a.kbm, 0, 0, 1, D, EL_OP, TOK_NONE};       // (row b, k=s): Kb[s][b]
-            stage_mat_t<TIO, TIO, 4>(Wt, B2, LDC, D, CHUNK, (long long)(((size_t)bh * L + (size_t)c * CHUNK) * D), ntok, tid);
+            stage_mat_t<TIO, TIO, 4>(Wt, B2, LDC, D, CHUNK, user_vec(a.ul, bh, (long long)c * CHUNK), ntok, tid);
             stage_mat_t<TIO, float, 4>(K2t, B3, LDC, D, CHUNK, (long long)(bhc * CHUNK * D), ntok, tid);
             stage_mat_t<TIO, T, 4>(Kbt, B1, LDC, D, CHUNK, (long long)(bhc * CHUNK * D), ntok, tid);
         }
@@ -1088,7 +1089,7 @@ __global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
 // Element-wise steps of the chunk-transform adjoint (device functions of the fused kernel).
 // Diagonal block: P = exp(scale*Sd - lse) on key <= query, dSd = scale * P (dPd - delta).
 template <typename TIO, bool FOX>
-__device__ __forceinline__ void chunk_diag(const DiagArgs& a, float* colsum, int chunk, int bh, int tid) {
+__device__ __forceinline__ void chunk_diag(const DiagArgs& a, const UserLayout& ul, float* colsum, int chunk, int bh, int tid) {
     typedef typename Compute<TIO>::type T;
     const size_t base = ((size_t)bh * a.NC + chunk) * 4096;
     if (FOX) {
@@ -1099,7 +1100,7 @@ __device__ __forceinline__ void chunk_diag(const DiagArgs& a, float* colsum, int
         const int t = idx >> 6, s = idx & 63, tg = chunk * CHUNK + t;
         float P = 0.f, ds = 0.f;
         if (s <= t && tg < a.L) {
-            float z = a.scale * a.sdm[base + idx] - a.lse[(size_t)bh * a.L + tg];
+            float z = a.scale * a.sdm[base + idx] - a.lse[user_scl(ul, bh, tg)];
             if (FOX) {     // PaTH-FoX: + c_t - c_s (the gate sums are kept in base-2 units)
                 const float* c = a.cum + (size_t)bh * a.NC * CHUNK + (size_t)chunk * CHUNK;
                 z += (c[t] - c[s]) * 0.69314718055994530942f;
@@ -1123,11 +1124,11 @@ __device__ __forceinline__ void chunk_diag(const DiagArgs& a, float* colsum, int
 
 // dbeta_a = R[a][a] + sum_s M[a][s] G[a][s];  dGs = diag(beta) M + (diag(beta) M)^T.
 template <typename TIO>
-__device__ __forceinline__ void chunk_beta(const BetaArgs& a, float* bs, int chunk, int bh, int tid) {
+__device__ __forceinline__ void chunk_beta(const BetaArgs& a, const UserLayout& ul, float* bs, int chunk, int bh, int tid) {
     const size_t base = ((size_t)bh * a.NC + chunk) * 4096;
     if (tid < CHUNK) {
         const int tg = chunk * CHUNK + tid;
-        bs[tid] = (tg < a.L) ? (float)reinterpret_cast<const TIO*>(a.beta)[(size_t)bh * a.L + tg] : 0.f;
+        bs[tid] = (tg < a.L) ? (float)reinterpret_cast<const TIO*>(a.beta)[user_scl(ul, bh, tg)] : 0.f;
     }
     __syncthreads();
     for (int idx = tid; idx < 4096; idx += 256) {
@@ -1143,19 +1144,19 @@ __device__ __forceinline__ void chunk_beta(const BetaArgs& a, float* bs, int chu
 
 // fp32 [BH][Lp][d] -> I/O type [BH][L][d]; dbeta likewise.
 template <typename TIO>
-__device__ __forceinline__ void chunk_store(const OutArgs& a, int chunk, int bh, int tid) {
+__device__ __forceinline__ void chunk_store(const OutArgs& a, const UserLayout& ul, int chunk, int bh, int tid) {
     const size_t Lp = (size_t)a.NC * CHUNK;
     for (int idx = tid; idx < CHUNK * a.d; idx += 256) {
         const int t = idx / a.d, c = idx % a.d, tg = chunk * CHUNK + t;
         if (tg >= a.L) continue;
-        const size_t src = ((size_t)bh * Lp + tg) * a.d + c, dst = ((size_t)bh * a.L + tg) * a.d + c;
+        const size_t src = ((size_t)bh * Lp + tg) * a.d + c, dst = (size_t)(user_vec(ul, bh, tg) + c);
         reinterpret_cast<TIO*>(a.dq)[dst] = (TIO)a.dqf[src];
         reinterpret_cast<TIO*>(a.dk)[dst] = (TIO)a.dkf[src];
         reinterpret_cast<TIO*>(a.dv)[dst] = (TIO)a.dvf[src];
         reinterpret_cast<TIO*>(a.dw)[dst] = (TIO)a.dwf[src];
     }
     if (tid < CHUNK && chunk * CHUNK + tid < a.L)
-        reinterpret_cast<TIO*>(a.dbeta)[(size_t)bh * a.L + chunk * CHUNK + tid] = (TIO)a.dbf[(size_t)bh * Lp + chunk * CHUNK + tid];
+        reinterpret_cast<TIO*>(a.dbeta)[user_scl(ul, bh, chunk * CHUNK + tid)] = (TIO)a.dbf[(size_t)bh * Lp + chunk * CHUNK + tid];
 }
 
 // The fused adjoint of the chunk transform: one workgroup per (chunk, head) runs the program.
@@ -1176,16 +1177,16 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
     for (int i = 0; i < pr.n; ++i) {
         const ChunkOp& op = pr.ops[i];
         __syncthreads();       // earlier steps' results are visible to the whole workgroup; LDS is free
-        if (op.kind == OP_DIAG) { chunk_diag<TIO, FOX>(pr.diag, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
-        if (op.kind == OP_BETA) { chunk_beta<TIO>(pr.beta, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
-        if (op.kind == OP_STORE) { chunk_store<TIO>(pr.out, chunk, bh, tid); continue; }
+        if (op.kind == OP_DIAG) { chunk_diag<TIO, FOX>(pr.diag, pr.ul, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
+        if (op.kind == OP_BETA) { chunk_beta<TIO>(pr.beta, pr.ul, reinterpret_cast<float*>(smem), chunk, bh, tid); continue; }
+        if (op.kind == OP_STORE) { chunk_store<TIO>(pr.out, pr.ul, chunk, bh, tid); continue; }
         // M = 64 for every product of the list; N = 64 or 128.  Results are handled in halves of 64
         // columns (one 32x32 block per wave and half), the B operand is staged half by half, so a
         // workgroup needs (64 + 64) x (K + pad) operand elements of LDS and four workgroups fit a CU.
         const int N = op.N, K = op.K, ld = K + FE;
         T* As = reinterpret_cast<T*>(smem);
         T* Bs = As + CHUNK * ld;
-        stage_mat<TIO, CHUNK_NB>(op.A, As, ld, CHUNK, K, bh, chunk, pr.L, tid, op.alpha);
+        stage_mat<TIO, CHUNK_NB>(op.A, pr.ul, As, ld, CHUNK, K, bh, chunk, pr.L, tid, op.alpha);
         const long long cbase = bh * op.c_bh + chunk * op.c_ch;
         const int mb = wv >> 1;
 #pragma unroll
@@ -1194,7 +1195,7 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
             if (o > 0) __syncthreads();                    // the first half's fragments have been read
             MatRef bhalf = op.B;                           // rows 64*o .. 64*o+63 of B (features, never tokens)
             bhalf.p = reinterpret_cast<const char*>(op.B.p) + (size_t)(64 * o) * op.B.rs * (op.B.type == EL_F32 ? 4 : sizeof(T));
-            stage_mat<TIO, CHUNK_NB>(bhalf, Bs, ld, 64, K, bh, chunk, pr.L, tid);
+            stage_mat<TIO, CHUNK_NB>(bhalf, pr.ul, Bs, ld, 64, K, bh, chunk, pr.L, tid);
             __syncthreads();
             const int cb = 2 * o + (wv & 1), cbl = wv & 1;
             if (op.first) {
@@ -1240,7 +1241,8 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     hipError_t e;
     hipLaunchKernelGGL((bwd_delta_kernel<TIO, D>), grid, dim3(256), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D>), grid, dim3(256), 0, st, p);
+    if (p.ul.vt != D) hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D, true>), grid, dim3(256), 0, st, p);
+    else hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D, false>), grid, dim3(256), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const size_t adj_bytes = Adj2Cfg<TIO, D>::smem_bytes, key_bytes = Key2Cfg<TIO, D>::smem_bytes;
     const int ntiles = (p.NC + 1) / 2;
@@ -1302,9 +1304,15 @@ hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream
 template <typename TIO, int D>
 static hipError_t launch_sb_chain_t(const SbChainArgs& a, int BH, hipStream_t st) {
     const size_t bytes = SbChainCfg<TIO, D>::smem_bytes;
-    hipError_t e = set_smem(&bwd_sb_chain_kernel<TIO, D>, bytes);
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_sb_chain_kernel<TIO, D>), dim3((a.NC + SBC - 1) / SBC, BH), dim3(256), bytes, st, a);
+    const dim3 grid((a.NC + SBC - 1) / SBC, BH);
+    hipError_t e;
+    if (a.ul.vt != D) {
+        if ((e = set_smem(&bwd_sb_chain_kernel<TIO, D, true>, bytes)) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_sb_chain_kernel<TIO, D, true>), grid, dim3(256), bytes, st, a);
+    } else {
+        if ((e = set_smem(&bwd_sb_chain_kernel<TIO, D, false>, bytes)) != hipSuccess) return e;
+        hipLaunchKernelGGL((bwd_sb_chain_kernel<TIO, D, false>), grid, dim3(256), bytes, st, a);
+    }
     return hipGetLastError();
 }
 

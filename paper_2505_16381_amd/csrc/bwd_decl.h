@@ -5,6 +5,7 @@
 namespace path {
 
 struct BwdParams {
+    UserLayout ul;                     // layout of q .. dO, lse and of the gradients
     const void *q, *k, *v, *w, *beta, *o, *dO;
     const float* lse;
     const void *kt, *vk, *ktT, *dpt;   // per-chunk fragment tiles from the chunk transform
@@ -34,6 +35,7 @@ struct MatRef {
     long long s_bh, s_ch;   // element strides per (batch*head) and per chunk
     int rs, ks;             // element strides of the row (m or n) and contraction index
     int type, tok;
+    int user;               // one of the caller's [.,.,.,d] tensors: the base follows the UserLayout instead of s_bh, s_ch
 };
 
 struct GemmArgs {
@@ -47,6 +49,7 @@ struct GemmArgs {
     int mask;
     int NC, L;
     int cmul, cadd, gridx;  // workgroup x handles chunk x * cmul + cadd (skipped if >= NC); gridx workgroups per head
+    UserLayout ul;
 };
 
 // Adjoint of the second blocking level, one workgroup per (super-block, head).
@@ -60,6 +63,7 @@ struct SbChainArgs {
     float* ddp;          // [BH][NC][d][d]   (updated)
     float* dkb;          // [BH][Lp][d]      (updated)
     int L, NC;
+    UserLayout ul;       // layout of w
 };
 
 struct DiagArgs {
@@ -103,6 +107,7 @@ struct ChunkOp {
 };
 constexpr int MAX_CHUNK_OPS = 26;
 struct ChunkProgram {
+    UserLayout ul;           // layout of the caller's tensors (operands marked `user`, lse, beta, the outputs)
     ChunkOp ops[MAX_CHUNK_OPS];
     int n;
     DiagArgs diag;
@@ -114,8 +119,9 @@ hipError_t launch_chunk_adjoint(const ChunkProgram& pr, int BH, int is_bf16, hip
 
 // The same steps as one hand-fused kernel (2-byte operand types): every input is a plain pointer.
 struct ChunkFusedArgs {
-    const void *q, *k, *v, *w, *beta, *d_o;      // I/O type, [BH][L][d] / [BH][L]
-    const float *lse, *delta;                    // [BH][L], [BH][Lp]
+    UserLayout ul;                               // layout of q .. d_o, lse and of the outputs
+    const void *q, *k, *v, *w, *beta, *d_o;      // I/O type, the caller's layout
+    const float *lse, *delta;                    // the caller's layout; [BH][Lp]
     const float *sdm, *gm;                       // [BH][NC][64][64]: raw diagonal logits, G
     const void *fm, *gktm, *nm, *aim, *ytm;      // operand type, [BH][NC][64][64]
     const void* utm;                             // operand type, [BH][NC][d][64]

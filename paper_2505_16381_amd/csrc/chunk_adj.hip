@@ -61,7 +61,7 @@ template <typename S, int ROWS, int COLS> struct GTile {
 #pragma unroll
         for (int u = 0; u < NV; ++u) {
             const int idx = tid + u * CA_NT, r = idx / (COLS / 8), c = (idx % (COLS / 8)) * 8;
-            if (r < nvalid) v[u] = *reinterpret_cast<const Vec8*>(src + (size_t)r * stride + c);
+            if (r < nvalid) v[u] = *reinterpret_cast<const Vec8*>(src + r * stride + c);
             else
 #pragma unroll
                 for (int e = 0; e < 8; ++e) v[u][e] = (S)0.f;
@@ -116,7 +116,7 @@ __device__ __forceinline__ void st_block(T* dst, int ld, int r0, int c0, const f
     for (int jj = 0; jj < 16; ++jj) dst[(r0 + acc_row(jj, h)) * ld + c0 + l32] = (T)acc[jj];
 }
 
-template <typename TIO, int D, bool FOX>
+template <typename TIO, int D, bool FOX, bool STRIDED>
 __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
     using C = CaCfg<TIO, D>;
     typedef typename C::T T;
@@ -141,7 +141,9 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
     const int L = a.L, NC = a.NC;
     const int ntok = (L - chunk * CHUNK < CHUNK) ? L - chunk * CHUNK : CHUNK;
     const size_t Lp = (size_t)NC * CHUNK;
-    const size_t ubase = ((size_t)bh * L + (size_t)chunk * CHUNK) * D;       // user [L][d] tensors
+    const long long ubase = user_vec(a.ul, bh, (long long)chunk * CHUNK);    // the caller's tensors: row of the chunk's first token
+    const int TS = STRIDED ? (int)a.ul.vt : D;                                // ... and their token stride (a compile-time
+                                                                              // constant unless the layout interleaves heads)
     const size_t pbase = ((size_t)bh * Lp + (size_t)chunk * CHUNK) * D;      // padded [Lp][d] workspace tensors
     const size_t cbase = ((size_t)bh * NC + chunk) * 4096;                   // 64 x 64 per chunk
     const size_t tpad = (size_t)bh * Lp + (size_t)chunk * CHUNK;             // per-token, padded
@@ -167,20 +169,20 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
 #pragma unroll
         for (int jj = 0; jj < 16; ++jj) {
             const int t = 32 * mbD + acc_row(jj, h);
-            if (t < ntok) g[(size_t)t * D + 32 * cbD + l32] = (TIO)acc[jj];
+            if (t < ntok) g[t * TS + 32 * cbD + l32] = (TIO)acc[jj];
         }
     };
 
     // ---- stage W, dO, V; per-token scalars ---------------------------------------------------
     GTile<TIO, 64, D> tW, tdO, tV;
-    tW.load(wg, D, ntok, tid);
-    tdO.load(dog, D, ntok, tid);
-    tV.load(vg, D, ntok, tid);
+    tW.load(wg, TS, ntok, tid);
+    tdO.load(dog, TS, ntok, tid);
+    tV.load(vg, TS, ntok, tid);
     if (tid < CHUNK) {
         const bool ok = tid < ntok;
-        lse_s[tid] = ok ? a.lse[(size_t)bh * L + chunk * CHUNK + tid] : 0.f;
+        lse_s[tid] = ok ? a.lse[user_scl(a.ul, bh, chunk * CHUNK + tid)] : 0.f;
         delta_s[tid] = a.delta[tpad + tid];
-        beta_s[tid] = ok ? (float)reinterpret_cast<const TIO*>(a.beta)[(size_t)bh * L + chunk * CHUNK + tid] : 0.f;
+        beta_s[tid] = ok ? (float)reinterpret_cast<const TIO*>(a.beta)[user_scl(a.ul, bh, chunk * CHUNK + tid)] : 0.f;
         if (FOX) { cum_s[tid] = a.cum[tpad + tid]; colsum[tid] = 0.f; colsum[CHUNK + tid] = 0.f; }
     }
     float sd[16];                                   // raw diagonal logits of this wave's block
@@ -194,7 +196,7 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
     f32x16 accV, accK, accQ, accW = zero16();
     if (actD) cin(a.dvp + pbase, accV);
     GTile<TIO, 64, D> tQ;
-    tQ.load(qg, D, ntok, tid);
+    tQ.load(qg, TS, ntok, tid);
     __syncthreads();
 
     // ---- dPd = dO V^T; P, dSd (diagonal block) -> Y0 = P, Y1 = dSd, both [query][key] ----------
@@ -261,7 +263,7 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
     tdKb.template store<T, false>(X3, LDD, tid);
     if (actD) cin(a.dqb + pbase, accQ);
     GTile<TIO, 64, D> tK;
-    tK.load(kg, D, ntok, tid);
+    tK.load(kg, TS, ntok, tid);
     GTile<T, 64, 64> tF;
     tF.load(reinterpret_cast<const T*>(a.fm) + cbase, 64, 64, tid);
     __syncthreads();
@@ -310,7 +312,7 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
     }
     GTile<T, 64, 64> tA;
     tA.load(reinterpret_cast<const T*>(a.aim) + cbase, 64, 64, tid);
-    tK.load(kg, D, ntok, tid);       // K once more, for dGk K at the end
+    tK.load(kg, TS, ntok, tid);       // K once more, for dGk K at the end
     __syncthreads();                 // every wave is done with dQb (X1), U (X2)
     if (actD) st_block<T>(X1, LDD, 32 * mbD, 32 * cbD, accU, l32, h);       // dU [token][feature]
     tK.template store<T, false>(X2, LDD, tid);
@@ -382,7 +384,7 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) s += __shfl_xor(s, off);
         if (lane == 0 && r < ntok)
-            reinterpret_cast<TIO*>(a.dbeta)[(size_t)bh * L + chunk * CHUNK + r] = (TIO)(s + rdiag[r]);
+            reinterpret_cast<TIO*>(a.dbeta)[user_scl(a.ul, bh, chunk * CHUNK + r)] = (TIO)(s + rdiag[r]);
     }
     __syncthreads();
 
@@ -396,20 +398,23 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
     }
 }
 
-template <typename TIO, int D, bool FOX>
-hipError_t launch_t(const ChunkFusedArgs& a, int BH, hipStream_t st) {
+template <typename TIO, int D, bool FOX, bool STRIDED>
+hipError_t launch_s(const ChunkFusedArgs& a, int BH, hipStream_t st) {
     using C = CaCfg<TIO, D>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_fused_kernel<TIO, D, FOX>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_fused_kernel<TIO, D, FOX, STRIDED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::TOTAL);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((chunk_fused_kernel<TIO, D, FOX>), dim3(a.NC, BH), dim3(CA_NT), (size_t)C::TOTAL, st, a);
+    hipLaunchKernelGGL((chunk_fused_kernel<TIO, D, FOX, STRIDED>), dim3(a.NC, BH), dim3(CA_NT), (size_t)C::TOTAL, st, a);
     return hipGetLastError();
 }
-
+template <typename TIO, int D, bool FOX>
+hipError_t launch_t(const ChunkFusedArgs& a, int BH, hipStream_t st) {
+    return a.ul.vt != D ? launch_s<TIO, D, FOX, true>(a, BH, st) : launch_s<TIO, D, FOX, false>(a, BH, st);
+}
 
 }  // namespace
 

@@ -15,10 +15,11 @@ __global__ __launch_bounds__(256) void fox_scan_kernel(ScanArgs a) {
     const int bh = blockIdx.x, tid = threadIdx.x;
     const int per = (a.n_out + 255) / 256;
     const int t0 = tid * per, t1 = (t0 + per < a.n_out) ? t0 + per : a.n_out;
-    const TIN* x = reinterpret_cast<const TIN*>(a.in) + (size_t)bh * a.in_stride;
-    TOUT* y = reinterpret_cast<TOUT*>(a.out) + (size_t)bh * a.out_stride;
+    const TIN* x = reinterpret_cast<const TIN*>(a.in) + (a.in_user ? user_scl(a.ul, bh, 0) : (long long)bh * a.in_stride);
+    TOUT* y = reinterpret_cast<TOUT*>(a.out) + (a.out_user ? user_scl(a.ul, bh, 0) : (long long)bh * a.out_stride);
+    const long long xs = a.in_user ? a.ul.st : 1, ys = a.out_user ? a.ul.st : 1;        // token strides
     const float* mi = a.minus ? a.minus + (size_t)bh * a.in_stride : nullptr;
-    auto val = [&](int t) { return (t < a.n_in) ? (float)x[t] - (mi ? mi[t] : 0.f) : 0.f; };
+    auto val = [&](int t) { return (t < a.n_in) ? (float)x[t * xs] - (mi ? mi[t] : 0.f) : 0.f; };
     float s = 0.f;
     for (int t = t0; t < t1; ++t) s += val(t);
     part[tid] = s;
@@ -35,8 +36,8 @@ __global__ __launch_bounds__(256) void fox_scan_kernel(ScanArgs a) {
     float acc = run - s;                       // sum of everything before this thread's run
     for (int t = t0; t < t1; ++t) {
         const float v = val(t);
-        if (a.inclusive) { acc += v; y[t] = (TOUT)(acc * a.scale_out); }
-        else { y[t] = (TOUT)(acc * a.scale_out); acc += v; }
+        if (a.inclusive) { acc += v; y[t * ys] = (TOUT)(acc * a.scale_out); }
+        else { y[t * ys] = (TOUT)(acc * a.scale_out); acc += v; }
     }
 }
 

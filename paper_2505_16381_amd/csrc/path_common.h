@@ -225,7 +225,23 @@ struct FwdWorkspace {
     size_t kt, vt, dp, xinit, sd, kt2, dp2, cum, total;
 };
 
+// Layout of the caller's tensors: element strides of the batch, head and token index, for the
+// [.,.,.,d] tensors (q, k, v, w, o and the gradients; d contiguous) and for the per-token scalars
+// (beta, lse, log f and their gradients).  [B,H,L,d]: {H*L*d, L*d, d | H*L, L, 1};
+// [B,L,H,d]: {L*H*d, d, H*d | L*H, 1, H}.  H = heads per batch entry (bh = b * H + h).
+struct UserLayout {
+    long long vb, vh, vt, sb, sh, st;
+    int H;
+};
+__host__ __device__ __forceinline__ long long user_vec(const UserLayout& u, int bh, long long t) {
+    return (bh / u.H) * u.vb + (bh % u.H) * u.vh + t * u.vt;
+}
+__host__ __device__ __forceinline__ long long user_scl(const UserLayout& u, int bh, long long t) {
+    return (bh / u.H) * u.sb + (bh % u.H) * u.sh + t * u.st;
+}
+
 struct FwdParams {
+    UserLayout ul;
     const void *q, *k, *v, *w, *beta;
     void* o;
     float* lse;

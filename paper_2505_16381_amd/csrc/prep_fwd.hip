@@ -55,7 +55,7 @@ template <typename TIO, int D> struct PrepCfg {
 
 // BWD: also write the backward-only outputs (all of them; their pointers are set).  A compile-time
 // switch, so that the forward's instantiation carries none of that code.
-template <typename TIO, int D, bool BWD>
+template <typename TIO, int D, bool BWD, bool STRIDED>
 __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     using C = PrepCfg<TIO, D>;
     using T = typename C::T;
@@ -87,12 +87,15 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     const int L = p.L, NC = p.NC;
     const int t0 = chunk * CHUNK;
     const int nvalid = (L - t0 < CHUNK) ? (L - t0) : CHUNK;
-    const size_t rowbase = ((size_t)bh * L + t0) * D;
+    const long long rowbase = user_vec(p.ul, bh, t0);       // the caller's layout: token stride TS between rows
+    // token stride of the caller's tensors; a compile-time constant unless the layout interleaves heads
+    // (then every row address costs vector arithmetic instead of an immediate offset)
+    const int TS = STRIDED ? (int)p.ul.vt : D;
     const TIO* Qg = reinterpret_cast<const TIO*>(p.q) + rowbase;
     const TIO* Kg = reinterpret_cast<const TIO*>(p.k) + rowbase;
     const TIO* Vg = reinterpret_cast<const TIO*>(p.v) + rowbase;
     const TIO* Wg = reinterpret_cast<const TIO*>(p.w) + rowbase;
-    const TIO* Bg = reinterpret_cast<const TIO*>(p.beta) + (size_t)bh * L + t0;
+    const TIO* Bg = reinterpret_cast<const TIO*>(p.beta) + user_scl(p.ul, bh, t0);
 
     // ---- phase 0: stage the chunk (zero rows past L) ---------------------------
     // All of a thread's loads are issued before the first conversion, so their latencies overlap.
@@ -104,10 +107,10 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         for (int it = 0; it < NIT; ++it) {
             const int idx = tid + it * 256, row = idx / (D / FE), cf = idx % (D / FE);
             if (row < nvalid) {
-                wr[it] = ld_frag<TIO>(Wg + (size_t)row * D + cf * FE);
+                wr[it] = ld_frag<TIO>(Wg + row * TS + cf * FE);
                 if (C::STAGE_QK) {
-                    qr[it] = ld_frag<TIO>(Qg + (size_t)row * D + cf * FE);
-                    kr[it] = ld_frag<TIO>(Kg + (size_t)row * D + cf * FE);
+                    qr[it] = ld_frag<TIO>(Qg + row * TS + cf * FE);
+                    kr[it] = ld_frag<TIO>(Kg + row * TS + cf * FE);
                 }
             }
         }
@@ -128,7 +131,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             }
         }
     }
-    if (tid < CHUNK) bs[tid] = (tid < nvalid) ? (float)Bg[tid] : 0.f;
+    if (tid < CHUNK) bs[tid] = (tid < nvalid) ? (float)Bg[tid * (int)p.ul.st] : 0.f;
     __syncthreads();
 
     // Operand views of Q and K (LDS when staged; global otherwise -- then rows
@@ -136,7 +139,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     // their products masked out by the zero W / explicit masks below).
     const T* Qp; const T* Kp; int ldqk;
     if (C::STAGE_QK) { Qp = sT + C::off_qs; Kp = sT + C::off_ks; ldqk = LDD; }
-    else { Qp = reinterpret_cast<const T*>(Qg); Kp = reinterpret_cast<const T*>(Kg); ldqk = D; }   // T == TIO here
+    else { Qp = reinterpret_cast<const T*>(Qg); Kp = reinterpret_cast<const T*>(Kg); ldqk = TS; }   // T == TIO here
 
     const int bi = wv >> 1, bj = wv & 1;   // this wave's 32x32 block of a 64x64 result
     const size_t bhc = (size_t)bh * NC + chunk;
@@ -405,7 +408,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 const int s = 32 * sb + acc_row(j, h);
-                acc[j] = (s < nvalid) ? (float)Vg[(size_t)s * D + c] : 0.f;
+                acc[j] = (s < nvalid) ? (float)Vg[s * TS + c] : 0.f;
             }
             FragV fr[SPB];
             pack_block<TIO>(acc, fr);
@@ -462,7 +465,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
                 f32x16 acc;
 #pragma unroll
                 for (int j = 0; j < 16; ++j)
-                    acc[j] = (s < nvalid) ? (float)Vg[(size_t)s * D + 32 * cb + acc_row(j, h)] : 0.f;
+                    acc[j] = (s < nvalid) ? (float)Vg[s * TS + 32 * cb + acc_row(j, h)] : 0.f;
                 FragV fr[SPB];
                 pack_block<TIO>(acc, fr);
 #pragma unroll
@@ -472,20 +475,24 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     }
 }
 
-template <typename T, int D, bool BWD>
-hipError_t launch_prep_fwd_b(const FwdParams& p, hipStream_t stream) {
+template <typename T, int D, bool BWD, bool STRIDED>
+hipError_t launch_prep_fwd_s(const FwdParams& p, hipStream_t stream) {
     using C = PrepCfg<T, D>;
     static_assert(sizeof(typename C::T) == sizeof(T), "tile sizes assume equal operand and I/O width");
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep_fwd_kernel<T, D, BWD>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep_fwd_kernel<T, D, BWD, STRIDED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     dim3 grid(p.NC, p.B * p.H);
-    hipLaunchKernelGGL((prep_fwd_kernel<T, D, BWD>), grid, dim3(256), C::smem_bytes, stream, p);
+    hipLaunchKernelGGL((prep_fwd_kernel<T, D, BWD, STRIDED>), grid, dim3(256), C::smem_bytes, stream, p);
     return hipGetLastError();
+}
+template <typename T, int D, bool BWD>
+hipError_t launch_prep_fwd_b(const FwdParams& p, hipStream_t stream) {
+    return p.ul.vt != D ? launch_prep_fwd_s<T, D, BWD, true>(p, stream) : launch_prep_fwd_s<T, D, BWD, false>(p, stream);
 }
 template <typename T, int D>
 hipError_t launch_prep_fwd_t(const FwdParams& p, hipStream_t stream) {

@@ -197,6 +197,12 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
     if (actD) cin(a.dvp + pbase, accV);
     GTile<TIO, 64, D> tQ;
     tQ.load(qg, TS, ntok, tid);
+    GTile<T, 64, 64> tY;
+    tY.load(reinterpret_cast<const T*>(a.ytm) + cbase, 64, 64, tid);
+    GTile<float, 64, D> tdQb;
+    tdQb.load(a.dqb + pbase, D, 64, tid);
+    GTile<T, D, 64> tU;
+    tU.load(utmg, 64, D, tid);
     __syncthreads();
 
     // ---- dPd = dO V^T; P, dSd (diagonal block) -> Y0 = P, Y1 = dSd, both [query][key] ----------
@@ -222,12 +228,8 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
         }
         if (FOX) atomicAdd(colsum + s, csum);
     }
-    GTile<T, 64, 64> tY;
-    tY.load(reinterpret_cast<const T*>(a.ytm) + cbase, 64, 64, tid);
-    GTile<float, 64, D> tdQb;
-    tdQb.load(a.dqb + pbase, D, 64, tid);
-    GTile<T, D, 64> tU;
-    tU.load(utmg, 64, D, tid);
+    GTile<float, 64, D> tdKb;
+    tdKb.load(a.dkb + pbase, D, 64, tid);
     __syncthreads();
     if (FOX && tid < CHUNK) {        // the diagonal block's column and row sums of the logit gradient
         a.dcol[tpad + tid] += colsum[tid];
@@ -245,8 +247,11 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
     tY.template store<T, true>(Y0, LDC, tid);          // -Y^T as stored ([r][s])
     tdQb.template store<T, true>(X1, LDD, tid);        // -dQb
     tU.template store<T, false>(X2, LDC, tid);         // U as stored: [feature][token]
-    GTile<float, 64, D> tdKb;
-    tdKb.load(a.dkb + pbase, D, 64, tid);
+    if (actD) cin(a.dqb + pbase, accQ);
+    GTile<TIO, 64, D> tK;
+    tK.load(kg, TS, ntok, tid);
+    GTile<T, 64, 64> tF;
+    tF.load(reinterpret_cast<const T*>(a.fm) + cbase, 64, 64, tid);
     __syncthreads();
 
     // ---- dK = dKb + dSd^T Q (kept open);  dF = tril(-dSd Y^T - dQb U^T) -> Y2 --------------------
@@ -261,11 +266,8 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
         st_block<T>(Y2, LDC, 32 * mb6, 32 * cb6, acc, l32, h);
     }
     tdKb.template store<T, false>(X3, LDD, tid);
-    if (actD) cin(a.dqb + pbase, accQ);
-    GTile<TIO, 64, D> tK;
-    tK.load(kg, TS, ntok, tid);
-    GTile<T, 64, 64> tF;
-    tF.load(reinterpret_cast<const T*>(a.fm) + cbase, 64, 64, tid);
+    GTile<float, D, D> tDD;
+    tDD.load(ddpg, D, D, tid);
     __syncthreads();
 
     // ---- dW = dF^T Q - Y dKb (kept open) ----------------------------------------------------------
@@ -276,8 +278,9 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
     __syncthreads();                 // Q (X0) and Y (Y0) are free
     tK.template store<T, false>(X0, LDD, tid);
     tF.template store<T, false>(Y3, LDC, tid);
-    GTile<float, D, D> tDD;
-    tDD.load(ddpg, D, D, tid);
+    GTile<T, 64, 64> tN, tG;
+    tN.load(reinterpret_cast<const T*>(a.nm) + cbase, 64, 64, tid);
+    tG.load(reinterpret_cast<const T*>(a.gktm) + cbase, 64, 64, tid);
     __syncthreads();
 
     // ---- dQ = dQb + dSd K + dF W;  dY = -(F^T dSd + W dKb^T) -> Y4 ---------------------------------
@@ -294,9 +297,9 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
         for (int jj = 0; jj < 16; ++jj) acc[jj] = -acc[jj];
         st_block<T>(Y4, LDC, 32 * mb6, 32 * cb6, acc, l32, h);
     }
-    GTile<T, 64, 64> tN, tG;
-    tN.load(reinterpret_cast<const T*>(a.nm) + cbase, 64, 64, tid);
-    tG.load(reinterpret_cast<const T*>(a.gktm) + cbase, 64, 64, tid);
+    GTile<T, 64, 64> tA;
+    tA.load(reinterpret_cast<const T*>(a.aim) + cbase, 64, 64, tid);
+    tK.load(kg, TS, ntok, tid);       // K once more, for dGk K at the end
     __syncthreads();                 // K (X0), dKb (X3), dSd (Y1), dF (Y2) are free
     tDD.template store<T, false>(X0, LDD, tid);        // ddP [a][b], spans X0 and X3
     tN.template store<T, false>(Y0, LDC, tid);
@@ -310,9 +313,6 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
         mm<T, D, false, true>(accU, XW, LDD, 32 * mbD, X0, LDD, 32 * cbD, l32, h);
         mm<T, D, true, false>(accW, X2, LDC, 32 * mbD, X0, LDD, 32 * cbD, l32, h);
     }
-    GTile<T, 64, 64> tA;
-    tA.load(reinterpret_cast<const T*>(a.aim) + cbase, 64, 64, tid);
-    tK.load(kg, TS, ntok, tid);       // K once more, for dGk K at the end
     __syncthreads();                 // every wave is done with dQb (X1), U (X2)
     if (actD) st_block<T>(X1, LDD, 32 * mbD, 32 * cbD, accU, l32, h);       // dU [token][feature]
     tK.template store<T, false>(X2, LDD, tid);

@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 METRIC = "PaTH attn fwd+bwd TFLOP/s and % bf16 MFMA peak at B=4,H=16,L=8192,d=128"
 PEAK_TFLOPS = 2500.0      # MI355X dense bf16/fp16 MFMA
-SWEEP_HBM_BYTES = 2.39e9  # measured HBM traffic of one sweep launch at the headline shape (see profiles/)
+SWEEP_HBM_BYTES = 2.47e9  # measured HBM traffic of one sweep launch at the headline shape (see profiles/)
 CHUNK = 64
 
 

@@ -20,7 +20,7 @@
 //
 // (sl = strictly lower part).  Every matrix is staged ONCE into LDS in the layout it has in
 // memory (converted to the operand type); a product whose contraction runs along the rows of a
-// stored matrix gathers its 16-byte fragments with 2-byte LDS reads instead of keeping a
+// stored matrix takes its 16-byte fragments with two transposing LDS reads instead of keeping a
 // transposed copy.  dK and dW accumulate in registers across the whole kernel; the 64 x 64
 // intermediates never leave LDS.  Per chunk the kernel reads about 0.46 MB and writes the four
 // gradients, against about 1.5 MB for the same steps run as separate staged products.

@@ -933,159 +933,6 @@ __global__ __launch_bounds__(256) void batched_gemm_kernel(GemmArgs a) {
 }
 
 // ---------------------------------------------------------------------------------------
-// Adjoint of the second blocking level (Kb2_c = Kb_c R_c^T, R_{c-1} = R_c P_c with R_last = I,
-// P_superblock = R_{first-1}; P_c = I - dP_c, dP_c = W_c^T U_c), fused: one workgroup per
-// (super-block J, head) walks the chunks c = first .. last with the gradient D of R_{c-1} in
-// accumulator registers (start: the gradient of P_superblock from the far ddP kernel),
-//     ddP_c -= R_c^T D                              (d x d x d)
-//     dKb_c += dKb2_c R_c                           (64 x d x d)
-//     D     <- D - (D U_c^T) W_c + dKb2_c^T Kb_c     (c < last)
-// Operands are staged in LDS with the contraction index contiguous (pitch K + 8), converted to
-// the operand type; a 32x32 block of a product reads 16-byte fragments from both.
-template <typename TIO, int D> struct SbChainCfg {
-    typedef typename Compute<TIO>::type T;
-    static constexpr int LD = D + 8, LDC = CHUNK + 8;
-    static constexpr size_t smem_bytes = (size_t)4 * D * LD * sizeof(T);
-};
-
-template <typename TIO, int D, bool STRIDED>
-__global__ __launch_bounds__(256) void bwd_sb_chain_kernel(SbChainArgs a) {
-    using C = SbChainCfg<TIO, D>;
-    using T = typename C::T;
-    constexpr int FE = Tr<T>::FE, KW = Tr<T>::KW, DB = D / 32, NOWN = DB * DB / 4, LD = C::LD, LDC = C::LDC;
-    static_assert(sizeof(T) == 2, "fused chain: 2-byte operands only");
-    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    T* B0 = reinterpret_cast<T*>(smem);      // R^T: B0[x][k] = R[k][x]; later -T1 [a][t] (pitch LDC)
-    T* B1 = B0 + D * LD;                     // D as [b][k] = D[k][b]; then D rows [a][k]; later Kb^T [b][s] (pitch LDC)
-    T* B2 = B1 + D * LD;                     // dKb2 rows [s][a]; later W^T [b][t] (pitch LDC)
-    T* B3 = B2 + D * LD;                     // U rows [t][k]; later dKb2^T [a][s] (pitch LDC)
-
-    const int J = blockIdx.x, bh = blockIdx.y, NC = a.NC, L = a.L;
-    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
-    const int c0 = J * SBC;
-    const int clast = (c0 + SBC - 1 < NC) ? c0 + SBC - 1 : NC - 1;
-    const size_t Lp = (size_t)NC * CHUNK;
-
-    // 32x32 block (mb, nb) of A B^T, operands in LDS with pitch ld, K contraction indices
-    // (compile-time); fragments are fetched four slabs at a time ahead of their products
-    auto block = [&](const T* As, const T* Bs, int ld, int mb, int nb, auto kc, f32x16 acc) {
-        constexpr int K = decltype(kc)::value;
-        const T* ap = As + (32 * mb + l32) * ld + FE * h;
-        const T* bp = Bs + (32 * nb + l32) * ld + FE * h;
-#pragma unroll
-        for (int k0 = 0; k0 < K; k0 += 4 * KW) {
-            typename Tr<T>::Frag fa[4], fb[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) { fa[u] = ld_frag<T>(ap + k0 + u * KW); fb[u] = ld_frag<T>(bp + k0 + u * KW); }
-#pragma unroll
-            for (int u = 0; u < 4; ++u) acc = Tr<T>::mma(fa[u], fb[u], acc);
-        }
-        return acc;
-    };
-    constexpr std::integral_constant<int, D> KD{};
-    constexpr std::integral_constant<int, CHUNK> KC{};
-
-    // D: block o of this wave = (rows a-block ab, lane b-block bb), blk = wv + 4*o
-    f32x16 Dacc[NOWN];
-    {
-        const float* src = a.dchain + ((size_t)bh * (NC + 1) + c0) * D * D;
-#pragma unroll
-        for (int o = 0; o < NOWN; ++o) {
-            const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) Dacc[o][jj] = src[(size_t)(32 * ab + acc_row(jj, h)) * D + 32 * bb + l32];
-        }
-    }
-
-    for (int c = c0; c <= clast; ++c) {
-        const size_t bhc = (size_t)bh * NC + c;
-        const int ntok = L - c * CHUNK;
-        const MatRef Rt{a.rm, 0, 0, 1, D, EL_OP, TOK_NONE};          // (row x, k): R[k][x]
-        const MatRef K2r{a.dk2, 0, 0, D, 1, EL_F32, TOK_NONE};       // (row s, k=a): dKb2[s][a]
-        __syncthreads();                                             // previous iteration's reads are done
-        stage_mat_t<TIO, T, 4>(Rt, B0, LD, D, D, (long long)(bhc * D * D), ntok, tid);
-        stage_mat_t<TIO, float, 4>(K2r, B2, LD, CHUNK, D, (long long)(bhc * CHUNK * D), ntok, tid);
-#pragma unroll
-        for (int o = 0; o < NOWN; ++o) {                             // B1[b][k] = D[k][b]
-            const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                typename Tr<T>::Vec4 v4;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) v4[r] = (T)Dacc[o][4 * g + r];
-                *reinterpret_cast<typename Tr<T>::Vec4*>(B1 + (32 * bb + l32) * LD + 32 * ab + 8 * g + 4 * h) = v4;
-            }
-        }
-        __syncthreads();
-        // ddP_c[x][b] -= sum_k R[k][x] D[k][b]
-        {
-            float* dst = a.ddp + bhc * (size_t)D * D;
-#pragma unroll
-            for (int o = 0; o < NOWN; ++o) {
-                const int blk = wv + 4 * o, xb = blk / DB, bb = blk % DB;
-                const f32x16 acc = block(B0, B1, LD, xb, bb, KD, zero16());
-#pragma unroll
-                // one addend per element and launch: the hardware add (no return value, so the wave
-                // does not wait for the old value) is as reproducible as a read-modify-write
-                for (int jj = 0; jj < 16; ++jj) unsafeAtomicAdd(dst + (size_t)(32 * xb + acc_row(jj, h)) * D + 32 * bb + l32, -acc[jj]);
-            }
-        }
-        // dKb_c[s][b] += sum_a dKb2[s][a] R[a][b]
-        {
-            float* dst = a.dkb + (bhc * CHUNK) * (size_t)D;
-            for (int blk = wv; blk < 2 * DB; blk += 4) {
-                const int sb = blk / DB, bb = blk % DB;
-                const f32x16 acc = block(B2, B0, LD, sb, bb, KD, zero16());
-#pragma unroll
-                for (int jj = 0; jj < 16; ++jj) unsafeAtomicAdd(dst + (size_t)(32 * sb + acc_row(jj, h)) * D + 32 * bb + l32, acc[jj]);
-            }
-        }
-        if (c == clast) break;
-        __syncthreads();                                             // B0, B1, B2 are free
-        // T1 = D U^T:  A = D rows (B1[a][k]),  B = U rows (B3[t][k] = utm[k][t])
-#pragma unroll
-        for (int o = 0; o < NOWN; ++o) {
-            const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) B1[(32 * ab + acc_row(jj, h)) * LD + 32 * bb + l32] = (T)Dacc[o][jj];
-        }
-        {
-            const MatRef Ur{a.utm, 0, 0, 1, CHUNK, EL_OP, TOK_NONE};     // (row t, k): utm[k][t]
-            stage_mat_t<TIO, T, 4>(Ur, B3, LD, CHUNK, D, (long long)(bhc * D * CHUNK), ntok, tid);
-        }
-        __syncthreads();
-        f32x16 t1[2 * DB / 4];
-#pragma unroll
-        for (int i = 0; i < 2 * DB / 4; ++i) {
-            const int blk = wv + 4 * i, ab = blk >> 1, tb = blk & 1;
-            t1[i] = block(B1, B3, LD, ab, tb, KD, zero16());          // rows a, lane t
-        }
-        __syncthreads();                                             // B1, B3 are free
-#pragma unroll
-        for (int i = 0; i < 2 * DB / 4; ++i) {                       // B0[a][t] = -T1[a][t]  (pitch LDC)
-            const int blk = wv + 4 * i, ab = blk >> 1, tb = blk & 1;
-#pragma unroll
-            for (int jj = 0; jj < 16; ++jj) B0[(32 * ab + acc_row(jj, h)) * LDC + 32 * tb + l32] = (T)(-t1[i][jj]);
-        }
-        {
-            const MatRef Wt{a.w, 0, 0, 1, STRIDED ? (int)a.ul.vt : D, EL_IO, TOK_K, 0};    // (row b, k=t): W[t][b], token stride of the caller's layout
-            const MatRef K2t{a.dk2, 0, 0, 1, D, EL_F32, TOK_NONE};      // (row a, k=s): dKb2[s][a]
-            const MatRef Kbt{a.kbm, 0, 0, 1, D, EL_OP, TOK_NONE};       // (row b, k=s): Kb[s][b]
-            stage_mat_t<TIO, TIO, 4>(Wt, B2, LDC, D, CHUNK, user_vec(a.ul, bh, (long long)c * CHUNK), ntok, tid);
-            stage_mat_t<TIO, float, 4>(K2t, B3, LDC, D, CHUNK, (long long)(bhc * CHUNK * D), ntok, tid);
-            stage_mat_t<TIO, T, 4>(Kbt, B1, LDC, D, CHUNK, (long long)(bhc * CHUNK * D), ntok, tid);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int o = 0; o < NOWN; ++o) {
-            const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
-            Dacc[o] = block(B0, B2, LDC, ab, bb, KC, Dacc[o]);    // - T1 W
-            Dacc[o] = block(B3, B1, LDC, ab, bb, KC, Dacc[o]);    // + dKb2^T Kb
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------
 // Element-wise steps of the chunk-transform adjoint (device functions of the fused kernel).
 // Diagonal block: P = exp(scale*Sd - lse) on key <= query, dSd = scale * P (dPd - delta).
 template <typename TIO, bool FOX>
@@ -1299,25 +1146,6 @@ hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream
     if (is_bf16) hipLaunchKernelGGL((batched_gemm_kernel<bf16_t>), grid, dim3(256), bytes, st, a);
     else hipLaunchKernelGGL((batched_gemm_kernel<float>), grid, dim3(256), bytes, st, a);
     return hipGetLastError();
-}
-
-template <typename TIO, int D>
-static hipError_t launch_sb_chain_t(const SbChainArgs& a, int BH, hipStream_t st) {
-    const size_t bytes = SbChainCfg<TIO, D>::smem_bytes;
-    const dim3 grid((a.NC + SBC - 1) / SBC, BH);
-    hipError_t e;
-    if (a.ul.vt != D) {
-        if ((e = set_smem(&bwd_sb_chain_kernel<TIO, D, true>, bytes)) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_sb_chain_kernel<TIO, D, true>), grid, dim3(256), bytes, st, a);
-    } else {
-        if ((e = set_smem(&bwd_sb_chain_kernel<TIO, D, false>, bytes)) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_sb_chain_kernel<TIO, D, false>), grid, dim3(256), bytes, st, a);
-    }
-    return hipGetLastError();
-}
-
-hipError_t launch_bwd_sb_chain(const SbChainArgs& a, int BH, int d, hipStream_t st) {
-    return d == 64 ? launch_sb_chain_t<bf16_t, 64>(a, BH, st) : launch_sb_chain_t<bf16_t, 128>(a, BH, st);
 }
 
 hipError_t launch_chunk_adjoint(const ChunkProgram& pr, int BH, int is_bf16, hipStream_t st) {

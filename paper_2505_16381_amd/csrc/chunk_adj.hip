@@ -431,7 +431,165 @@ hipError_t launch_t(const ChunkFusedArgs& a, int BH, hipStream_t st) {
     return a.ul.vt != D ? launch_s<TIO, D, FOX, true>(a, BH, st) : launch_s<TIO, D, FOX, false>(a, BH, st);
 }
 
+
+// ---------------------------------------------------------------------------------------
+// Adjoint of the second blocking level (Kb2_c = Kb_c R_c^T, R_{c-1} = R_c P_c with R_last = I,
+// P_superblock = R_{first-1}; P_c = I - dP_c, dP_c = W_c^T U_c), fused: one workgroup per
+// (super-block J, head) walks the chunks c = first .. last with the gradient G of R_{c-1} in
+// accumulator registers (start: the gradient of P_superblock from the far ddP kernel),
+//     ddP_c -= R_c^T G                              (d x d x d)
+//     dKb_c += dKb2_c R_c                           (64 x d x d)
+//     G     <- G - (G U_c^T) W_c + dKb2_c^T Kb_c     (c < last)
+// The five operands of a chunk are fetched into registers one chunk ahead and staged in LDS as
+// they lie in memory (16-byte writes, no bank conflicts); products that contract along the rows
+// of a stored matrix take their fragments with transposing LDS reads.
+template <typename TIO, int D> struct SbCfg {
+    typedef typename Compute<TIO>::type T;
+    static constexpr int LDD = D + 8, LDC = CHUNK + 8;
+    static constexpr int DD = D * LDD * 2, TD = 64 * LDD * 2, DT = D * LDC * 2;     // bytes: d x d, 64 x d, d x 64 tiles
+    static constexpr int R_ = 0, G_ = DD, K2 = 2 * DD, U_ = K2 + TD, W_ = U_ + DT, KB = W_ + TD, T1 = KB + TD;
+    static constexpr int TOTAL = T1 + DT;
+    static_assert(TOTAL <= 160 * 1024, "LDS budget");
+};
+
+template <typename TIO, int D, bool STRIDED>
+__global__ __launch_bounds__(CA_NT) void sb_chain_kernel(SbChainArgs a) {
+    using C = SbCfg<TIO, D>;
+    typedef typename C::T T;
+    constexpr int LDD = C::LDD, LDC = C::LDC, DB = D / 32;
+    constexpr int NOWN = (DB * DB + 7) / 8;          // d x d blocks per wave: blocks wv, wv + 8, ...
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    T* sR = reinterpret_cast<T*>(smem + C::R_);       // R_c [k][x]
+    T* sG = reinterpret_cast<T*>(smem + C::G_);       // G [a][b]
+    T* sK2 = reinterpret_cast<T*>(smem + C::K2);      // dKb2_c [s][a]
+    T* sU = reinterpret_cast<T*>(smem + C::U_);       // U_c as stored: [feature][token]
+    T* sW = reinterpret_cast<T*>(smem + C::W_);       // W_c [t][b]
+    T* sKb = reinterpret_cast<T*>(smem + C::KB);      // Kb_c [s][b]
+    T* sT1 = reinterpret_cast<T*>(smem + C::T1);      // -(G U^T) [a][t]
+
+    const int J = blockIdx.x, bh = blockIdx.y, NC = a.NC, L = a.L;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
+    const int c0 = J * SBC;
+    const int clast = (c0 + SBC - 1 < NC) ? c0 + SBC - 1 : NC - 1;
+    const int TS = STRIDED ? (int)a.ul.vt : D;        // token stride of W
+    const bool act = wv < 2 * DB;                     // 64 x d and d x 64 results: one block per wave
+    const int hb = act ? wv / DB : 0, db = wv % DB;   // ... block (hb, db) of a 64 x d result, (db, hb) of a d x 64 one
+
+    f32x16 G[NOWN];
+    {
+        const float* src = a.dchain + ((size_t)bh * (NC + 1) + c0) * D * D;
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) {
+            const int blk = wv + 8 * o, ab = blk / DB, bb = blk % DB;
+            if (blk < DB * DB) {
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) G[o][jj] = src[(size_t)(32 * ab + acc_row(jj, h)) * D + 32 * bb + l32];
+            }
+        }
+    }
+    GTile<T, D, D> tR;
+    GTile<float, 64, D> tK2;
+    GTile<T, D, 64> tU;
+    GTile<TIO, 64, D> tW;
+    GTile<T, 64, D> tKb;
+    auto fetch = [&](int c) {
+        const size_t bhc = (size_t)bh * NC + c;
+        const int ntok = (L - c * CHUNK < CHUNK) ? L - c * CHUNK : CHUNK;
+        tR.load(reinterpret_cast<const T*>(a.rm) + bhc * D * D, D, D, tid);
+        tK2.load(a.dk2 + bhc * CHUNK * D, D, 64, tid);
+        if (c < clast) {
+            tU.load(reinterpret_cast<const T*>(a.utm) + bhc * D * CHUNK, 64, D, tid);
+            tW.load(reinterpret_cast<const TIO*>(a.w) + user_vec(a.ul, bh, (long long)c * CHUNK), TS, ntok, tid);
+            tKb.load(reinterpret_cast<const T*>(a.kbm) + bhc * CHUNK * D, D, 64, tid);
+        }
+    };
+    fetch(c0);
+    for (int c = c0; c <= clast; ++c) {
+        const size_t bhc = (size_t)bh * NC + c;
+        __syncthreads();                              // the previous chunk's reads are done
+        tR.template store<T, false>(sR, LDD, tid);
+        tK2.template store<T, false>(sK2, LDD, tid);
+        if (c < clast) {
+            tU.template store<T, false>(sU, LDC, tid);
+            tW.template store<T, false>(sW, LDD, tid);
+            tKb.template store<T, false>(sKb, LDD, tid);
+        }
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) {
+            const int blk = wv + 8 * o, ab = blk / DB, bb = blk % DB;
+            if (blk < DB * DB) st_block<T>(sG, LDD, 32 * ab, 32 * bb, G[o], l32, h);
+        }
+        if (c < clast) fetch(c + 1);
+        __syncthreads();
+        // ddP_c[x][b] -= sum_k R[k][x] G[k][b]
+        {
+            float* dst = a.ddp + bhc * (size_t)D * D;
+#pragma unroll 1
+            for (int o = 0; o < NOWN; ++o) {
+                const int blk = wv + 8 * o, xb = blk / DB, bb = blk % DB;
+                if (blk < DB * DB) {
+                    f32x16 acc = zero16();
+                    mm<T, D, true, true>(acc, sR, LDD, 32 * xb, sG, LDD, 32 * bb, l32, h);
+                    // one addend per element and launch: the hardware add (no return value, so the wave
+                    // does not wait for the old value) is as reproducible as a read-modify-write
+#pragma unroll
+                    for (int jj = 0; jj < 16; ++jj) unsafeAtomicAdd(dst + (size_t)(32 * xb + acc_row(jj, h)) * D + 32 * bb + l32, -acc[jj]);
+                }
+            }
+        }
+        // dKb_c[s][b] += sum_a dKb2[s][a] R[a][b]
+        if (act) {
+            float* dst = a.dkb + (bhc * CHUNK) * (size_t)D;
+            f32x16 acc = zero16();
+            mm<T, D, false, true>(acc, sK2, LDD, 32 * hb, sR, LDD, 32 * db, l32, h);
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) unsafeAtomicAdd(dst + (size_t)(32 * hb + acc_row(jj, h)) * D + 32 * db + l32, acc[jj]);
+        }
+        if (c == clast) break;
+        // T1[a][t] = sum_k G[a][k] U[t][k]
+        if (act) {
+            f32x16 acc = zero16();
+            mm<T, D, false, true>(acc, sG, LDD, 32 * db, sU, LDC, 32 * hb, l32, h);
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) acc[jj] = -acc[jj];
+            st_block<T>(sT1, LDC, 32 * db, 32 * hb, acc, l32, h);
+        }
+        __syncthreads();
+        // G += -T1 W + dKb2^T Kb
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) {
+            const int blk = wv + 8 * o, ab = blk / DB, bb = blk % DB;
+            if (blk < DB * DB) {
+                mm<T, 64, false, true>(G[o], sT1, LDC, 32 * ab, sW, LDD, 32 * bb, l32, h);
+                mm<T, 64, true, true>(G[o], sK2, LDD, 32 * ab, sKb, LDD, 32 * bb, l32, h);
+            }
+        }
+    }
+}
+
+template <typename TIO, int D, bool STRIDED>
+hipError_t launch_sb_s(const SbChainArgs& a, int BH, hipStream_t st) {
+    using C = SbCfg<TIO, D>;
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sb_chain_kernel<TIO, D, STRIDED>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::TOTAL);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((sb_chain_kernel<TIO, D, STRIDED>), dim3((a.NC + SBC - 1) / SBC, BH), dim3(CA_NT), (size_t)C::TOTAL, st, a);
+    return hipGetLastError();
+}
+template <typename TIO, int D>
+hipError_t launch_sb_t(const SbChainArgs& a, int BH, hipStream_t st) {
+    return a.ul.vt != D ? launch_sb_s<TIO, D, true>(a, BH, st) : launch_sb_s<TIO, D, false>(a, BH, st);
+}
+
 }  // namespace
+
+hipError_t launch_bwd_sb_chain(const SbChainArgs& a, int BH, int d, hipStream_t st) {
+    return d == 64 ? launch_sb_t<bf16_t, 64>(a, BH, st) : launch_sb_t<bf16_t, 128>(a, BH, st);
+}
 
 hipError_t launch_chunk_fused(const ChunkFusedArgs& a, int BH, int d, hipStream_t st) {
     const bool fox = a.cum != nullptr;

@@ -24,7 +24,10 @@
 
 namespace path {
 
-constexpr int FWD2_THREADS = 256;
+#ifndef FWD2_CPT
+#define FWD2_CPT 2                  // query chunks per workgroup (two waves each); 4 was tried: 6 % slower
+#endif
+constexpr int FWD2_THREADS = 128 * FWD2_CPT;
 
 template <typename TIO, int D> struct Fwd2Cfg {
     typedef typename Compute<TIO>::type T;
@@ -43,7 +46,7 @@ __device__ __forceinline__ void wait_tiles_and_sync() {
 // forget gates, here in base-2 units); the query's own + c_i cancels in the softmax and is added
 // to the log-sum-exp at the end.
 template <typename TIO, int D, bool FOX>
-__global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p) {
+__global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_kernel(FwdParams p) {
     using C = Fwd2Cfg<TIO, D>;
     using T = typename C::T;
     using Frag = typename Tr<T>::Frag;
@@ -60,7 +63,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
     float* sC = reinterpret_cast<float*>(sP + DPF);             // FOX: [2 stages][32] gate sums of the stage's keys
 
     const int BH = p.B * p.H, L = p.L, NC = p.NC;
-    const int ntiles = (NC + 1) / 2;
+    const int ntiles = (NC + FWD2_CPT - 1) / FWD2_CPT;
     // XCD-aware numbering: workgroup b runs on XCD b % 8; that XCD takes heads xcd, xcd+8, ...
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int bh = (slot / ntiles) * 8 + xcd;
@@ -68,11 +71,12 @@ __global__ __launch_bounds__(FWD2_THREADS, 2) void attn_fwd2_kernel(FwdParams p)
     if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
 
-    const int cq = tile * 2 + (wv >> 1);            // this wave's chunk
+    const int cq = tile * FWD2_CPT + (wv >> 1);     // this wave's chunk
     const int qb = wv & 1;                          // ... and which 32-query half of it
     const bool active = cq < NC;
-    const int jtop = (tile * 2 + 1 < NC) ? tile * 2 + 1 : NC - 1;
-    const int jsb = (tile * 2 / SBC) * SBC;         // first chunk of the tile's own super-block
+    const int jtop = (tile * FWD2_CPT + FWD2_CPT - 1 < NC) ? tile * FWD2_CPT + FWD2_CPT - 1 : NC - 1;
+    static_assert(SBC % FWD2_CPT == 0, "a tile must lie in one super-block");
+    const int jsb = (tile * FWD2_CPT / SBC) * SBC;  // first chunk of the tile's own super-block
     const int nsb = (NC + SBC - 1) / SBC;
     const float sl2 = p.scale * 1.44269504088896340736f;
 
@@ -269,7 +273,7 @@ hipError_t launch_attn_fwd2_f(const FwdParams& p, hipStream_t stream) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int ntiles = (p.NC + 1) / 2;
+    const int ntiles = (p.NC + FWD2_CPT - 1) / FWD2_CPT;
     const int BH = p.B * p.H;
     dim3 grid((unsigned)(((BH + 7) / 8) * 8 * ntiles));
     const size_t bytes = C::smem_bytes;

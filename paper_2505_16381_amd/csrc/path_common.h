@@ -181,9 +181,15 @@ __device__ __forceinline__ f32x16 gemm_rows(const T* ap, const T* bp, f32x16 acc
 // sides, at most 4095) covers the rest.
 template <int NT, int NFRAG, typename Frag>
 __device__ __forceinline__ void async_copy_tile(const Frag* g, Frag* s, int tid, int wv) {
-    static_assert(sizeof(Frag) == 16 && NFRAG % NT == 0, "whole groups of fragments");
-    constexpr int NPT = NFRAG / NT;
+    static_assert(sizeof(Frag) == 16 && NFRAG % 64 == 0 && (NFRAG % NT == 0 || NFRAG < NT), "whole groups of fragments");
     const int lane = tid & 63;
+    if (NFRAG < NT) {          // fewer groups than waves: the first NFRAG/64 waves take one each (wave-uniform test)
+        if (wv * 64 < NFRAG)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(reinterpret_cast<const char*>(g) + (unsigned)((wv * 64 + lane) * 16)),
+                                             (__attribute__((address_space(3))) void*)(s + wv * 64), 16, 0, 0);
+        return;
+    }
+    constexpr int NPT = NFRAG / NT > 0 ? NFRAG / NT : 1;
 #pragma unroll
     for (int i0 = 0; i0 < NPT; i0 += 4) {
         const char* ga = reinterpret_cast<const char*>(g) + (unsigned)(((wv * NPT + i0) * 64 + lane) * 16);

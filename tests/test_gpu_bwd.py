@@ -84,6 +84,20 @@ def test_bwd_special_betas(gpu, oracle, dtype):
     _check(gpu, oracle, x, dtype, 0.125, tag="bwd special betas")
 
 
+@pytest.mark.parametrize("dtype,scale", [("fp32", 1.0), ("fp32", 0.03), ("bf16", 1.0), ("bf16", 0.3)])
+def test_bwd_other_scales(gpu, oracle, dtype, scale):
+    """`scale` is a free argument (the paper's logits are unscaled, scale = 1): the kernels fold it into the
+    exponent and into the finished sums, so values far from d^-1/2 are worth a case of their own.  With
+    scale = 1 the inputs are shrunk so that the logits stay in the range the other tests cover."""
+    L, d = 1100, 64
+    x = si.make_inputs(1, 2, L, d, dtype, 760 + int(100 * scale), 0.0, with_do=True)
+    if scale == 1.0:
+        x["q"] = (x["q"] * 0.35).astype(x["q"].dtype)
+        if dtype == "bf16":
+            x["q"] = si.round_to_bf16(x["q"])
+    _check(gpu, oracle, x, dtype, scale, tag=f"bwd scale={scale}")
+
+
 def test_bwd_gradient_identities_on_gpu(gpu):
     """w.dw = 2 beta dbeta and dw_0 = dbeta_0 = 0 hold for the GPU gradients too (fp32)."""
     x = si.make_inputs(1, 2, 192, 64, "fp32", 800, 0.0, with_do=True)

@@ -401,12 +401,36 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
 //     dV^T  += dO^T P             A = doT tile,  B = P   (registers)
 //     dKb^T += Xs^T dS            A = xsT tile,  B = dS  (registers)
 // The two query halves are summed through LDS at the end (no atomics).
+//
+// With 16-bit operands the near kernel also takes the near part of ddP_j (see bwd_ddp_kernel):
+//     ddP_j -= Xs^T g               A = xsT tile,  B = gT tile
+// over the same pairs (i, j), whose xsT tile it has staged anyway.  The gT tile takes the LDS
+// space of the doT tile; the dO^T fragments are then read out of the doq tile with the
+// transposing LDS read.
+//
+// Fragment of the TRANSPOSE of a fragment-order tile (rows q in 32-row halves of DS slabs,
+// contraction c).  Element e of a fragment belongs to contraction index 16 s + acc_row(e, h) of
+// its slab s, in both tiles, so the lane needs tile[q = 16 qs + acc_row(e, h)][c = 32 b + l32],
+// e = 0..7: two transposing reads, of rows 16 qs + 4 h + 0..3 and the same + 8 (in each block of
+// 16 lanes, lane i points at 4 consecutive c of row .. + i/4 and receives column i of the four rows).
+template <typename E, int DS>
+__device__ __forceinline__ typename Tr<E>::Frag ld_tile_frag_tr(const E* tile, int qs, int b, int l32, int h) {
+    static_assert(sizeof(E) == 2, "16-bit transposing reads");
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    const int i = l32 & 15;
+    const E* p = tile + (size_t)((((qs >> 1) * DS + 2 * b + (l32 >> 4)) * 64 + (i & 1) * 32 + 16 * (qs & 1) + 4 * h + (i >> 2)) * 8 + 4 * ((i >> 1) & 1));
+    union { v4s v[2]; typename Tr<E>::Frag f; } u;
+    u.v[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p));
+    u.v[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p + 64));
+    return u.f;
+}
+
 template <typename TIO, int D> struct Key2Cfg {
     typedef typename Compute<TIO>::type T;
     static constexpr int FE = Tr<T>::FE;
     static constexpr int KV_FRAGS = CHUNK * D / FE;
     static constexpr int NBUF = (sizeof(T) == 2) ? 2 : 1;                     // fp32 tiles are too big to double-buffer
-    static constexpr int STAGE_FRAGS = 4 * KV_FRAGS + 32;                     // xs | xsT | doq | doT | lse2 | delta
+    static constexpr int STAGE_FRAGS = 4 * KV_FRAGS + 32;                     // xs | xsT | doq | doT (near, 16-bit: gT) | lse2 | delta
     static constexpr size_t tile_bytes = (size_t)NBUF * STAGE_FRAGS * 16;
     static constexpr size_t red_bytes = (size_t)2 * 2 * (D / 32) * 1024 * 4 + 256;   // dV, dKb (and FOX column sums) of the two upper waves
     static constexpr size_t smem_bytes = tile_bytes > red_bytes ? tile_bytes : red_bytes;
@@ -420,6 +444,8 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     using FragV = typename Tr<TIO>::Frag;
     constexpr int KW = Tr<T>::KW, SPB = 32 / KW, DB = D / 32, DS = D / KW, QS = CHUNK / KW;
     constexpr int KVF = C::KV_FRAGS, NBUF = C::NBUF, STF = C::STAGE_FRAGS;
+    constexpr bool NFUSE = !FAR && sizeof(T) == 2;          // the near part of ddP is taken here too
+    constexpr int NOWN = NFUSE ? DB * DB / 4 : 1;           // its 32x32 blocks per wave
 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     Frag* sbase = reinterpret_cast<Frag*>(smem);
@@ -460,6 +486,9 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     f32x16 dVt[DB], dKt[DB];
 #pragma unroll
     for (int b = 0; b < DB; ++b) { dVt[b] = zero16(); dKt[b] = zero16(); }
+    f32x16 ddPa[NOWN];
+#pragma unroll
+    for (int o = 0; o < NOWN; ++o) ddPa[o] = zero16();
     // PaTH-FoX: this lane's key has gate sum ckj; dcol collects the column sum of the logit gradient
     const int key_tok = (wactive ? jw : j) * CHUNK + 32 * kh + l32;
     const float ckj = FOX ? p.cum[(size_t)bh * Lp + key_tok] : 0.f;
@@ -478,8 +507,10 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
             async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf + KVF, tid, wv);
         if (part < 0 || part == 1)
             async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doq) + bhi), buf + 2 * KVF, tid, wv);
-        if (part < 0 || part == 3)
-            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doT) + bhi), buf + 3 * KVF, tid, wv);
+        if (part < 0 || part == 3) {
+            if (NFUSE) async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.gs) + slot), buf + 3 * KVF, tid, wv);
+            else async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doT) + bhi), buf + 3 * KVF, tid, wv);
+        }
         if ((part < 0 || part == 0) && tid < 32) {     // 64 floats of lse2 (lanes 0-15) and of delta (lanes 16-31): 16 bytes per lane
             const float* src = (tid < 16 ? p.lse2p : p.delta) + (size_t)bh * Lp + (size_t)i * CHUNK + 4 * (tid & 15);
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
@@ -550,7 +581,8 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 Frag tb[2 * SPB];
 #pragma unroll
                 for (int u = 0; u < 2 * SPB; ++u) {
-                    ta[u] = sDT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
+                    if constexpr (NFUSE) ta[u] = ld_tile_frag_tr<TIO, DS>(reinterpret_cast<const TIO*>(sDQ), qh * SPB + u % SPB, b + u / SPB, l32, h);
+                    else ta[u] = sDT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
                     tb[u] = sXT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
                 }
 #pragma unroll
@@ -676,6 +708,27 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 upd(qh, Pb, dSb);
                 if (FAR && spread && qq == 0) issue(i + 1, 2);
             }
+            if (NFUSE && j >= 1) {         // ddP_j: chunk 0 has no transform to the left of it
+                const Frag* sG = sX + 3 * KVF;
+#pragma unroll
+                for (int o = 0; o < NOWN; ++o) {
+                    const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
+                    Frag fa[QS], fb[QS];
+#pragma unroll
+                    for (int s = 0; s < QS; ++s) { fa[s] = sXT[(ab * QS + s) * 64 + lane]; fb[s] = sG[(bb * QS + s) * 64 + lane]; }
+#pragma unroll
+                    for (int s = 0; s < QS; ++s) ddPa[o] = Tr<T>::mma(fa[s], fb[s], ddPa[o]);
+                }
+            }
+        }
+    }
+    if (NFUSE) {
+#pragma unroll
+        for (int o = 0; o < NOWN; ++o) {
+            const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj)
+                p.ddp[((size_t)bh * NC + j) * D * D + (size_t)(32 * ab + acc_row(jj, h)) * D + 32 * bb + l32] = -ddPa[o][jj];
         }
     }
     if (FAR) {
@@ -1120,7 +1173,8 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     const size_t ddp_bytes = DdpCfg<TIO, D>::smem_bytes;
     if ((e = set_smem(&bwd_ddp_kernel<TIO, D, false>, ddp_bytes)) != hipSuccess) return e;
     if ((e = set_smem(&bwd_ddp_kernel<TIO, D, true>, ddp_bytes)) != hipSuccess) return e;
-    hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D, false>), grid, dim3(256), ddp_bytes, st, p);
+    if (sizeof(typename Compute<TIO>::type) != 2)       // 16-bit operands: the near key-side kernel has written ddP
+        hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D, false>), grid, dim3(256), ddp_bytes, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
     const dim3 grid_sb((p.NC + SBC - 1) / SBC, p.B * p.H);
     hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D, true>), grid_sb, dim3(256), ddp_bytes, st, p);

@@ -6,7 +6,7 @@
 //      forward's two blocking levels: the chunks of i's own super-block one by one ("near", keys
 //      Kb, product dP_j), the super-blocks further left as a whole ("far": one state for the
 //      super-block's SBC chunks, second-level keys Kb2, product dP2 = I - P_superblock).
-//   2. bwd_delta:    delta_t = dO_t . o_t.
+//   2. bwd_dotile:   delta_t = dO_t . o_t, and dO as operand tiles.
 //   3. bwd_adjoint2: per query chunk i, left-to-right over key chunks j:
 //        dS = scale * P o (dO V_j^T - delta),   P = exp(scale * Xs Kb_j^T - lse)
 //        g(i,j) = dS Kb_j + g(i,j-1) (I - dP_j)^T          (g(i,-1) = 0)
@@ -29,41 +29,50 @@
 namespace path {
 
 // ---------------------------------------------------------------------------------------
-template <typename TIO, int D>
-__global__ __launch_bounds__(256) void bwd_delta_kernel(BwdParams p) {
-    const int chunk = blockIdx.x, bh = blockIdx.y, tid = threadIdx.x;
-    const int row = tid >> 2, part = tid & 3;
-    const int tg = chunk * CHUNK + row;
-    float s = 0.f;
-    if (tg < p.L) {
-        const TIO* a = reinterpret_cast<const TIO*>(p.o) + user_vec(p.ul, bh, tg) + part * (D / 4);
-        const TIO* b = reinterpret_cast<const TIO*>(p.dO) + user_vec(p.ul, bh, tg) + part * (D / 4);
-#pragma unroll
-        for (int c = 0; c < D / 4; ++c) s += (float)a[c] * (float)b[c];
-    }
-    s += __shfl_xor(s, 1);
-    s += __shfl_xor(s, 2);
-    if (part == 0) {
-        p.delta[(size_t)bh * p.NC * CHUNK + tg] = s;
-        // log-sum-exp in base-2 units; with gates (PaTH-FoX) minus the query's own gate sum, so that
-        // P = exp2(scale2 * s - c_key - lse2p)
-        p.lse2p[(size_t)bh * p.NC * CHUNK + tg] = (tg < p.L) ? p.lse[user_scl(p.ul, bh, tg)] * 1.44269504088896340736f - (p.cum ? p.cum[(size_t)bh * p.NC * CHUNK + tg] : 0.f) : 3.0e38f;      // rows past L: P = exp2(-huge) = 0
-    }
-}
-
-// ---------------------------------------------------------------------------------------
-// dO of a query chunk as two fragment-order tiles (I/O type; rows past L are zero):
+// Per query chunk: delta_t = dO_t . o_t, the row constants of the softmax, and dO as two
+// fragment-order tiles (I/O type; rows past L are zero):
 //   doq (rows q, contraction c)  and  doT (rows c, contraction q).
+// dO is read once, in 16-byte vectors, and staged in LDS; both tiles are built from there.
 template <typename TIO, int D, bool STRIDED>
 __global__ __launch_bounds__(256) void bwd_dotile_kernel(BwdParams p) {
     using FragV = typename Tr<TIO>::Frag;
     constexpr int KW = Tr<TIO>::KW, SPB = 32 / KW, DB = D / 32, QS = CHUNK / KW;
+    constexpr int VE = 16 / (int)sizeof(TIO), VPR = D / VE, LD = D + VE;      // vector length, vectors per row, LDS pitch
+    typedef TIO Vec __attribute__((ext_vector_type(VE)));
+    __shared__ __attribute__((aligned(16))) TIO sdo[CHUNK * LD];
     const int i = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int L = p.L, NC = p.NC;
-    const TIO* dO = reinterpret_cast<const TIO*>(p.dO) + user_vec(p.ul, bh, (long long)i * CHUNK);
+    const long long tok0 = user_vec(p.ul, bh, (long long)i * CHUNK);
+    const TIO* dO = reinterpret_cast<const TIO*>(p.dO) + tok0;
+    const TIO* O = reinterpret_cast<const TIO*>(p.o) + tok0;
     const int TS = STRIDED ? (int)p.ul.vt : D;       // token stride: a compile-time constant unless heads are interleaved
     const int nvalid = (L - i * CHUNK < CHUNK) ? L - i * CHUNK : CHUNK;
+#pragma unroll
+    for (int idx = tid; idx < CHUNK * VPR; idx += 256) {
+        const int row = idx / VPR, v = idx % VPR;
+        Vec a, b;
+#pragma unroll
+        for (int e = 0; e < VE; ++e) { a[e] = (TIO)0.f; b[e] = (TIO)0.f; }
+        if (row < nvalid) {
+            a = *reinterpret_cast<const Vec*>(dO + (size_t)row * TS + v * VE);
+            b = *reinterpret_cast<const Vec*>(O + (size_t)row * TS + v * VE);
+        }
+        *reinterpret_cast<Vec*>(sdo + row * LD + v * VE) = a;
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < VE; ++e) s += (float)a[e] * (float)b[e];
+#pragma unroll
+        for (int m = 1; m < VPR; m <<= 1) s += __shfl_xor(s, m);     // the VPR lanes of a row are neighbours
+        if (v == 0) {
+            const int tg = i * CHUNK + row;
+            p.delta[(size_t)bh * NC * CHUNK + tg] = s;
+            // log-sum-exp in base-2 units; with gates (PaTH-FoX) minus the query's own gate sum, so that
+            // P = exp2(scale2 * s - c_key - lse2p)
+            p.lse2p[(size_t)bh * NC * CHUNK + tg] = (row < nvalid) ? p.lse[user_scl(p.ul, bh, tg)] * 1.44269504088896340736f - (p.cum ? p.cum[(size_t)bh * NC * CHUNK + tg] : 0.f) : 3.0e38f;      // rows past L: P = exp2(-huge) = 0
+        }
+    }
+    __syncthreads();
     FragV* dq = reinterpret_cast<FragV*>(reinterpret_cast<TIO*>(p.doq) + ((size_t)bh * NC + i) * CHUNK * D);
     FragV* dt = reinterpret_cast<FragV*>(reinterpret_cast<TIO*>(p.doT) + ((size_t)bh * NC + i) * CHUNK * D);
     for (int blk = wv; blk < 2 * DB; blk += 4) {
@@ -71,10 +80,8 @@ __global__ __launch_bounds__(256) void bwd_dotile_kernel(BwdParams p) {
         f32x16 a, b;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int q1 = 32 * qb + l32, c1 = 32 * cb + acc_row(j, h);      // registers rows c, lane q
-            a[j] = (q1 < nvalid) ? (float)dO[q1 * TS + c1] : 0.f;
-            const int q2 = 32 * qb + acc_row(j, h), c2 = 32 * cb + l32;      // registers rows q, lane c
-            b[j] = (q2 < nvalid) ? (float)dO[q2 * TS + c2] : 0.f;
+            a[j] = (float)sdo[(32 * qb + l32) * LD + 32 * cb + acc_row(j, h)];      // registers rows c, lane q
+            b[j] = (float)sdo[(32 * qb + acc_row(j, h)) * LD + 32 * cb + l32];      // registers rows q, lane c
         }
         FragV fa[SPB], fb[SPB];
         pack_block<TIO>(a, fa);
@@ -1139,8 +1146,6 @@ template <typename TIO, int D>
 static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     dim3 grid(p.NC, p.B * p.H);
     hipError_t e;
-    hipLaunchKernelGGL((bwd_delta_kernel<TIO, D>), grid, dim3(256), 0, st, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
     if (p.ul.vt != D) hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D, true>), grid, dim3(256), 0, st, p);
     else hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D, false>), grid, dim3(256), 0, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;

@@ -313,10 +313,11 @@ static path_status_t bwd_impl(BwdMode mode, const UserLayout& ul, const void* q,
     if (mode == BWD_FWD_PREP) return PATH_OK;
     if (fwd_mode) {
         fp.o = const_cast<void*>(o); fp.lse = const_cast<float*>(lse); fp.cum = cum;
+        fp.emit_states = 1;            // the sweep leaves the query states for the backward of the pair
         if (!hip_ok(launch_attn_fwd2(fp, d, bf, st), "forward sweep (training pair)")) return PATH_ERR_HIP;
         return PATH_OK;
     }
-    if (NC > 1 && !hip_ok(launch_attn_states(fp, d, bf, st), "query states")) return PATH_ERR_HIP;
+    if (mode != BWD_RESUME && NC > 1 && !hip_ok(launch_attn_states(fp, d, bf, st), "query states")) return PATH_ERR_HIP;
 
     // 2.-4. delta, adjoint scan over key chunks, key-side reductions
     BwdParams bp = {};

@@ -45,7 +45,12 @@ __device__ __forceinline__ void wait_tiles_and_sync() {
 // FOX (PaTH-FoX, paper Sec. 2.2 extension): the logit of key j gets - c_j (c = cumulative log of the
 // forget gates, here in base-2 units); the query's own + c_i cancels in the softmax and is added
 // to the log-sum-exp at the end.
-template <typename TIO, int D, bool FOX>
+//
+// EMIT (forward of a training pair): the query states the backward needs are written on the way,
+// in the arrangement of the backward's own states sweep (see states_bwd.hip): whenever a wave
+// meets a new key block -- a chunk j < cq of its own super-block, or a super-block further left --
+// it stores its state as the tiles xs and xsT of the pair (cq, block).
+template <typename TIO, int D, bool FOX, bool EMIT>
 __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_kernel(FwdParams p) {
     using C = Fwd2Cfg<TIO, D>;
     using T = typename C::T;
@@ -138,6 +143,25 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
         if (!active || j > cq) continue;
         const Frag* sK = sKV + (size_t)(u & 1) * 2 * HF;
         const FragV* sV = reinterpret_cast<const FragV*>(sK + HF);
+
+        if (EMIT && kb == 0 && j < cq && (j >= jsb || (j % SBC) == SBC - 1)) {
+            constexpr int QS = CHUNK / KW;
+            const size_t slot = ((size_t)bh * num_block_slots(NC) + block_slot(cq, j >= jsb ? j : j - (SBC - 1), NC)) * (size_t)CHUNK * D;
+            Frag* xd = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xs) + slot);
+#pragma unroll
+            for (int s = 0; s < DS; ++s) xd[((size_t)qb * DS + s) * 64 + lane] = Xh[s];
+            Frag* xt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xsT) + slot);
+            Frag idf[SPB];
+            identity_frags<T>(idf, l32, h);
+#pragma unroll
+            for (int b = 0; b < DB; ++b) {
+                const f32x16 tr = transpose32<T>(Xh + b * SPB, idf);     // rows q, lane c (block b)
+                Frag fr[SPB];
+                pack_block<T>(tr, fr);
+#pragma unroll
+                for (int s2 = 0; s2 < SPB; ++s2) xt[((size_t)b * QS + qb * SPB + s2) * 64 + lane] = fr[s2];
+            }
+        }
 
         // ---- logits of 32 keys (raw, unscaled) -------------------------------------------
         f32x16 S;
@@ -263,12 +287,12 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     }
 }
 
-template <typename TIO, int D, bool FOX>
+template <typename TIO, int D, bool FOX, bool EMIT>
 hipError_t launch_attn_fwd2_f(const FwdParams& p, hipStream_t stream) {
     using C = Fwd2Cfg<TIO, D>;
     static bool attr_set = false;
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd2_kernel<TIO, D, FOX>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd2_kernel<TIO, D, FOX, EMIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
         if (e != hipSuccess) return e;
         attr_set = true;
@@ -277,12 +301,13 @@ hipError_t launch_attn_fwd2_f(const FwdParams& p, hipStream_t stream) {
     const int BH = p.B * p.H;
     dim3 grid((unsigned)(((BH + 7) / 8) * 8 * ntiles));
     const size_t bytes = C::smem_bytes;
-    hipLaunchKernelGGL((attn_fwd2_kernel<TIO, D, FOX>), grid, dim3(FWD2_THREADS), bytes, stream, p);
+    hipLaunchKernelGGL((attn_fwd2_kernel<TIO, D, FOX, EMIT>), grid, dim3(FWD2_THREADS), bytes, stream, p);
     return hipGetLastError();
 }
 template <typename TIO, int D>
 hipError_t launch_attn_fwd2_t(const FwdParams& p, hipStream_t stream) {
-    return p.cum ? launch_attn_fwd2_f<TIO, D, true>(p, stream) : launch_attn_fwd2_f<TIO, D, false>(p, stream);
+    if (p.emit_states) return p.cum ? launch_attn_fwd2_f<TIO, D, true, true>(p, stream) : launch_attn_fwd2_f<TIO, D, false, true>(p, stream);
+    return p.cum ? launch_attn_fwd2_f<TIO, D, true, false>(p, stream) : launch_attn_fwd2_f<TIO, D, false, false>(p, stream);
 }
 
 hipError_t launch_attn_fwd2(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {

@@ -265,6 +265,7 @@ struct FwdParams {
     //   per pair (query chunk i, key block), slot block_slot(i, c): xs (rows q, contraction c) and
     //               xsT (rows c, contraction q): the query state of chunk i as used against the block.
     void *ktT, *vk, *xs, *xsT, *kt2T, *dpt2;
+    int emit_states;      // forward sweep of a training pair: also write xs and xsT
     // Backward only: per-chunk matrices of the transform, row-major 64x64 (operand type) --
     // fm = F[t][t'], gktm[s][t'] = strictLower(W K^T)[t'][s], nm = N, aim = A^{-1},
     // ytm[s][t] = Y[t][s]; utm [d][64]: utm[c][t] = U[t][c]; fp32: gm = W W^T, sdm[t][s] = Sd;

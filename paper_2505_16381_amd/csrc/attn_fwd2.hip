@@ -150,16 +150,18 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
             Frag* xd = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xs) + slot);
 #pragma unroll
             for (int s = 0; s < DS; ++s) xd[((size_t)qb * DS + s) * 64 + lane] = Xh[s];
-            Frag* xt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xsT) + slot);
-            Frag idf[SPB];
-            identity_frags<T>(idf, l32, h);
+            if (sizeof(T) == 4 || j < jsb) {     // (16-bit operands: the near blocks' consumer transposes xs itself)
+                Frag* xt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xsT) + slot);
+                Frag idf[SPB];
+                identity_frags<T>(idf, l32, h);
 #pragma unroll
-            for (int b = 0; b < DB; ++b) {
-                const f32x16 tr = transpose32<T>(Xh + b * SPB, idf);     // rows q, lane c (block b)
-                Frag fr[SPB];
-                pack_block<T>(tr, fr);
+                for (int b = 0; b < DB; ++b) {
+                    const f32x16 tr = transpose32<T>(Xh + b * SPB, idf);     // rows q, lane c (block b)
+                    Frag fr[SPB];
+                    pack_block<T>(tr, fr);
 #pragma unroll
-                for (int s2 = 0; s2 < SPB; ++s2) xt[((size_t)b * QS + qb * SPB + s2) * 64 + lane] = fr[s2];
+                    for (int s2 = 0; s2 < SPB; ++s2) xt[((size_t)b * QS + qb * SPB + s2) * 64 + lane] = fr[s2];
+                }
             }
         }
 

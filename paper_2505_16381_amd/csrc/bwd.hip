@@ -510,7 +510,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
         const size_t bhi = ((size_t)bh * NC + i) * CHUNK * D;
         if (part < 0 || part == 0)
             async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot), buf, tid, wv);
-        if (part < 0 || part == 2)
+        if ((part < 0 || part == 2) && !NFUSE)       // (near, 16-bit: Xs^T fragments are read out of the xs tile)
             async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xsT) + slot), buf + KVF, tid, wv);
         if (part < 0 || part == 1)
             async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.doq) + bhi), buf + 2 * KVF, tid, wv);
@@ -590,7 +590,8 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 for (int u = 0; u < 2 * SPB; ++u) {
                     if constexpr (NFUSE) ta[u] = ld_tile_frag_tr<TIO, DS>(reinterpret_cast<const TIO*>(sDQ), qh * SPB + u % SPB, b + u / SPB, l32, h);
                     else ta[u] = sDT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
-                    tb[u] = sXT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
+                    if constexpr (NFUSE) tb[u] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sX), qh * SPB + u % SPB, b + u / SPB, l32, h);
+                    else tb[u] = sXT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
                 }
 #pragma unroll
                 for (int u = 0; u < 2 * SPB; ++u) {
@@ -722,7 +723,10 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                     const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
                     Frag fa[QS], fb[QS];
 #pragma unroll
-                    for (int s = 0; s < QS; ++s) { fa[s] = sXT[(ab * QS + s) * 64 + lane]; fb[s] = sG[(bb * QS + s) * 64 + lane]; }
+                    for (int s = 0; s < QS; ++s) {
+                        if constexpr (NFUSE) fa[s] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sX), s, ab, l32, h);
+                        fb[s] = sG[(bb * QS + s) * 64 + lane];
+                    }
 #pragma unroll
                     for (int s = 0; s < QS; ++s) ddPa[o] = Tr<T>::mma(fa[s], fb[s], ddPa[o]);
                 }

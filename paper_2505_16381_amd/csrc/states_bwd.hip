@@ -4,7 +4,8 @@
 // by one, the super-blocks further left as a whole (second blocking level, see prep2_fwd.hip) --
 // as two fragment-order tiles per (chunk, block) pair: xs (rows q, contraction c), which is
 // the operand copy of the state itself, and xsT (rows c, contraction q), its transpose taken
-// through the matrix unit.
+// through the matrix unit (with 16-bit operands only for the far blocks: the near blocks'
+// consumer reads xs with the transposing LDS read instead).
 //
 // One workgroup = 4 waves = two query chunks; wave w owns the 32-query half (w & 1) of chunk
 // 2*tile + (w >> 1).  The state keeps an fp32 master; per step one -dP tile (chunk or
@@ -92,6 +93,7 @@ __global__ __launch_bounds__(256) void bwd_states_kernel(FwdParams p) {
 #pragma unroll
             for (int s = 0; s < DS; ++s) xd[((size_t)qb * DS + s) * 64 + lane] = Xb[s];
             Frag* xt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xsT) + slot);
+            if (sizeof(T) == 4 || !near)       // (16-bit operands: the near blocks' consumer transposes xs itself)
 #pragma unroll
             for (int b = 0; b < DB; ++b) {
                 const f32x16 tr = transpose32<T>(Xb + b * SPB, idf);     // rows q, lane c (block b)

@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 METRIC = "PaTH attn fwd+bwd TFLOP/s and % bf16 MFMA peak at B=4,H=16,L=8192,d=128"
 PEAK_TFLOPS = 2500.0      # MI355X dense bf16/fp16 MFMA
-SWEEP_HBM_BYTES = 2.47e9  # measured HBM traffic of one sweep launch at the headline shape (see profiles/)
+SWEEP_HBM_BYTES = 4.52e9  # measured HBM traffic of one launch of the pair's sweep at the headline shape (see profiles/)
 CHUNK = 64
 
 
@@ -300,12 +300,15 @@ def main():
                 "path_inclusive_tflops": (fl_f + path_extra_flops(B, H, L, d)) / ((prep_ms + sweep_ms) * 1e-3) / 1e12},
         "bwd": ({"ms": bwd_ms, "attn_equiv_tflops": 2.5 * fl_f / (bwd_ms * 1e-3) / 1e12} if do_bwd else None),
         "standalone_calls": alone,
-        "roofline": {"kernel": "attn_fwd_kernel (sweep)", "bound": "mfma", "achieved": sweep_tflops,
+        "roofline": {"kernel": "attn_fwd2_kernel (sweep; in the training pair it also writes the backward's query states)"
+                               if do_bwd else "attn_fwd2_kernel (sweep)", "bound": "mfma", "achieved": sweep_tflops,
                      "peak": PEAK_TFLOPS, "unit": "TFLOP/s", "frac": sweep_tflops / PEAK_TFLOPS,
                      "traffic": SWEEP_HBM_BYTES if (args.config == 2 and not args.shape) else None,
                      "note": "achieved = attention-equivalent flops of the launch / HIP-event time of the sweep kernel; "
                              "traffic = HBM bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE "
-                             "(profiles/fwd_bwd_headline_L8192_d128_hbm_traffic.txt), vs 1.2e9 algorithmic"},
+                             "(profiles/fwd_bwd_headline_L8192_d128_hbm_traffic.txt): 2.42e9 in + 2.10e9 out, of which "
+                             "1.96e9 are the query states kept for the backward; the forward alone needs 1.2e9 "
+                             "(the stand-alone forward's sweep, without that output: 1.4 ms, frac 0.31, same profile)"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, cfg, scale)

@@ -149,7 +149,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
             const size_t slot = ((size_t)bh * num_block_slots(NC) + block_slot(cq, j >= jsb ? j : j - (SBC - 1), NC)) * (size_t)CHUNK * D;
             Frag* xd = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xs) + slot);
 #pragma unroll
-            for (int s = 0; s < DS; ++s) xd[((size_t)qb * DS + s) * 64 + lane] = Xh[s];
+            for (int s = 0; s < DS; ++s) __builtin_nontemporal_store(Xh[s], &xd[((size_t)qb * DS + s) * 64 + lane]);     // streamed: keep the key/value tiles in L2
             if (sizeof(T) == 4 || j < jsb) {     // (16-bit operands: the near blocks' consumer transposes xs itself)
                 Frag* xt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xsT) + slot);
                 Frag idf[SPB];
@@ -160,7 +160,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
                     Frag fr[SPB];
                     pack_block<T>(tr, fr);
 #pragma unroll
-                    for (int s2 = 0; s2 < SPB; ++s2) xt[((size_t)b * QS + qb * SPB + s2) * 64 + lane] = fr[s2];
+                    for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &xt[((size_t)b * QS + qb * SPB + s2) * 64 + lane]);
                 }
             }
         }

@@ -374,7 +374,7 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
                 Frag fr[SPB];
                 pack_block<T>(tr, fr);
 #pragma unroll
-                for (int s2 = 0; s2 < SPB; ++s2) gt[((size_t)b * QS + qb * SPB + s2) * 64 + lane] = fr[s2];
+                for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &gt[((size_t)b * QS + qb * SPB + s2) * 64 + lane]);   // streamed: the key tiles stay in L2
             }
         }
     }

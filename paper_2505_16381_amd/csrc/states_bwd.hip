@@ -91,7 +91,7 @@ __global__ __launch_bounds__(256) void bwd_states_kernel(FwdParams p) {
             const size_t slot = ((size_t)bh * nslots + block_slot(cq, c, NC)) * (size_t)CHUNK * D;
             Frag* xd = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xs) + slot);
 #pragma unroll
-            for (int s = 0; s < DS; ++s) xd[((size_t)qb * DS + s) * 64 + lane] = Xb[s];
+            for (int s = 0; s < DS; ++s) __builtin_nontemporal_store(Xb[s], &xd[((size_t)qb * DS + s) * 64 + lane]);
             Frag* xt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xsT) + slot);
             if (sizeof(T) == 4 || !near)       // (16-bit operands: the near blocks' consumer transposes xs itself)
 #pragma unroll
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(256) void bwd_states_kernel(FwdParams p) {
                 Frag fr[SPB];
                 pack_block<T>(tr, fr);
 #pragma unroll
-                for (int s2 = 0; s2 < SPB; ++s2) xt[((size_t)b * QS + qb * SPB + s2) * 64 + lane] = fr[s2];
+                for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &xt[((size_t)b * QS + qb * SPB + s2) * 64 + lane]);
             }
         }
         if (c > 0) {                           // X <- X (I - dP) of the chunk / super-block just left

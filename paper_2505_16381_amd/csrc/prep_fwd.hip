@@ -97,6 +97,34 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     const TIO* Wg = reinterpret_cast<const TIO*>(p.w) + rowbase;
     const TIO* Bg = reinterpret_cast<const TIO*>(p.beta) + user_scl(p.ul, bh, t0);
 
+    // V is only re-arranged (tiles V^T and, for the backward, V): the wave's elements of both, fetched at the
+    // start and held in registers until the output phase.
+    constexpr int NBV = (D / 32) * 2 / 4;           // 32x32 blocks of a 64 x d tile per wave
+    typedef typename Tr<TIO>::Vec4 VecIO4;
+    TIO vt_r[NBV][16];                              // V^T blocks: registers rows s, lane c
+    VecIO4 vk_r[BWD ? NBV : 1][4];                  // V blocks: registers rows c (4 consecutive per load), lane s
+    auto load_v = [&]() {
+#pragma unroll
+        for (int i = 0; i < NBV; ++i) {
+            const int blk = wv + 4 * i;
+            const int cb = blk >> 1, sb = blk & 1;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int s = 32 * sb + acc_row(j, h);
+                vt_r[i][j] = (s < nvalid) ? Vg[s * TS + 32 * cb + l32] : (TIO)0.f;
+            }
+            if (BWD && p.ktT) {
+                const int s = 32 * sb + l32;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) vk_r[i][g][r] = (TIO)0.f;
+                    if (s < nvalid) vk_r[i][g] = *reinterpret_cast<const VecIO4*>(Vg + s * TS + 32 * cb + 8 * g + 4 * h);
+                }
+            }
+        }
+    };
+
     // ---- phase 0: stage the chunk (zero rows past L) ---------------------------
     // All of a thread's loads are issued before the first conversion, so their latencies overlap.
     {
@@ -114,6 +142,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
                 }
             }
         }
+        load_v();                     // needed only at the very end: in flight during everything in between
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int idx = tid + it * 256, row = idx / (D / FE), cf = idx % (D / FE);
@@ -403,13 +432,9 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         for (int i = 0; i < NB / 4; ++i) {
             const int blk = wv + 4 * i;
             const int cb = blk >> 1, sb = blk & 1;
-            const int c = 32 * cb + l32;
             f32x16 acc;
 #pragma unroll
-            for (int j = 0; j < 16; ++j) {
-                const int s = 32 * sb + acc_row(j, h);
-                acc[j] = (s < nvalid) ? (float)Vg[s * TS + c] : 0.f;
-            }
+            for (int j = 0; j < 16; ++j) acc[j] = (float)vt_r[i][j];
             FragV fr[SPB];
             pack_block<TIO>(acc, fr);
 #pragma unroll
@@ -461,11 +486,9 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             for (int i = 0; i < NB / 4; ++i) {
                 const int blk = wv + 4 * i;
                 const int cb = blk >> 1, sb = blk & 1;
-                const int s = 32 * sb + l32;
                 f32x16 acc;
 #pragma unroll
-                for (int j = 0; j < 16; ++j)
-                    acc[j] = (s < nvalid) ? (float)Vg[s * TS + 32 * cb + acc_row(j, h)] : 0.f;
+                for (int j = 0; j < 16; ++j) acc[j] = (float)vk_r[i][j >> 2][j & 3];
                 FragV fr[SPB];
                 pack_block<TIO>(acc, fr);
 #pragma unroll

@@ -174,6 +174,50 @@ __device__ __forceinline__ f32x16 gemm_rows(const T* ap, const T* bp, f32x16 acc
     return acc;
 }
 
+// Operand fragment of a matrix stored [k][row] (row contiguous) for the lane (l32, h) of a 32x32x16 product:
+// the eight values X[kk + 8h + e][r0 + l32], e = 0..7.  Two transposing LDS reads (ds_read_b64_tr_b16): in
+// each block of 16 lanes, lane j supplies the address of four consecutive values, and lane i receives
+// element i % 4 of the chunks of lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4.  With lane j pointing at
+// X[kb + j/4][rb + 4 (j%4)], lane i therefore gets X[kb + e][rb + i], e = 0..3.
+template <typename T>
+__device__ __forceinline__ typename Tr<T>::Frag ld_frag_tr(const T* X, int ld, int kk, int r0, int l32, int h) {
+    static_assert(sizeof(T) == 2, "16-bit transposing reads");
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    const int j = l32 & 15;
+    const T* p = X + (kk + 8 * h + (j >> 2)) * ld + r0 + (l32 & 16) + 4 * (j & 3);
+    union { v4s v[2]; typename Tr<T>::Frag f; } u;
+    u.v[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p));
+    u.v[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p + 4 * ld));
+    return u.f;
+}
+
+// acc[m][n] += sum_k A(m,k) B(n,k) for one 32x32 block (rows ar0.., columns br0..).
+// TA == false: A is stored [m][k] (16-byte fragment reads); TA == true: A is stored [k][m] (transposing reads).  Same for B.
+template <typename T, int K, bool TA, bool TB>
+__device__ __forceinline__ void mm(f32x16& acc, const T* A, int lda, int ar0, const T* B, int ldb, int br0, int l32, int h) {
+    // four slabs (64 contraction indices) at a time: their fragments are fetched ahead of the four products
+#pragma unroll
+    for (int k0 = 0; k0 < K; k0 += 64) {
+        typename Tr<T>::Frag fa[4], fb[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const int k = k0 + 16 * s + 8 * h;
+            if (TA) {
+                fa[s] = ld_frag_tr<T>(A, lda, k0 + 16 * s, ar0, l32, h);
+            } else {
+                fa[s] = ld_frag<T>(A + (ar0 + l32) * lda + k);
+            }
+            if (TB) {
+                fb[s] = ld_frag_tr<T>(B, ldb, k0 + 16 * s, br0, l32, h);
+            } else {
+                fb[s] = ld_frag<T>(B + (br0 + l32) * ldb + k);
+            }
+        }
+#pragma unroll
+        for (int s = 0; s < 4; ++s) acc = Tr<T>::mma(fa[s], fb[s], acc);
+    }
+}
+
 // Linear copy of NFRAG 16-byte fragments global -> LDS, asynchronous (direct-to-LDS), by a workgroup of
 // NT threads.  One instruction moves 64 consecutive fragments (lane = fragment); wave wv takes the
 // groups wv*NPT .. wv*NPT + NPT-1 (NPT = NFRAG / NT), which are 1 KB apart, so that one

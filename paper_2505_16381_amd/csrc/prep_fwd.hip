@@ -68,8 +68,12 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     T* sT = reinterpret_cast<T*>(smem);
     T* Ws = sT + C::off_ws;
-    T* Ut = Ws;                      // U^T re-uses W's rows once phase 1 is over
+    // 16-bit operands: products with W^T take their fragments from the rows of W with transposing LDS reads, and
+    // U^T has the space a transposed copy of W would need.  fp32 operands (no such read): W^T is written out,
+    // element by element, while the chunk is staged, and U^T re-uses W's rows once phase 1 is over.
+    constexpr bool WTR = sizeof(T) == 2;
     T* Wt = sT + C::off_wt;
+    T* Ut = WTR ? Wt : Ws;
     T* Fs = sT + C::off_f;
     T* Gk = sT + C::off_gk;
     T* Yt = sT + C::off_yt;
@@ -152,8 +156,9 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
                 if (C::STAGE_QK) { qv = cvt_frag<T, TIO>(qr[it]); kv = cvt_frag<T, TIO>(kr[it]); }
             }
             *reinterpret_cast<Frag*>(Ws + row * LDD + cf * FE) = wv_;
+            if (!WTR)
 #pragma unroll
-            for (int e = 0; e < FE; ++e) Wt[(cf * FE + e) * LDC + row] = wv_[e];
+                for (int e = 0; e < FE; ++e) Wt[(cf * FE + e) * LDC + row] = wv_[e];
             if (C::STAGE_QK) {
                 *reinterpret_cast<Frag*>(sT + C::off_qs + row * LDD + cf * FE) = qv;
                 *reinterpret_cast<Frag*>(sT + C::off_ks + row * LDD + cf * FE) = kv;
@@ -176,6 +181,26 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     // Row of Q/K this lane supplies as an operand row (clamped for the global path).
     auto qk_row = [&](int r) { return (C::STAGE_QK || r < nvalid) ? r : 0; };
     auto qk_ok = [&](int r) { return C::STAGE_QK || r < nvalid; };
+
+    // (W^T block cb) x (rows xr0.. of X)^T and (rows xr0.. of X) x (W^T block cb)^T, contraction over the chunk's tokens
+    auto wt_times = [&](int cb, const T* X, int xr0) {
+        if constexpr (WTR) {
+            f32x16 acc = zero16();
+            mm<T, CHUNK, true, false>(acc, Ws, LDD, 32 * cb, X, LDC, xr0, l32, h);
+            return acc;
+        } else {
+            return gemm32<T, CHUNK>(Wt, LDC, 32 * cb, X, LDC, xr0, l32, h, zero16());
+        }
+    };
+    auto times_wt = [&](const T* X, int xr0, int cb) {
+        if constexpr (WTR) {
+            f32x16 acc = zero16();
+            mm<T, CHUNK, false, true>(acc, X, LDC, xr0, Ws, LDD, 32 * cb, l32, h);
+            return acc;
+        } else {
+            return gemm32<T, CHUNK>(X, LDC, xr0, Wt, LDC, 32 * cb, l32, h, zero16());
+        }
+    };
 
     // ---- phase 1: products of the inputs ----------------------------------------
     // G block -> Af[t][s] = beta_t G[t][s] for s < t, else 0.
@@ -306,14 +331,14 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             *reinterpret_cast<Vec4*>(Yt + s * LDC + 32 * bi + 8 * g + 4 * h) = v4;
         }
     }
-    // U^T blocks: rows c (W^T), cols t (N rows).  (Ut aliases Ws: all reads of Ws are done.)
+    // U^T blocks: rows c (W^T), cols t (N rows).  (fp32 operands: Ut aliases Ws, all reads of Ws are done.)
     {
         f32x16 accU[D / 64];
 #pragma unroll
         for (int i = 0; i < D / 64; ++i) {
             const int blk = wv + 4 * i;                 // (D/32)*2 blocks over 4 waves
             const int cb = blk >> 1, tb = blk & 1;
-            accU[i] = gemm32<T, CHUNK>(Wt, LDC, 32 * cb, Nt, LDC, 32 * tb, l32, h, zero16());
+            accU[i] = wt_times(cb, Nt, 32 * tb);
         }
         __syncthreads();                                 // nobody still reads Ws (phase 1) -- and keeps phases apart
 #pragma unroll
@@ -363,7 +388,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         for (int i = 0; i < NB / 4; ++i) {
             const int blk = wv + 4 * i;
             const int ab = blk / (D / 32), bb = blk % (D / 32);
-            f32x16 acc = gemm32<T, CHUNK>(Wt, LDC, 32 * ab, Ut, LDC, 32 * bb, l32, h, zero16());
+            f32x16 acc = wt_times(ab, Ut, 32 * bb);
 #pragma unroll
             for (int j = 0; j < 16; ++j) acc[j] = -acc[j];
             Frag fr[SPB];
@@ -381,7 +406,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         for (int i = 0; i < NB / 4; ++i) {
             const int blk = wv + 4 * i;
             const int cb = blk >> 1, sb = blk & 1;
-            f32x16 acc = gemm32<T, CHUNK>(Wt, LDC, 32 * cb, Yt, LDC, 32 * sb, l32, h, zero16());
+            f32x16 acc = wt_times(cb, Yt, 32 * sb);
             const int s = 32 * sb + l32;
             const T* krow = Kp + (size_t)qk_row(s) * ldqk + 32 * cb + 4 * h;
             const bool ok = qk_ok(s);
@@ -449,7 +474,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             for (int i = 0; i < NBP / 4; ++i) {
                 const int blk = wv + 4 * i;
                 const int bb = blk / (D / 32), cb = blk % (D / 32);
-                f32x16 acc = gemm32<T, CHUNK>(Ut, LDC, 32 * bb, Wt, LDC, 32 * cb, l32, h, zero16());
+                f32x16 acc = times_wt(Ut, 32 * bb, cb);
 #pragma unroll
                 for (int j = 0; j < 16; ++j) acc[j] = -acc[j];
                 Frag fr[SPB];
@@ -467,7 +492,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             for (int i = 0; i < NB / 4; ++i) {
                 const int blk = wv + 4 * i;
                 const int cb = blk >> 1, sb = blk & 1;
-                f32x16 acc = gemm32<T, CHUNK>(Yt, LDC, 32 * sb, Wt, LDC, 32 * cb, l32, h, zero16());
+                f32x16 acc = times_wt(Yt, 32 * sb, cb);
                 const int c = 32 * cb + l32;
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {

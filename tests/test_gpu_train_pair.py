@@ -77,6 +77,29 @@ def test_training_pair_matches_the_oracle_and_the_separate_calls(gpu, oracle, dt
     assert worst <= (1e-4 if dtype == "fp32" else 2e-2)
 
 
+def test_training_pair_at_the_headline_shape_equals_the_separate_calls(gpu):
+    """The shape and launch configuration bench.py times (B=4, H=16, L=8192, d=128, bf16, the pair): o, lse and all
+    gradients are bit-equal to those of path_attn_fwd / path_attn_bwd, which tests/test_gpu_fwd.py and
+    tests/test_gpu_bwd.py hold against the oracle at this shape."""
+    torch, pa = gpu
+    x, c = si.make_config(2, with_do=True)
+    dv = _dev(torch, x, "bf16")
+    B, H, L, d = c["B"], c["H"], c["L"], c["d"]
+    scale = d ** -0.5
+    ws = torch.empty(pa.path_attn_workspace_bytes(B, H, L, d, pa.PATH_BF16, True), dtype=torch.uint8, device="cuda")
+    for rep in range(2):       # twice in the same workspace: nothing of the first step may leak into the second
+        o, lse = pa.path_attn_train_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], ws, scale=scale)
+        got = pa.path_attn_train_bwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], o, lse, dv["dO"], ws, scale=scale)
+    torch.cuda.synchronize()
+    o2, lse2 = pa.path_attn_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], scale=scale)
+    got2 = pa.path_attn_bwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], o2, lse2, dv["dO"], scale=scale)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o2) and torch.equal(lse, lse2)
+    for i, (a, b) in enumerate(zip(got, got2)):
+        assert torch.isfinite(a.float()).all(), i
+        assert torch.equal(a, b), i
+
+
 def test_training_pair_rejects_a_forward_sized_workspace(gpu):
     torch, pa = gpu
     B, H, L, d = 1, 1, 128, 64

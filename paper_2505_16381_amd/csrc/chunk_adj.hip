@@ -476,32 +476,52 @@ __global__ __launch_bounds__(CA_NT) void sb_chain_kernel(SbChainArgs a) {
             if (blk < DB * DB) st_block<T>(sG, LDD, 32 * ab, 32 * bb, G[o], l32, h);
         }
         if (c < clast) fetch(c + 1);
-        __syncthreads();
-        // ddP_c[x][b] -= sum_k R[k][x] G[k][b]
-        {
-            float* dst = a.ddp + bhc * (size_t)D * D;
-#pragma unroll 1
-            for (int o = 0; o < NOWN; ++o) {
-                const int blk = wv + 8 * o, xb = blk / DB, bb = blk % DB;
-                if (blk < DB * DB) {
-                    f32x16 acc = zero16();
-                    mm<T, D, true, true>(acc, sR, LDD, 32 * xb, sG, LDD, 32 * bb, l32, h);
-                    // one addend per element and launch: the hardware add (no return value, so the wave
-                    // does not wait for the old value) is as reproducible as a read-modify-write
+        // The two results of this step are added to what the key-side kernels left in ddP_c and dKb_c: every
+        // element has exactly one writer here, so a plain read-modify-write does (hardware atomic adds, tried
+        // first because they need no old value, ran at the L2's atomic rate and doubled the kernel's time).
+        // The old values are requested well before they are used: those of the wave's first ddP block and of
+        // its dKb block now, those of its second ddP block after the first is stored -- that block's product
+        // is taken last, after the update of G (R and this step's G stay in LDS until the next step).
+        static_assert(NOWN <= 2, "two d x d blocks per wave at most");
+        float* const ddp_dst = a.ddp + bhc * (size_t)D * D;
+        float* const dkb_dst = a.dkb + (bhc * CHUNK) * (size_t)D;
+        auto ddp_load = [&](int o, f32x16& old) {
+            const int blk = wv + 8 * o, xb = blk / DB, bb = blk % DB;
+            if (blk < DB * DB) {
 #pragma unroll
-                    for (int jj = 0; jj < 16; ++jj) unsafeAtomicAdd(dst + (size_t)(32 * xb + acc_row(jj, h)) * D + 32 * bb + l32, -acc[jj]);
-                }
+                for (int jj = 0; jj < 16; ++jj) old[jj] = ddp_dst[(size_t)(32 * xb + acc_row(jj, h)) * D + 32 * bb + l32];
             }
+        };
+        // ddP_c[x][b] -= sum_k R[k][x] G[k][b]
+        auto ddp_block = [&](int o, const f32x16& old) {
+            const int blk = wv + 8 * o, xb = blk / DB, bb = blk % DB;
+            if (blk < DB * DB) {
+                f32x16 acc = zero16();
+                mm<T, D, true, true>(acc, sR, LDD, 32 * xb, sG, LDD, 32 * bb, l32, h);
+#pragma unroll
+                for (int jj = 0; jj < 16; ++jj) ddp_dst[(size_t)(32 * xb + acc_row(jj, h)) * D + 32 * bb + l32] = old[jj] - acc[jj];
+            }
+        };
+        f32x16 ddp_old, dkb_old;
+        ddp_load(0, ddp_old);
+        if (act) {
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) dkb_old[jj] = dkb_dst[(size_t)(32 * hb + acc_row(jj, h)) * D + 32 * db + l32];
         }
+        __syncthreads();
+        ddp_block(0, ddp_old);
+        if (NOWN > 1) ddp_load(1, ddp_old);
         // dKb_c[s][b] += sum_a dKb2[s][a] R[a][b]
         if (act) {
-            float* dst = a.dkb + (bhc * CHUNK) * (size_t)D;
             f32x16 acc = zero16();
             mm<T, D, false, true>(acc, sK2, LDD, 32 * hb, sR, LDD, 32 * db, l32, h);
 #pragma unroll
-            for (int jj = 0; jj < 16; ++jj) unsafeAtomicAdd(dst + (size_t)(32 * hb + acc_row(jj, h)) * D + 32 * db + l32, acc[jj]);
+            for (int jj = 0; jj < 16; ++jj) dkb_dst[(size_t)(32 * hb + acc_row(jj, h)) * D + 32 * db + l32] = dkb_old[jj] + acc[jj];
         }
-        if (c == clast) break;
+        if (c == clast) {
+            if (NOWN > 1) ddp_block(1, ddp_old);
+            break;
+        }
         // T1[a][t] = sum_k G[a][k] U[t][k]
         if (act) {
             f32x16 acc = zero16();
@@ -520,6 +540,7 @@ __global__ __launch_bounds__(CA_NT) void sb_chain_kernel(SbChainArgs a) {
                 mm<T, 64, true, true>(G[o], sK2, LDD, 32 * ab, sKb, LDD, 32 * bb, l32, h);
             }
         }
+        if (NOWN > 1) ddp_block(1, ddp_old);
     }
 }
 

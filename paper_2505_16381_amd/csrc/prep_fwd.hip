@@ -358,14 +358,21 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
         T* nm = reinterpret_cast<T*>(p.nm) + bhc * 4096;
         T* yt = reinterpret_cast<T*>(p.ytm) + bhc * 4096;
         T* ut = reinterpret_cast<T*>(p.utm) + bhc * (size_t)D * 64;
-        for (int idx = tid; idx < 4096; idx += 256) {
-            const int r = idx >> 6, c = idx & 63;
-            fm[idx] = Fs[r * LDC + c];
-            gk[idx] = Gk[r * LDC + c];
-            nm[idx] = Nt[r * LDC + c];
-            yt[idx] = Yt[r * LDC + c];
+        // 16 bytes per lane (the LDS rows are 16-byte aligned: LDC * sizeof(T) is a multiple of 16)
+        typedef T RowVec __attribute__((ext_vector_type(16 / sizeof(T))));
+        constexpr int VE = 16 / (int)sizeof(T), VPR = 64 / VE;
+        static_assert((LDC * sizeof(T)) % 16 == 0, "aligned rows");
+        for (int idx = tid; idx < 64 * VPR; idx += 256) {
+            const int r = idx / VPR, c = (idx % VPR) * VE;
+            *reinterpret_cast<RowVec*>(fm + r * 64 + c) = *reinterpret_cast<const RowVec*>(Fs + r * LDC + c);
+            *reinterpret_cast<RowVec*>(gk + r * 64 + c) = *reinterpret_cast<const RowVec*>(Gk + r * LDC + c);
+            *reinterpret_cast<RowVec*>(nm + r * 64 + c) = *reinterpret_cast<const RowVec*>(Nt + r * LDC + c);
+            *reinterpret_cast<RowVec*>(yt + r * 64 + c) = *reinterpret_cast<const RowVec*>(Yt + r * LDC + c);
         }
-        for (int idx = tid; idx < D * 64; idx += 256) ut[idx] = Ut[(idx >> 6) * LDC + (idx & 63)];
+        for (int idx = tid; idx < D * VPR; idx += 256) {
+            const int r = idx / VPR, c = (idx % VPR) * VE;
+            *reinterpret_cast<RowVec*>(ut + r * 64 + c) = *reinterpret_cast<const RowVec*>(Ut + r * LDC + c);
+        }
     }
     // (a) Sd^T = K Q^T - Y^T F^T, accumulator order: [bhc][qb][kb][g][lane][4]
     {

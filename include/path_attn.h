@@ -160,10 +160,12 @@ path_status_t path_attn_fox_bwd(const void* q, const void* k, const void* v, con
 
 /*
  * Training pair: forward and backward of one step that share a workspace, so that the chunk
- * transform (paper Sec. 3.2) runs once per step instead of once in each.  path_attn_train_fwd
+ * transform (paper Sec. 3.2) and the recurrence of the query states (Sec. 3.3) run once per step
+ * instead of once in each: the forward's sweep also writes the states the backward starts from.
+ * path_attn_train_fwd
  * computes o and lse exactly as path_attn_fwd (log_f == NULL) or path_attn_fox_fwd (log_f given)
  * do, but in a workspace of the BACKWARD's size (path_attn_workspace_bytes(..., for_backward = 1)),
- * where it leaves the transformed operands; path_attn_train_bwd then computes the gradients exactly
+ * where it leaves the transformed operands and the query states; path_attn_train_bwd then computes the gradients exactly
  * as path_attn_bwd / path_attn_fox_bwd do (dlog_f given iff log_f is), provided that the workspace
  * has not been written since path_attn_train_fwd returned and that q, k, v, w, beta, log_f are the
  * same tensors with the same contents.  The price is that the workspace stays alive between the

@@ -588,10 +588,8 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 Frag tb[2 * SPB];
 #pragma unroll
                 for (int u = 0; u < 2 * SPB; ++u) {
-                    if constexpr (NFUSE) ta[u] = ld_tile_frag_tr<TIO, DS>(reinterpret_cast<const TIO*>(sDQ), qh * SPB + u % SPB, b + u / SPB, l32, h);
-                    else ta[u] = sDT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
-                    if constexpr (NFUSE) tb[u] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sX), qh * SPB + u % SPB, b + u / SPB, l32, h);
-                    else tb[u] = sXT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
+                    ta[u] = sDT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
+                    tb[u] = sXT[((b + u / SPB) * QS + qh * SPB + u % SPB) * 64 + lane];
                 }
 #pragma unroll
                 for (int u = 0; u < 2 * SPB; ++u) {
@@ -713,23 +711,48 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                 sdp(qh, S, dP);
                 if (FAR && spread) issue(i + 1, qq == 0 ? 1 : 3);
                 soft(qh, S, dP, Pb, dSb);
-                upd(qh, Pb, dSb);
-                if (FAR && spread && qq == 0) issue(i + 1, 2);
-            }
-            if (NFUSE && j >= 1) {         // ddP_j: chunk 0 has no transform to the left of it
-                const Frag* sG = sX + 3 * KVF;
+                if constexpr (NFUSE) {
+                    // dV^T, dKb^T and the wave's ddP blocks, one 32-row block b of Xs^T at a time: its four
+                    // fragments (all 64 queries) serve ddP, and the two of the wave's own query half serve dKb^T --
+                    // every fragment is read from LDS once per step (the reads, not the products, bound this loop).
+                    // The wave's ddP blocks wv, wv + 4, ... all lie in column block bb of g (d = 128: one per row
+                    // block b; d = 64: the single block (wv / 2, wv % 2)), whose fragments are read once too.
+                    static_assert(DB == 4 || DB == 2, "block ownership below");
+                    const Frag* sG = sX + 3 * KVF;
+                    const int bb = DB == 4 ? wv : (wv & 1);
+                    const bool with_ddp = j >= 1;          // chunk 0 has no transform to the left of it
+                    Frag fb[QS];
 #pragma unroll
-                for (int o = 0; o < NOWN; ++o) {
-                    const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
-                    Frag fa[QS], fb[QS];
+                    for (int s = 0; s < QS; ++s) fb[s] = with_ddp ? sG[(bb * QS + s) * 64 + lane] : Tr<T>::zero();
 #pragma unroll
-                    for (int s = 0; s < QS; ++s) {
-                        if constexpr (NFUSE) fa[s] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sX), s, ab, l32, h);
-                        fb[s] = sG[(bb * QS + s) * 64 + lane];
+                    for (int b = 0; b < DB; ++b) {
+                        Frag fa[QS];
+                        FragV ta[SPB];
+#pragma unroll
+                        for (int s = 0; s < QS; ++s) fa[s] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sX), s, b, l32, h);
+#pragma unroll
+                        for (int u = 0; u < SPB; ++u) ta[u] = ld_tile_frag_tr<TIO, DS>(reinterpret_cast<const TIO*>(sDQ), qh * SPB + u, b, l32, h);
+#pragma unroll
+                        for (int u = 0; u < SPB; ++u) {
+                            Frag tb = fa[u];
+                            if (qh) tb = fa[SPB + u];
+                            dVt[b] = Tr<TIO>::mma(ta[u], Pb[u], dVt[b]);
+                            dKt[b] = Tr<T>::mma(tb, dSb[u], dKt[b]);
+                        }
+                        if (with_ddp && (DB == 4 || b == (wv >> 1))) {
+                            constexpr int NO = DB == 4 ? DB : 1;
+#pragma unroll
+                            for (int o = 0; o < NO; ++o)
+                                if (DB != 4 || o == b) {
+#pragma unroll
+                                    for (int s = 0; s < QS; ++s) ddPa[o] = Tr<T>::mma(fa[s], fb[s], ddPa[o]);
+                                }
+                        }
                     }
-#pragma unroll
-                    for (int s = 0; s < QS; ++s) ddPa[o] = Tr<T>::mma(fa[s], fb[s], ddPa[o]);
+                } else {
+                    upd(qh, Pb, dSb);
                 }
+                if (FAR && spread && qq == 0) issue(i + 1, 2);
             }
         }
     }

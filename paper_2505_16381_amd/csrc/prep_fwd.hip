@@ -26,37 +26,49 @@ template <typename TIO, int D> struct PrepCfg {
     typedef typename Compute<TIO>::type T;
     static constexpr int FE = Tr<T>::FE;
     static constexpr int KW = Tr<T>::KW;
-    static constexpr bool STAGE_QK = sizeof(TIO) == 2;   // fp32 reads Q,K fragments from global
     static constexpr int LDD = D + FE;                 // padded length-D rows
     static constexpr int LDC = CHUNK + FE;             // padded length-64 rows
     static constexpr int LDA = CHUNK + 4;              // fp32 solve matrix
-    static constexpr int WSUT = (CHUNK * LDD > D * LDC) ? CHUNK * LDD : D * LDC;
+    static constexpr int LDH = 32 + 4;                 // fp32 32x32 helpers of the blocked inverse
+    // Q and K are not staged: their operand fragments come straight from global memory (the chunk's rows are
+    // read a few times, out of L2), converted to the operand type on the way.
+    //
+    // 2-byte operands use a compact map (81 KB: TWO workgroups per CU, so that the barriers and the
+    // half-empty phases of one overlap the work of the other -- the kernel is a chain of short dependent
+    // phases, not a stream): U^T has the space a transposed copy of W would take; where it is large enough
+    // (d = 128) the fp32 inverse A^{-1} lives there before U^T is written; F, needed only by the output phase,
+    // is computed there and takes the place of the fp32 matrix A, which is dead by then.
+    // fp32 operands keep separate blocks (N overwrites A^{-1} in place; one workgroup per CU).
+    static constexpr bool COMPACT = sizeof(T) == 2;
+    static constexpr int WSUT = COMPACT ? CHUNK * LDD : ((CHUNK * LDD > D * LDC) ? CHUNK * LDD : D * LDC);   // fp32: U^T re-uses W's rows
     // element offsets (in T) -- every block is a multiple of 16 bytes
-    static constexpr size_t off_ws = 0;                               // W rows, later U^T
-    static constexpr size_t off_wt = off_ws + WSUT;                   // W^T
-    static constexpr size_t off_f = off_wt + (size_t)D * LDC;         // F
-    static constexpr size_t off_gk = off_f + (size_t)CHUNK * LDC;     // (strictLower(W K^T))^T
+    static constexpr size_t off_ws = 0;                               // W rows (fp32: later U^T)
+    static constexpr size_t off_wt = off_ws + WSUT;                   // fp32: W^T; 2-byte: U^T
+    static constexpr size_t off_f_sep = off_wt + (size_t)D * LDC;     // F (fp32 map)
+    static constexpr size_t off_gk = COMPACT ? off_wt + (size_t)D * LDC : off_f_sep + (size_t)CHUNK * LDC;     // (strictLower(W K^T))^T
     static constexpr size_t off_yt = off_gk + (size_t)CHUNK * LDC;    // Y^T
     static constexpr size_t off_nt = off_yt + (size_t)CHUNK * LDC;    // N (operand precision)
     static constexpr bool NT_IN_XF = sizeof(T) == 4;                  // fp32: N overwrites A^{-1} in place (same shape)
-    static constexpr size_t off_qs = off_nt + (NT_IN_XF ? 0 : (size_t)CHUNK * LDC);    // Q rows (staged only)
-    static constexpr size_t off_ks = off_qs + (STAGE_QK ? (size_t)CHUNK * LDD : 0);
-    static constexpr size_t t_elems = off_ks + (STAGE_QK ? (size_t)CHUNK * LDD : 0);
+    static constexpr size_t t_elems = off_nt + (NT_IN_XF ? 0 : (size_t)CHUNK * LDC);
     static constexpr size_t off_af_bytes = ((t_elems * sizeof(T) + 15) / 16) * 16;   // fp32 A / solve
+    static constexpr size_t off_f = COMPACT ? off_af_bytes / sizeof(T) : off_f_sep;  // F (2-byte: in A's place, from phase 4 on)
     static constexpr size_t off_beta_bytes = off_af_bytes + (size_t)CHUNK * LDA * 4;
-    static constexpr int LDH = 32 + 4;                 // fp32 32x32 helpers of the blocked inverse
-    static constexpr size_t off_xf_bytes = off_beta_bytes + CHUNK * 4;            // A^{-1}, fp32 [64][LDA]
+    static constexpr bool XF_IN_UT = COMPACT && (size_t)D * LDC * sizeof(T) >= (size_t)CHUNK * LDA * 4;
+    static constexpr size_t off_xf_bytes = XF_IN_UT ? off_wt * sizeof(T) : off_beta_bytes + CHUNK * 4;   // A^{-1}, fp32 [64][LDA]
     // the two 32x32 fp32 helpers live in Y^T's space (Y^T is written only after the inverse is done)
     static constexpr size_t off_xt1_bytes = off_yt * sizeof(T);                       // (A^{-1})_11^T
     static constexpr size_t off_tt_bytes = off_xt1_bytes + (size_t)32 * LDH * 4;      // (A_21 (A^{-1})_11)^T
     static_assert(2 * 32 * LDH * 4 <= CHUNK * LDC * sizeof(T), "helpers must fit in Y^T");
-    static constexpr size_t smem_bytes = off_xf_bytes + (size_t)CHUNK * LDA * 4;
+    static_assert(!COMPACT || (size_t)CHUNK * LDC * sizeof(T) <= (size_t)CHUNK * LDA * 4, "F must fit in A's place");
+    static constexpr size_t smem_bytes = XF_IN_UT ? off_beta_bytes + CHUNK * 4 : off_xf_bytes + (size_t)CHUNK * LDA * 4;
+    static_assert(!COMPACT || smem_bytes <= 80 * 1024, "two workgroups per CU");
+    static constexpr int WGS_PER_CU = COMPACT ? 2 : 1;
 };
 
 // BWD: also write the backward-only outputs (all of them; their pointers are set).  A compile-time
 // switch, so that the forward's instantiation carries none of that code.
 template <typename TIO, int D, bool BWD, bool STRIDED>
-__global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
+__global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_kernel(FwdParams p) {
     using C = PrepCfg<TIO, D>;
     using T = typename C::T;
     using Frag = typename Tr<T>::Frag;
@@ -85,6 +97,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     float* XT1 = reinterpret_cast<float*>(smem + C::off_xt1_bytes);
     float* TT = reinterpret_cast<float*>(smem + C::off_tt_bytes);
     constexpr int LDH = C::LDH;
+    constexpr bool COMPACT = C::COMPACT;
 
     const int chunk = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
@@ -134,53 +147,52 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     {
         typedef typename Tr<TIO>::Frag FragIO;
         constexpr int NIT = CHUNK * (D / FE) / 256;
-        FragIO wr[NIT], qr[C::STAGE_QK ? NIT : 1], kr[C::STAGE_QK ? NIT : 1];
+        FragIO wr[NIT];
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int idx = tid + it * 256, row = idx / (D / FE), cf = idx % (D / FE);
-            if (row < nvalid) {
-                wr[it] = ld_frag<TIO>(Wg + row * TS + cf * FE);
-                if (C::STAGE_QK) {
-                    qr[it] = ld_frag<TIO>(Qg + row * TS + cf * FE);
-                    kr[it] = ld_frag<TIO>(Kg + row * TS + cf * FE);
-                }
-            }
+            if (row < nvalid) wr[it] = ld_frag<TIO>(Wg + row * TS + cf * FE);
         }
         load_v();                     // needed only at the very end: in flight during everything in between
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int idx = tid + it * 256, row = idx / (D / FE), cf = idx % (D / FE);
-            Frag wv_ = Tr<T>::zero(), qv = Tr<T>::zero(), kv = Tr<T>::zero();
-            if (row < nvalid) {
-                wv_ = cvt_frag<T, TIO>(wr[it]);
-                if (C::STAGE_QK) { qv = cvt_frag<T, TIO>(qr[it]); kv = cvt_frag<T, TIO>(kr[it]); }
-            }
+            Frag wv_ = Tr<T>::zero();
+            if (row < nvalid) wv_ = cvt_frag<T, TIO>(wr[it]);
             *reinterpret_cast<Frag*>(Ws + row * LDD + cf * FE) = wv_;
             if (!WTR)
 #pragma unroll
                 for (int e = 0; e < FE; ++e) Wt[(cf * FE + e) * LDC + row] = wv_[e];
-            if (C::STAGE_QK) {
-                *reinterpret_cast<Frag*>(sT + C::off_qs + row * LDD + cf * FE) = qv;
-                *reinterpret_cast<Frag*>(sT + C::off_ks + row * LDD + cf * FE) = kv;
-            }
         }
     }
     if (tid < CHUNK) bs[tid] = (tid < nvalid) ? (float)Bg[tid * (int)p.ul.st] : 0.f;
     __syncthreads();
 
-    // Operand views of Q and K (LDS when staged; global otherwise -- then rows
-    // past L must not be touched, so those lanes are redirected to row 0 and
-    // their products masked out by the zero W / explicit masks below).
-    const T* Qp; const T* Kp; int ldqk;
-    if (C::STAGE_QK) { Qp = sT + C::off_qs; Kp = sT + C::off_ks; ldqk = LDD; }
-    else { Qp = reinterpret_cast<const T*>(Qg); Kp = reinterpret_cast<const T*>(Kg); ldqk = TS; }   // T == TIO here
+    // Q and K are read from global memory.  Rows past L must not be touched: those lanes are redirected to
+    // row 0 and their products masked out by the zero W / the explicit masks below.
 
     const int bi = wv >> 1, bj = wv & 1;   // this wave's 32x32 block of a 64x64 result
     const size_t bhc = (size_t)bh * NC + chunk;
 
     // Row of Q/K this lane supplies as an operand row (clamped for the global path).
-    auto qk_row = [&](int r) { return (C::STAGE_QK || r < nvalid) ? r : 0; };
-    auto qk_ok = [&](int r) { return C::STAGE_QK || r < nvalid; };
+    auto qk_row = [&](int r) { return r < nvalid ? r : 0; };
+    auto qk_ok = [&](int r) { return r < nvalid; };
+    // operand fragment of row r of Q or K: the FE elements from column k on
+    auto qk_frag = [&](const TIO* base, int r, int k) { return cvt_frag<T, TIO>(ld_frag<TIO>(base + (size_t)qk_row(r) * TS + k)); };
+    // F block: rows t (Q), cols t' (W); keep t' <= t.
+    auto f_block = [&]() {
+        const int ar = 32 * (wv >> 1) + l32, bjj = wv & 1;
+        f32x16 acc = zero16();
+        const T* bp = Ws + (size_t)(32 * bjj + l32) * LDD + FE * h;
+#pragma unroll
+        for (int k0 = 0; k0 < D; k0 += KW) acc = Tr<T>::mma(qk_frag(Qg, ar, k0 + FE * h), ld_frag<T>(bp + k0), acc);
+        const int tp = 32 * bjj + l32;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int t = 32 * (wv >> 1) + acc_row(j, h);
+            Fs[t * LDC + tp] = (tp <= t && t < nvalid) ? (T)acc[j] : (T)0.f;
+        }
+    };
 
     // (W^T block cb) x (rows xr0.. of X)^T and (rows xr0.. of X) x (W^T block cb)^T, contraction over the chunk's tokens
     auto wt_times = [&](int cb, const T* X, int xr0) {
@@ -214,31 +226,14 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             if (BWD && p.gm) p.gm[bhc * 4096 + t * 64 + s] = acc[j];
         }
     }
-    // F block: rows t (Q), cols t' (W); keep t' <= t.
-    {
-        const int ar = 32 * bi + l32;
-        f32x16 acc = zero16();
-        {
-            const T* ap = Qp + (size_t)qk_row(ar) * ldqk + FE * h;
-            const T* bp = Ws + (size_t)(32 * bj + l32) * LDD + FE * h;
-#pragma unroll
-            for (int k0 = 0; k0 < D; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
-        }
-        const int tp = 32 * bj + l32;
-#pragma unroll
-        for (int j = 0; j < 16; ++j) {
-            const int t = 32 * bi + acc_row(j, h);
-            Fs[t * LDC + tp] = (tp <= t && t < nvalid) ? (T)acc[j] : (T)0.f;
-        }
-    }
+    if (!COMPACT) f_block();          // (2-byte operands: at the start of phase 4, in A's place)
     // Gk block: rows t' (W), cols s (K); stored transposed Gk[s][t'], keep t' > s.
     {
         f32x16 acc = zero16();
         {
             const T* ap = Ws + (size_t)(32 * bi + l32) * LDD + FE * h;
-            const T* bp = Kp + (size_t)qk_row(32 * bj + l32) * ldqk + FE * h;
 #pragma unroll
-            for (int k0 = 0; k0 < D; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), acc);
+            for (int k0 = 0; k0 < D; k0 += KW) acc = Tr<T>::mma(ld_frag<T>(ap + k0), qk_frag(Kg, 32 * bj + l32, k0 + FE * h), acc);
         }
         const int s = 32 * bj + l32;
 #pragma unroll
@@ -255,10 +250,8 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     // K Q^T block (rows s = keys, cols t = queries): first term of Sd^T, kept in registers.
     f32x16 accS = zero16();
     {
-        const T* ap = Kp + (size_t)qk_row(32 * bi + l32) * ldqk + FE * h;
-        const T* bp = Qp + (size_t)qk_row(32 * bj + l32) * ldqk + FE * h;
 #pragma unroll
-        for (int k0 = 0; k0 < D; k0 += KW) accS = Tr<T>::mma(ld_frag<T>(ap + k0), ld_frag<T>(bp + k0), accS);
+        for (int k0 = 0; k0 < D; k0 += KW) accS = Tr<T>::mma(qk_frag(Kg, 32 * bi + l32, k0 + FE * h), qk_frag(Qg, 32 * bj + l32, k0 + FE * h), accS);
     }
     __syncthreads();
 
@@ -352,6 +345,10 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
     __syncthreads();
 
     // ---- phase 4: outputs -----------------------------------------------------------
+    if (COMPACT) {       // F, into the space of the fp32 matrix A (dead since the inverse)
+        f_block();
+        __syncthreads();
+    }
     if (BWD && p.fm) {   // backward: keep the chunk's matrices (row-major, operand type)
         T* fm = reinterpret_cast<T*>(p.fm) + bhc * 4096;
         T* gk = reinterpret_cast<T*>(p.gktm) + bhc * 4096;
@@ -415,11 +412,11 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             const int cb = blk >> 1, sb = blk & 1;
             f32x16 acc = wt_times(cb, Yt, 32 * sb);
             const int s = 32 * sb + l32;
-            const T* krow = Kp + (size_t)qk_row(s) * ldqk + 32 * cb + 4 * h;
+            const TIO* krow = Kg + (size_t)qk_row(s) * TS + 32 * cb + 4 * h;
             const bool ok = qk_ok(s);
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                Vec4 k4 = *reinterpret_cast<const Vec4*>(krow + 8 * g);
+                const VecIO4 k4 = *reinterpret_cast<const VecIO4*>(krow + 8 * g);
 #pragma unroll
                 for (int r = 0; r < 4; ++r) acc[4 * g + r] = (ok ? (float)k4[r] : 0.f) - acc[4 * g + r];
             }
@@ -445,13 +442,13 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
             const int cb = blk >> 1, tb = blk & 1;
             f32x16 acc = gemm32<T, CHUNK>(Ut, LDC, 32 * cb, Fs, LDC, 32 * tb, l32, h, zero16());
             const int t = 32 * tb + l32;
-            const T* qrow = Qp + (size_t)qk_row(t) * ldqk + 32 * cb + 4 * h;
+            const TIO* qrow = Qg + (size_t)qk_row(t) * TS + 32 * cb + 4 * h;
             const bool ok = qk_ok(t);
             // xinit: [bh][query block of 32][d block][g][lane][4]
             float* xdst = p.xinit + ((((size_t)bh * NC + chunk) * 2 + tb) * (D / 32) + cb) * 1024;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                Vec4 q4 = *reinterpret_cast<const Vec4*>(qrow + 8 * g);
+                const VecIO4 q4 = *reinterpret_cast<const VecIO4*>(qrow + 8 * g);
                 f32x4 v4;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) v4[r] = (ok ? (float)q4[r] : 0.f) - acc[4 * g + r];
@@ -504,7 +501,7 @@ __global__ __launch_bounds__(256) void prep_fwd_kernel(FwdParams p) {
 #pragma unroll
                 for (int j = 0; j < 16; ++j) {
                     const int s = 32 * sb + acc_row(j, h);
-                    const float kv = qk_ok(s) ? (float)Kp[(size_t)qk_row(s) * ldqk + c] : 0.f;
+                    const float kv = qk_ok(s) ? (float)Kg[(size_t)qk_row(s) * TS + c] : 0.f;
                     acc[j] = kv - acc[j];
                 }
                 Frag fr[SPB];

@@ -361,14 +361,14 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
         static_assert((LDC * sizeof(T)) % 16 == 0, "aligned rows");
         for (int idx = tid; idx < 64 * VPR; idx += 256) {
             const int r = idx / VPR, c = (idx % VPR) * VE;
-            *reinterpret_cast<RowVec*>(fm + r * 64 + c) = *reinterpret_cast<const RowVec*>(Fs + r * LDC + c);
-            *reinterpret_cast<RowVec*>(gk + r * 64 + c) = *reinterpret_cast<const RowVec*>(Gk + r * LDC + c);
-            *reinterpret_cast<RowVec*>(nm + r * 64 + c) = *reinterpret_cast<const RowVec*>(Nt + r * LDC + c);
-            *reinterpret_cast<RowVec*>(yt + r * 64 + c) = *reinterpret_cast<const RowVec*>(Yt + r * LDC + c);
+            __builtin_nontemporal_store(*reinterpret_cast<const RowVec*>(Fs + r * LDC + c), reinterpret_cast<RowVec*>(fm + r * 64 + c));
+            __builtin_nontemporal_store(*reinterpret_cast<const RowVec*>(Gk + r * LDC + c), reinterpret_cast<RowVec*>(gk + r * 64 + c));
+            __builtin_nontemporal_store(*reinterpret_cast<const RowVec*>(Nt + r * LDC + c), reinterpret_cast<RowVec*>(nm + r * 64 + c));
+            __builtin_nontemporal_store(*reinterpret_cast<const RowVec*>(Yt + r * LDC + c), reinterpret_cast<RowVec*>(yt + r * 64 + c));
         }
         for (int idx = tid; idx < D * VPR; idx += 256) {
             const int r = idx / VPR, c = (idx % VPR) * VE;
-            *reinterpret_cast<RowVec*>(ut + r * 64 + c) = *reinterpret_cast<const RowVec*>(Ut + r * LDC + c);
+            __builtin_nontemporal_store(*reinterpret_cast<const RowVec*>(Ut + r * LDC + c), reinterpret_cast<RowVec*>(ut + r * 64 + c));
         }
     }
     // (a) Sd^T = K Q^T - Y^T F^T, accumulator order: [bhc][qb][kb][g][lane][4]
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
             f32x4 v4;
 #pragma unroll
             for (int r = 0; r < 4; ++r) v4[r] = accS[4 * g + r] - corr[4 * g + r];
-            *reinterpret_cast<f32x4*>(dst + (g * 64 + lane) * 4) = v4;
+            __builtin_nontemporal_store(v4, reinterpret_cast<f32x4*>(dst + (g * 64 + lane) * 4));
             if (BWD && p.sdm) *reinterpret_cast<f32x4*>(p.sdm + bhc * 4096 + (32 * bj + l32) * 64 + 32 * bi + 8 * g + 4 * h) = v4;
         }
     }
@@ -398,7 +398,7 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
             Frag fr[SPB];
             pack_block<T>(acc, fr);
 #pragma unroll
-            for (int s = 0; s < SPB; ++s) dst[((size_t)bb * (D / KW) + ab * SPB + s) * 64 + lane] = fr[s];
+            for (int s = 0; s < SPB; ++s) __builtin_nontemporal_store(fr[s], &dst[((size_t)bb * (D / KW) + ab * SPB + s) * 64 + lane]);
         }
     }
     // (c) Kb tile (rows = key s, contraction = c): acc rows c, cols s;  Kb^T = K^T - W^T Y.
@@ -423,7 +423,7 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
             Frag fr[SPB];
             pack_block<T>(acc, fr);
 #pragma unroll
-            for (int s2 = 0; s2 < SPB; ++s2) kdst[((size_t)sb * (D / KW) + cb * SPB + s2) * 64 + lane] = fr[s2];
+            for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &kdst[((size_t)sb * (D / KW) + cb * SPB + s2) * 64 + lane]);
             if (BWD && p.kbm) {       // backward only: the same keys row-major [token][c]
                 typedef typename Tr<T>::Vec4 TVec4;
                 T* kb = reinterpret_cast<T*>(p.kbm) + (bhc * CHUNK + s) * (size_t)D + 32 * cb + 4 * h;
@@ -452,7 +452,7 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
                 f32x4 v4;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) v4[r] = (ok ? (float)q4[r] : 0.f) - acc[4 * g + r];
-                *reinterpret_cast<f32x4*>(xdst + (g * 64 + lane) * 4) = v4;
+                __builtin_nontemporal_store(v4, reinterpret_cast<f32x4*>(xdst + (g * 64 + lane) * 4));
             }
         }
         // (e) V^T tile (rows = c, contraction = key s): plain re-layout of V.
@@ -467,7 +467,7 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
             FragV fr[SPB];
             pack_block<TIO>(acc, fr);
 #pragma unroll
-            for (int s2 = 0; s2 < SPB; ++s2) vdst[(((size_t)sb * (D / 32) + cb) * SPB + s2) * 64 + lane] = fr[s2];   // [key half][d block][slab]
+            for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &vdst[(((size_t)sb * (D / 32) + cb) * SPB + s2) * 64 + lane]);   // [key half][d block][slab]
         }
         if (BWD && p.dpt) {
             // -dP in the transposed arrangement (rows c, contraction b) = -dP[c][b]: accumulate with rows b,
@@ -484,7 +484,7 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
                 Frag fr[SPB];
                 pack_block<T>(acc, fr);
 #pragma unroll
-                for (int s2 = 0; s2 < SPB; ++s2) pdst[((size_t)cb * (D / KW) + bb * SPB + s2) * 64 + lane] = fr[s2];
+                for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &pdst[((size_t)cb * (D / KW) + bb * SPB + s2) * 64 + lane]);
             }
         }
         if (BWD && p.ktT) {
@@ -507,7 +507,7 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
                 Frag fr[SPB];
                 pack_block<T>(acc, fr);
 #pragma unroll
-                for (int s2 = 0; s2 < SPB; ++s2) tdst[((size_t)cb * QS + sb * SPB + s2) * 64 + lane] = fr[s2];
+                for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &tdst[((size_t)cb * QS + sb * SPB + s2) * 64 + lane]);
             }
             // vk (rows s, contraction c) = V[s][c] (I/O type): registers rows c, lane s
             FragV* vkd = reinterpret_cast<FragV*>(reinterpret_cast<TIO*>(p.vk) + bhc * (size_t)CHUNK * D);
@@ -521,7 +521,7 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
                 FragV fr[SPB];
                 pack_block<TIO>(acc, fr);
 #pragma unroll
-                for (int s2 = 0; s2 < SPB; ++s2) vkd[((size_t)sb * (D / KW) + cb * SPB + s2) * 64 + lane] = fr[s2];
+                for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &vkd[((size_t)sb * (D / KW) + cb * SPB + s2) * 64 + lane]);
             }
         }
     }

@@ -88,8 +88,8 @@ __global__ __launch_bounds__(256) void bwd_dotile_kernel(BwdParams p) {
         pack_block<TIO>(b, fb);
 #pragma unroll
         for (int s = 0; s < SPB; ++s) {
-            dq[((size_t)qb * (D / KW) + cb * SPB + s) * 64 + lane] = fa[s];
-            dt[((size_t)cb * QS + qb * SPB + s) * 64 + lane] = fb[s];
+            __builtin_nontemporal_store(fa[s], &dq[((size_t)qb * (D / KW) + cb * SPB + s) * 64 + lane]);
+            __builtin_nontemporal_store(fb[s], &dt[((size_t)cb * QS + qb * SPB + s) * 64 + lane]);
         }
     }
 }
@@ -762,7 +762,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
             const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj)
-                p.ddp[((size_t)bh * NC + j) * D * D + (size_t)(32 * ab + acc_row(jj, h)) * D + 32 * bb + l32] = -ddPa[o][jj];
+                __builtin_nontemporal_store(-ddPa[o][jj], &p.ddp[((size_t)bh * NC + j) * D * D + (size_t)(32 * ab + acc_row(jj, h)) * D + 32 * bb + l32]);
         }
     }
     if (FAR) {

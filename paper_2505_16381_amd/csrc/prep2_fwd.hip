@@ -98,7 +98,7 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
             for (int idx = tid; idx < CHUNK * D / FE; idx += 256) k2[idx] = k1[idx];
             if (k2T) {
                 const Frag* k1T = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.ktT) + bhc * (size_t)CHUNK * D);
-                for (int idx = tid; idx < CHUNK * D / FE; idx += 256) k2T[idx] = k1T[idx];
+                for (int idx = tid; idx < CHUNK * D / FE; idx += 256) __builtin_nontemporal_store(k1T[idx], &k2T[idx]);
             }
         } else {
             // Kb2^T[cc][s] = Kb^T[cc][s] - sum_b E[cc][b] Kb[s][b]   (registers rows cc, lane s)
@@ -116,13 +116,13 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
                     for (int e = 0; e < FE; ++e) fr[s2][e] = (T)((float)kf[e] - acc[s2 * FE + e]);
                 }
 #pragma unroll
-                for (int s2 = 0; s2 < SPB; ++s2) k2[((size_t)sb2 * DS + cb * SPB + s2) * 64 + lane] = fr[s2];
+                for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &k2[((size_t)sb2 * DS + cb * SPB + s2) * 64 + lane]);
                 if (k2T) {     // backward only: the arrangement (rows cc, contraction s)
                     const f32x16 tr = transpose32<T>(fr, idf);      // rows s, lane cc
                     Frag ft[SPB];
                     pack_block<T>(tr, ft);
 #pragma unroll
-                    for (int s2 = 0; s2 < SPB; ++s2) k2T[((size_t)cb * (CHUNK / KW) + sb2 * SPB + s2) * 64 + lane] = ft[s2];
+                    for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(ft[s2], &k2T[((size_t)cb * (CHUNK / KW) + sb2 * SPB + s2) * 64 + lane]);
                 }
             }
         }
@@ -175,7 +175,7 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
                 Frag ng;
 #pragma unroll
                 for (int e = 0; e < FE; ++e) ng[e] = (T)(-(float)fin[s][e]);
-                dt[((size_t)ab * DS + bb * SPB + s) * 64 + lane] = ng;
+                __builtin_nontemporal_store(ng, &dt[((size_t)ab * DS + bb * SPB + s) * 64 + lane]);
             }
         }
         f32x16 tr = transpose32<T>(fin, idf);                   // rows a, lane b
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
         Frag fr[SPB];
         pack_block<T>(tr, fr);
 #pragma unroll
-        for (int s = 0; s < SPB; ++s) dst[((size_t)bb * DS + ab * SPB + s) * 64 + lane] = fr[s];
+        for (int s = 0; s < SPB; ++s) __builtin_nontemporal_store(fr[s], &dst[((size_t)bb * DS + ab * SPB + s) * 64 + lane]);
     }
 }
 

@@ -196,7 +196,7 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
         const size_t slot = ((size_t)bh * nslots + block_slot(cq, j, NC)) * (size_t)CHUNK * D;
         const Frag* xg = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + slot);
 #pragma unroll
-        for (int s = 0; s < DS; ++s) x[s] = xg[((size_t)qb * DS + s) * 64 + lane];
+        for (int s = 0; s < DS; ++s) x[s] = __builtin_nontemporal_load(&xg[((size_t)qb * DS + s) * 64 + lane]);     // read once: leave L2 to the key tiles
     };
     Frag Xnext[DS], Xb[DS];
 #pragma unroll

@@ -105,6 +105,8 @@ __global__ __launch_bounds__(256) void bwd_dotile_kernel(BwdParams p) {
 //     g^T <- g^T + Kb_j^T dS^T - dP_j g^T      A = ktT tile / dpt tile,  B = dS^T / g^T (registers)
 // After step j the state is also written, transposed through the matrix unit, as the tile
 // gT (rows b, contraction q) of pair (cq, j+1) for the key-side kernels.
+// This kernel runs fp32 operands (one workgroup per CU, one stage of tiles); 16-bit operands use
+// bwd_adjoint2_lite_kernel below (two workgroups per CU).
 template <typename TIO, int D> struct Adj2Cfg {
     typedef typename Compute<TIO>::type T;
     static constexpr int FE = Tr<T>::FE;
@@ -232,81 +234,7 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
         if (next_starts) load_x(j + 1, Xnext);
 
         Frag dSb[QS];
-        if (sizeof(T) == 2) {
-            // The two key halves, software-pipelined by hand: the element-wise part of one half is
-            // interleaved, element by element, with the products that follow it (one wave per SIMD:
-            // nothing else hides it).  The scheduling barriers and the empty asm statements keep the
-            // compiler from undoing the order.
-            f32x16 S0 = zero16(), dP0 = zero16(), S1 = zero16(), dP1 = zero16();
-            f32x4 ck0[4], ck1[4];
-            if (FOX) {      // gate sums of the 16 keys this lane holds (rows 8g + 4h + r of each 32-key block)
-                const float* ck = p.cum + (size_t)bh * Lp + (size_t)j * CHUNK + 4 * h;
-#pragma unroll
-                for (int g = 0; g < 4; ++g) { ck0[g] = *reinterpret_cast<const f32x4*>(ck + 8 * g); ck1[g] = *reinterpret_cast<const f32x4*>(ck + 32 + 8 * g); }
-            }
-            auto elem = [&](int jj, f32x16& S, const f32x16& dP, const f32x4* ck) {
-                float sv = S[jj], dv = dP[jj];
-                asm volatile("" : "+v"(sv), "+v"(dv));
-                const float arg = __builtin_fmaf(sv, sl2, -lse2) - (FOX ? ck[jj >> 2][jj & 3] : 0.f);
-                float ds = __builtin_amdgcn_exp2f(arg) * (dv - dl);      // scale * P * (dP - delta)
-                if (FOX) drow += ds;
-                asm volatile("" : "+v"(ds));
-                S[jj] = ds;
-            };
-            Frag ka[DS], ta[DB * SPB];
-            FragV va[DS];
-#pragma unroll
-            for (int u = 0; u < DS; ++u) { ka[u] = sK[u * 64 + lane]; va[u] = sV[u * 64 + lane]; }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < DS; ++u) {
-                S0 = Tr<T>::mma(ka[u], Xb[u], S0);
-                dP0 = Tr<TIO>::mma(va[u], dOb[u], dP0);
-            }
-            __builtin_amdgcn_sched_barrier(0);
-            if (spread) issue(j + 1, 1);
-            // logits and dP of key half 1  ||  element-wise part of half 0
-#pragma unroll
-            for (int u = 0; u < DS; ++u) { ka[u] = sK[(DS + u) * 64 + lane]; va[u] = sV[(DS + u) * 64 + lane]; }
-            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int u = 0; u < DS; ++u) {
-                S1 = Tr<T>::mma(ka[u], Xb[u], S1);
-                __builtin_amdgcn_sched_barrier(0);
-                if (2 * u < 16) elem(2 * u, S0, dP0, ck0);
-                __builtin_amdgcn_sched_barrier(0);
-                dP1 = Tr<TIO>::mma(va[u], dOb[u], dP1);
-                __builtin_amdgcn_sched_barrier(0);
-                if (2 * u + 1 < 16) elem(2 * u + 1, S0, dP0, ck0);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            if (DS < 8) {
-#pragma unroll
-                for (int jj = 2 * DS; jj < 16; ++jj) elem(jj, S0, dP0, ck0);
-            }
-            pack_block<T>(S0, dSb);
-            if (spread) issue(j + 1, 2);
-            // g^T += Kb^T dS^T, keys of half 0  ||  element-wise part of half 1
-#pragma unroll
-            for (int u = 0; u < DB * SPB; ++u) ta[u] = sKT[((u / SPB) * QS + u % SPB) * 64 + lane];
-            __builtin_amdgcn_sched_barrier(0);
-            constexpr int EPM = 16 / (DB * SPB);       // elements per product
-#pragma unroll
-            for (int u = 0; u < DB * SPB; ++u) {
-                Gm[u / SPB] = Tr<T>::mma(ta[u], dSb[u % SPB], Gm[u / SPB]);
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int e = 0; e < EPM; ++e) elem(EPM * u + e, S1, dP1, ck1);
-                __builtin_amdgcn_sched_barrier(0);
-            }
-            pack_block<T>(S1, dSb + SPB);
-            if (spread) issue(j + 1, 3);
-            // ... keys of half 1
-#pragma unroll
-            for (int u = 0; u < DB * SPB; ++u) ta[u] = sKT[((u / SPB) * QS + SPB + u % SPB) * 64 + lane];
-#pragma unroll
-            for (int u = 0; u < DB * SPB; ++u) Gm[u / SPB] = Tr<T>::mma(ta[u], dSb[SPB + u % SPB], Gm[u / SPB]);
-        } else {
+        {
     #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
                 f32x16 S = zero16(), dP = zero16();
@@ -383,6 +311,176 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
         if (h == 0) p.drow[(size_t)bh * Lp + tq] = drow / p.scale;      // the sums above carry the factor scale
     }
     // dQb of the wave's queries: row-major fp32 [q][c] from registers (rows c, lane q)
+    if (active) {
+        float* dst = p.dqb + ((size_t)bh * Lp + tq) * D + 4 * h;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 v4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v4[r] = Gm[b][4 * g + r];
+                *reinterpret_cast<f32x4*>(dst + 32 * b + 8 * g) = v4;
+            }
+    }
+}
+
+// ---------------------------------------------------------------------------------------
+// The adjoint scan for 16-bit operands with TWO workgroups per CU: the same arithmetic as
+// bwd_adjoint2_kernel, arranged to fit 256 registers per wave and one 80 KB stage per workgroup, so that
+// the second workgroup's waves fill the gaps of the first (tile requests, LDS latencies, the dependent
+// chain logits -> exponentials -> update) instead of hand-interleaved halves of one wave.  Per step: one
+// request for the chunk's four tiles, no prefetch; the state fragments of a new block are fetched while
+// those tiles are on their way; the operand copy of g exists only while a block boundary needs it.
+template <typename TIO, int D, bool FOX>
+__global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) {
+    using C = Adj2Cfg<TIO, D>;
+    using T = typename C::T;
+    using Frag = typename Tr<T>::Frag;
+    using FragV = typename Tr<TIO>::Frag;
+    static_assert(sizeof(T) == 2, "16-bit operands");
+    constexpr int KW = Tr<T>::KW, SPB = 32 / KW, DB = D / 32, DS = D / KW, QS = CHUNK / KW;
+    constexpr int KVF = C::KV_FRAGS, DPF = C::DP_FRAGS;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    Frag* sK = reinterpret_cast<Frag*>(smem);
+    const FragV* sV = reinterpret_cast<const FragV*>(sK + KVF);
+    const Frag* sKT = sK + 2 * KVF;
+    const Frag* sDP = sK + 3 * KVF;
+
+    const int BH = p.B * p.H, NC = p.NC;
+    const int ntiles = (NC + 1) / 2;
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;        // numbering as in bwd_adjoint2_kernel
+    const int bh = (slot / ntiles) * 8 + xcd;
+    const int tile = ntiles - 1 - slot % ntiles;
+    if (bh >= BH) return;
+    const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
+    const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
+    const bool active = cq < NC;
+    const int jmax = ((tile * 2 + 1 < NC) ? tile * 2 + 1 : NC - 1) - 1;
+    const int jsb = (tile * 2 / SBC) * SBC;
+    const size_t Lp = (size_t)NC * CHUNK, nslots = num_block_slots(NC);
+    const float sl2 = p.scale * 1.44269504088896340736f;
+    const int tq = cq * CHUNK + 32 * qb + l32;
+    const int nsb = (NC + SBC - 1) / SBC;
+
+    FragV dOb[DS];
+    float lse2 = 0.f, dl = 0.f, drow = 0.f;
+    if (active) {
+        const FragV* dq = reinterpret_cast<const FragV*>(reinterpret_cast<const TIO*>(p.doq) + ((size_t)bh * NC + cq) * CHUNK * D);
+#pragma unroll
+        for (int s = 0; s < DS; ++s) dOb[s] = dq[((size_t)qb * DS + s) * 64 + lane];
+        lse2 = p.lse2p[(size_t)bh * Lp + tq] - __builtin_log2f(p.scale);     // the exponential then yields scale * P
+        dl = p.delta[(size_t)bh * Lp + tq];
+    }
+    f32x16 Gm[DB];
+    Frag Xb[DS];
+#pragma unroll
+    for (int b = 0; b < DB; ++b) Gm[b] = zero16();
+#pragma unroll
+    for (int s = 0; s < DS; ++s) Xb[s] = Tr<T>::zero();
+    auto block_start = [&](int j) { return j >= jsb || j % SBC == 0; };
+
+    for (int j = 0; j <= jmax; ++j) {
+        const bool far = j < jsb;
+        const bool mine = active && j < cq;
+        const bool first = block_start(j);
+        __syncthreads();                           // everyone is done with the previous chunk's tiles
+        {
+            const size_t bhc = (size_t)bh * NC + j;
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2 : p.kt) + bhc * CHUNK * D), sK, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), sK + KVF, tid, wv);
+            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2T : p.ktT) + bhc * CHUNK * D), sK + 2 * KVF, tid, wv);
+            if (j > 0 && first) {
+                const T* src = far ? reinterpret_cast<const T*>(p.dpt2) + ((size_t)bh * nsb + j / SBC) * (size_t)D * D
+                                   : reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D;
+                async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(src), sK + 3 * KVF, tid, wv);
+            }
+        }
+        if (mine && first) {                       // the state of the block that starts here
+            const size_t xslot = ((size_t)bh * nslots + block_slot(cq, j, NC)) * (size_t)CHUNK * D;
+            const Frag* xg = reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(p.xs) + xslot);
+#pragma unroll
+            for (int s = 0; s < DS; ++s) Xb[s] = __builtin_nontemporal_load(&xg[((size_t)qb * DS + s) * 64 + lane]);
+        }
+        wait_async_and_sync();
+        if (!mine) continue;
+
+        if (j > 0 && first) {                      // g <- g (I - dP_blk)^T: the product with the state before this step
+            Frag Gb[DS];
+#pragma unroll
+            for (int b = 0; b < DB; ++b) pack_block<T>(Gm[b], Gb + b * SPB);
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+                for (int s0 = 0; s0 < DS; s0 += 4) {
+                    Frag pa[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) pa[u] = sDP[(b * DS + s0 + u) * 64 + lane];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) Gm[b] = Tr<T>::mma(pa[u], Gb[s0 + u], Gm[b]);
+                }
+        }
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb) {
+            f32x16 S = zero16(), dP = zero16();
+#pragma unroll
+            for (int s0 = 0; s0 < DS; s0 += 2) {
+                Frag ka[2];
+                FragV va[2];
+#pragma unroll
+                for (int u = 0; u < 2; ++u) { ka[u] = sK[(kb * DS + s0 + u) * 64 + lane]; va[u] = sV[(kb * DS + s0 + u) * 64 + lane]; }
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    S = Tr<T>::mma(ka[u], Xb[s0 + u], S);
+                    dP = Tr<TIO>::mma(va[u], dOb[s0 + u], dP);
+                }
+            }
+            f32x4 ck4[4];
+            if (FOX) {      // gate sums of the 16 keys this lane holds (rows 8g + 4h + r of the 32-key block)
+                const float* ck = p.cum + (size_t)bh * Lp + (size_t)j * CHUNK + 32 * kb + 4 * h;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) ck4[g] = *reinterpret_cast<const f32x4*>(ck + 8 * g);
+            }
+#pragma unroll
+            for (int jj = 0; jj < 16; ++jj) {
+                const float arg = __builtin_fmaf(S[jj], sl2, -lse2) - (FOX ? ck4[jj >> 2][jj & 3] : 0.f);
+                const float ds = __builtin_amdgcn_exp2f(arg) * (dP[jj] - dl);      // scale * P * (dP - delta)
+                if (FOX) drow += ds;
+                S[jj] = ds;
+            }
+            Frag dSh[SPB];
+            pack_block<T>(S, dSh);
+            // g^T += Kb^T dS^T, the 32 keys of this half
+#pragma unroll
+            for (int b = 0; b < DB; ++b) {
+                Frag ta[SPB];
+#pragma unroll
+                for (int u = 0; u < SPB; ++u) ta[u] = sKT[(b * QS + kb * SPB + u) * 64 + lane];
+#pragma unroll
+                for (int u = 0; u < SPB; ++u) Gm[b] = Tr<T>::mma(ta[u], dSh[u], Gm[b]);
+            }
+        }
+        if (j + 1 < cq && block_start(j + 1)) {    // g after this block: tile gT (rows b, contraction q) of the pair (cq, next block)
+            Frag idf[SPB];
+            identity_frags<T>(idf, l32, h);
+            const size_t slot2 = ((size_t)bh * nslots + block_slot(cq, j + 1, NC)) * (size_t)CHUNK * D;
+            Frag* gt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.gs) + slot2);
+#pragma unroll
+            for (int b = 0; b < DB; ++b) {
+                Frag gb[SPB];
+                pack_block<T>(Gm[b], gb);
+                const f32x16 tr = transpose32<T>(gb, idf);       // rows q, lane b
+                Frag fr[SPB];
+                pack_block<T>(tr, fr);
+#pragma unroll
+                for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &gt[((size_t)b * QS + qb * SPB + s2) * 64 + lane]);
+            }
+        }
+    }
+    if (FOX && active) {
+        drow += __shfl_xor(drow, 32);
+        if (h == 0) p.drow[(size_t)bh * Lp + tq] = drow / p.scale;
+    }
     if (active) {
         float* dst = p.dqb + ((size_t)bh * Lp + tq) * D + 4 * h;
 #pragma unroll
@@ -1182,8 +1280,14 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     const dim3 grid_adj((unsigned)(8 * ((BH + 7) / 8) * ntiles));
     const dim3 grid_key((unsigned)(8 * ((BH + 7) / 8) * nsb * SBC)), grid_key_far((unsigned)(8 * ((BH + 7) / 8) * nsb * (SBC / 2)));
     if (p.cum) {       // PaTH-FoX instantiations
+        if constexpr (sizeof(typename Compute<TIO>::type) == 2) {
+            const size_t lite_bytes = (size_t)Adj2Cfg<TIO, D>::STAGE_FRAGS * 16;
+            if ((e = set_smem(&bwd_adjoint2_lite_kernel<TIO, D, true>, lite_bytes)) != hipSuccess) return e;
+            hipLaunchKernelGGL((bwd_adjoint2_lite_kernel<TIO, D, true>), grid_adj, dim3(256), lite_bytes, st, p);
+        } else {
         if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D, true>, adj_bytes)) != hipSuccess) return e;
         hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D, true>), grid_adj, dim3(256), adj_bytes, st, p);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, false, true>, key_bytes)) != hipSuccess) return e;
         if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, true, true>, key_bytes)) != hipSuccess) return e;
@@ -1192,8 +1296,14 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
         hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, true, true>), grid_key_far, dim3(256), key_bytes, st, p);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     } else {
+        if constexpr (sizeof(typename Compute<TIO>::type) == 2) {
+            const size_t lite_bytes = (size_t)Adj2Cfg<TIO, D>::STAGE_FRAGS * 16;
+            if ((e = set_smem(&bwd_adjoint2_lite_kernel<TIO, D, false>, lite_bytes)) != hipSuccess) return e;
+            hipLaunchKernelGGL((bwd_adjoint2_lite_kernel<TIO, D, false>), grid_adj, dim3(256), lite_bytes, st, p);
+        } else {
         if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D, false>, adj_bytes)) != hipSuccess) return e;
         hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D, false>), grid_adj, dim3(256), adj_bytes, st, p);
+        }
         if ((e = hipGetLastError()) != hipSuccess) return e;
         if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, false, false>, key_bytes)) != hipSuccess) return e;
         if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, true, false>, key_bytes)) != hipSuccess) return e;

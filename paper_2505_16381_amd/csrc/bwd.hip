@@ -816,34 +816,42 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
                     // The wave's ddP blocks wv, wv + 4, ... all lie in column block bb of g (d = 128: one per row
                     // block b; d = 64: the single block (wv / 2, wv % 2)), whose fragments are read once too.
                     static_assert(DB == 4 || DB == 2, "block ownership below");
+                    // The wave's own query half comes first, the other one second, both by address (qh is uniform over
+                    // the wave): no selects between registers.  Chunk 0 has no transform to the left of it: its sums
+                    // are taken like the others (its adjoint-state tile is valid memory, whatever it holds) and
+                    // written as zeros at the end -- a test here would put the accumulators behind a branch, and
+                    // the compiler then copies them between the register files around every product.
                     const Frag* sG = sX + 3 * KVF;
                     const int bb = DB == 4 ? wv : (wv & 1);
-                    const bool with_ddp = j >= 1;          // chunk 0 has no transform to the left of it
-                    Frag fb[QS];
+                    const int own = qh * SPB, oth = (1 - qh) * SPB;
+                    Frag fbo[SPB], fbx[SPB];
 #pragma unroll
-                    for (int s = 0; s < QS; ++s) fb[s] = with_ddp ? sG[(bb * QS + s) * 64 + lane] : Tr<T>::zero();
+                    for (int u = 0; u < SPB; ++u) { fbo[u] = sG[(bb * QS + own + u) * 64 + lane]; fbx[u] = sG[(bb * QS + oth + u) * 64 + lane]; }
 #pragma unroll
                     for (int b = 0; b < DB; ++b) {
-                        Frag fa[QS];
+                        Frag fo[SPB], fx[SPB];
                         FragV ta[SPB];
 #pragma unroll
-                        for (int s = 0; s < QS; ++s) fa[s] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sX), s, b, l32, h);
-#pragma unroll
-                        for (int u = 0; u < SPB; ++u) ta[u] = ld_tile_frag_tr<TIO, DS>(reinterpret_cast<const TIO*>(sDQ), qh * SPB + u, b, l32, h);
+                        for (int u = 0; u < SPB; ++u) {
+                            fo[u] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sX), own + u, b, l32, h);
+                            fx[u] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sX), oth + u, b, l32, h);
+                            ta[u] = ld_tile_frag_tr<TIO, DS>(reinterpret_cast<const TIO*>(sDQ), own + u, b, l32, h);
+                        }
 #pragma unroll
                         for (int u = 0; u < SPB; ++u) {
-                            Frag tb = fa[u];
-                            if (qh) tb = fa[SPB + u];
                             dVt[b] = Tr<TIO>::mma(ta[u], Pb[u], dVt[b]);
-                            dKt[b] = Tr<T>::mma(tb, dSb[u], dKt[b]);
+                            dKt[b] = Tr<T>::mma(fo[u], dSb[u], dKt[b]);
                         }
-                        if (with_ddp && (DB == 4 || b == (wv >> 1))) {
+                        if (DB == 4 || b == (wv >> 1)) {
                             constexpr int NO = DB == 4 ? DB : 1;
 #pragma unroll
                             for (int o = 0; o < NO; ++o)
                                 if (DB != 4 || o == b) {
 #pragma unroll
-                                    for (int s = 0; s < QS; ++s) ddPa[o] = Tr<T>::mma(fa[s], fb[s], ddPa[o]);
+                                    for (int u = 0; u < SPB; ++u) {
+                                        ddPa[o] = Tr<T>::mma(fo[u], fbo[u], ddPa[o]);
+                                        ddPa[o] = Tr<T>::mma(fx[u], fbx[u], ddPa[o]);
+                                    }
                                 }
                         }
                     }
@@ -860,7 +868,7 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
             const int blk = wv + 4 * o, ab = blk / DB, bb = blk % DB;
 #pragma unroll
             for (int jj = 0; jj < 16; ++jj)
-                __builtin_nontemporal_store(-ddPa[o][jj], &p.ddp[((size_t)bh * NC + j) * D * D + (size_t)(32 * ab + acc_row(jj, h)) * D + 32 * bb + l32]);
+                __builtin_nontemporal_store(j >= 1 ? -ddPa[o][jj] : 0.f, &p.ddp[((size_t)bh * NC + j) * D * D + (size_t)(32 * ab + acc_row(jj, h)) * D + 32 * bb + l32]);
         }
     }
     if (FAR) {

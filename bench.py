@@ -308,7 +308,7 @@ def main():
                              "traffic = HBM bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE "
                              "(profiles/fwd_bwd_headline_L8192_d128_hbm_traffic.txt): 2.42e9 in + 2.10e9 out, of which "
                              "1.96e9 are the query states kept for the backward; the forward alone needs 1.2e9 "
-                             "(the stand-alone forward's sweep, without that output: 1.4 ms, frac 0.31, same profile)"},
+                             "(the stand-alone forward's sweep, without that output: 1.4-1.5 ms, frac 0.29-0.31, same profile)"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, cfg, scale)

@@ -63,7 +63,7 @@ NAMES = ("dq", "dk", "dv", "dw", "dbeta", "dlogf")
 
 
 @pytest.mark.parametrize("dtype,L,d", [("fp32", 64, 64), ("fp32", 200, 128), ("fp32", 1100, 64), ("bf16", 300, 64),
-                                       ("bf16", 1030, 128)])
+                                       ("bf16", 1030, 128), ("fp32", 2200, 64), ("bf16", 3100, 128)])
 def test_fox_backward_matches_the_oracle(gpu, oracle, dtype, L, d):
     torch, pa = gpu
     x = _inputs(1, 2, L, d, dtype, 1400 + L + d)
@@ -83,3 +83,35 @@ def test_fox_backward_matches_the_oracle(gpu, oracle, dtype, L, d):
     print(f"[fox bwd {dtype} L={L} d={d}] rel err " + " ".join(msg), flush=True)
     assert worst <= (1e-4 if dtype == "fp32" else 2e-2), msg
     assert float(got[5][:, :, 0].abs().max()) == 0.0
+
+
+def test_fox_headline_shape_sampled_head(gpu, oracle):
+    """PaTH-FoX at the shape bench.py times (B=4, H=16, L=8192, d=128, bf16; eight super-blocks, every
+    key-side and scan kernel in its FoX instantiation at full grid size): the whole batch runs on the
+    GPU, one head is checked against the oracle, forward and backward."""
+    torch, pa = gpu
+    B, H, L, d = 4, 16, 8192, 128
+    x = _inputs(B, H, L, d, "bf16", 1500)
+    dv = _dev(gpu, x, "bf16")
+    scale = d ** -0.5
+    o, lse = pa.path_attn_fox_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], dv["logf"], scale=scale)
+    got = pa.path_attn_fox_bwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], dv["logf"], o, lse, dv["dO"], scale=scale)
+    torch.cuda.synchronize()
+    head = 29
+    sel = lambda a: np.ascontiguousarray(a.reshape((B * H,) + a.shape[2:])[head][None, None])
+    xs = {n: sel(a) for n, a in x.items()}
+    o_ref, lse_ref = oracle.fwd(xs["q"], xs["k"], xs["v"], xs["w"], xs["beta"], scale, logf=xs["logf"])
+    eo = np.abs(sel(o.float().cpu().numpy()) - o_ref).max()
+    el = np.abs(sel(lse.cpu().numpy()) - lse_ref).max()
+    print(f"[fox headline fwd] max|do|={eo:.2e} max|dlse|={el:.2e}", flush=True)
+    assert eo <= 2e-2 and el <= 1e-3
+    ref = oracle.bwd(xs["q"], xs["k"], xs["v"], xs["w"], xs["beta"], xs["dO"], scale, logf=xs["logf"])
+    msg, worst = [], 0.0
+    for n, g, r in zip(NAMES, got, ref):
+        g = sel(g.float().cpu().numpy()).astype(np.float64)
+        assert np.isfinite(g).all(), n
+        e = np.abs(g - r).max() / max(np.abs(r).max(), 1e-2)
+        msg.append(f"{n}={e:.2e}")
+        worst = max(worst, e)
+    print("[fox headline bwd] rel err " + " ".join(msg), flush=True)
+    assert worst <= 2e-2, msg

@@ -71,8 +71,10 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     const int ntiles = (NC + FWD2_CPT - 1) / FWD2_CPT;
     // XCD-aware numbering: workgroup b runs on XCD b % 8; that XCD takes heads xcd, xcd+8, ...
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int bh = (slot / ntiles) * 8 + xcd;
-    const int tile = ntiles - 1 - slot % ntiles;
+    // (the division runs on the vector unit; its result, uniform over the workgroup, goes back to scalar
+    // registers, so that everything derived from it -- loop bounds, tile addresses -- is scalar arithmetic)
+    const int bh = __builtin_amdgcn_readfirstlane((slot / ntiles) * 8 + xcd);
+    const int tile = __builtin_amdgcn_readfirstlane(ntiles - 1 - slot % ntiles);
     if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
 

@@ -135,8 +135,8 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     // after the other, all tiles of a head together (heaviest first).  They walk the key chunks
     // from 0 upwards at the same pace, so each tile is fetched once per head into that XCD's L2.
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
-    const int bh = (slot / ntiles) * 8 + xcd;
-    const int tile = ntiles - 1 - slot % ntiles;
+    const int bh = __builtin_amdgcn_readfirstlane((slot / ntiles) * 8 + xcd);        // (divisions run on the vector unit:
+    const int tile = __builtin_amdgcn_readfirstlane(ntiles - 1 - slot % ntiles);     // back to scalar registers)
     if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
@@ -350,8 +350,8 @@ __global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) 
     const int BH = p.B * p.H, NC = p.NC;
     const int ntiles = (NC + 1) / 2;
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;        // numbering as in bwd_adjoint2_kernel
-    const int bh = (slot / ntiles) * 8 + xcd;
-    const int tile = ntiles - 1 - slot % ntiles;
+    const int bh = __builtin_amdgcn_readfirstlane((slot / ntiles) * 8 + xcd);        // (divisions run on the vector unit:
+    const int tile = __builtin_amdgcn_readfirstlane(ntiles - 1 - slot % ntiles);     // back to scalar registers)
     if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
@@ -566,8 +566,9 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     const int L = p.L, NC = p.NC;
     const int nsb_g = (NC + SBC - 1) / SBC;
     const int xcd = blockIdx.x & 7, kk = blockIdx.x >> 3;
-    const int j = (kk / NPOS % nsb_g) * SBC + (kk % NPOS) * CPW;       // first key chunk of the workgroup
-    const int bh = (kk / (NPOS * nsb_g)) * 8 + xcd;
+    // (the divisions run on the vector unit; their results go back to scalar registers)
+    const int j = __builtin_amdgcn_readfirstlane((kk / NPOS % nsb_g) * SBC + (kk % NPOS) * CPW);       // first key chunk of the workgroup
+    const int bh = __builtin_amdgcn_readfirstlane((kk / (NPOS * nsb_g)) * 8 + xcd);
     if (bh >= p.B * p.H || j >= NC) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int kh = wv & 1;

@@ -32,8 +32,9 @@ __global__ __launch_bounds__(256) void bwd_states_kernel(FwdParams p) {
 
     const int BH = p.B * p.H, NC = p.NC;
     const int ntiles = (NC + 1) / 2;
-    const int tile = ntiles - 1 - (int)(blockIdx.x / BH);      // heaviest (right-most) tiles first
-    const int bh = blockIdx.x % BH;
+    // (divisions run on the vector unit; the results, uniform over the workgroup, go back to scalar registers)
+    const int tile = __builtin_amdgcn_readfirstlane(ntiles - 1 - (int)(blockIdx.x / BH));      // heaviest (right-most) tiles first
+    const int bh = __builtin_amdgcn_readfirstlane((int)(blockIdx.x % BH));
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
     const bool active = cq < NC;

@@ -25,7 +25,7 @@ if ROOT not in sys.path:
 
 METRIC = "PaTH attn fwd+bwd TFLOP/s and % bf16 MFMA peak at B=4,H=16,L=8192,d=128"
 PEAK_TFLOPS = 2500.0      # MI355X dense bf16/fp16 MFMA
-SWEEP_HBM_BYTES = 4.52e9  # measured HBM traffic of one launch of the pair's sweep at the headline shape (see profiles/)
+SWEEP_HBM_BYTES = 4.69e9  # measured HBM traffic of one launch of the pair's sweep at the headline shape (see profiles/)
 CHUNK = 64
 
 
@@ -306,7 +306,7 @@ def main():
                      "traffic": SWEEP_HBM_BYTES if (args.config == 2 and not args.shape) else None,
                      "note": "achieved = attention-equivalent flops of the launch / HIP-event time of the sweep kernel; "
                              "traffic = HBM bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE "
-                             "(profiles/fwd_bwd_headline_L8192_d128_hbm_traffic.txt): 2.42e9 in + 2.10e9 out, of which "
+                             "(profiles/fwd_bwd_headline_L8192_d128_hbm_traffic.txt): 2.57e9 in + 2.12e9 out (the fetched bytes vary between runs, 2.4-2.6e9), of which "
                              "1.96e9 are the query states kept for the backward; the forward alone needs 1.2e9 "
                              "(the stand-alone forward's sweep, without that output: 1.4-1.5 ms, frac 0.29-0.31, same profile)"},
     }

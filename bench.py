@@ -44,7 +44,7 @@ def path_extra_flops(B, H, L, d):
     return (prep + upd) * B * H
 
 
-def cpu_baseline(x, cfg, scale, n_rows=3072):
+def cpu_baseline(x, cfg, scale, n_rows=6144):
     """The fp64 oracle, as it stands, on a bounded row sample of the same workload."""
     import numpy as np
     from oracle import path_oracle

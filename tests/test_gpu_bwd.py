@@ -110,13 +110,18 @@ def test_bwd_gradient_identities_on_gpu(gpu):
 
 
 def test_config3_backward_full_shape_sampled_heads(gpu, oracle):
-    """Full benchmark shape on the GPU; the oracle (not row-separable) on a sample of heads."""
+    """Full benchmark shape on the GPU; the oracle (not row-separable) on a sample of heads: both ends and
+    every residue of the head index modulo 8 (the kernels number their workgroups per XCD, head = 8 * slot +
+    xcd) twice over."""
     x, c = si.make_config(3)
-    _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, heads=[0, 37, 127], tag="cfg3")
+    heads = [0, 1, 10, 19, 28, 37, 46, 55, 64, 73, 82, 91, 100, 109, 118, 127]
+    assert sorted(h % 8 for h in heads) == sorted(list(range(8)) * 2)
+    _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, heads=heads, tag="cfg3")
 
 
 def test_headline_shape_backward_sampled_head(gpu, oracle):
     """The shape and launch configuration bench.py times (B=4, H=16, L=8192, d=128, bf16):
-    the whole batch runs on the GPU, one head is checked against the oracle."""
+    the whole batch runs on the GPU, five heads (first, last, three residues modulo 8 in between) are checked
+    against the oracle."""
     x, c = si.make_config(2, with_do=True)
-    _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, heads=[41], tag="headline shape")
+    _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, heads=[0, 13, 41, 50, 63], tag="headline shape")

@@ -49,14 +49,18 @@ def test_fox_forward_matches_the_oracle(gpu, oracle, dtype, L, d):
     assert eo <= (1e-4 if dtype == "fp32" else 2e-2) and el <= 1e-3
 
 
-def test_unit_gates_reproduce_plain_path_bit_for_bit_in_o(gpu):
+def test_unit_gates_reproduce_plain_path(gpu):
+    """log f = 0 everywhere: the gated kernel subtracts a zero gate sum from the base-2 logit in a step of its
+    own (two roundings in the exponent where the plain kernel's fused multiply-add has one), so o may differ from
+    plain PaTH's by a rounding step of the bf16 result (2^-6 for |o| in [2,4)) and lse by a few fp32 steps --
+    not bit for bit, and not more."""
     torch, pa = gpu
     x = _inputs(1, 2, 500, 64, "bf16", 1300)
     dv = _dev(gpu, x, "bf16")
     zero = torch.zeros_like(dv["logf"])
     o1, l1 = pa.path_attn_fox_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], zero, scale=0.125)
     o0, l0 = pa.path_attn_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], scale=0.125)
-    assert float((o1.float() - o0.float()).abs().max()) <= 2e-2 and float((l1 - l0).abs().max()) <= 1e-5
+    assert float((o1.float() - o0.float()).abs().max()) <= 2.0 ** -6 and float((l1 - l0).abs().max()) <= 1e-5
 
 
 NAMES = ("dq", "dk", "dv", "dw", "dbeta", "dlogf")

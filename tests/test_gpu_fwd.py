@@ -171,17 +171,21 @@ def test_config1_bf16_full_and_beta_zero(gpu, oracle):
 
 
 def _sample_rows(L, n, seed):
+    """Seeded sample of query rows: the last 64 (longest products), random ones, the first chunk boundaries and
+    the three rows around EVERY super-block boundary (multiples of 1024 tokens: last row that has no far block
+    to its left in the new super-block, first row of it, and the one after)."""
     rng = np.random.default_rng(seed)
-    return np.unique(np.concatenate([np.arange(L - 64, L), rng.integers(0, L, n), [0, 1, 63, 64, 65, 127, 128]]))
+    edges = np.concatenate([[s - 1, s, s + 1] for s in range(1024, L, 1024)]) if L > 1024 else np.zeros(0, int)
+    return np.unique(np.concatenate([np.arange(L - 64, L), rng.integers(0, L, n), [0, 1, 63, 64, 65, 127, 128], edges]).astype(int))
 
 
 def test_config2_headline_sampled_rows(gpu, oracle):
     x, c = si.make_config(2)
-    rows = _sample_rows(c["L"], 48, 7)
+    rows = _sample_rows(c["L"], 200, 7)
     _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, rows=rows, tag="cfg2")
 
 
 def test_config4_long_context_sampled_rows(gpu, oracle):
     x, c = si.make_config(4)
-    rows = _sample_rows(c["L"], 32, 8)
+    rows = _sample_rows(c["L"], 130, 8)
     _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, rows=rows, tag="cfg4")

@@ -86,3 +86,41 @@ def test_last_key_enters_untouched_and_order_of_transitions_matters():
         wt = x["w"][b, h, t].astype(np.float64)
         u2 = (np.eye(5) - float(x["beta"][b, h, t]) * np.outer(wt, wt)) @ u2
     assert np.abs(u2 - u).max() > 1e-3
+
+
+def test_round_cache_hook_rounds_what_is_stored_and_what_is_used():
+    # The hook models a cache kept in a narrower type.  Pinned against the un-hooked step (itself pinned
+    # above) and against plain softmax attention written out here: (1) it is called once per step, on the
+    # refreshed keys with the arriving key appended, i.e. on exactly what the un-hooked step returns;
+    # (2) what the step returns as the new cache is the hook's result, a fixed point of the rounding;
+    # (3) the logits use the ROUNDED keys -- o and lse equal softmax attention over the returned cache,
+    # and differ from the un-hooked step's; (4) an identity hook changes nothing; (5) with beta = 0 and
+    # keys that the narrow type holds exactly, rounding is invisible.
+    x = _x(L=14, d=8, seed=33)
+    scale = 0.4
+    rnd = lambda a: si.round_to_bf16(a.astype(np.float32)).astype(np.float64)
+    n = 9
+    kc0 = dec.key_prefill(x["k"][:, :, :n], x["w"][:, :, :n], x["beta"][:, :, :n])
+    vc0 = x["v"][:, :, :n].astype(np.float64)
+    a = (x["q"][:, :, n], x["k"][:, :, n], x["v"][:, :, n], x["w"][:, :, n], x["beta"][:, :, n])
+    o_plain, lse_plain, kc_plain, vc_plain = dec.decode_step(*a, kc0, vc0, scale)
+    seen = []
+    def hook(k):
+        seen.append(k.copy())
+        return rnd(k)
+    o_r, lse_r, kc_r, vc_r = dec.decode_step(*a, kc0, vc0, scale, round_cache=hook)
+    assert len(seen) == 1 and np.array_equal(seen[0], kc_plain)                       # (1)
+    assert np.array_equal(kc_r, rnd(kc_plain)) and np.array_equal(rnd(kc_r), kc_r)    # (2)
+    assert np.array_equal(vc_r, vc_plain)                                             # values are not touched
+    s = scale * np.einsum("bhnd,bhd->bhn", kc_r, a[0].astype(np.float64))             # (3)
+    p = np.exp(s - s.max(-1, keepdims=True)); z = p.sum(-1, keepdims=True)
+    assert np.abs(np.einsum("bhn,bhnd->bhd", p / z, vc_r) - o_r).max() <= 1e-14
+    assert np.abs(np.log(z[..., 0]) + s.max(-1) - lse_r).max() <= 1e-14
+    assert np.abs(o_r - o_plain).max() > 1e-5                                         # the rounding is visible
+    o_i, lse_i, kc_i, _ = dec.decode_step(*a, kc0, vc0, scale, round_cache=lambda k: k)   # (4)
+    assert np.array_equal(o_i, o_plain) and np.array_equal(lse_i, lse_plain) and np.array_equal(kc_i, kc_plain)
+    kb = rnd(x["k"][:, :, :n + 1].astype(np.float64))                                 # (5)
+    zero = np.zeros_like(x["beta"][:, :, n])
+    o5, l5, k5, _ = dec.decode_step(a[0], kb[:, :, n], a[2], a[3], zero, kb[:, :, :n], vc0, scale, round_cache=rnd)
+    o6, l6, k6, _ = dec.decode_step(a[0], kb[:, :, n], a[2], a[3], zero, kb[:, :, :n], vc0, scale)
+    assert np.array_equal(o5, o6) and np.array_equal(l5, l6) and np.array_equal(k5, k6)

@@ -23,8 +23,24 @@
  *    token and per head.  No grouped-query sharing.
  *  - dtype `dt` is the storage type of q,k,v,w,beta,o and of all gradients
  *    (PATH_F32: float, PATH_BF16: bfloat16).  lse is always float.
- *    PATH_BF16 contracts on bf16 MFMA with fp32 accumulation; PATH_F32
- *    contracts on fp32 MFMA.
+ *  - Arithmetic.  PATH_F32 contracts on fp32 MFMA throughout.  PATH_BF16 accumulates
+ *    in fp32 and contracts on 16-bit MFMA with TWO operand types: the softmax
+ *    probabilities, the values and d_o are bf16 operands; everything the method
+ *    TRANSPORTS -- the query state, the boundary-adjusted keys, the chunk products
+ *    I - P, the matrices inside the chunk transform, and in the backward the
+ *    gradients of the query state and of the chunk products -- are fp16 operands
+ *    (11-bit significand: bf16's 8 bits there put the log-sum-exp 1e-3 .. 3e-3
+ *    off; same MFMA rate).
+ *  - Range rule for PATH_BF16 (a consequence of the fp16 operands; fp16 ends at
+ *    65504, no status code reports a violation): the transitions are contractions
+ *    for beta in [0,2], |w| <= 1, so every transported quantity is bounded by the
+ *    Euclidean norms of the rows of q and k -- those norms must stay below 65504;
+ *    in the backward the state gradients are bounded by
+ *    scale * L * max|d_o| * max|v| * max_row|k| and must stay below it too.  Beyond
+ *    the bound (or for beta, w outside those ranges, where products can grow with
+ *    L) results are UNDEFINED: infinities or NaNs may appear in any output, never
+ *    a fault.  Magnitudes below 6e-8 (fp16's smallest subnormal) flush to zero in
+ *    the transported operands.  PATH_F32 has fp32's range throughout.
  *  - d must be 64 or 128; any L >= 1 (a ragged last chunk is handled inside).
  *  - `scale` multiplies the finished bilinear form (the paper's logits are
  *    unscaled: pass 1.0f for those); it must be > 0 (else PATH_ERR_UNSUPPORTED).
@@ -39,6 +55,15 @@
  *  - Errors are reported by return code before anything is launched (bad
  *    arguments) or after a failed launch (PATH_ERR_HIP); the library never
  *    aborts or throws.  Outputs are fully overwritten on PATH_OK.
+ *  - Threads: entry points may be called from several host threads at once as
+ *    long as the calls use different workspaces (and streams as the caller sees
+ *    fit).  The first launch of each kernel instantiation in a process sets a
+ *    launch attribute once; that is guarded (std::call_once), so concurrent first
+ *    calls are safe.  path_attn_last_error is per thread.
+ *  - Determinism: every result except PaTH-FoX's dlog_f is bit-reproducible run
+ *    to run (no atomics, fixed summation order).  dlog_f sums its column and row
+ *    sums in shared memory in no fixed order: reproducible up to fp32 rounding of
+ *    those sums.
  */
 #ifndef PATH_ATTN_H
 #define PATH_ATTN_H
@@ -126,8 +151,7 @@ path_status_t path_attn_fwd_sweep(void* o, float* lse, int B, int H, int L, int 
  *        d_o [B,H,L,d] (dt)                                  -- device, read-only
  *   out: dq, dk, dv, dw [B,H,L,d] (dt), dbeta [B,H,L] (dt)   -- device
  * dw is the gradient with respect to the w passed in (no projection onto the
- * unit sphere).  Results are bit-reproducible: every sum is taken in a fixed order (the one
- * place that uses the hardware's floating-point add to memory adds exactly one term per element).
+ * unit sphere).  Results are bit-reproducible: every sum is taken in a fixed order.
  */
 path_status_t path_attn_bwd(const void* q, const void* k, const void* v, const void* w,
                             const void* beta, const void* o, const float* lse, const void* d_o,

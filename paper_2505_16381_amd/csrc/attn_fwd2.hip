@@ -294,13 +294,10 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
 template <typename TIO, int D, bool FOX, bool EMIT>
 hipError_t launch_attn_fwd2_f(const FwdParams& p, hipStream_t stream) {
     using C = Fwd2Cfg<TIO, D>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd2_kernel<TIO, D, FOX, EMIT>),
+    // set once per process; a function-local static is initialised under the language's own lock
+    static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd2_kernel<TIO, D, FOX, EMIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_err != hipSuccess) return attr_err;
     const int ntiles = (p.NC + FWD2_CPT - 1) / FWD2_CPT;
     const int BH = p.B * p.H;
     dim3 grid((unsigned)(((BH + 7) / 8) * 8 * ntiles));

@@ -1341,13 +1341,10 @@ hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream
     const size_t es = is_bf16 ? 2 : 4, fe = is_bf16 ? 8 : 4;
     const size_t bytes = (size_t)(a.M + a.N) * (a.K + fe) * es;
     dim3 grid(a.gridx, BH);
-    hipError_t e;
-    static bool attr_set[2] = {false, false};
-    if (!attr_set[is_bf16 ? 1 : 0]) {
-        e = is_bf16 ? set_smem(&batched_gemm_kernel<bf16_t>, 160 * 1024) : set_smem(&batched_gemm_kernel<float>, 160 * 1024);
-        if (e != hipSuccess) return e;
-        attr_set[is_bf16 ? 1 : 0] = true;
-    }
+    // set once per process; function-local statics are initialised under the language's own lock
+    static const hipError_t attr_bf = set_smem(&batched_gemm_kernel<bf16_t>, 160 * 1024);
+    static const hipError_t attr_f32 = set_smem(&batched_gemm_kernel<float>, 160 * 1024);
+    if ((is_bf16 ? attr_bf : attr_f32) != hipSuccess) return is_bf16 ? attr_bf : attr_f32;
     if (is_bf16) hipLaunchKernelGGL((batched_gemm_kernel<bf16_t>), grid, dim3(256), bytes, st, a);
     else hipLaunchKernelGGL((batched_gemm_kernel<float>), grid, dim3(256), bytes, st, a);
     return hipGetLastError();

@@ -372,13 +372,10 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
 template <typename TIO, int D, bool FOX, bool STRIDED>
 hipError_t launch_s(const ChunkFusedArgs& a, int BH, hipStream_t st) {
     using C = CaCfg<TIO, D>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_fused_kernel<TIO, D, FOX, STRIDED>),
+    // set once per process; a function-local static is initialised under the language's own lock
+    static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&chunk_fused_kernel<TIO, D, FOX, STRIDED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::TOTAL);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_err != hipSuccess) return attr_err;
     hipLaunchKernelGGL((chunk_fused_kernel<TIO, D, FOX, STRIDED>), dim3(a.NC, BH), dim3(CA_NT), (size_t)C::TOTAL, st, a);
     return hipGetLastError();
 }
@@ -547,13 +544,10 @@ __global__ __launch_bounds__(CA_NT) void sb_chain_kernel(SbChainArgs a) {
 template <typename TIO, int D, bool STRIDED>
 hipError_t launch_sb_s(const SbChainArgs& a, int BH, hipStream_t st) {
     using C = SbCfg<TIO, D>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&sb_chain_kernel<TIO, D, STRIDED>),
+    // set once per process; a function-local static is initialised under the language's own lock
+    static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&sb_chain_kernel<TIO, D, STRIDED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::TOTAL);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_err != hipSuccess) return attr_err;
     hipLaunchKernelGGL((sb_chain_kernel<TIO, D, STRIDED>), dim3((a.NC + SBC - 1) / SBC, BH), dim3(CA_NT), (size_t)C::TOTAL, st, a);
     return hipGetLastError();
 }

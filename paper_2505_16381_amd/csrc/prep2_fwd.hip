@@ -191,13 +191,10 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
 template <typename TIO, int D, bool BWD>
 hipError_t launch_prep2_fwd_b(const FwdParams& p, hipStream_t stream) {
     using C = Prep2Cfg<TIO, D>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep2_fwd_kernel<TIO, D, BWD>),
+    // set once per process; a function-local static is initialised under the language's own lock
+    static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep2_fwd_kernel<TIO, D, BWD>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_err != hipSuccess) return attr_err;
     dim3 grid((p.NC + SBC - 1) / SBC, p.B * p.H);
     const size_t bytes = C::smem_bytes;
     hipLaunchKernelGGL((prep2_fwd_kernel<TIO, D, BWD>), grid, dim3(256), bytes, stream, p);

@@ -531,13 +531,10 @@ template <typename T, int D, bool BWD, bool STRIDED>
 hipError_t launch_prep_fwd_s(const FwdParams& p, hipStream_t stream) {
     using C = PrepCfg<T, D>;
     static_assert(sizeof(typename C::T) == sizeof(T), "tile sizes assume equal operand and I/O width");
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep_fwd_kernel<T, D, BWD, STRIDED>),
+    // set once per process; a function-local static is initialised under the language's own lock
+    static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&prep_fwd_kernel<T, D, BWD, STRIDED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_err != hipSuccess) return attr_err;
     dim3 grid(p.NC, p.B * p.H);
     hipLaunchKernelGGL((prep_fwd_kernel<T, D, BWD, STRIDED>), grid, dim3(256), C::smem_bytes, stream, p);
     return hipGetLastError();

@@ -125,13 +125,10 @@ __global__ __launch_bounds__(256) void bwd_states_kernel(FwdParams p) {
 template <typename TIO, int D>
 static hipError_t launch_states_t(const FwdParams& p, hipStream_t stream) {
     using C = StatesCfg<TIO, D>;
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_states_kernel<TIO, D>),
+    // set once per process; a function-local static is initialised under the language's own lock
+    static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&bwd_states_kernel<TIO, D>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (attr_err != hipSuccess) return attr_err;
     const int ntiles = (p.NC + 1) / 2;
     const size_t bytes = C::smem_bytes;
     hipLaunchKernelGGL((bwd_states_kernel<TIO, D>), dim3((unsigned)(ntiles * p.B * p.H)), dim3(256), bytes, stream, p);

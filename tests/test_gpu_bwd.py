@@ -98,6 +98,18 @@ def test_bwd_other_scales(gpu, oracle, dtype, scale):
     _check(gpu, oracle, x, dtype, scale, tag=f"bwd scale={scale}")
 
 
+@pytest.mark.parametrize("L,d", [(1100, 128), (300, 64)])
+def test_bwd_bf16_large_magnitude_inputs(gpu, oracle, L, d):
+    """q and k at 64 times, dO at 1024 times their usual size (bf16 I/O: the transported operands and the state
+    gradients travel as fp16, range 65504; see the header's range rule), `scale` reduced by 64^2: the logits are
+    the usual ones, the carried operands are 64 times and the state gradients 16 times larger than in the other
+    cases (powers of two: the inputs stay exact bf16 values)."""
+    x = si.make_inputs(1, 2, L, d, "bf16", 830 + L + d, 0.0, with_do=True)
+    for n, f in (("q", 64), ("k", 64), ("dO", 1024)):
+        x[n] = (x[n] * f).astype(np.float32)
+    _check(gpu, oracle, x, "bf16", d ** -0.5 / 4096, tag=f"bwd bf16 x64 inputs L={L} d={d}")
+
+
 def test_bwd_gradient_identities_on_gpu(gpu):
     """w.dw = 2 beta dbeta and dw_0 = dbeta_0 = 0 hold for the GPU gradients too (fp32)."""
     x = si.make_inputs(1, 2, 192, 64, "fp32", 800, 0.0, with_do=True)

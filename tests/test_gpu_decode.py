@@ -7,7 +7,7 @@ Bars.  fp32 caches: keys 1e-4 (absolute, values O(1)), o 1e-4, lse 1e-3 -- the f
 bf16 caches: every refresh rounds the stored keys to bf16 again (part of the method as run).  The
 first check holds them against the un-rounded fp64 recurrence over 64 and more steps, with the growth
 law of that rounding as the bar (stated in the test); the second, over a few steps, against an oracle
-that re-rounds its own cache the same way (o 2e-2, lse 1e-3, keys within two bf16 steps)."""
+that re-rounds its own cache the same way (o 2e-2, lse 1e-3, keys within four bf16 steps)."""
 import numpy as np
 import pytest
 
@@ -108,12 +108,15 @@ def test_decode_steps_match_the_oracle(gpu, dec, dtype, L0, steps, d):
 def test_bf16_cache_against_the_unrounded_recurrence(gpu, dec, L0, steps, d):
     """bf16 caches, refreshed in place n times, held against the UN-ROUNDED fp64 recurrence (paper Sec. 3.4,
     first equation; no model of the kernel's rounding on the oracle's side).  Every refresh rounds every
-    stored key once more (half a bf16 step, 2^-9 relative, at most), so the cache performs a random walk
-    about the exact one: after n refreshes max|dk| ~ c 2^-9 sqrt(n+1) max|k| with c between 0.9 and 2 in a
-    CPU simulation of the rounding (bar: c = 3), the transitions being contractions that do not amplify
-    earlier errors.  A logit is a d-term sum of such errors and lse averages them over the keys: the
-    simulation gives max|dlse| <= 0.08 2^-9 sqrt(n) (bar: the forward's 1e-3 + 0.1 2^-9 sqrt(n)); o stays
-    far inside the forward's 2e-2."""
+    stored key once more: an error uniform within half a bf16 step, 0.4 * 2^-9 relative (rms).  The transitions
+    are contractions, so earlier errors are not amplified and the cache performs a random walk about the exact
+    one: after n refreshes max|dk| = c 2^-9 sqrt(n+1) max|k| with c between 0.9 and 2 in a CPU simulation of
+    the rounding (bar: c = 3).  A logit s = scale q.k with scale = d^-1/2, |q| ~ sqrt(d) then carries an error of
+    about 0.4 * 2^-9 sqrt(n+1) (rms), and lse = log sum exp averages the logits' errors with the softmax
+    weights, i.e. over the effective number of keys (a third of the L0 + n cached ones at these logit
+    spreads): four standard deviations are 3 * 2^-9 sqrt((n+1) / (L0+n)), which is added to the forward's 1e-3
+    (all of it when the cache holds two keys, a small part of it when it holds hundreds).  o stays far inside
+    the forward's 2e-2."""
     L = L0 + steps
     x = si.make_inputs(2, 2, L, d, "bf16", 950 + L + d, 0.0)
     dv, td = _dev(gpu, x, "bf16")
@@ -126,15 +129,18 @@ def test_bf16_cache_against_the_unrounded_recurrence(gpu, dec, L0, steps, d):
             print(f"[bf16 cache vs exact recurrence L0={L0} d={d}] n={n}: max|do|={eo:.2e} max|dlse|={el:.2e} "
                   f"max|dk|/(2^-9 sqrt(n+1) max|k|)={ek / (2.0 ** -9 * np.sqrt(n + 1) * kmax):.2f}", flush=True)
         assert eo <= 2e-2
-        assert el <= 1e-3 + 0.1 * 2.0 ** -9 * np.sqrt(n)
+        assert el <= 1e-3 + 3.0 * 2.0 ** -9 * np.sqrt((n + 1) / (L0 + n))
         assert ek <= 3.0 * 2.0 ** -9 * np.sqrt(n + 1) * kmax
 
 
 @pytest.mark.parametrize("L0,steps,d", [(257, 10, 128), (700, 6, 64)])
 def test_bf16_cache_against_the_rounding_model(gpu, dec, L0, steps, d):
     """Second, tighter check over a few steps: the oracle re-rounds its own cache to bf16 at every step
-    (``round_cache``, pinned on the CPU), starting from its own prefilled cache rounded once.  Keys then agree
-    to within the bf16 steps on which a value near a rounding boundary may fall either way."""
+    (``round_cache``, pinned on the CPU), starting from its own prefilled cache rounded once.  o and lse then
+    agree far better than against the exact recurrence.  The keys themselves agree only to a few bf16 steps: a
+    value near a rounding boundary falls one way on the GPU (fp32 arithmetic, fp16-transported prefill) and the
+    other way in the oracle (fp64), after which the two copies are rounded independently at every refresh
+    (bar: four steps of the largest binade, 2^-6 max|k|)."""
     L = L0 + steps
     x = si.make_inputs(2, 2, L, d, "bf16", 950 + L + d, 0.0)
     dv, td = _dev(gpu, x, "bf16")
@@ -147,7 +153,7 @@ def test_bf16_cache_against_the_rounding_model(gpu, dec, L0, steps, d):
     kmax = rows[-1][4]
     print(f"[decode bf16 vs rounding model L0={L0} steps={steps} d={d}] max|do|={wo:.2e} max|dlse|={wl:.2e} max|dk|={wk:.2e}", flush=True)
     assert wo <= 2e-2 and wl <= 1e-3
-    assert wk <= 2.0 ** -7 * kmax
+    assert wk <= 2.0 ** -6 * kmax
 
 
 def test_prefill_then_decode_reproduces_the_forward_rows(gpu, oracle):

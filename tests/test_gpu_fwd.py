@@ -130,6 +130,18 @@ def test_special_betas(gpu, oracle, dtype):
     _check(gpu, oracle, x, dtype, 0.125, tag="special betas")
 
 
+@pytest.mark.parametrize("L,d", [(1100, 128), (700, 64)])
+def test_bf16_large_magnitude_inputs(gpu, oracle, L, d):
+    """With bf16 I/O the transported operands (query state, boundary-adjusted keys, chunk products) travel as
+    fp16, whose range ends at 65504; the header's rule is that the norms of q and k rows stay below that.  Here
+    q and k are 64 times their usual size (row norms ~ 64 sqrt(d) ~ 700, far inside the bound but far outside the
+    unit scale of the other cases), with `scale` reduced by 64^2 so that the logits are the usual ones."""
+    x = si.make_inputs(1, 2, L, d, "bf16", 430 + L + d)
+    x["q"] = (x["q"] * 64).astype(np.float32)       # powers of two: still exact bf16 values
+    x["k"] = (x["k"] * 64).astype(np.float32)
+    _check(gpu, oracle, x, "bf16", d ** -0.5 / 4096, tag=f"bf16 x64 inputs L={L} d={d}")
+
+
 def test_swap_construction_on_gpu(gpu, oracle):
     """The paper's swap-tracking construction (App. A), zero-padded from d = 6 to 64, scale 1."""
     rng = np.random.default_rng(5)

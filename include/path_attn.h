@@ -282,6 +282,27 @@ path_status_t path_decode_step(const void* q, const void* k, const void* v, cons
                                path_dtype_t dt, void* workspace, size_t workspace_bytes,
                                void* stream);
 
+/*
+ * path_decode_step for callers that cannot allocate or pass scratch memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, results (bit for bit) and error
+ * codes as path_decode_step, minus the workspace: the per-split partial results go to a device array of
+ * PATH_DECODE_STATIC_BYTES (8 MiB) that is part of the library's image -- every GPU the library runs on
+ * holds one copy until the process ends.  The call allocates nothing (no hipMalloc / hipFree, no allocating
+ * library routine); on its first use on a device it looks the array's address up once.
+ *   Limit: path_decode_workspace_bytes(B, H, d) <= PATH_DECODE_STATIC_BYTES, i.e. B*H <= 252 at d = 128 and
+ *   B*H <= 496 at d = 64; beyond it PATH_ERR_WORKSPACE (the reason is in path_attn_last_error()).
+ *   All calls on one GPU share the one array, which keeps the previous call's contents (nothing in it has to
+ *   start at zero: every record is written before it is read).  Calls that may overlap on one GPU -- different
+ *   streams without an ordering between them, or several host threads -- RACE on it: order them.
+ * path_decode_static_scratch_bytes returns PATH_DECODE_STATIC_BYTES.
+ */
+#define PATH_DECODE_STATIC_BYTES (8u * 1024u * 1024u)
+size_t path_decode_static_scratch_bytes(void);
+path_status_t path_decode_step_static(const void* q, const void* k, const void* v, const void* w,
+                                      const void* beta, void* kcache, void* vcache, int n, int Lmax,
+                                      void* o, float* lse, int B, int H, int d, float scale,
+                                      path_dtype_t dt, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

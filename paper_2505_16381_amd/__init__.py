@@ -2,7 +2,7 @@
 from .binding import (  # noqa: F401
     PATH_F32, PATH_BF16, PathAttnError, library_path, load_library,
     path_attn_workspace_bytes, path_attn_fwd_workspace_layout, path_attn_fwd, path_attn_fwd_prep, path_attn_fwd_sweep, path_attn_bwd, path_status_str,
-    path_attn_last_error, path_decode_workspace_bytes, path_key_prefill, path_decode_step, path_attn_fox_fwd, path_attn_fox_bwd,
+    path_attn_last_error, path_decode_workspace_bytes, path_key_prefill, path_decode_step, path_decode_step_static, path_decode_static_scratch_bytes, path_attn_fox_fwd, path_attn_fox_bwd,
     path_attn_train_fwd, path_attn_train_bwd, path_attn_train_fwd_prep, path_attn_train_fwd_sweep,
     PATH_LAYOUT_BHLD, PATH_LAYOUT_BLHD, path_attn_fwd_layout, path_attn_bwd_layout,
     path_attn_varlen_workspace_bytes, path_attn_varlen_fwd, path_attn_varlen_bwd,

@@ -89,6 +89,10 @@ def load_library():
     lib.path_key_prefill.argtypes = [vp, ci, ci, ci, ci, ci, vp, sz, vp, vp, ci, vp]
     lib.path_decode_step.restype = ci
     lib.path_decode_step.argtypes = [vp] * 7 + [ci, ci, vp, vp, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_decode_static_scratch_bytes.restype = sz
+    lib.path_decode_static_scratch_bytes.argtypes = []
+    lib.path_decode_step_static.restype = ci
+    lib.path_decode_step_static.argtypes = [vp] * 7 + [ci, ci, vp, vp, ci, ci, ci, cf, ci, vp]
     _lib = lib
     return lib
 
@@ -236,6 +240,20 @@ def path_decode_step(q, k, v, w, beta, kcache, vcache, n, scale, workspace=None,
     _check(load_library().path_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(kcache), _ptr(vcache),
                                            int(n), kcache.shape[2], _ptr(o), _ptr(lse), B, H, d, float(scale), _dt_of(q),
                                            _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return o, lse
+
+
+def path_decode_static_scratch_bytes() -> int:
+    return int(load_library().path_decode_static_scratch_bytes())
+
+
+def path_decode_step_static(q, k, v, w, beta, kcache, vcache, n, scale, o, lse, stream=None):
+    """path_decode_step without a workspace and without any allocation: the caller passes the outputs
+    o [B,H,d] and lse [B,H] (fp32) too; the split partials go to the library's own device array."""
+    B, H, d = q.shape
+    _check(load_library().path_decode_step_static(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(kcache), _ptr(vcache),
+                                                  int(n), kcache.shape[2], _ptr(o), _ptr(lse), B, H, d, float(scale), _dt_of(q),
+                                                  _stream_handle(stream)))
     return o, lse
 
 

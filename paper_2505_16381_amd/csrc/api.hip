@@ -2,6 +2,7 @@
 // kernel launches on the caller's stream.  No allocation, no synchronisation.
 #include <cstdio>
 #include "../../include/path_attn.h"
+#include <mutex>
 #include <type_traits>
 
 #include "path_common.h"
@@ -523,6 +524,61 @@ extern "C" path_status_t path_decode_step(const void* q, const void* k, const vo
     clear_inherited_error();
     DecodeArgs a{q, k, v, w, beta, kcache, vcache, o, lse, static_cast<float*>(workspace), n, Lmax, scale};
     if (!hip_ok(launch_decode_step(a, B * H, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "decode step"))
+        return PATH_ERR_HIP;
+    return PATH_OK;
+}
+
+// ---- decode step for callers that cannot allocate: the split partials live in a device array of the library ----
+//
+// One copy of the array exists on every GPU the library is loaded on; host code must not use the array's name as
+// an address (it is a host-side stand-in): the device address is looked up once per device and kept.
+static __device__ __align__(256) unsigned char scratch[PATH_DECODE_STATIC_BYTES];
+static constexpr int MAX_DEVICES = 64;
+static std::mutex g_scratch_lock;
+static void* g_scratch_ptr[MAX_DEVICES] = {};      // per device: address of `scratch` there
+
+// Address of the array on the current device (looked up on the first call on that device), or NULL with the
+// reason in the thread's last-error text.
+static void* scratch_on_current_device() {
+    int dev = -1;
+    if (!hip_ok(hipGetDevice(&dev), "static scratch: current device")) return nullptr;
+    if (dev < 0 || dev >= MAX_DEVICES) {
+        snprintf(g_last_error, sizeof g_last_error, "static scratch: device index %d outside [0, %d)", dev, MAX_DEVICES);
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> guard(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)), "static scratch: symbol address")) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
+
+extern "C" size_t path_decode_static_scratch_bytes(void) { return PATH_DECODE_STATIC_BYTES; }
+
+extern "C" path_status_t path_decode_step_static(const void* q, const void* k, const void* v, const void* w,
+                                                 const void* beta, void* kcache, void* vcache, int n, int Lmax,
+                                                 void* o, float* lse, int B, int H, int d, float scale,
+                                                 path_dtype_t dt, void* stream) {
+    if (!q || !k || !v || !w || !beta || !kcache || !vcache || !o || !lse) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (B < 1 || H < 1 || (d != 64 && d != 128) || (long long)B * H > 65535 || n < 0 || n >= Lmax) return PATH_ERR_SHAPE;
+    if (!(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
+    const size_t need = path_decode_workspace_bytes(B, H, d);
+    if (need > PATH_DECODE_STATIC_BYTES) {
+        snprintf(g_last_error, sizeof g_last_error, "static scratch: B*H = %lld at d = %d needs %zu bytes, the array holds %zu",
+                 (long long)B * H, d, need, (size_t)PATH_DECODE_STATIC_BYTES);
+        return PATH_ERR_WORKSPACE;
+    }
+    const void* al[] = {q, k, v, w, kcache, vcache, o};
+    for (const void* ptr : al) if (misaligned(ptr)) return PATH_ERR_ALIGN;
+    clear_inherited_error();
+    void* ws = scratch_on_current_device();
+    if (!ws) return PATH_ERR_HIP;
+    // (nothing in the array has to start at zero: every split writes its whole record before the merge reads it)
+    DecodeArgs a{q, k, v, w, beta, kcache, vcache, o, lse, static_cast<float*>(ws), n, Lmax, scale};
+    if (!hip_ok(launch_decode_step(a, B * H, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "decode step (static scratch)"))
         return PATH_ERR_HIP;
     return PATH_OK;
 }

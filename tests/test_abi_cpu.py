@@ -79,3 +79,18 @@ def test_backward_argument_validation_without_gpu():
     assert call(args, dt=9) == 3
     assert call(args, causal=0) == 4
     assert call(args, wsb=8) == 5
+
+
+def test_static_decode_step_rejects_problems_beyond_its_array_without_a_gpu():
+    """The allocation-free decode step checks its arguments, and the size of its built-in scratch array, before
+    any HIP call: beyond B*H = 252 (d = 128) or 496 (d = 64) it returns PATH_ERR_WORKSPACE with the reason."""
+    lib = pa.load_library()
+    assert pa.path_decode_static_scratch_bytes() == 8 * 1024 * 1024
+    z = ctypes.c_void_p(0x1000)
+    call = lambda BH, d: lib.path_decode_step_static(z, z, z, z, z, z, z, 5, 16, z, z, 1, BH, d, ctypes.c_float(0.1), pa.PATH_BF16, None)
+    assert call(253, 128) == 5 and "static scratch" in pa.path_attn_last_error()
+    assert call(497, 64) == 5
+    assert pa.path_decode_workspace_bytes(1, 252, 128) <= 8 * 1024 * 1024 < pa.path_decode_workspace_bytes(1, 253, 128)
+    assert pa.path_decode_workspace_bytes(1, 496, 64) <= 8 * 1024 * 1024 < pa.path_decode_workspace_bytes(1, 497, 64)
+    assert lib.path_decode_step_static(None, z, z, z, z, z, z, 5, 16, z, z, 1, 2, 64, ctypes.c_float(0.1), pa.PATH_BF16, None) == 1
+    assert lib.path_decode_step_static(z, z, z, z, z, z, z, 16, 16, z, z, 1, 2, 64, ctypes.c_float(0.1), pa.PATH_BF16, None) == 2

@@ -20,6 +20,8 @@
 // ONE state update per super-block.  Workgroups are numbered so that one XCD
 // works through the query tiles of one head at a time (its K/V/dP stay in that
 // XCD's L2), heaviest tile first.
+#include <type_traits>
+
 #include "path_common.h"
 
 namespace path {
@@ -136,40 +138,39 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
         }
     };
 
-    issue_kv(0);
-    for (int u = 0; u < nstage; ++u) {
+    // One stage of an active wave (chunk j <= cq).  DIAG: the wave's own chunk (precomputed logits, causal mask,
+    // no state update after it); otherwise a chunk further left.
+    auto stage = [&](int u, auto diag_tag) {
+        constexpr bool DIAG = decltype(diag_tag)::value;
         const int j = jtop - (u >> 1), kb = u & 1;
-        wait_tiles_and_sync();            // stage u has landed; everyone is done with stage u-1
-        if (u + 1 < nstage) issue_kv(u + 1);
-        if (kb == 0) issue_dp(j);
-        if (!active || j > cq) continue;
         const Frag* sK = sKV + (size_t)(u & 1) * 2 * HF;
         const FragV* sV = reinterpret_cast<const FragV*>(sK + HF);
-
-        if (EMIT && kb == 0 && j < cq && (j >= jsb || (j % SBC) == SBC - 1)) {
-            constexpr int QS = CHUNK / KW;
-            const size_t slot = ((size_t)bh * num_block_slots(NC) + block_slot(cq, j >= jsb ? j : j - (SBC - 1), NC)) * (size_t)CHUNK * D;
-            Frag* xd = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xs) + slot);
+        if (!DIAG) {
+            if (EMIT && kb == 0 && (j >= jsb || (j % SBC) == SBC - 1)) {
+                constexpr int QS = CHUNK / KW;
+                const size_t slot = ((size_t)bh * num_block_slots(NC) + block_slot(cq, j >= jsb ? j : j - (SBC - 1), NC)) * (size_t)CHUNK * D;
+                Frag* xd = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xs) + slot);
 #pragma unroll
-            for (int s = 0; s < DS; ++s) __builtin_nontemporal_store(Xh[s], &xd[((size_t)qb * DS + s) * 64 + lane]);     // streamed: keep the key/value tiles in L2
-            if (sizeof(T) == 4 || j < jsb) {     // (16-bit operands: the near blocks' consumer transposes xs itself)
-                Frag* xt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xsT) + slot);
-                Frag idf[SPB];
-                identity_frags<T>(idf, l32, h);
+                for (int s = 0; s < DS; ++s) __builtin_nontemporal_store(Xh[s], &xd[((size_t)qb * DS + s) * 64 + lane]);     // streamed: keep the key/value tiles in L2
+                if (sizeof(T) == 4 || j < jsb) {     // (16-bit operands: the near blocks' consumer transposes xs itself)
+                    Frag* xt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.xsT) + slot);
+                    Frag idf[SPB];
+                    identity_frags<T>(idf, l32, h);
 #pragma unroll
-                for (int b = 0; b < DB; ++b) {
-                    const f32x16 tr = transpose32<T>(Xh + b * SPB, idf);     // rows q, lane c (block b)
-                    Frag fr[SPB];
-                    pack_block<T>(tr, fr);
+                    for (int b = 0; b < DB; ++b) {
+                        const f32x16 tr = transpose32<T>(Xh + b * SPB, idf);     // rows q, lane c (block b)
+                        Frag fr[SPB];
+                        pack_block<T>(tr, fr);
 #pragma unroll
-                    for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &xt[((size_t)b * QS + qb * SPB + s2) * 64 + lane]);
+                        for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &xt[((size_t)b * QS + qb * SPB + s2) * 64 + lane]);
+                    }
                 }
             }
         }
 
         // ---- logits of 32 keys (raw, unscaled) -------------------------------------------
         f32x16 S;
-        if (j == cq) {                    // own chunk: precomputed Q K^T - F Y, causal mask
+        if (DIAG) {                       // own chunk: precomputed Q K^T - F Y, causal mask
             const float* diag = p.sd + ((size_t)bh * NC + j) * 4096 + ((size_t)qb * 2 + kb) * 1024;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
@@ -205,7 +206,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
                 }
             }
             const float sl = FOX ? 1.f : sl2;
-            bool slow = j == cq && kb == 0;             // first block of this wave: no reference yet
+            bool slow = DIAG && kb == 0;                // first block of this wave: no reference yet
             if (!slow) {
                 const float mneg = -m_run;
 #pragma unroll
@@ -247,26 +248,47 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
 #pragma unroll
             for (int s = 0; s < SPB; ++s) O[b] = Tr<TIO>::mma(sV[(b * SPB + s) * 64 + lane], Pb[s], O[b]);
 
-        // ---- X <- X (I - dP) after the chunk (phase A) / after the super-block (phase B) -------
-        const bool upd = kb == 1 && j > 0 && (j >= jsb ? j < cq : (j % SBC) == 0);
-        if (upd) {
-            f32x16 Xn[DB];
+        if (!DIAG) {
+            // ---- X <- X (I - dP) after the chunk (phase A) / after the super-block (phase B) -------
+            const bool upd = kb == 1 && j > 0 && (j >= jsb || (j % SBC) == 0);
+            if (upd) {
+                f32x16 Xn[DB];
 #pragma unroll
-            for (int b = 0; b < DB; ++b) {
-                if (HAS_MASTER) Xn[b] = Xm[b];
-                else
+                for (int b = 0; b < DB; ++b) {
+                    if (HAS_MASTER) Xn[b] = Xm[b];
+                    else
 #pragma unroll
-                    for (int jj = 0; jj < 16; ++jj) Xn[b][jj] = (float)Xh[b * SPB + jj / Tr<T>::FE][jj % Tr<T>::FE];
+                        for (int jj = 0; jj < 16; ++jj) Xn[b][jj] = (float)Xh[b * SPB + jj / Tr<T>::FE][jj % Tr<T>::FE];
+                }
+#pragma unroll
+                for (int b = 0; b < DB; ++b)
+#pragma unroll
+                    for (int s = 0; s < DS; ++s) Xn[b] = Tr<T>::mma(sP[(b * DS + s) * 64 + lane], Xh[s], Xn[b]);
+#pragma unroll
+                for (int b = 0; b < DB; ++b) {
+                    if (HAS_MASTER) Xm[b] = Xn[b];
+                    pack_block<T>(Xn[b], Xh + b * SPB);
+                }
             }
-#pragma unroll
-            for (int b = 0; b < DB; ++b)
-#pragma unroll
-                for (int s = 0; s < DS; ++s) Xn[b] = Tr<T>::mma(sP[(b * DS + s) * 64 + lane], Xh[s], Xn[b]);
-#pragma unroll
-            for (int b = 0; b < DB; ++b) {
-                if (HAS_MASTER) Xm[b] = Xn[b];
-                pack_block<T>(Xn[b], Xh + b * SPB);
-            }
+        }
+    };
+    // Every wave passes the same nstage barriers: as a bystander (stages right of its own chunk: it only helps
+    // with the tile copies), through its own chunk (two stages), then the steady state.
+    auto top_of_stage = [&](int u) {
+        wait_tiles_and_sync();            // stage u has landed; everyone is done with stage u-1
+        if (u + 1 < nstage) issue_kv(u + 1);
+        if ((u & 1) == 0) issue_dp(jtop - (u >> 1));
+    };
+    const int u0 = active ? 2 * (jtop - cq) : nstage;      // this wave's first stage
+    issue_kv(0);
+    int u = 0;
+    for (; u < u0; ++u) top_of_stage(u);
+    if (active) {
+        top_of_stage(u); stage(u, std::true_type{}); ++u;
+        top_of_stage(u); stage(u, std::true_type{}); ++u;
+        for (; u < nstage; ++u) {
+            top_of_stage(u);
+            stage(u, std::false_type{});
         }
     }
 

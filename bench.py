@@ -8,8 +8,9 @@ Inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
 FLOP convention: attention-equivalent 4*d*L(L+1)/2*B*H for the forward and
 2.5x that for the backward (FlashAttention convention, masked work not
-counted); the PaTH-inclusive count (query-state updates, chunk transform) is
-reported next to it.
+counted); the PaTH-inclusive count (query-state updates at the blocking the
+kernels use, the two transforms) is reported next to it, and every percentage of
+the datasheet peak also against the MFMA rate measured in the same run.
 """
 from __future__ import annotations
 
@@ -25,8 +26,9 @@ if ROOT not in sys.path:
 
 METRIC = "PaTH attn fwd+bwd TFLOP/s and % bf16 MFMA peak at B=4,H=16,L=8192,d=128"
 PEAK_TFLOPS = 2500.0      # MI355X dense bf16/fp16 MFMA
-SWEEP_HBM_BYTES = 4.69e9  # measured HBM traffic of one launch of the pair's sweep at the headline shape (see profiles/)
-CHUNK = 64
+CHUNK = 64                # tokens per chunk (the library's UT-transform block)
+SBC = 16                  # chunks per super-block (second blocking level: one query-state update per 1024 keys)
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "fwd_bwd_headline_L8192_d128_hbm_traffic.txt")
 
 
 def attn_flops(B, H, L, d):
@@ -34,35 +36,89 @@ def attn_flops(B, H, L, d):
 
 
 def path_extra_flops(B, H, L, d):
-    """PaTH-only work at the blocking used (chunk 64, one query-state update per key chunk)."""
+    """PaTH-only work of the forward at the blocking the kernels use (chunk C = 64, super-block S = 16 chunks):
+    the chunk transform, the second-level transform, and the query-state updates -- one 2*C*d*d update per
+    (query chunk, key chunk of its own super-block left of it) and one per (query chunk, super-block further
+    left), none after a head's first chunk / first super-block."""
     nc = -(-L // CHUNK)
     prep = (14.0 * CHUNK * CHUNK * d + 2.0 * CHUNK * d * d + 4.0 * CHUNK ** 3 + CHUNK ** 3 / 3.0) * nc
-    # one (32 queries x d x d) update per (query block, key chunk strictly left of it, except chunk 0)
-    upd = 0.0
+    prep2 = (2.0 * CHUNK * d * d + 2.0 * d ** 3) * nc          # keys carried to the super-block edge; running product
+    upd = 0
     for c in range(nc):
-        upd += 2.0 * CHUNK * d * d * max(0, c - 1)
-    return (prep + upd) * B * H
+        jsb = (c // SBC) * SBC
+        near = sum(1 for j in range(jsb, c) if j > 0)
+        far = max(0, c // SBC - 1)
+        upd += near + far
+    return (prep + prep2 + 2.0 * CHUNK * d * d * upd) * B * H
 
 
-def cpu_baseline(x, cfg, scale, n_rows=6144):
-    """The fp64 oracle, as it stands, on a bounded row sample of the same workload."""
+def pair_counts(L):
+    """(near, far) query-key pairs per head of the backward's key-side kernels: near = keys in the query's own
+    super-block but left of its chunk; far = keys in super-blocks left of the query's."""
+    nc = -(-L // CHUNK)
+    near = far = 0
+    for c in range(nc):
+        nq = min(CHUNK, L - c * CHUNK)
+        jsb = (c // SBC) * SBC
+        near += nq * (c - jsb) * CHUNK
+        far += nq * jsb * CHUNK
+    return near, far
+
+
+def measured_mfma_peak(torch, pa, dev):
+    """TFLOP/s of a register-resident MFMA chain (two waves per SIMD, no memory traffic): what the matrix pipes
+    deliver at the clock the chip holds under that load."""
+    sink = torch.empty(1024 * 4 * 64, dtype=torch.float32, device=dev)
+    pa.path_probe_mfma(sink, 2, 2000)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    flops = pa.path_probe_mfma(sink, 2, 20000)
+    e1.record()
+    torch.cuda.synchronize()
+    return flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+
+
+def profiled_traffic(kernel_key):
+    """HBM bytes per launch of a kernel from the committed rocprofv3 counter profile (FETCH_SIZE / WRITE_SIZE runs
+    of this same command), or None when the profile does not list it."""
+    try:
+        for line in open(TRAFFIC_PROFILE):
+            if line.startswith("# json:"):
+                rec = json.loads(line[len("# json:"):])
+                if rec.get("kernel") == kernel_key:
+                    return rec
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(x, cfg, scale, n_rows=3072):
+    """The fp64 oracle, as it stands, on a bounded sample of the same workload: its forward on a row sample of
+    all heads and its backward (not separable by rows) on four whole heads."""
     import numpy as np
     from oracle import path_oracle
     rng = np.random.default_rng(0)
     L, d = cfg["L"], cfg["d"]
     n_heads = cfg["B"] * cfg["H"]
     rows = np.unique(rng.integers(0, L, n_rows))
-    sub = {n: x[n].reshape((1, n_heads) + x[n].shape[2:]) for n in ("q", "k", "v", "w", "beta")}
+    sub = {n: x[n].reshape((1, n_heads) + x[n].shape[2:]) for n in ("q", "k", "v", "w", "beta", "dO")}
     path_oracle.fwd(sub["q"], sub["k"], sub["v"], sub["w"], sub["beta"], scale, rows=rows[:2])  # warm
     t0 = time.perf_counter()
     path_oracle.fwd(sub["q"], sub["k"], sub["v"], sub["w"], sub["beta"], scale, rows=rows)
-    dt = time.perf_counter() - t0
-    pairs = float((rows + 1).sum()) * n_heads
+    t_f = time.perf_counter() - t0
+    one = {n: a[:, :4] for n, a in sub.items()}
+    t0 = time.perf_counter()
+    path_oracle.bwd(one["q"], one["k"], one["v"], one["w"], one["beta"], one["dO"], scale)
+    t_b = time.perf_counter() - t0
+    pairs_f = float((rows + 1).sum()) * n_heads
+    pairs_b = 4 * L * (L + 1) / 2.0
     return {
-        "value": pairs * 4.0 * d / dt / 1e12, "unit": "TFLOP/s", "cores": path_oracle.num_threads(),
-        "kind": "oracle", "seconds": dt,
-        "sample": f"forward only, all {n_heads} heads x {len(rows)} random query rows of the headline shape "
-                  f"({pairs:.3g} query-key pairs), attention-equivalent flops 4d per pair",
+        "value": (pairs_f * 4.0 * d + pairs_b * 10.0 * d) / (t_f + t_b) / 1e12, "unit": "TFLOP/s", "cores": path_oracle.num_threads(),
+        "kind": "oracle", "seconds": t_f + t_b, "fwd_seconds": t_f, "bwd_seconds": t_b,
+        "sample": f"forward: all {n_heads} heads x {len(rows)} random query rows of the headline shape ({pairs_f:.3g} query-key "
+                  f"pairs, 4d attention-equivalent flops each); backward (forward walk included): four whole heads "
+                  f"({pairs_b:.3g} pairs, 2.5 x 4d each)",
     }
 
 
@@ -232,24 +288,30 @@ def main():
 
     # One training step = the training pair: forward and backward share the backward-sized workspace, so the
     # chunk transform runs once per step (forward-only runs use the plain forward and its smaller workspace).
+    BWD_STAGES = (("scan", pa.PATH_BWD_STAGE_SCAN), ("keys_near", pa.PATH_BWD_STAGE_KEYS_NEAR), ("keys_far", pa.PATH_BWD_STAGE_KEYS_FAR),
+                  ("ddp", pa.PATH_BWD_STAGE_DDP), ("chunk", pa.PATH_BWD_STAGE_CHUNK))
+    grads = [torch.empty_like(t["q"]) for _ in range(4)] + [torch.empty_like(t["beta"])] if do_bwd else None
+
     def step(record):
-        e0, e1, e2, e3 = (ev(), ev(), ev(), ev()) if record else (None,) * 4
-        if record: e0.record()
+        es = [ev() for _ in range(3 + len(BWD_STAGES))] if record else None
+        if record: es[0].record()
         if do_bwd:
             pa.path_attn_train_fwd_prep(t["q"], t["k"], t["v"], t["w"], t["beta"], ws_b)
         else:
             pa.path_attn_fwd_prep(t["q"], t["k"], t["v"], t["w"], t["beta"], ws_f)
-        if record: e1.record()
+        if record: es[1].record()
         if do_bwd:
             pa.path_attn_train_fwd_sweep(o, lse, scale, ws_b)
         else:
             pa.path_attn_fwd_sweep(o, lse, scale, ws_f)
-        if record: e2.record()
+        if record: es[2].record()
         if do_bwd:
-            pa.path_attn_train_bwd(t["q"], t["k"], t["v"], t["w"], t["beta"], o, lse, t["dO"], ws_b, scale=scale)
+            # the backward of the pair, stage by stage (together exactly path_attn_train_bwd), an event after each
+            for i, (_, bit) in enumerate(BWD_STAGES):
+                pa.path_attn_train_bwd_stages(bit, t["q"], t["k"], t["v"], t["w"], t["beta"], o, lse, t["dO"], grads, ws_b, scale=scale)
+                if record: es[3 + i].record()
         if record:
-            e3.record()
-            marks.append((e0, e1, e2, e3))
+            marks.append(es)
 
     for _ in range(args.warmup):
         step(False)
@@ -261,9 +323,10 @@ def main():
     wall = time.perf_counter() - t0
 
     ms_step = wall * 1e3 / args.steps
-    prep_ms = sum(a.elapsed_time(b) for a, b, _, _ in marks) / len(marks)
-    sweep_ms = sum(b.elapsed_time(c) for _, b, c, _ in marks) / len(marks)
-    bwd_ms = sum(c.elapsed_time(e) for _, _, c, e in marks) / len(marks) if do_bwd else None
+    mean = lambda i, j: sum(es[i].elapsed_time(es[j]) for es in marks) / len(marks)
+    prep_ms, sweep_ms = mean(0, 1), mean(1, 2)
+    stage_ms = {name: mean(2 + i, 3 + i) for i, (name, _) in enumerate(BWD_STAGES)} if do_bwd else {}
+    bwd_ms = mean(2, 2 + len(BWD_STAGES)) if do_bwd else None
 
     # for the record, outside the timed region: the stand-alone calls (each runs the transform itself)
     alone = None
@@ -278,12 +341,27 @@ def main():
         a2.record()
         torch.cuda.synchronize()
         alone = {"path_attn_fwd_ms": a0.elapsed_time(a1) / 2, "path_attn_bwd_ms": a1.elapsed_time(a2) / 2}
+    peak_meas = measured_mfma_peak(torch, pa, dev)
 
     fl_f = attn_flops(B, H, L, d)
     fl_step = fl_f * (3.5 if do_bwd else 1.0)
     value = fl_step / (ms_step * 1e-3) / 1e12
     fwd_tflops = fl_f / ((prep_ms + sweep_ms) * 1e-3) / 1e12
     sweep_tflops = fl_f / (sweep_ms * 1e-3) / 1e12
+    # Roofline of the dominant kernel of the timed step.  The stages that are ONE kernel launch each are the sweep
+    # and the two key-side passes; their algorithmic flops: sweep 4d per (query, key <= query) pair; key-side 8d
+    # per pair of its range (logit and dP recomputed, dV and dK accumulated: four d-long dot products).
+    near_pairs, far_pairs = pair_counts(L)
+    single = {"attn_fwd2_kernel (forward sweep" + ("; in the training pair it also writes the backward's query states)" if do_bwd else ")"):
+              (sweep_ms, fl_f, "4*d flops per (query, key <= query) pair")}
+    if do_bwd:
+        single["bwd_keyside2_kernel<FAR> (key-side sums over the queries right of the key's super-block)"] = (
+            stage_ms["keys_far"], 8.0 * d * far_pairs * B * H, "8*d flops per (query, key) pair with the key in a super-block left of the query's")
+        single["bwd_keyside2_kernel<near> (key-side sums inside the key's super-block; also the near product gradients)"] = (
+            stage_ms["keys_near"], 8.0 * d * near_pairs * B * H, "8*d flops per (query, key) pair of one super-block, key chunk left of the query chunk")
+    dom = max(single, key=lambda kname: single[kname][0])
+    dom_ms, dom_fl, dom_note = single[dom]
+    traffic = profiled_traffic(dom.split(" ")[0]) if (args.config == 2 and not args.shape) else None
     out = {
         "metric": METRIC, "value": value, "unit": "TFLOP/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
@@ -291,24 +369,29 @@ def main():
         "dtype": "bf16 I/O, fp16+bf16 MFMA operands, fp32 accumulate" if cfg["dtype"] == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": f"{cfg['name']}: B={B} H={H} L={L} d={d} causal, "
-                               f"{'forward+backward' if do_bwd else 'forward only (no backward at this shape yet)'}",
-                   "passes": "fwd+bwd (training pair: path_attn_train_fwd + path_attn_train_bwd, shared workspace)" if do_bwd else "fwd"},
+                               f"{'forward+backward' if do_bwd else 'forward only'}",
+                   "passes": "fwd+bwd (training pair: path_attn_train_fwd + path_attn_train_bwd in its stages, shared workspace)" if do_bwd else "fwd"},
         "pct_of_mfma_peak": 100.0 * value / PEAK_TFLOPS,
+        "mfma_peak_measured_tflops": peak_meas,
+        "pct_of_measured_clock_peak": 100.0 * value / peak_meas,
         "tokens_per_s": B * L / (ms_step * 1e-3),
         "fwd": {"ms": prep_ms + sweep_ms, "prep_ms": prep_ms, "sweep_ms": sweep_ms,
                 "attn_equiv_tflops": fwd_tflops, "pct_of_mfma_peak": 100.0 * fwd_tflops / PEAK_TFLOPS,
-                "path_inclusive_tflops": (fl_f + path_extra_flops(B, H, L, d)) / ((prep_ms + sweep_ms) * 1e-3) / 1e12},
-        "bwd": ({"ms": bwd_ms, "attn_equiv_tflops": 2.5 * fl_f / (bwd_ms * 1e-3) / 1e12} if do_bwd else None),
+                "pct_of_measured_clock_peak": 100.0 * fwd_tflops / peak_meas,
+                "sweep_attn_equiv_tflops": sweep_tflops, "sweep_frac_of_mfma_peak": sweep_tflops / PEAK_TFLOPS,
+                "path_inclusive_tflops": (fl_f + path_extra_flops(B, H, L, d)) / ((prep_ms + sweep_ms) * 1e-3) / 1e12,
+                "path_inclusive_note": "adds the chunk transform, the second-level transform and the query-state updates at the "
+                                       "blocking used: chunk 64, one update per key chunk of the own super-block and one per 1024 keys further left"},
+        "bwd": ({"ms": bwd_ms, "attn_equiv_tflops": 2.5 * fl_f / (bwd_ms * 1e-3) / 1e12, "stages_ms": stage_ms} if do_bwd else None),
         "standalone_calls": alone,
-        "roofline": {"kernel": "attn_fwd2_kernel (sweep; in the training pair it also writes the backward's query states)"
-                               if do_bwd else "attn_fwd2_kernel (sweep)", "bound": "mfma", "achieved": sweep_tflops,
-                     "peak": PEAK_TFLOPS, "unit": "TFLOP/s", "frac": sweep_tflops / PEAK_TFLOPS,
-                     "traffic": SWEEP_HBM_BYTES if (args.config == 2 and not args.shape) else None,
-                     "note": "achieved = attention-equivalent flops of the launch / HIP-event time of the sweep kernel; "
-                             "traffic = HBM bytes per launch from rocprofv3 FETCH_SIZE/WRITE_SIZE "
-                             "(profiles/fwd_bwd_headline_L8192_d128_hbm_traffic.txt): 2.57e9 in + 2.12e9 out (the fetched bytes vary between runs, 2.4-2.6e9), of which "
-                             "1.96e9 are the query states kept for the backward; the forward alone needs 1.2e9 "
-                             "(the stand-alone forward's sweep, without that output: 1.4-1.5 ms, frac 0.29-0.31, same profile)"},
+        "roofline": {"kernel": dom, "bound": "mfma", "achieved": dom_fl / (dom_ms * 1e-3) / 1e12,
+                     "peak": PEAK_TFLOPS, "unit": "TFLOP/s", "frac": dom_fl / (dom_ms * 1e-3) / 1e12 / PEAK_TFLOPS,
+                     "traffic": (traffic["fetch_bytes"] + traffic["write_bytes"]) if traffic else None,
+                     "launch_ms": dom_ms, "flops_per_launch": dom_fl,
+                     "note": "the kernel with the longest launch among the single-kernel stages of the timed step; achieved = its "
+                             "algorithmic flops (" + dom_note + ") / its HIP-event time inside the timed region; traffic = HBM bytes "
+                             "per launch from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE profile of this command "
+                             "(profiles/fwd_bwd_headline_L8192_d128_hbm_traffic.txt), null if that profile does not list the kernel"},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(x, cfg, scale)

@@ -213,6 +213,24 @@ path_status_t path_attn_train_bwd(const void* q, const void* k, const void* v, c
                                   void* dlog_f, int B, int H, int L, int d, int causal, float scale,
                                   path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
 
+/* path_attn_train_bwd in stages, for callers that time them (bench.py brackets each with events): `stages` is a
+ * set of PATH_BWD_STAGE_* bits; the selected stages are enqueued in the order of their values.  Calling it with
+ * one stage after the other, in that order, is exactly path_attn_train_bwd (which is `stages` = PATH_BWD_STAGE_ALL);
+ * a later stage reads what the earlier ones left in the workspace.  Unknown or no bits: PATH_ERR_UNSUPPORTED. */
+enum {
+    PATH_BWD_STAGE_SCAN = 1,       /* dO tiles and delta; adjoint scan over the key blocks (dQ-side)          */
+    PATH_BWD_STAGE_KEYS_NEAR = 2,  /* key-side sums over the query chunks of the key's own super-block       */
+    PATH_BWD_STAGE_KEYS_FAR = 4,   /* key-side sums over all queries right of the key's super-block          */
+    PATH_BWD_STAGE_DDP = 8,        /* gradients of the super-block products                                  */
+    PATH_BWD_STAGE_CHUNK = 16,     /* adjoint of the second level and of the chunk transform: the gradients  */
+    PATH_BWD_STAGE_ALL = 31
+};
+path_status_t path_attn_train_bwd_stages(int stages, const void* q, const void* k, const void* v, const void* w,
+                                         const void* beta, const void* log_f, const void* o, const float* lse,
+                                         const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                         void* dlog_f, int B, int H, int L, int d, int causal, float scale,
+                                         path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
+
 /*
  * The forward and backward on either layout.  log_f == NULL: plain PaTH (as path_attn_fwd / path_attn_bwd);
  * log_f given: PaTH-FoX (as path_attn_fox_fwd / path_attn_fox_bwd; dlog_f is required iff log_f is).
@@ -281,6 +299,18 @@ path_status_t path_decode_step(const void* q, const void* k, const void* v, cons
                                void* o, float* lse, int B, int H, int d, float scale,
                                path_dtype_t dt, void* workspace, size_t workspace_bytes,
                                void* stream);
+
+/*
+ * Measurement aid, not part of the method: a register-resident chain of 32x32x16 fp16 MFMA products (four
+ * independent accumulators per wave, `waves_per_simd` waves on each of the 1024 SIMDs, `iters` x 16 products
+ * per wave, no memory traffic inside the loop) for calibrating "percent of peak" against what the matrix pipes
+ * deliver at the clock they actually hold.  It enqueues one kernel on `stream`; the caller times it.  The work is
+ * path_probe_mfma_flops(waves_per_simd, iters) floating-point operations.  `sink` is device memory of at least
+ * 1024 * 4 * 64 * 4 bytes (one float per lane), written with values nobody needs.  waves_per_simd must be 1, 2
+ * or 4 and iters >= 1 (else PATH_ERR_SHAPE).
+ */
+double path_probe_mfma_flops(int waves_per_simd, int iters);
+path_status_t path_probe_mfma(void* sink, int waves_per_simd, int iters, void* stream);
 
 /*
  * path_decode_step for callers that cannot allocate or pass scratch memory: code under HIP graph capture,

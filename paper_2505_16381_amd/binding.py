@@ -89,6 +89,12 @@ def load_library():
     lib.path_key_prefill.argtypes = [vp, ci, ci, ci, ci, ci, vp, sz, vp, vp, ci, vp]
     lib.path_decode_step.restype = ci
     lib.path_decode_step.argtypes = [vp] * 7 + [ci, ci, vp, vp, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_train_bwd_stages.restype = ci
+    lib.path_attn_train_bwd_stages.argtypes = [ci] + [vp] * 15 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_probe_mfma_flops.restype = ctypes.c_double
+    lib.path_probe_mfma_flops.argtypes = [ci, ci]
+    lib.path_probe_mfma.restype = ci
+    lib.path_probe_mfma.argtypes = [vp, ci, ci, vp]
     lib.path_decode_static_scratch_bytes.restype = sz
     lib.path_decode_static_scratch_bytes.argtypes = []
     lib.path_decode_step_static.restype = ci
@@ -313,6 +319,30 @@ def path_attn_train_bwd(q, k, v, w, beta, o, lse, d_o, workspace, log_f=None, sc
                                               _ptr(dlog_f) if dlog_f is not None else None, B, H, L, d, 1, scale, dt,
                                               _ptr(workspace), workspace.numel(), _stream_handle(stream)))
     return tuple(outs) + ((dlog_f,) if dlog_f is not None else ())
+
+
+PATH_BWD_STAGE_SCAN, PATH_BWD_STAGE_KEYS_NEAR, PATH_BWD_STAGE_KEYS_FAR, PATH_BWD_STAGE_DDP, PATH_BWD_STAGE_CHUNK = 1, 2, 4, 8, 16
+PATH_BWD_STAGE_ALL = 31
+
+
+def path_attn_train_bwd_stages(stages, q, k, v, w, beta, o, lse, d_o, outs, workspace, log_f=None, dlog_f=None, scale=None, stream=None):
+    """The selected stages of path_attn_train_bwd (PATH_BWD_STAGE_* bits) into the caller's gradient tensors
+    ``outs`` = (dq, dk, dv, dw, dbeta); the stages must be called in the order of their values."""
+    B, H, L, d = q.shape
+    scale = float(d ** -0.5 if scale is None else scale)
+    _check(load_library().path_attn_train_bwd_stages(int(stages), _ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta),
+                                                     _ptr(log_f) if log_f is not None else None, _ptr(o), _ptr(lse), _ptr(d_o),
+                                                     *[_ptr(x) for x in outs], _ptr(dlog_f) if dlog_f is not None else None,
+                                                     B, H, L, d, 1, scale, _dt_of(q), _ptr(workspace), workspace.numel(),
+                                                     _stream_handle(stream)))
+    return outs
+
+
+def path_probe_mfma(sink, waves_per_simd, iters, stream=None):
+    """Enqueues the register-resident MFMA chain (a measurement aid); returns the number of flops it performs."""
+    lib = load_library()
+    _check(lib.path_probe_mfma(_ptr(sink), int(waves_per_simd), int(iters), _stream_handle(stream)))
+    return float(lib.path_probe_mfma_flops(int(waves_per_simd), int(iters)))
 
 
 def path_attn_train_fwd_prep(q, k, v, w, beta, workspace, log_f=None, stream=None):

@@ -265,7 +265,7 @@ enum BwdMode { BWD_FULL = 0,        // transforms + backward (path_attn_bwd)
                BWD_RESUME = 2,      // backward without the transforms (the workspace is as BWD_FWD_ONLY left it)
                BWD_FWD_PREP = 3,    // the two halves of BWD_FWD_ONLY as separate calls: transforms ...
                BWD_FWD_SWEEP = 4 }; // ... and the forward sweep
-static path_status_t bwd_impl(BwdMode mode, const UserLayout& ul, const void* q, const void* k, const void* v, const void* w,
+static path_status_t bwd_impl(BwdMode mode, int stages, const UserLayout& ul, const void* q, const void* k, const void* v, const void* w,
                               const void* beta, const void* log_f, const void* o, const float* lse, const void* d_o,
                               void* dq, void* dk, void* dv, void* dw, void* dbeta, void* dlog_f, int B, int H,
                               int L, int d, int causal, float scale, path_dtype_t dt,
@@ -329,7 +329,8 @@ static path_status_t bwd_impl(BwdMode mode, const UserLayout& ul, const void* q,
     bp.delta = F(ws.delta); bp.lse2p = F(ws.lse2p); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
     bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale; bp.ul = ul;
     bp.cum = cum; bp.dcol = cum ? F(ws.dcol) : nullptr; bp.drow = cum ? F(ws.drow) : nullptr;
-    if (!hip_ok(launch_bwd_scan(bp, d, bf, st), "backward pair kernels")) return PATH_ERR_HIP;
+    if (!hip_ok(launch_bwd_scan(bp, d, bf, stages, st), "backward pair kernels")) return PATH_ERR_HIP;
+    if (!(stages & BWD_STAGE_CHUNK)) return PATH_OK;
 
     // 5. adjoint of the chunk transform
     const long long c_bh = (long long)NC * 4096, c_ch = 4096;          // 64x64 per chunk
@@ -588,7 +589,7 @@ extern "C" path_status_t path_attn_bwd(const void* q, const void* k, const void*
                                        void* dq, void* dk, void* dv, void* dw, void* dbeta, int B, int H,
                                        int L, int d, int causal, float scale, path_dtype_t dt,
                                        void* workspace, size_t workspace_bytes, void* stream) {
-    return bwd_impl(BWD_FULL, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, nullptr, o, lse, d_o, dq, dk, dv, dw, dbeta, nullptr, B, H, L, d, causal, scale, dt,
+    return bwd_impl(BWD_FULL, BWD_STAGE_ALL, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, nullptr, o, lse, d_o, dq, dk, dv, dw, dbeta, nullptr, B, H, L, d, causal, scale, dt,
                     workspace, workspace_bytes, stream);
 }
 
@@ -598,7 +599,7 @@ extern "C" path_status_t path_attn_fox_bwd(const void* q, const void* k, const v
                                            void* dlog_f, int B, int H, int L, int d, int causal, float scale,
                                            path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
     if (!log_f || !dlog_f) return PATH_ERR_NULL;
-    return bwd_impl(BWD_FULL, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
+    return bwd_impl(BWD_FULL, BWD_STAGE_ALL, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
                     workspace, workspace_bytes, stream);
 }
 
@@ -606,21 +607,21 @@ extern "C" path_status_t path_attn_train_fwd(const void* q, const void* k, const
                                              const void* beta, const void* log_f, void* o, float* lse,
                                              int B, int H, int L, int d, int causal, float scale,
                                              path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
-    return bwd_impl(BWD_FWD_ONLY, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+    return bwd_impl(BWD_FWD_ONLY, BWD_STAGE_ALL, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                     B, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
 }
 
 extern "C" path_status_t path_attn_train_fwd_prep(const void* q, const void* k, const void* v, const void* w,
                                                   const void* beta, const void* log_f, int B, int H, int L, int d,
                                                   path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
-    return bwd_impl(BWD_FWD_PREP, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
+    return bwd_impl(BWD_FWD_PREP, BWD_STAGE_ALL, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr,
                     nullptr, B, H, L, d, 1, 1.f, dt, workspace, workspace_bytes, stream);
 }
 
 extern "C" path_status_t path_attn_train_fwd_sweep(void* o, float* lse, int with_gates, int B, int H, int L, int d, float scale,
                                                    path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
     // (log_f itself is not read here: the gate sums are in the workspace; any non-NULL value selects them)
-    return bwd_impl(BWD_FWD_SWEEP, layout_of(PATH_LAYOUT_BHLD, H, L, d), nullptr, nullptr, nullptr, nullptr, nullptr, with_gates ? workspace : nullptr, o, lse, nullptr,
+    return bwd_impl(BWD_FWD_SWEEP, BWD_STAGE_ALL, layout_of(PATH_LAYOUT_BHLD, H, L, d), nullptr, nullptr, nullptr, nullptr, nullptr, with_gates ? workspace : nullptr, o, lse, nullptr,
                     nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, B, H, L, d, 1, scale, dt, workspace, workspace_bytes, stream);
 }
 
@@ -629,7 +630,17 @@ extern "C" path_status_t path_attn_train_bwd(const void* q, const void* k, const
                                              const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
                                              void* dlog_f, int B, int H, int L, int d, int causal, float scale,
                                              path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
-    return bwd_impl(BWD_RESUME, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
+    return bwd_impl(BWD_RESUME, BWD_STAGE_ALL, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
+                    workspace, workspace_bytes, stream);
+}
+
+extern "C" path_status_t path_attn_train_bwd_stages(int stages, const void* q, const void* k, const void* v, const void* w,
+                                                    const void* beta, const void* log_f, const void* o, const float* lse,
+                                                    const void* d_o, void* dq, void* dk, void* dv, void* dw, void* dbeta,
+                                                    void* dlog_f, int B, int H, int L, int d, int causal, float scale,
+                                                    path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
+    if (stages <= 0 || (stages & ~BWD_STAGE_ALL)) return PATH_ERR_UNSUPPORTED;
+    return bwd_impl(BWD_RESUME, stages, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, causal, scale, dt,
                     workspace, workspace_bytes, stream);
 }
 
@@ -651,7 +662,7 @@ extern "C" path_status_t path_attn_bwd_layout(const void* q, const void* k, cons
                                               float scale, path_dtype_t dt, void* workspace, size_t workspace_bytes,
                                               void* stream) {
     if (!layout_ok(layout)) return PATH_ERR_UNSUPPORTED;
-    return bwd_impl(BWD_FULL, layout_of(layout, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f,
+    return bwd_impl(BWD_FULL, BWD_STAGE_ALL, layout_of(layout, H, L, d), q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f,
                     B, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
 }
 
@@ -714,7 +725,7 @@ extern "C" path_status_t path_attn_varlen_bwd(const void* q, const void* k, cons
         const long long t0 = cu_seqlens[s];
         const int L = cu_seqlens[s + 1] - cu_seqlens[s];
         const long long hd = (long long)H * d;
-        const path_status_t st = bwd_impl(BWD_FULL, layout_of(PATH_LAYOUT_BLHD, H, L, d), at_token(q, t0, hd, es), at_token(k, t0, hd, es),
+        const path_status_t st = bwd_impl(BWD_FULL, BWD_STAGE_ALL, layout_of(PATH_LAYOUT_BLHD, H, L, d), at_token(q, t0, hd, es), at_token(k, t0, hd, es),
                                           at_token(v, t0, hd, es), at_token(w, t0, hd, es), at_token(beta, t0, H, es),
                                           at_token(log_f, t0, H, es), at_token(o, t0, hd, es), at_token(lse, t0, H, 4),
                                           at_token(d_o, t0, hd, es), at_token(dq, t0, hd, es), at_token(dk, t0, hd, es),

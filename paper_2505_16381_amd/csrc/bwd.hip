@@ -1276,54 +1276,62 @@ template <typename K> static hipError_t set_smem(K kernel, size_t bytes) {
     return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
+// stages: which of the kernels to launch (BWD_STAGE_* bits; all of them is the whole pass, in this order)
 template <typename TIO, int D>
-static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
+static hipError_t launch_scan_t(const BwdParams& p, int stages, hipStream_t st) {
     dim3 grid(p.NC, p.B * p.H);
-    hipError_t e;
-    if (p.ul.vt != D) hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D, true>), grid, dim3(256), 0, st, p);
-    else hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D, false>), grid, dim3(256), 0, st, p);
-    if ((e = hipGetLastError()) != hipSuccess) return e;
+    hipError_t e = hipSuccess;
+    if (stages & BWD_STAGE_SCAN) {
+        if (p.ul.vt != D) hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D, true>), grid, dim3(256), 0, st, p);
+        else hipLaunchKernelGGL((bwd_dotile_kernel<TIO, D, false>), grid, dim3(256), 0, st, p);
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     const size_t adj_bytes = Adj2Cfg<TIO, D>::smem_bytes, key_bytes = Key2Cfg<TIO, D>::smem_bytes;
     const int ntiles = (p.NC + 1) / 2;
     const int BH = p.B * p.H, nsb = (p.NC + SBC - 1) / SBC;
     const dim3 grid_adj((unsigned)(8 * ((BH + 7) / 8) * ntiles));
     const dim3 grid_key((unsigned)(8 * ((BH + 7) / 8) * nsb * SBC)), grid_key_far((unsigned)(8 * ((BH + 7) / 8) * nsb * (SBC / 2)));
     if (p.cum) {       // PaTH-FoX instantiations
-        if constexpr (sizeof(typename Compute<TIO>::type) == 2) {
-            const size_t lite_bytes = (size_t)Adj2Cfg<TIO, D>::STAGE_FRAGS * 16;
-            if ((e = set_smem(&bwd_adjoint2_lite_kernel<TIO, D, true>, lite_bytes)) != hipSuccess) return e;
-            hipLaunchKernelGGL((bwd_adjoint2_lite_kernel<TIO, D, true>), grid_adj, dim3(256), lite_bytes, st, p);
-        } else {
-        if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D, true>, adj_bytes)) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D, true>), grid_adj, dim3(256), adj_bytes, st, p);
+        if (stages & BWD_STAGE_SCAN) {
+            if constexpr (sizeof(typename Compute<TIO>::type) == 2) {
+                const size_t lite_bytes = (size_t)Adj2Cfg<TIO, D>::STAGE_FRAGS * 16;
+                if ((e = set_smem(&bwd_adjoint2_lite_kernel<TIO, D, true>, lite_bytes)) != hipSuccess) return e;
+                hipLaunchKernelGGL((bwd_adjoint2_lite_kernel<TIO, D, true>), grid_adj, dim3(256), lite_bytes, st, p);
+            } else {
+                if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D, true>, adj_bytes)) != hipSuccess) return e;
+                hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D, true>), grid_adj, dim3(256), adj_bytes, st, p);
+            }
+            if ((e = hipGetLastError()) != hipSuccess) return e;
         }
-        if ((e = hipGetLastError()) != hipSuccess) return e;
         if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, false, true>, key_bytes)) != hipSuccess) return e;
         if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, true, true>, key_bytes)) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, false, true>), grid_key, dim3(256), key_bytes, st, p);
+        if (stages & BWD_STAGE_KEYS_NEAR) hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, false, true>), grid_key, dim3(256), key_bytes, st, p);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, true, true>), grid_key_far, dim3(256), key_bytes, st, p);
+        if (stages & BWD_STAGE_KEYS_FAR) hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, true, true>), grid_key_far, dim3(256), key_bytes, st, p);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     } else {
-        if constexpr (sizeof(typename Compute<TIO>::type) == 2) {
-            const size_t lite_bytes = (size_t)Adj2Cfg<TIO, D>::STAGE_FRAGS * 16;
-            if ((e = set_smem(&bwd_adjoint2_lite_kernel<TIO, D, false>, lite_bytes)) != hipSuccess) return e;
-            hipLaunchKernelGGL((bwd_adjoint2_lite_kernel<TIO, D, false>), grid_adj, dim3(256), lite_bytes, st, p);
-        } else {
-        if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D, false>, adj_bytes)) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D, false>), grid_adj, dim3(256), adj_bytes, st, p);
+        if (stages & BWD_STAGE_SCAN) {
+            if constexpr (sizeof(typename Compute<TIO>::type) == 2) {
+                const size_t lite_bytes = (size_t)Adj2Cfg<TIO, D>::STAGE_FRAGS * 16;
+                if ((e = set_smem(&bwd_adjoint2_lite_kernel<TIO, D, false>, lite_bytes)) != hipSuccess) return e;
+                hipLaunchKernelGGL((bwd_adjoint2_lite_kernel<TIO, D, false>), grid_adj, dim3(256), lite_bytes, st, p);
+            } else {
+                if ((e = set_smem(&bwd_adjoint2_kernel<TIO, D, false>, adj_bytes)) != hipSuccess) return e;
+                hipLaunchKernelGGL((bwd_adjoint2_kernel<TIO, D, false>), grid_adj, dim3(256), adj_bytes, st, p);
+            }
+            if ((e = hipGetLastError()) != hipSuccess) return e;
         }
-        if ((e = hipGetLastError()) != hipSuccess) return e;
         if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, false, false>, key_bytes)) != hipSuccess) return e;
         if ((e = set_smem(&bwd_keyside2_kernel<TIO, D, true, false>, key_bytes)) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, false, false>), grid_key, dim3(256), key_bytes, st, p);
+        if (stages & BWD_STAGE_KEYS_NEAR) hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, false, false>), grid_key, dim3(256), key_bytes, st, p);
         if ((e = hipGetLastError()) != hipSuccess) return e;
-        hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, true, false>), grid_key_far, dim3(256), key_bytes, st, p);
+        if (stages & BWD_STAGE_KEYS_FAR) hipLaunchKernelGGL((bwd_keyside2_kernel<TIO, D, true, false>), grid_key_far, dim3(256), key_bytes, st, p);
         if ((e = hipGetLastError()) != hipSuccess) return e;
     }
     const size_t ddp_bytes = DdpCfg<TIO, D>::smem_bytes;
     if ((e = set_smem(&bwd_ddp_kernel<TIO, D, false>, ddp_bytes)) != hipSuccess) return e;
     if ((e = set_smem(&bwd_ddp_kernel<TIO, D, true>, ddp_bytes)) != hipSuccess) return e;
+    if (!(stages & BWD_STAGE_DDP)) return hipSuccess;
     if (sizeof(typename Compute<TIO>::type) != 2)       // 16-bit operands: the near key-side kernel has written ddP
         hipLaunchKernelGGL((bwd_ddp_kernel<TIO, D, false>), grid, dim3(256), ddp_bytes, st, p);
     if ((e = hipGetLastError()) != hipSuccess) return e;
@@ -1332,9 +1340,9 @@ static hipError_t launch_scan_t(const BwdParams& p, hipStream_t st) {
     return hipGetLastError();
 }
 
-hipError_t launch_bwd_scan(const BwdParams& p, int d, int is_bf16, hipStream_t st) {
-    if (is_bf16) return d == 64 ? launch_scan_t<bf16_t, 64>(p, st) : launch_scan_t<bf16_t, 128>(p, st);
-    return d == 64 ? launch_scan_t<float, 64>(p, st) : launch_scan_t<float, 128>(p, st);
+hipError_t launch_bwd_scan(const BwdParams& p, int d, int is_bf16, int stages, hipStream_t st) {
+    if (is_bf16) return d == 64 ? launch_scan_t<bf16_t, 64>(p, stages, st) : launch_scan_t<bf16_t, 128>(p, stages, st);
+    return d == 64 ? launch_scan_t<float, 64>(p, stages, st) : launch_scan_t<float, 128>(p, stages, st);
 }
 
 hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream_t st) {

@@ -135,7 +135,11 @@ struct ChunkFusedArgs {
 };
 hipError_t launch_chunk_fused(const ChunkFusedArgs& a, int BH, int d, hipStream_t st);
 
-hipError_t launch_bwd_scan(const BwdParams& p, int d, int is_bf16, hipStream_t st);
+// Stages of the backward after the transforms, as bits (the public PATH_BWD_STAGE_* values of the header):
+// dO tiles + adjoint scan | near key-side | far key-side | far (fp32: and near) ddP | second-level chain and
+// chunk-transform adjoint.  launch_bwd_scan runs the first four as asked, in this order.
+enum { BWD_STAGE_SCAN = 1, BWD_STAGE_KEYS_NEAR = 2, BWD_STAGE_KEYS_FAR = 4, BWD_STAGE_DDP = 8, BWD_STAGE_CHUNK = 16, BWD_STAGE_ALL = 31 };
+hipError_t launch_bwd_scan(const BwdParams& p, int d, int is_bf16, int stages, hipStream_t st);
 hipError_t launch_batched_gemm(const GemmArgs& a, int BH, int is_bf16, hipStream_t st);
 hipError_t launch_bwd_sb_chain(const SbChainArgs& a, int BH, int d, hipStream_t st);    // 2-byte operand types only
 

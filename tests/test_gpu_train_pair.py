@@ -107,3 +107,41 @@ def test_training_pair_rejects_a_forward_sized_workspace(gpu):
     small = torch.empty(pa.path_attn_workspace_bytes(B, H, L, d, pa.PATH_F32, False), dtype=torch.uint8, device="cuda")
     with pytest.raises(pa.PathAttnError):
         pa.path_attn_train_fwd(x["q"], x["k"], x["v"], x["w"], x["beta"], small)
+
+
+@pytest.mark.parametrize("dtype,L,d", [("bf16", 2200, 128), ("fp32", 1100, 64)])
+def test_backward_in_stages_equals_the_whole_call(gpu, dtype, L, d):
+    """path_attn_train_bwd_stages, one stage after the other in the order of the stage bits, is exactly
+    path_attn_train_bwd (bench.py times the stages this way); an unknown bit is refused."""
+    torch, pa = gpu
+    B, H = 1, 3
+    x = _inputs(B, H, L, d, dtype, 2300 + L + d, False)
+    dv = _dev(torch, x, dtype)
+    scale = d ** -0.5
+    dt = pa.PATH_F32 if dtype == "fp32" else pa.PATH_BF16
+    ws = torch.empty(pa.path_attn_workspace_bytes(B, H, L, d, dt, True), dtype=torch.uint8, device="cuda")
+    o, lse = pa.path_attn_train_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], ws, scale=scale)
+    whole = pa.path_attn_train_bwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], o, lse, dv["dO"], ws, scale=scale)
+    torch.cuda.synchronize()
+    o, lse = pa.path_attn_train_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], ws, scale=scale)
+    outs = [torch.full_like(dv["q"], 7.0) for _ in range(4)] + [torch.full_like(dv["beta"], 7.0)]
+    for bit in (pa.PATH_BWD_STAGE_SCAN, pa.PATH_BWD_STAGE_KEYS_NEAR, pa.PATH_BWD_STAGE_KEYS_FAR, pa.PATH_BWD_STAGE_DDP, pa.PATH_BWD_STAGE_CHUNK):
+        pa.path_attn_train_bwd_stages(bit, dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], o, lse, dv["dO"], outs, ws, scale=scale)
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(zip(whole, outs)):
+        assert torch.equal(a, b), i
+    with pytest.raises(pa.PathAttnError) as e:
+        pa.path_attn_train_bwd_stages(64, dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], o, lse, dv["dO"], outs, ws, scale=scale)
+    assert e.value.code == 4
+
+
+def test_mfma_probe_runs_and_reports_its_work(gpu):
+    torch, pa = gpu
+    sink = torch.zeros(1024 * 4 * 64, dtype=torch.float32, device="cuda")
+    for wps in (1, 2, 4):
+        flops = pa.path_probe_mfma(sink, wps, 50)
+        assert flops == 256.0 * 4 * wps * 50 * 16 * 2 * 32 * 32 * 16
+    torch.cuda.synchronize()
+    assert bool(torch.isfinite(sink).all())
+    with pytest.raises(pa.PathAttnError):
+        pa.path_probe_mfma(sink, 3, 50)

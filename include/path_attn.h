@@ -108,6 +108,19 @@ const char* path_attn_last_error(void);
  * arguments the entry points would reject. */
 size_t path_attn_workspace_bytes(int B, int H, int L, int d, path_dtype_t dt, int for_backward);
 
+/* A memory-bounded backward.  path_attn_bwd (and path_attn_fox_bwd, path_attn_bwd_layout, path_attn_varlen_bwd)
+ * accept ANY workspace that holds at least one head: every (batch, head) is an independent problem, so with less
+ * than path_attn_workspace_bytes(..., 1) the backward passes over the heads in groups of as many as fit -- the
+ * same kernels on smaller grids, the same arithmetic, bit-identical gradients; the price is more launches and,
+ * for small groups, a GPU that is not filled.  The query states that dominate the workspace (one per (query
+ * chunk, key block) pair) are stored only for the group in flight.
+ *   path_attn_bwd_workspace_bytes_for_heads: bytes that let `heads` (clamped to B*H) heads pass together;
+ *     heads = 1 is the minimum any backward accepts.  0 for arguments the entry points reject.
+ *   path_attn_bwd_heads_per_pass: heads per pass a workspace of that size gives (0: too small even for one).
+ * The training pair (path_attn_train_*) keeps the states of ALL heads between its two calls and needs the full size. */
+size_t path_attn_bwd_workspace_bytes_for_heads(int B, int H, int L, int d, path_dtype_t dt, int heads);
+int path_attn_bwd_heads_per_pass(int B, int H, int L, int d, path_dtype_t dt, size_t workspace_bytes);
+
 /* Introspection for tests and profiling: byte offsets, inside the forward
  * workspace, of the five intermediates the chunk-preprocessing kernel (paper
  * Sec. 3.2) hands to the sweep kernel, in this order: boundary-adjusted key

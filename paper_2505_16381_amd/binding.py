@@ -89,6 +89,10 @@ def load_library():
     lib.path_key_prefill.argtypes = [vp, ci, ci, ci, ci, ci, vp, sz, vp, vp, ci, vp]
     lib.path_decode_step.restype = ci
     lib.path_decode_step.argtypes = [vp] * 7 + [ci, ci, vp, vp, ci, ci, ci, cf, ci, vp, sz, vp]
+    lib.path_attn_bwd_workspace_bytes_for_heads.restype = sz
+    lib.path_attn_bwd_workspace_bytes_for_heads.argtypes = [ci, ci, ci, ci, ci, ci]
+    lib.path_attn_bwd_heads_per_pass.restype = ci
+    lib.path_attn_bwd_heads_per_pass.argtypes = [ci, ci, ci, ci, ci, sz]
     lib.path_attn_train_bwd_stages.restype = ci
     lib.path_attn_train_bwd_stages.argtypes = [ci] + [vp] * 15 + [ci, ci, ci, ci, ci, cf, ci, vp, sz, vp]
     lib.path_probe_mfma_flops.restype = ctypes.c_double
@@ -109,6 +113,15 @@ def path_status_str(code: int) -> str:
 
 def path_attn_workspace_bytes(B, H, L, d, dt, for_backward=False) -> int:
     return int(load_library().path_attn_workspace_bytes(B, H, L, d, dt, int(bool(for_backward))))
+
+
+def path_attn_bwd_workspace_bytes_for_heads(B, H, L, d, dt, heads) -> int:
+    """Bytes that let the self-contained backward pass over ``heads`` heads at a time (1 = the minimum)."""
+    return int(load_library().path_attn_bwd_workspace_bytes_for_heads(B, H, L, d, dt, int(heads)))
+
+
+def path_attn_bwd_heads_per_pass(B, H, L, d, dt, workspace_bytes) -> int:
+    return int(load_library().path_attn_bwd_heads_per_pass(B, H, L, d, dt, int(workspace_bytes)))
 
 
 def path_attn_fwd_workspace_layout(B, H, L, d, dt):

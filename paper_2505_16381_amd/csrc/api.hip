@@ -137,6 +137,19 @@ extern "C" size_t path_attn_workspace_bytes(int B, int H, int L, int d, path_dty
     return fwd_workspace(B, H, L, d, es).total;
 }
 
+static int heads_per_pass(int B, int H, int L, int d, size_t es, size_t bytes);
+
+extern "C" size_t path_attn_bwd_workspace_bytes_for_heads(int B, int H, int L, int d, path_dtype_t dt, int heads) {
+    if (!shape_ok(B, H, L, d) || (dt != PATH_F32 && dt != PATH_BF16) || heads < 1) return 0;
+    if (heads > B * H) heads = B * H;
+    return bwd_workspace(1, heads, L, d, dt == PATH_BF16 ? 2 : 4).total;
+}
+
+extern "C" int path_attn_bwd_heads_per_pass(int B, int H, int L, int d, path_dtype_t dt, size_t workspace_bytes) {
+    if (!shape_ok(B, H, L, d) || (dt != PATH_F32 && dt != PATH_BF16)) return 0;
+    return heads_per_pass(B, H, L, d, dt == PATH_BF16 ? 2 : 4, workspace_bytes);
+}
+
 extern "C" path_status_t path_attn_fwd_workspace_layout(int B, int H, int L, int d, path_dtype_t dt,
                                                         size_t offsets[6]) {
     if (!offsets) return PATH_ERR_NULL;
@@ -155,6 +168,7 @@ static bool layout_ok(int layout) { return layout == PATH_LAYOUT_BHLD || layout 
 static UserLayout layout_of(int layout, int H, int L, int d) {
     UserLayout u;
     u.H = H;
+    u.bh0 = 0;
     if (layout == PATH_LAYOUT_BLHD) {
         u.vb = (long long)L * H * d; u.vh = d; u.vt = (long long)H * d;
         u.sb = (long long)L * H; u.sh = 1; u.st = H;
@@ -265,6 +279,24 @@ enum BwdMode { BWD_FULL = 0,        // transforms + backward (path_attn_bwd)
                BWD_RESUME = 2,      // backward without the transforms (the workspace is as BWD_FWD_ONLY left it)
                BWD_FWD_PREP = 3,    // the two halves of BWD_FWD_ONLY as separate calls: transforms ...
                BWD_FWD_SWEEP = 4 }; // ... and the forward sweep
+static path_status_t bwd_run(BwdMode mode, int stages, const UserLayout& ul, const void* q, const void* k, const void* v, const void* w,
+                             const void* beta, const void* log_f, const void* o, const float* lse, const void* d_o,
+                             void* dq, void* dk, void* dv, void* dw, void* dbeta, void* dlog_f, int B, int H,
+                             int L, int d, float scale, path_dtype_t dt, void* workspace, void* stream);
+
+// Heads per pass of a self-contained backward in a workspace of `bytes`: all B*H if they fit, else the largest
+// number of heads whose workspace does (0: not even one).
+static int heads_per_pass(int B, int H, int L, int d, size_t es, size_t bytes) {
+    const int BH = B * H;
+    if (bwd_workspace(1, BH, L, d, es).total <= bytes) return BH;
+    int lo = 0, hi = BH;                               // the size grows with the number of heads
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) / 2;
+        if (bwd_workspace(1, mid, L, d, es).total <= bytes) lo = mid; else hi = mid;
+    }
+    return lo;
+}
+
 static path_status_t bwd_impl(BwdMode mode, int stages, const UserLayout& ul, const void* q, const void* k, const void* v, const void* w,
                               const void* beta, const void* log_f, const void* o, const float* lse, const void* d_o,
                               void* dq, void* dk, void* dv, void* dw, void* dbeta, void* dlog_f, int B, int H,
@@ -283,10 +315,36 @@ static path_status_t bwd_impl(BwdMode mode, int stages, const UserLayout& ul, co
     if (!causal || !(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
     const void* al[] = {q, k, v, w, o, d_o, dq, dk, dv, dw};
     for (const void* ptr : al) if (misaligned(ptr)) return PATH_ERR_ALIGN;      // (NULL is aligned)
+    const size_t es = dt == PATH_BF16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(workspace) & 255) return PATH_ERR_WORKSPACE;
+    clear_inherited_error();
+    if (mode != BWD_FULL) {            // the halves of a training pair share everything in the workspace: all heads at once
+        if (workspace_bytes < bwd_workspace(B, H, L, d, es).total) return PATH_ERR_WORKSPACE;
+        return bwd_run(mode, stages, ul, q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, B, H, L, d, scale, dt, workspace, stream);
+    }
+    // The self-contained backward passes over the heads in groups of as many as the workspace holds: the heads are
+    // independent problems, so a smaller workspace costs launches, not arithmetic.
+    const int BH = B * H, G = heads_per_pass(B, H, L, d, es, workspace_bytes);
+    if (G < 1) return PATH_ERR_WORKSPACE;
+    for (int bh0 = 0; bh0 < BH; bh0 += G) {
+        UserLayout ug = ul;
+        ug.bh0 = bh0;
+        const path_status_t st = bwd_run(mode, stages, ug, q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f,
+                                         1, BH - bh0 < G ? BH - bh0 : G, L, d, scale, dt, workspace, stream);
+        if (st != PATH_OK) return st;
+    }
+    return PATH_OK;
+}
+
+// One pass: the heads ul.bh0 .. ul.bh0 + B*H - 1 of the caller's tensors, numbered from 0 in the workspace.
+static path_status_t bwd_run(BwdMode mode, int stages, const UserLayout& ul, const void* q, const void* k, const void* v, const void* w,
+                             const void* beta, const void* log_f, const void* o, const float* lse, const void* d_o,
+                             void* dq, void* dk, void* dv, void* dw, void* dbeta, void* dlog_f, int B, int H,
+                             int L, int d, float scale, path_dtype_t dt, void* workspace, void* stream) {
+    const bool fwd_mode = mode == BWD_FWD_ONLY || mode == BWD_FWD_PREP || mode == BWD_FWD_SWEEP;
     const int bf = dt == PATH_BF16;
     const size_t es = bf ? 2 : 4;
     const BwdWorkspace ws = bwd_workspace(B, H, L, d, es);
-    if (workspace_bytes < ws.total || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PATH_ERR_WORKSPACE;
     unsigned char* base = static_cast<unsigned char*>(workspace);
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int NC = (L + CHUNK - 1) / CHUNK, BH = B * H;
@@ -304,7 +362,6 @@ static path_status_t bwd_impl(BwdMode mode, int stages, const UserLayout& ul, co
     fp.ktT = base + ws.ktT; fp.vk = base + ws.vk; fp.dpt = base + ws.dpt; fp.xs = base + ws.xs; fp.xsT = base + ws.xsT;
     fp.fm = base + ws.fm; fp.gktm = base + ws.gktm; fp.nm = base + ws.nm; fp.aim = base + ws.aim;
     fp.ytm = base + ws.ytm; fp.utm = base + ws.utm; fp.gm = F(ws.gm); fp.sdm = F(ws.sdm);
-    clear_inherited_error();
     float* cum = log_f ? F(ws.f.cum) : nullptr;
     if (mode != BWD_RESUME && mode != BWD_FWD_SWEEP) {
         if (log_f && !hip_ok(launch_gate_sums(log_f, ul, cum, B, H, L, dt, st), "gate sums (backward)")) return PATH_ERR_HIP;

@@ -282,14 +282,20 @@ struct FwdWorkspace {
 // [.,.,.,d] tensors (q, k, v, w, o and the gradients; d contiguous) and for the per-token scalars
 // (beta, lse, log f and their gradients).  [B,H,L,d]: {H*L*d, L*d, d | H*L, L, 1};
 // [B,L,H,d]: {L*H*d, d, H*d | L*H, 1, H}.  H = heads per batch entry (bh = b * H + h).
+// bh0: the kernels of one launch may work on a slice of the heads (a backward that passes over the heads in
+// groups to bound its workspace); they number their heads from 0, and head bh of the launch is head bh0 + bh of
+// the caller's tensors.
 struct UserLayout {
     long long vb, vh, vt, sb, sh, st;
     int H;
+    int bh0;
 };
 __host__ __device__ __forceinline__ long long user_vec(const UserLayout& u, int bh, long long t) {
+    bh += u.bh0;
     return (bh / u.H) * u.vb + (bh % u.H) * u.vh + t * u.vt;
 }
 __host__ __device__ __forceinline__ long long user_scl(const UserLayout& u, int bh, long long t) {
+    bh += u.bh0;
     return (bh / u.H) * u.sb + (bh % u.H) * u.sh + t * u.st;
 }
 

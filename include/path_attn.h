@@ -265,10 +265,15 @@ path_status_t path_attn_bwd_layout(const void* q, const void* k, const void* v, 
  * Variable-length batches: nseq sequences packed along the token axis, q, k, v, w, o and gradients
  * [T,H,d], beta, lse, log_f and gradients [T,H] (T = cu_seqlens[nseq]); sequence s owns the tokens
  * cu_seqlens[s] .. cu_seqlens[s+1]-1 and attends only to itself.  cu_seqlens is a HOST array of nseq+1
- * ints (cu_seqlens[0] = 0, strictly increasing; else PATH_ERR_SHAPE); it is read before the call returns.
- * Each sequence is one problem of its own length in the [1,L_s,H,d] layout; the sequences are enqueued one
- * after the other on `stream` and share the workspace, which must hold
- * path_attn_varlen_workspace_bytes(...) bytes (that of the longest sequence).  log_f / dlog_f as above.
+ * ints (cu_seqlens[0] = 0, strictly increasing; else PATH_ERR_SHAPE); it is read before the call returns
+ * (copied to the head of the workspace on `stream`).
+ * The whole batch is ONE set of kernel launches: sequence s is batch entry s of a problem whose workspace
+ * arrays are sized for the longest sequence, every kernel takes its bounds from the entry's own length, and
+ * workgroups beyond a shorter sequence's end exit at once -- results are bit-identical to calling the
+ * fixed-length entry points sequence by sequence on [1,L_s,H,d] tensors.  The workspace must hold
+ * path_attn_varlen_workspace_bytes(...) bytes: the sequence table plus path_attn_workspace_bytes(nseq, H,
+ * longest length, ...); the backward also accepts less, down to the table plus one head's worth (see the
+ * memory-bounded backward above).  log_f / dlog_f as above.
  */
 size_t path_attn_varlen_workspace_bytes(const int* cu_seqlens, int nseq, int H, int d, path_dtype_t dt,
                                         int for_backward);

@@ -169,6 +169,7 @@ static UserLayout layout_of(int layout, int H, int L, int d) {
     UserLayout u;
     u.H = H;
     u.bh0 = 0;
+    u.cu = nullptr;
     if (layout == PATH_LAYOUT_BLHD) {
         u.vb = (long long)L * H * d; u.vh = d; u.vt = (long long)H * d;
         u.sb = (long long)L * H; u.sh = 1; u.st = H;
@@ -723,7 +724,10 @@ extern "C" path_status_t path_attn_bwd_layout(const void* q, const void* k, cons
                     B, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
 }
 
-// Packed sequences [T,H,d]: sequence s is a [1,L_s,H,d] problem whose tensors start at token cu_seqlens[s].
+// Packed sequences [T,H,d]: ONE set of launches for the whole batch.  Sequence s is batch entry s of a problem
+// with B = nseq whose workspace arrays are sized for the longest sequence; the kernels take every bound from the
+// entry's own length (a device copy of cu_seqlens, kept at the start of the workspace) and address the caller's
+// tensors from token cu_seqlens[s] on.  Workgroups beyond a shorter sequence's last chunk exit at once.
 static bool varlen_ok(const int* cu, int nseq, int* lmax) {
     if (!cu || nseq < 1 || cu[0] != 0) return false;
     int m = 0;
@@ -735,37 +739,52 @@ static bool varlen_ok(const int* cu, int nseq, int* lmax) {
     *lmax = m;
     return true;
 }
-template <typename P> static P* at_token(P* base, long long tok, long long per_token, size_t es) {
-    typedef typename std::conditional<std::is_const<P>::value, const unsigned char, unsigned char>::type B;
-    return base ? reinterpret_cast<P*>(reinterpret_cast<B*>(base) + (size_t)(tok * per_token) * es) : nullptr;
+static size_t cu_table_bytes(int nseq) { return align256((size_t)(nseq + 1) * sizeof(int)); }
+static UserLayout varlen_layout(int H, int d, const int* cu_device) {
+    UserLayout u;
+    u.H = H; u.bh0 = 0; u.cu = cu_device;
+    u.vb = 0; u.vh = d; u.vt = (long long)H * d;
+    u.sb = 0; u.sh = 1; u.st = H;
+    return u;
+}
+// copies the table to the head of the workspace (the host array may be pageable: the runtime stages it before
+// the call returns) and splits the workspace
+static path_status_t varlen_setup(const int* cu, int nseq, int H, int d, path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                                  void* stream, int* lmax, UserLayout* ul, void** rest, size_t* rest_bytes) {
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (!varlen_ok(cu, nseq, lmax) || !shape_ok(nseq, H, *lmax, d)) return PATH_ERR_SHAPE;
+    if (!workspace) return PATH_ERR_NULL;
+    const size_t tb = cu_table_bytes(nseq);
+    if (workspace_bytes <= tb || (reinterpret_cast<uintptr_t>(workspace) & 255)) return PATH_ERR_WORKSPACE;
+    clear_inherited_error();
+    if (!hip_ok(hipMemcpyAsync(workspace, cu, (size_t)(nseq + 1) * sizeof(int), hipMemcpyHostToDevice, static_cast<hipStream_t>(stream)),
+                "sequence table copy"))
+        return PATH_ERR_HIP;
+    *ul = varlen_layout(H, d, static_cast<const int*>(workspace));
+    *rest = static_cast<unsigned char*>(workspace) + tb;
+    *rest_bytes = workspace_bytes - tb;
+    return PATH_OK;
 }
 
 extern "C" size_t path_attn_varlen_workspace_bytes(const int* cu_seqlens, int nseq, int H, int d, path_dtype_t dt,
                                                    int for_backward) {
     int lmax = 0;
     if (!varlen_ok(cu_seqlens, nseq, &lmax)) return 0;
-    return path_attn_workspace_bytes(1, H, lmax, d, dt, for_backward);
+    const size_t body = path_attn_workspace_bytes(nseq, H, lmax, d, dt, for_backward);
+    return body ? cu_table_bytes(nseq) + body : 0;
 }
 
 extern "C" path_status_t path_attn_varlen_fwd(const void* q, const void* k, const void* v, const void* w,
                                               const void* beta, const void* log_f, void* o, float* lse,
                                               const int* cu_seqlens, int nseq, int H, int d, int causal, float scale,
                                               path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
-    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
     int lmax = 0;
-    if (!varlen_ok(cu_seqlens, nseq, &lmax)) return PATH_ERR_SHAPE;
-    const size_t es = dt == PATH_BF16 ? 2 : 4;
-    for (int s = 0; s < nseq; ++s) {         // one after the other on the stream: they share the workspace
-        const long long t0 = cu_seqlens[s];
-        const int L = cu_seqlens[s + 1] - cu_seqlens[s];
-        const long long hd = (long long)H * d;
-        const path_status_t st = fwd_impl(0, layout_of(PATH_LAYOUT_BLHD, H, L, d), at_token(q, t0, hd, es), at_token(k, t0, hd, es),
-                                          at_token(v, t0, hd, es), at_token(w, t0, hd, es), at_token(beta, t0, H, es),
-                                          at_token(log_f, t0, H, es), log_f != nullptr, at_token(o, t0, hd, es),
-                                          at_token(lse, t0, H, 4), 1, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
-        if (st != PATH_OK) return st;
-    }
-    return PATH_OK;
+    UserLayout ul;
+    void* rest = nullptr;
+    size_t rest_bytes = 0;
+    const path_status_t st = varlen_setup(cu_seqlens, nseq, H, d, dt, workspace, workspace_bytes, stream, &lmax, &ul, &rest, &rest_bytes);
+    if (st != PATH_OK) return st;
+    return fwd_impl(0, ul, q, k, v, w, beta, log_f, log_f != nullptr, o, lse, nseq, H, lmax, d, causal, scale, dt, rest, rest_bytes, stream);
 }
 
 extern "C" path_status_t path_attn_varlen_bwd(const void* q, const void* k, const void* v, const void* w,
@@ -774,21 +793,12 @@ extern "C" path_status_t path_attn_varlen_bwd(const void* q, const void* k, cons
                                               void* dlog_f, const int* cu_seqlens, int nseq, int H, int d, int causal,
                                               float scale, path_dtype_t dt, void* workspace, size_t workspace_bytes,
                                               void* stream) {
-    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
     int lmax = 0;
-    if (!varlen_ok(cu_seqlens, nseq, &lmax)) return PATH_ERR_SHAPE;
-    const size_t es = dt == PATH_BF16 ? 2 : 4;
-    for (int s = 0; s < nseq; ++s) {
-        const long long t0 = cu_seqlens[s];
-        const int L = cu_seqlens[s + 1] - cu_seqlens[s];
-        const long long hd = (long long)H * d;
-        const path_status_t st = bwd_impl(BWD_FULL, BWD_STAGE_ALL, layout_of(PATH_LAYOUT_BLHD, H, L, d), at_token(q, t0, hd, es), at_token(k, t0, hd, es),
-                                          at_token(v, t0, hd, es), at_token(w, t0, hd, es), at_token(beta, t0, H, es),
-                                          at_token(log_f, t0, H, es), at_token(o, t0, hd, es), at_token(lse, t0, H, 4),
-                                          at_token(d_o, t0, hd, es), at_token(dq, t0, hd, es), at_token(dk, t0, hd, es),
-                                          at_token(dv, t0, hd, es), at_token(dw, t0, hd, es), at_token(dbeta, t0, H, es),
-                                          at_token(dlog_f, t0, H, es), 1, H, L, d, causal, scale, dt, workspace, workspace_bytes, stream);
-        if (st != PATH_OK) return st;
-    }
-    return PATH_OK;
+    UserLayout ul;
+    void* rest = nullptr;
+    size_t rest_bytes = 0;
+    const path_status_t st = varlen_setup(cu_seqlens, nseq, H, d, dt, workspace, workspace_bytes, stream, &lmax, &ul, &rest, &rest_bytes);
+    if (st != PATH_OK) return st;
+    return bwd_impl(BWD_FULL, BWD_STAGE_ALL, ul, q, k, v, w, beta, log_f, o, lse, d_o, dq, dk, dv, dw, dbeta, dlog_f, nseq, H, lmax, d,
+                    causal, scale, dt, rest, rest_bytes, stream);
 }

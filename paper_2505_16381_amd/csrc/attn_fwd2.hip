@@ -69,7 +69,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     Frag* sP = sKV + 4 * HF;                                    // -dP tile
     float* sC = reinterpret_cast<float*>(sP + DPF);             // FOX: [2 stages][32] gate sums of the stage's keys
 
-    const int BH = p.B * p.H, L = p.L, NC = p.NC;
+    const int BH = p.B * p.H, NC = p.NC;            // NC: chunks per head in the workspace arrays and in the grid's numbering
     const int ntiles = (NC + FWD2_CPT - 1) / FWD2_CPT;
     // XCD-aware numbering: workgroup b runs on XCD b % 8; that XCD takes heads xcd, xcd+8, ...
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -80,10 +80,12 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
 
+    const int L = seq_len(p.ul, bh, p.L), NCown = (L + CHUNK - 1) / CHUNK;     // this head's own length (packed batches: may be shorter)
+    if (tile * FWD2_CPT >= NCown) return;
     const int cq = tile * FWD2_CPT + (wv >> 1);     // this wave's chunk
     const int qb = wv & 1;                          // ... and which 32-query half of it
-    const bool active = cq < NC;
-    const int jtop = (tile * FWD2_CPT + FWD2_CPT - 1 < NC) ? tile * FWD2_CPT + FWD2_CPT - 1 : NC - 1;
+    const bool active = cq < NCown;
+    const int jtop = (tile * FWD2_CPT + FWD2_CPT - 1 < NCown) ? tile * FWD2_CPT + FWD2_CPT - 1 : NCown - 1;
     static_assert(SBC % FWD2_CPT == 0, "a tile must lie in one super-block");
     const int jsb = (tile * FWD2_CPT / SBC) * SBC;  // first chunk of the tile's own super-block
     const int nsb = (NC + SBC - 1) / SBC;

@@ -42,7 +42,8 @@ __global__ __launch_bounds__(256) void bwd_dotile_kernel(BwdParams p) {
     __shared__ __attribute__((aligned(16))) TIO sdo[CHUNK * LD];
     const int i = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
-    const int L = p.L, NC = p.NC;
+    const int L = seq_len(p.ul, bh, p.L), NC = p.NC;      // this head's own length; NC: chunks per head in the workspace arrays
+    if (i * CHUNK >= L) return;                            // (packed batch: a shorter sequence has fewer chunks)
     const long long tok0 = user_vec(p.ul, bh, (long long)i * CHUNK);
     const TIO* dO = reinterpret_cast<const TIO*>(p.dO) + tok0;
     const TIO* O = reinterpret_cast<const TIO*>(p.o) + tok0;
@@ -129,7 +130,7 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     Frag* sbase = reinterpret_cast<Frag*>(smem);
 
-    const int BH = p.B * p.H, L = p.L, NC = p.NC;
+    const int BH = p.B * p.H, NC = p.NC;
     const int ntiles = (NC + 1) / 2;
     // XCD-aware numbering: workgroup n runs on XCD n % 8; that XCD takes heads xcd, xcd+8, ... one
     // after the other, all tiles of a head together (heaviest first).  They walk the key chunks
@@ -139,9 +140,11 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
     const int tile = __builtin_amdgcn_readfirstlane(ntiles - 1 - slot % ntiles);     // back to scalar registers)
     if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
+    const int NCo = (seq_len(p.ul, bh, p.L) + CHUNK - 1) / CHUNK;          // this head's own chunks (NC: per head in the workspace arrays)
+    if (tile * 2 >= NCo) return;
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
-    const bool active = cq < NC;
-    const int jmax = ((tile * 2 + 1 < NC) ? tile * 2 + 1 : NC - 1) - 1;     // last key chunk any wave needs
+    const bool active = cq < NCo;
+    const int jmax = ((tile * 2 + 1 < NCo) ? tile * 2 + 1 : NCo - 1) - 1;   // last key chunk any wave needs
     const int jsb = (tile * 2 / SBC) * SBC;                                // first chunk of the tile's own super-block
     const size_t Lp = (size_t)NC * CHUNK, nslots = num_block_slots(NC);
     const float sl2 = p.scale * 1.44269504088896340736f;
@@ -354,9 +357,11 @@ __global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) 
     const int tile = __builtin_amdgcn_readfirstlane(ntiles - 1 - slot % ntiles);     // back to scalar registers)
     if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
+    const int NCo = (seq_len(p.ul, bh, p.L) + CHUNK - 1) / CHUNK;          // this head's own chunks (NC: per head in the workspace arrays)
+    if (tile * 2 >= NCo) return;
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
-    const bool active = cq < NC;
-    const int jmax = ((tile * 2 + 1 < NC) ? tile * 2 + 1 : NC - 1) - 1;
+    const bool active = cq < NCo;
+    const int jmax = ((tile * 2 + 1 < NCo) ? tile * 2 + 1 : NCo - 1) - 1;
     const int jsb = (tile * 2 / SBC) * SBC;
     const size_t Lp = (size_t)NC * CHUNK, nslots = num_block_slots(NC);
     const float sl2 = p.scale * 1.44269504088896340736f;
@@ -563,22 +568,24 @@ __global__ __launch_bounds__(256) void bwd_keyside2_kernel(BwdParams p) {
     // Far: TWO key chunks per workgroup (they share every staged tile), wave w = key half (w & 1)
     // of chunk j + (w >> 1), both query halves in turn.
     constexpr int CPW = FAR ? 2 : 1, NPOS = SBC / CPW;
-    const int L = p.L, NC = p.NC;
+    const int NC = p.NC;                                        // chunks per head in the workspace arrays and the grid's numbering
     const int nsb_g = (NC + SBC - 1) / SBC;
     const int xcd = blockIdx.x & 7, kk = blockIdx.x >> 3;
     // (the divisions run on the vector unit; their results go back to scalar registers)
     const int j = __builtin_amdgcn_readfirstlane((kk / NPOS % nsb_g) * SBC + (kk % NPOS) * CPW);       // first key chunk of the workgroup
     const int bh = __builtin_amdgcn_readfirstlane((kk / (NPOS * nsb_g)) * 8 + xcd);
-    if (bh >= p.B * p.H || j >= NC) return;
+    if (bh >= p.B * p.H) return;
+    const int NCo = (seq_len(p.ul, bh, p.L) + CHUNK - 1) / CHUNK;      // this head's own chunks
+    if (j >= NCo) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int kh = wv & 1;
     const int jw = FAR ? j + (wv >> 1) : j;                            // this wave's key chunk
-    const bool wactive = jw < NC;
+    const bool wactive = jw < NCo;
     const size_t Lp = (size_t)NC * CHUNK, nslots = num_block_slots(NC);
     const float sl2 = p.scale * 1.44269504088896340736f;
     const int sb_end = (j / SBC + 1) * SBC;                       // first chunk right of j's super-block
     const int i0 = FAR ? sb_end : j + 1;
-    const int i1 = FAR ? NC : (sb_end < NC ? sb_end : NC);
+    const int i1 = FAR ? NCo : (sb_end < NCo ? sb_end : NCo);
 
     Frag Kb[DS];
     FragV Vb[DS];
@@ -954,12 +961,13 @@ __global__ __launch_bounds__(256) void bwd_ddp_kernel(BwdParams p) {
     Frag* sbase = reinterpret_cast<Frag*>(smem);
     const int j = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
-    const int NC = p.NC;
+    const int NC = p.NC;                                          // chunks per head in the workspace arrays
+    const int NCo = (seq_len(p.ul, bh, p.L) + CHUNK - 1) / CHUNK;  // this head's own chunks
     const size_t nslots = num_block_slots(NC);
     const int cj = FAR ? j * SBC : j;                             // a key chunk of the block
     const int sb_end = (cj / SBC + 1) * SBC;
     const int i0 = FAR ? sb_end : j + 1;
-    const int i1 = FAR ? NC : (sb_end < NC ? sb_end : NC);
+    const int i1 = FAR ? NCo : (sb_end < NCo ? sb_end : NCo);       // (no queries to the right: the sums are zero)
     f32x16 acc[NOWN];
 #pragma unroll
     for (int o = 0; o < NOWN; ++o) acc[o] = zero16();
@@ -1095,10 +1103,11 @@ __global__ __launch_bounds__(256) void batched_gemm_kernel(GemmArgs a) {
     T* As = reinterpret_cast<T*>(smem);
     T* Bs = As + a.M * ld;
     const int chunk = blockIdx.x * a.cmul + a.cadd, bh = blockIdx.y;
-    if (chunk >= a.NC) return;
+    const int Lown = seq_len(a.ul, bh, a.L);               // this head's own length (packed batches: may be shorter than a.L)
+    if (chunk >= a.NC || chunk * CHUNK >= Lown) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
-    stage_mat<TIO>(a.A, a.ul, As, ld, a.M, a.K, bh, chunk, a.L, tid);
-    stage_mat<TIO>(a.B, a.ul, Bs, ld, a.N, a.K, bh, chunk, a.L, tid);
+    stage_mat<TIO>(a.A, a.ul, As, ld, a.M, a.K, bh, chunk, Lown, tid);
+    stage_mat<TIO>(a.B, a.ul, Bs, ld, a.N, a.K, bh, chunk, Lown, tid);
     __syncthreads();
     const int nb = a.N / 32, nblk = (a.M / 32) * nb;
     const long long cbase = bh * a.c_bh + chunk * a.c_ch;
@@ -1140,7 +1149,7 @@ __device__ __forceinline__ void chunk_diag(const DiagArgs& a, const UserLayout& 
     for (int idx = tid; idx < 4096; idx += 256) {
         const int t = idx >> 6, s = idx & 63, tg = chunk * CHUNK + t;
         float P = 0.f, ds = 0.f;
-        if (s <= t && tg < a.L) {
+        if (s <= t && tg < seq_len(ul, bh, a.L)) {
             float z = a.scale * a.sdm[base + idx] - a.lse[user_scl(ul, bh, tg)];
             if (FOX) {     // PaTH-FoX: + c_t - c_s (the gate sums are kept in base-2 units)
                 const float* c = a.cum + (size_t)bh * a.NC * CHUNK + (size_t)chunk * CHUNK;
@@ -1169,7 +1178,7 @@ __device__ __forceinline__ void chunk_beta(const BetaArgs& a, const UserLayout& 
     const size_t base = ((size_t)bh * a.NC + chunk) * 4096;
     if (tid < CHUNK) {
         const int tg = chunk * CHUNK + tid;
-        bs[tid] = (tg < a.L) ? (float)reinterpret_cast<const TIO*>(a.beta)[user_scl(ul, bh, tg)] : 0.f;
+        bs[tid] = (tg < seq_len(ul, bh, a.L)) ? (float)reinterpret_cast<const TIO*>(a.beta)[user_scl(ul, bh, tg)] : 0.f;
     }
     __syncthreads();
     for (int idx = tid; idx < 4096; idx += 256) {
@@ -1187,16 +1196,17 @@ __device__ __forceinline__ void chunk_beta(const BetaArgs& a, const UserLayout& 
 template <typename TIO>
 __device__ __forceinline__ void chunk_store(const OutArgs& a, const UserLayout& ul, int chunk, int bh, int tid) {
     const size_t Lp = (size_t)a.NC * CHUNK;
+    const int Lown = seq_len(ul, bh, a.L);
     for (int idx = tid; idx < CHUNK * a.d; idx += 256) {
         const int t = idx / a.d, c = idx % a.d, tg = chunk * CHUNK + t;
-        if (tg >= a.L) continue;
+        if (tg >= Lown) continue;
         const size_t src = ((size_t)bh * Lp + tg) * a.d + c, dst = (size_t)(user_vec(ul, bh, tg) + c);
         reinterpret_cast<TIO*>(a.dq)[dst] = (TIO)a.dqf[src];
         reinterpret_cast<TIO*>(a.dk)[dst] = (TIO)a.dkf[src];
         reinterpret_cast<TIO*>(a.dv)[dst] = (TIO)a.dvf[src];
         reinterpret_cast<TIO*>(a.dw)[dst] = (TIO)a.dwf[src];
     }
-    if (tid < CHUNK && chunk * CHUNK + tid < a.L)
+    if (tid < CHUNK && chunk * CHUNK + tid < Lown)
         reinterpret_cast<TIO*>(a.dbeta)[user_scl(ul, bh, chunk * CHUNK + tid)] = (TIO)a.dbf[(size_t)bh * Lp + chunk * CHUNK + tid];
 }
 
@@ -1214,6 +1224,8 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int chunk = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
+    const int Lown = seq_len(pr.ul, bh, pr.L);             // this head's own length (packed batches: may be shorter than pr.L)
+    if (chunk * CHUNK >= Lown) return;
     f32x16 acc[2];
     for (int i = 0; i < pr.n; ++i) {
         const ChunkOp& op = pr.ops[i];
@@ -1227,7 +1239,7 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
         const int N = op.N, K = op.K, ld = K + FE;
         T* As = reinterpret_cast<T*>(smem);
         T* Bs = As + CHUNK * ld;
-        stage_mat<TIO, CHUNK_NB>(op.A, pr.ul, As, ld, CHUNK, K, bh, chunk, pr.L, tid, op.alpha);
+        stage_mat<TIO, CHUNK_NB>(op.A, pr.ul, As, ld, CHUNK, K, bh, chunk, Lown, tid, op.alpha);
         const long long cbase = bh * op.c_bh + chunk * op.c_ch;
         const int mb = wv >> 1;
 #pragma unroll
@@ -1236,7 +1248,7 @@ __global__ __launch_bounds__(256, 3) void chunk_adjoint_kernel(ChunkProgram pr) 
             if (o > 0) __syncthreads();                    // the first half's fragments have been read
             MatRef bhalf = op.B;                           // rows 64*o .. 64*o+63 of B (features, never tokens)
             bhalf.p = reinterpret_cast<const char*>(op.B.p) + (size_t)(64 * o) * op.B.rs * (op.B.type == EL_F32 ? 4 : sizeof(T));
-            stage_mat<TIO, CHUNK_NB>(bhalf, pr.ul, Bs, ld, 64, K, bh, chunk, pr.L, tid);
+            stage_mat<TIO, CHUNK_NB>(bhalf, pr.ul, Bs, ld, 64, K, bh, chunk, Lown, tid);
             __syncthreads();
             const int cb = 2 * o + (wv & 1), cbl = wv & 1;
             if (op.first) {

@@ -109,7 +109,8 @@ __global__ __launch_bounds__(CA_NT) void chunk_fused_kernel(ChunkFusedArgs a) {
 
     const int chunk = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
-    const int L = a.L, NC = a.NC;
+    const int L = seq_len(a.ul, bh, a.L), NC = a.NC;      // this head's own length; NC: chunks per head in the workspace arrays
+    if (chunk * CHUNK >= L) return;                        // (packed batch: a shorter sequence has fewer chunks)
     const int ntok = (L - chunk * CHUNK < CHUNK) ? L - chunk * CHUNK : CHUNK;
     const size_t Lp = (size_t)NC * CHUNK;
     const long long ubase = user_vec(a.ul, bh, (long long)chunk * CHUNK);    // the caller's tensors: row of the chunk's first token
@@ -420,10 +421,12 @@ __global__ __launch_bounds__(CA_NT) void sb_chain_kernel(SbChainArgs a) {
     T* sKb = reinterpret_cast<T*>(smem + C::KB);      // Kb_c [s][b]
     T* sT1 = reinterpret_cast<T*>(smem + C::T1);      // -(G U^T) [a][t]
 
-    const int J = blockIdx.x, bh = blockIdx.y, NC = a.NC, L = a.L;
+    const int J = blockIdx.x, bh = blockIdx.y, NC = a.NC;           // NC: chunks per head in the workspace arrays
+    const int L = seq_len(a.ul, bh, a.L), NCo = (L + CHUNK - 1) / CHUNK;   // this head's own length and chunks
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
     const int c0 = J * SBC;
-    const int clast = (c0 + SBC - 1 < NC) ? c0 + SBC - 1 : NC - 1;
+    if (c0 >= NCo) return;                            // (packed batch: a shorter sequence has fewer super-blocks)
+    const int clast = (c0 + SBC - 1 < NCo) ? c0 + SBC - 1 : NCo - 1;
     const int TS = STRIDED ? (int)a.ul.vt : D;        // token stride of W
     const bool act = wv < 2 * DB;                     // 64 x d and d x 64 results: one block per wave
     const int hb = act ? wv / DB : 0, db = wv % DB;   // ... block (hb, db) of a 64 x d result, (db, hb) of a d x 64 one

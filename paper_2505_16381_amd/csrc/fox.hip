@@ -13,13 +13,16 @@ template <typename TIN, typename TOUT>
 __global__ __launch_bounds__(256) void fox_scan_kernel(ScanArgs a) {
     __shared__ float part[256];
     const int bh = blockIdx.x, tid = threadIdx.x;
-    const int per = (a.n_out + 255) / 256;
-    const int t0 = tid * per, t1 = (t0 + per < a.n_out) ? t0 + per : a.n_out;
+    // packed batches: this head's own length bounds what is read, and what is written to a tensor of the caller
+    const int Lown = seq_len(a.ul, bh, a.n_in);
+    const int n_in = a.n_in < Lown ? a.n_in : Lown, n_out = (a.out_user && Lown < a.n_out) ? Lown : a.n_out;
+    const int per = (n_out + 255) / 256;
+    const int t0 = tid * per, t1 = (t0 + per < n_out) ? t0 + per : n_out;
     const TIN* x = reinterpret_cast<const TIN*>(a.in) + (a.in_user ? user_scl(a.ul, bh, 0) : (long long)bh * a.in_stride);
     TOUT* y = reinterpret_cast<TOUT*>(a.out) + (a.out_user ? user_scl(a.ul, bh, 0) : (long long)bh * a.out_stride);
     const long long xs = a.in_user ? a.ul.st : 1, ys = a.out_user ? a.ul.st : 1;        // token strides
     const float* mi = a.minus ? a.minus + (size_t)bh * a.in_stride : nullptr;
-    auto val = [&](int t) { return (t < a.n_in) ? (float)x[t * xs] - (mi ? mi[t] : 0.f) : 0.f; };
+    auto val = [&](int t) { return (t < n_in) ? (float)x[t * xs] - (mi ? mi[t] : 0.f) : 0.f; };
     float s = 0.f;
     for (int t = t0; t < t1; ++t) s += val(t);
     part[tid] = s;

@@ -285,18 +285,31 @@ struct FwdWorkspace {
 // bh0: the kernels of one launch may work on a slice of the heads (a backward that passes over the heads in
 // groups to bound its workspace); they number their heads from 0, and head bh of the launch is head bh0 + bh of
 // the caller's tensors.
+// cu (device pointer, NULL for batches of one length): packed variable-length batches [T,H,d] / [T,H].  Batch
+// entry b is the sequence of the tokens cu[b] .. cu[b+1]-1; its length replaces the launch's L in every bound
+// (the launch's L and chunk count remain the STRIDES of the workspace arrays, sized for the longest sequence),
+// and its tensors start at token cu[b] (vt, st are the token strides; vb, sb are not used).
 struct UserLayout {
     long long vb, vh, vt, sb, sh, st;
     int H;
     int bh0;
+    const int* cu;
 };
-__host__ __device__ __forceinline__ long long user_vec(const UserLayout& u, int bh, long long t) {
+__device__ __forceinline__ long long user_vec(const UserLayout& u, int bh, long long t) {
     bh += u.bh0;
+    if (u.cu) return ((long long)u.cu[bh / u.H] + t) * u.vt + (bh % u.H) * u.vh;
     return (bh / u.H) * u.vb + (bh % u.H) * u.vh + t * u.vt;
 }
-__host__ __device__ __forceinline__ long long user_scl(const UserLayout& u, int bh, long long t) {
+__device__ __forceinline__ long long user_scl(const UserLayout& u, int bh, long long t) {
     bh += u.bh0;
+    if (u.cu) return ((long long)u.cu[bh / u.H] + t) * u.st + (bh % u.H) * u.sh;
     return (bh / u.H) * u.sb + (bh % u.H) * u.sh + t * u.st;
+}
+// length of head bh's sequence: the launch's L, or the head's own in a packed batch
+__device__ __forceinline__ int seq_len(const UserLayout& u, int bh, int L) {
+    if (!u.cu) return L;
+    const int b = (bh + u.bh0) / u.H;
+    return u.cu[b + 1] - u.cu[b];
 }
 
 struct FwdParams {

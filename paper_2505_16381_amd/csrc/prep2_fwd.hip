@@ -42,9 +42,11 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
 
     const int sb = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
-    const int NC = p.NC;
+    const int NC = p.NC;                                                   // chunks per head in the workspace arrays
+    const int NCown = (seq_len(p.ul, bh, p.L) + CHUNK - 1) / CHUNK;        // this head's own (packed batches: may be fewer)
     const int c0 = sb * SBC;
-    const int clast = (c0 + SBC - 1 < NC) ? c0 + SBC - 1 : NC - 1;
+    if (c0 >= NCown) return;
+    const int clast = (c0 + SBC - 1 < NCown) ? c0 + SBC - 1 : NCown - 1;
 
     Frag idf[SPB];
     identity_frags<T>(idf, l32, h);

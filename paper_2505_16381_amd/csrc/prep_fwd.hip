@@ -101,8 +101,9 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
 
     const int chunk = blockIdx.x, bh = blockIdx.y;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
-    const int L = p.L, NC = p.NC;
+    const int L = seq_len(p.ul, bh, p.L), NC = p.NC;      // this head's own length; NC: chunks per head in the workspace arrays
     const int t0 = chunk * CHUNK;
+    if (t0 >= L) return;                                   // (packed batch: a shorter sequence has fewer chunks)
     const int nvalid = (L - t0 < CHUNK) ? (L - t0) : CHUNK;
     const long long rowbase = user_vec(p.ul, bh, t0);       // the caller's layout: token stride TS between rows
     // token stride of the caller's tensors; a compile-time constant unless the layout interleaves heads

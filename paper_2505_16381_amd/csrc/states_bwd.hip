@@ -36,9 +36,11 @@ __global__ __launch_bounds__(256) void bwd_states_kernel(FwdParams p) {
     const int tile = __builtin_amdgcn_readfirstlane(ntiles - 1 - (int)(blockIdx.x / BH));      // heaviest (right-most) tiles first
     const int bh = __builtin_amdgcn_readfirstlane((int)(blockIdx.x % BH));
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
+    const int NCown = (seq_len(p.ul, bh, p.L) + CHUNK - 1) / CHUNK;   // this head's own chunks (NC: per head in the workspace arrays)
+    if (tile * 2 >= NCown) return;
     const int cq = tile * 2 + (wv >> 1), qb = wv & 1;
-    const bool active = cq < NC;
-    const int ctop = (tile * 2 + 1 < NC) ? tile * 2 + 1 : NC - 1;     // right-most chunk of the tile
+    const bool active = cq < NCown;
+    const int ctop = (tile * 2 + 1 < NCown) ? tile * 2 + 1 : NCown - 1;     // right-most chunk of the tile
     const int I = (tile * 2) / SBC, jsb = I * SBC;                    // both chunks lie in super-block I
     const int nnear = ctop - jsb;                                     // near steps: j = ctop-1 .. jsb
     const int nsteps = nnear + I;                                     // then far steps: J = I-1 .. 0

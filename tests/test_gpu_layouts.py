@@ -133,5 +133,57 @@ def test_layout_and_varlen_argument_checks(gpu):
         pa.path_attn_fwd_layout(x["q"], x["k"], x["v"], x["w"], x["beta"], 7)                 # unknown layout
     assert pa.path_attn_varlen_workspace_bytes([0, 5, 5], 2, 64, pa.PATH_F32) == 0           # an empty sequence
     assert pa.path_attn_varlen_workspace_bytes([1, 5], 2, 64, pa.PATH_F32) == 0              # does not start at 0
-    assert pa.path_attn_varlen_workspace_bytes([0, 5, 70], 2, 64, pa.PATH_F32) == pa.path_attn_workspace_bytes(1, 2, 65, 64, pa.PATH_F32)
+    # one set of launches for the batch: the sequence table, then the arrays of a batch of two at the longest length
+    assert pa.path_attn_varlen_workspace_bytes([0, 5, 70], 2, 64, pa.PATH_F32) == 256 + pa.path_attn_workspace_bytes(2, 2, 65, 64, pa.PATH_F32)
     assert lib is not None
+
+
+def test_varlen_batch_of_many_short_sequences_in_one_set_of_launches(gpu):
+    """64 sequences of 256..2048 tokens (bf16, H = 4, d = 64) as ONE problem: forward and backward are bit-equal
+    (dlog_f aside: none here) to a loop over the sequences on [1,L,H,d] tensors, and the time of both is printed."""
+    import time
+    torch, pa = gpu
+    rng = np.random.default_rng(77)
+    H, d, nseq = 4, 64, 64
+    lens = [int(v) for v in rng.integers(256, 2049, nseq)]
+    lens[3], lens[17] = 256, 2048
+    cu = [0]
+    for n in lens:
+        cu.append(cu[-1] + n)
+    T = cu[-1]
+    g = torch.Generator(device="cuda").manual_seed(5)
+    rn = lambda *shape: torch.randn(*shape, device="cuda", generator=g)
+    q, k, v, dO = (rn(T, H, d).to(torch.bfloat16) for _ in range(4))
+    w = torch.nn.functional.normalize(rn(T, H, d), dim=-1).to(torch.bfloat16)
+    beta = (2 * torch.sigmoid(rn(T, H))).to(torch.bfloat16)
+    scale = d ** -0.5
+
+    def one_grid():
+        o, lse = pa.path_attn_varlen_fwd(q, k, v, w, beta, cu, scale=scale)
+        return (o, lse) + tuple(pa.path_attn_varlen_bwd(q, k, v, w, beta, o, lse, dO, cu, scale=scale))
+
+    def per_sequence():
+        outs = [torch.empty_like(q), torch.empty((T, H), dtype=torch.float32, device="cuda")] + [torch.empty_like(q) for _ in range(4)] + [torch.empty_like(beta)]
+        for i in range(nseq):
+            sl = slice(cu[i], cu[i + 1])
+            a = [t[sl][None] for t in (q, k, v, w, beta)]
+            o1, l1 = pa.path_attn_fwd_layout(*a, pa.PATH_LAYOUT_BLHD, scale=scale)
+            gr = pa.path_attn_bwd_layout(*a, o1, l1, dO[sl][None], pa.PATH_LAYOUT_BLHD, scale=scale)
+            for dst, src in zip(outs, (o1, l1) + tuple(gr)):
+                dst[sl] = src[0]
+        return tuple(outs)
+
+    a = one_grid()
+    b = per_sequence()
+    torch.cuda.synchronize()
+    for i, (x, y) in enumerate(zip(a, b)):
+        assert torch.equal(x, y), i
+    times = {}
+    for name, f in (("one set of launches", one_grid), ("loop over the sequences", per_sequence)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            f()
+        torch.cuda.synchronize()
+        times[name] = (time.perf_counter() - t0) / 3 * 1e3
+    print(f"[varlen 64 sequences, {T} tokens, H={H} d={d}] forward+backward: " + ", ".join(f"{n} {t:.2f} ms" for n, t in times.items()), flush=True)

@@ -73,6 +73,25 @@ def test_reflections_preserve_walk_norm(oracle):
     assert np.all(np.diff(n[::-1]) <= 1e-12)  # n[::-1] runs from i down to 0
 
 
+def test_long_context_inputs_keep_the_walk_bounded(oracle):
+    """The long-context configuration draws beta close to 2 and rounds w and beta to bf16, so a few tokens land on
+    exactly 2.0 and beta |w|^2 may exceed 2 by about 1e-3 (Sec. 6 advises clipping in training; the operator itself
+    does not clip).  On those very inputs the walk over all 32768 tokens must not grow: the norm of the walking
+    query stays within 1 % of its start, so the transported operands stay inside the range the 16-bit path assumes."""
+    from paper_2505_16381_amd import synth_inputs
+    x, _ = synth_inputs.make_config(4, H=3)          # the configuration's recipe and length, three heads of it
+    L = x["q"].shape[2]
+    beta = x["beta"][0, 0].astype(np.float64)
+    wn2 = (x["w"][0, 0].astype(np.float64) ** 2).sum(-1)
+    assert (beta == 2.0).sum() >= 1 and (beta * wn2).max() > 2.0        # the instance really has the hard tokens
+    worst = 0.0
+    for h in range(3):
+        q, k, w, b = (x[n][0, h].astype(np.float64) for n in ("q", "k", "w", "beta"))
+        n = oracle.walk_norms(q, k, w, b, L - 1)
+        worst = max(worst, n.max() / np.linalg.norm(q[L - 1]))
+    assert worst <= 1.01, worst
+
+
 # --- T3: explicit d x d products, order as in S_t = S_{t-1} H_t + v_t k_t^T ---
 def test_logits_match_explicit_matrix_products(oracle):
     rng = np.random.default_rng(3)

@@ -3,11 +3,14 @@
 //  * Key prefill (the section's second formula): the cache a prompt leaves behind holds
 //    k_i^(l) = H_l ... H_{i+1} k_i.  Blockwise with suffix products, on top of what the forward's
 //    preprocessing already wrote: Kb2_c (keys carried to their super-block's right edge) and
-//    -dP2_J = -(I - P_superblock J).  One workgroup per head walks the super-blocks right to left
-//    with E = I - R (R = P2_last ... P2_{J+1}) kept transposed in fp32 registers,
+//    -dP2_J = -(I - P_superblock J).  With E = I - R (R = P2_last ... P2_{J+1}) kept transposed in
+//    fp32 registers,
 //        K^(l)_c = Kb2_c - Kb2_c E^T ,      E <- E + dP2_J - E dP2_J ,
 //    exactly the second level's own recurrence one level up (see prep2_fwd.hip), so the cost is
-//    linear in l.  Results go row-major into the key cache, in the cache's storage type.
+//    linear in l.  One workgroup per (head, super-block): it runs the d x d recurrence from the
+//    right end down to its own super-block (a few small products per step, the same for every
+//    workgroup of the head, hence the same E) and carries only its own super-block's keys.
+//    Results go row-major into the key cache, in the cache's storage type.
 //
 //  * Decode step (the section's first equation): when token t arrives every cached key is
 //    refreshed in place, k_i <- k_i - beta_t (w_t . k_i) w_t, and attention of q_t over the
@@ -42,23 +45,27 @@ __global__ __launch_bounds__(256) void key_prefill_kernel(PrefillArgs a) {
     Frag* sDP = Es + DPF;                          // -dP2 tile (rows b, contraction a)
     Frag* sK = sDP + DPF;                          // Kb2 tile of the current chunk (rows s, contraction c)
 
-    const int bh = blockIdx.x;
+    const int bh = blockIdx.x, Jme = blockIdx.y;   // this workgroup carries the keys of super-block Jme
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, h = lane >> 5, l32 = lane & 31;
     const int NC = a.NC, L = a.L, nsb = (NC + SBC - 1) / SBC;
+    if (Jme >= nsb) return;
 
     Frag idf[SPB];
     identity_frags<T>(idf, l32, h);
     f32x16 Fm[NE];      // E^T: block o = (rows b-block bb, lane a-block ab), blk = wv + 4*o
 
-    for (int J = nsb - 1; J >= 0; --J) {
+    for (int J = nsb - 1; J >= Jme; --J) {
         const bool lastsb = J == nsb - 1;          // E = 0: plain copy
         const int c0 = J * SBC, c1 = (c0 + SBC < NC) ? c0 + SBC : NC;
-        for (int c = c0; c < c1; ++c) {
+        if (J > Jme) {                             // on the way down: only the product of super-block J
+            __syncthreads();                       // sDP is free
+            async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(a.dp2) + ((size_t)bh * nsb + J) * (size_t)D * D), sDP, tid, wv);
+            wait_async_and_sync();
+        }
+        for (int c = c0; c < c1 && J == Jme; ++c) {
             const size_t bhc = (size_t)bh * NC + c;
             __syncthreads();                       // sK is free (and, first time round, Es is written)
             async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(a.kt2) + bhc * (size_t)CHUNK * D), sK, tid, wv);
-            if (c == c0 && J > 0)
-                async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(a.dp2) + ((size_t)bh * nsb + J) * (size_t)D * D), sDP, tid, wv);
             wait_async_and_sync();
             // K^(l)^T[cc][s] = Kb2^T[cc][s] - sum_b E[cc][b] Kb2[s][b]   (registers rows cc, lane s)
 #pragma unroll
@@ -88,7 +95,7 @@ __global__ __launch_bounds__(256) void key_prefill_kernel(PrefillArgs a) {
                 }
             }
         }
-        if (J == 0) break;
+        if (J == Jme) break;
         // E^T <- E^T + dP2^T - dP2^T E^T   (registers rows b, lane a)
 #pragma unroll
         for (int o = 0; o < NE; ++o) {
@@ -254,7 +261,7 @@ static hipError_t launch_prefill_t(const PrefillArgs& a, int BH, hipStream_t st)
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&key_prefill_kernel<TIO, D>),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((key_prefill_kernel<TIO, D>), dim3(BH), dim3(256), bytes, st, a);
+    hipLaunchKernelGGL((key_prefill_kernel<TIO, D>), dim3(BH, (a.NC + SBC - 1) / SBC), dim3(256), bytes, st, a);
     return hipGetLastError();
 }
 hipError_t launch_key_prefill(const PrefillArgs& a, int BH, int d, int is_bf16, hipStream_t st) {

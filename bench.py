@@ -65,15 +65,16 @@ def pair_counts(L):
     return near, far
 
 
-def measured_mfma_peak(torch, pa, dev):
+def measured_mfma_peak(torch, pa, dev, random_operands=False):
     """TFLOP/s of a register-resident MFMA chain (two waves per SIMD, no memory traffic): what the matrix pipes
-    deliver at the clock the chip holds under that load."""
+    deliver at the clock the chip holds under that load -- with smooth operands, or with operands of random sign
+    and significand (the kind the kernels multiply: more power per product, lower clock)."""
     sink = torch.empty(1024 * 4 * 64, dtype=torch.float32, device=dev)
-    pa.path_probe_mfma(sink, 2, 2000)
+    pa.path_probe_mfma(sink, 2, 2000, random_operands=random_operands)
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
-    flops = pa.path_probe_mfma(sink, 2, 20000)
+    flops = pa.path_probe_mfma(sink, 2, 20000, random_operands=random_operands)
     e1.record()
     torch.cuda.synchronize()
     return flops / (e0.elapsed_time(e1) * 1e-3) / 1e12
@@ -342,6 +343,7 @@ def main():
         torch.cuda.synchronize()
         alone = {"path_attn_fwd_ms": a0.elapsed_time(a1) / 2, "path_attn_bwd_ms": a1.elapsed_time(a2) / 2}
     peak_meas = measured_mfma_peak(torch, pa, dev)
+    peak_rand = measured_mfma_peak(torch, pa, dev, random_operands=True)
 
     fl_f = attn_flops(B, H, L, d)
     fl_step = fl_f * (3.5 if do_bwd else 1.0)
@@ -374,10 +376,13 @@ def main():
         "pct_of_mfma_peak": 100.0 * value / PEAK_TFLOPS,
         "mfma_peak_measured_tflops": peak_meas,
         "pct_of_measured_clock_peak": 100.0 * value / peak_meas,
+        "mfma_peak_measured_random_operands_tflops": peak_rand,
+        "pct_of_measured_random_operand_peak": 100.0 * value / peak_rand,
         "tokens_per_s": B * L / (ms_step * 1e-3),
         "fwd": {"ms": prep_ms + sweep_ms, "prep_ms": prep_ms, "sweep_ms": sweep_ms,
                 "attn_equiv_tflops": fwd_tflops, "pct_of_mfma_peak": 100.0 * fwd_tflops / PEAK_TFLOPS,
                 "pct_of_measured_clock_peak": 100.0 * fwd_tflops / peak_meas,
+                "sweep_pct_of_measured_random_operand_peak": 100.0 * sweep_tflops / peak_rand,
                 "sweep_attn_equiv_tflops": sweep_tflops, "sweep_frac_of_mfma_peak": sweep_tflops / PEAK_TFLOPS,
                 "path_inclusive_tflops": (fl_f + path_extra_flops(B, H, L, d)) / ((prep_ms + sweep_ms) * 1e-3) / 1e12,
                 "path_inclusive_note": "adds the chunk transform, the second-level transform and the query-state updates at the "

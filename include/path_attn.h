@@ -329,6 +329,14 @@ path_status_t path_decode_step(const void* q, const void* k, const void* v, cons
  */
 double path_probe_mfma_flops(int waves_per_simd, int iters);
 path_status_t path_probe_mfma(void* sink, int waves_per_simd, int iters, void* stream);
+/*
+ * The same chain with a choice of operands.  random_operands = 0: smooth, slowly varying values (what
+ * path_probe_mfma runs); != 0: fp16 values of random sign, random significand and magnitudes 0.25 .. 4, the kind
+ * of operands the method's kernels multiply.  The products draw more power on those, the chip holds a lower
+ * clock, and the rate drops from about 2.1 to about 1.6 PFLOP/s: the second figure is the practical ceiling of an
+ * MFMA-bound kernel on real data.
+ */
+path_status_t path_probe_mfma_operands(void* sink, int waves_per_simd, int iters, int random_operands, void* stream);
 
 /*
  * path_decode_step for callers that cannot allocate or pass scratch memory: code under HIP graph capture,

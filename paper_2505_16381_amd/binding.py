@@ -99,6 +99,8 @@ def load_library():
     lib.path_probe_mfma_flops.argtypes = [ci, ci]
     lib.path_probe_mfma.restype = ci
     lib.path_probe_mfma.argtypes = [vp, ci, ci, vp]
+    lib.path_probe_mfma_operands.restype = ci
+    lib.path_probe_mfma_operands.argtypes = [vp, ci, ci, ci, vp]
     lib.path_decode_static_scratch_bytes.restype = sz
     lib.path_decode_static_scratch_bytes.argtypes = []
     lib.path_decode_step_static.restype = ci
@@ -351,10 +353,14 @@ def path_attn_train_bwd_stages(stages, q, k, v, w, beta, o, lse, d_o, outs, work
     return outs
 
 
-def path_probe_mfma(sink, waves_per_simd, iters, stream=None):
-    """Enqueues the register-resident MFMA chain (a measurement aid); returns the number of flops it performs."""
+def path_probe_mfma(sink, waves_per_simd, iters, stream=None, random_operands=False):
+    """Enqueues the register-resident MFMA chain (a measurement aid); returns the number of flops it performs.
+    random_operands: operands of random sign and significand (what the kernels multiply) instead of smooth ones."""
     lib = load_library()
-    _check(lib.path_probe_mfma(_ptr(sink), int(waves_per_simd), int(iters), _stream_handle(stream)))
+    if random_operands:
+        _check(lib.path_probe_mfma_operands(_ptr(sink), int(waves_per_simd), int(iters), 1, _stream_handle(stream)))
+    else:
+        _check(lib.path_probe_mfma(_ptr(sink), int(waves_per_simd), int(iters), _stream_handle(stream)))
     return float(lib.path_probe_mfma_flops(int(waves_per_simd), int(iters)))
 
 

@@ -141,6 +141,7 @@ def test_mfma_probe_runs_and_reports_its_work(gpu):
     for wps in (1, 2, 4):
         flops = pa.path_probe_mfma(sink, wps, 50)
         assert flops == 256.0 * 4 * wps * 50 * 16 * 2 * 32 * 32 * 16
+        assert pa.path_probe_mfma(sink, wps, 50, random_operands=True) == flops
     torch.cuda.synchronize()
     assert bool(torch.isfinite(sink).all())
     with pytest.raises(pa.PathAttnError):

@@ -183,6 +183,72 @@ def bench_decode(args, torch, pa, si, dev):
     print(json.dumps(out))
 
 
+def bench_ring(args, torch, pa, si, dev):
+    """One device's share of the sequence-parallel forward (ring of paper Sec. 3.5) at the headline head shape: the
+    device holds a segment of L tokens of a longer sequence; timed are its own segment (transforms + sweep) and one
+    hop over an earlier segment of the same length (dense: every query attends every key, 4*d flops per pair)."""
+    cfg = dict(si.CONFIGS[args.config])
+    if args.shape:
+        cfg.update(dict(zip(("B", "H", "L", "d"), (int(v) for v in args.shape.split(",")))))
+    B, H, L, d = cfg["B"], cfg["H"], cfg["L"], cfg["d"]
+    g = torch.Generator(device="cuda").manual_seed(20250516)
+    rn = lambda *shape: torch.randn(*shape, device=dev, generator=g)
+    segs = []
+    for _ in range(2):                              # an earlier segment and the device's own
+        q, k, v = (rn(B, H, L, d).to(torch.bfloat16) for _ in range(3))
+        w = torch.nn.functional.normalize(rn(B, H, L, d), dim=-1).to(torch.bfloat16)
+        beta = (2 * torch.sigmoid(rn(B, H, L))).to(torch.bfloat16)
+        segs.append((q, k, v, w, beta))
+    ws = [torch.empty(pa.path_attn_workspace_bytes(B, H, L, d, pa.PATH_BF16, False), dtype=torch.uint8, device=dev) for _ in range(2)]
+    st = [torch.empty(pa.path_attn_ring_state_bytes(B, H, L, d), dtype=torch.uint8, device=dev) for _ in range(2)]
+    scale = d ** -0.5
+    o = torch.empty_like(segs[1][0])
+    lse = torch.empty((B, H, L), dtype=torch.float32, device=dev)
+    pa.path_attn_ring_local(*segs[0], st[0], ws[0], scale=scale)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+
+    def step(marks=None):
+        pa.path_attn_ring_local(*segs[1], st[1], ws[1], scale=scale)
+        if marks: marks[1].record()
+        pa.path_attn_ring_hop(st[1], B, H, L, ws[0], L, d, pa.PATH_BF16, scale=scale)
+        if marks: marks[2].record()
+        pa.path_attn_ring_finish(st[1], o, lse)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    allm = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        m = [ev() for _ in range(4)]
+        m[0].record()
+        step(m)
+        m[3].record()
+        allm.append(m)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    mean = lambda i, j: sum(m[i].elapsed_time(m[j]) for m in allm) / len(allm)
+    local_ms, hop_ms, fin_ms = mean(0, 1), mean(1, 2), mean(2, 3)
+    hop_fl = 4.0 * d * L * L * B * H
+    es = 2
+    hop_bytes = (2.0 * L * d + ((L + 1023) // 1024) * d * d) * es * B * H       # what the hop needs from the other device
+    out = {
+        "metric": "PaTH sequence-parallel forward, one device's share: own segment + one hop, attention-equivalent TFLOP/s",
+        "value": (attn_flops(B, H, L, d) + hop_fl) / (wall / args.steps) / 1e12, "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": wall * 1e3 / args.steps, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16 I/O, fp16+bf16 MFMA operands, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": f"segment of L={L} tokens per device, B={B} H={H} d={d}: own segment, one hop over an earlier segment, normalisation"},
+        "own_segment_ms": local_ms, "hop_ms": hop_ms, "finish_ms": fin_ms,
+        "hop_operand_bytes": hop_bytes,
+        "hop_link_ms_at_153GBps": hop_bytes / 153e9 * 1e3,
+        "roofline": {"kernel": "attn_fwd2_kernel<hop> (every query of the segment against every key of an earlier segment)", "bound": "mfma",
+                     "achieved": hop_fl / (hop_ms * 1e-3) / 1e12, "peak": PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": hop_fl / (hop_ms * 1e-3) / 1e12 / PEAK_TFLOPS, "traffic": None,
+                     "note": "4*d flops per (query, key) pair, all pairs; HIP-event time of the hop"},
+    }
+    print(json.dumps(out))
+
+
 def bench_fox(args, torch, pa, si, dev):
     """PaTH-FoX (forget gates on the logits, paper Sec. 2.2 extension) forward + backward at the
     chosen configuration's shape; same FLOP convention as the headline line."""
@@ -244,9 +310,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--fwd-only", action="store_true")
     ap.add_argument("--shape", type=str, default=None, help="override B,H,L,d of the chosen configuration (exploration only)")
-    ap.add_argument("--workload", choices=["train", "decode", "fox"], default="train",
+    ap.add_argument("--workload", choices=["train", "decode", "fox", "ring"], default="train",
                     help="train (default): the headline forward+backward step; decode: one decoding step "
-                         "(in-place key-cache refresh + attention) over a cache of L tokens, its own JSON line")
+                         "(in-place key-cache refresh + attention) over a cache of L tokens; fox: PaTH-FoX forward+backward; ring: one "
+                         "device's share of the sequence-parallel forward (own segment + one hop); each its own JSON line")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (each (batch, head) is independent; "
@@ -263,6 +330,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.workload == "decode":
         return bench_decode(args, torch, pa, si, dev)
+    if args.workload == "ring":
+        return bench_ring(args, torch, pa, si, dev)
     if args.workload == "fox":
         return bench_fox(args, torch, pa, si, dev)
     over = {}

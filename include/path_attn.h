@@ -319,6 +319,43 @@ path_status_t path_decode_step(const void* q, const void* k, const void* v, cons
                                void* stream);
 
 /*
+ * Sequence-parallel forward: ONE device's share of the ring of paper Sec. 3.5 ("context parallelism": the
+ * sequence is split into contiguous segments, one per device; a device attends its own segment, then the
+ * segments to its left one hop at a time, applying one d x d product per super-block it has passed).  The three
+ * calls below are what a device runs; moving the earlier segments' tiles between devices is the caller's
+ * business (on one GPU a test walks the segments in turn).  Plain PaTH, [B,H,L,d] layout, forward only.
+ *
+ *   path_attn_ring_local   the device's own segment (L tokens, causal inside it): chunk transform, second level
+ *                          and sweep.  Leaves in `state` (path_attn_ring_state_bytes(B,H,L,d) bytes, 16-byte
+ *                          aligned, caller-owned device memory) what the sweep holds per query -- the query state,
+ *                          now carried to the segment's left edge, the unnormalised output, the running maximum
+ *                          and row sum, all fp32 -- and in `workspace` (path_attn_workspace_bytes(B,H,L,d,dt,0))
+ *                          the segment's tiles, which devices to the RIGHT need for their hops: the regions of
+ *                          the second-level keys, the values and the super-block products (2 L d + ceil(L/1024) d^2
+ *                          elements per head).
+ *   path_attn_ring_hop     attends the Lq queries of `state` to every key of an EARLIER segment of Lk tokens,
+ *                          given as the workspace path_attn_ring_local filled on that segment (same B, H, d, dt),
+ *                          and carries the state across that segment.  Hops are made nearest segment first.  Lk
+ *                          must be a multiple of 64 (PATH_ERR_SHAPE): only the last segment of a sequence may be
+ *                          ragged, and it is nobody's earlier segment.
+ *   path_attn_ring_finish  o = O / l, lse = m + log l from `state` (after the last hop; for the first segment
+ *                          right after path_attn_ring_local).
+ *
+ * With segment lengths that are multiples of 1024 (the second blocking level) the result is bit-identical to
+ * path_attn_fwd on the whole sequence: the same tiles, the same products in the same order, the state kept in
+ * fp32 between the calls.  Other lengths differ from it by rounding only.  Errors as for path_attn_fwd.
+ */
+size_t path_attn_ring_state_bytes(int B, int H, int L, int d);
+path_status_t path_attn_ring_local(const void* q, const void* k, const void* v, const void* w, const void* beta,
+                                   void* state, int B, int H, int L, int d, float scale, path_dtype_t dt,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+path_status_t path_attn_ring_hop(void* state, int B, int H, int Lq, const void* remote_workspace,
+                                 size_t remote_workspace_bytes, int Lk, int d, float scale, path_dtype_t dt,
+                                 void* stream);
+path_status_t path_attn_ring_finish(const void* state, void* o, float* lse, int B, int H, int L, int d,
+                                    path_dtype_t dt, void* stream);
+
+/*
  * Measurement aid, not part of the method: a register-resident chain of 32x32x16 fp16 MFMA products (four
  * independent accumulators per wave, `waves_per_simd` waves on each of the 1024 SIMDs, `iters` x 16 products
  * per wave, no memory traffic inside the loop) for calibrating "percent of peak" against what the matrix pipes

@@ -12,6 +12,7 @@ hipError_t launch_prep_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t s
 
 hipError_t launch_prep2_fwd(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 hipError_t launch_attn_fwd2(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
+hipError_t launch_ring_finish(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 hipError_t launch_attn_states(const FwdParams& p, int d, int is_bf16, hipStream_t stream);
 }  // namespace path
 #include "bwd_decl.h"
@@ -261,6 +262,69 @@ extern "C" path_status_t path_attn_fwd(const void* q, const void* k, const void*
                                        size_t workspace_bytes, void* stream) {
     return fwd_impl(0, layout_of(PATH_LAYOUT_BHLD, H, L, d), q, k, v, w, beta, nullptr, 0, o, lse, B, H, L, d, causal, scale, dt,
                     workspace, workspace_bytes, stream);
+}
+
+// ---- sequence-parallel forward: one device's share of the ring (paper Sec. 3.5) ------------------------------
+extern "C" size_t path_attn_ring_state_bytes(int B, int H, int L, int d) {
+    if (!shape_ok(B, H, L, d)) return 0;
+    const size_t NC = (size_t)(L + CHUNK - 1) / CHUNK;
+    return (size_t)B * H * NC * 2 * ring_rec_floats(d) * sizeof(float);
+}
+
+extern "C" path_status_t path_attn_ring_local(const void* q, const void* k, const void* v, const void* w, const void* beta,
+                                              void* state, int B, int H, int L, int d, float scale, path_dtype_t dt,
+                                              void* workspace, size_t workspace_bytes, void* stream) {
+    if (!q || !k || !v || !w || !beta || !state || !workspace) return PATH_ERR_NULL;
+    if (!(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
+    FwdParams p = {};
+    const path_status_t st = fwd_setup(p, layout_of(PATH_LAYOUT_BHLD, H, L, d), B, H, L, d, dt, workspace, workspace_bytes);
+    if (st != PATH_OK) return st;
+    if (misaligned(q) || misaligned(k) || misaligned(v) || misaligned(w) || misaligned(state)) return PATH_ERR_ALIGN;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    clear_inherited_error();
+    p.q = q; p.k = k; p.v = v; p.w = w; p.beta = beta;
+    if (!hip_ok(launch_prep_fwd(p, d, dt == PATH_BF16, hs), "chunk transform")) return PATH_ERR_HIP;
+    if (!hip_ok(launch_prep2_fwd(p, d, dt == PATH_BF16, hs), "second-level transform")) return PATH_ERR_HIP;
+    p.scale = scale; p.ring = 1; p.ring_state = static_cast<float*>(state); p.NCq = p.NC;
+    if (!hip_ok(launch_attn_fwd2(p, d, dt == PATH_BF16, hs), "sweep of the own segment")) return PATH_ERR_HIP;
+    return PATH_OK;
+}
+
+extern "C" path_status_t path_attn_ring_hop(void* state, int B, int H, int Lq, const void* remote_workspace,
+                                            size_t remote_workspace_bytes, int Lk, int d, float scale, path_dtype_t dt,
+                                            void* stream) {
+    if (!state || !remote_workspace) return PATH_ERR_NULL;
+    if (!(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
+    if (!shape_ok(B, H, Lq, d)) return PATH_ERR_SHAPE;
+    if (Lk % CHUNK != 0) {      // padded keys of a ragged segment would be attended: only the LAST segment may be ragged, and it is nobody's earlier segment
+        snprintf(g_last_error, sizeof g_last_error, "path_attn_ring_hop: the earlier segment's length %d is not a multiple of 64", Lk);
+        return PATH_ERR_SHAPE;
+    }
+    FwdParams p = {};
+    // the earlier segment's tiles: its workspace as path_attn_ring_local laid it out (the sweep reads kt2, vt, dp2)
+    const path_status_t st = fwd_setup(p, layout_of(PATH_LAYOUT_BHLD, H, Lk, d), B, H, Lk, d, dt, const_cast<void*>(remote_workspace),
+                                       remote_workspace_bytes);
+    if (st != PATH_OK) return st;
+    if (misaligned(state)) return PATH_ERR_ALIGN;
+    clear_inherited_error();
+    p.scale = scale; p.ring = 2; p.ring_state = static_cast<float*>(state); p.NCq = (Lq + CHUNK - 1) / CHUNK;
+    if (!hip_ok(launch_attn_fwd2(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "ring hop")) return PATH_ERR_HIP;
+    return PATH_OK;
+}
+
+extern "C" path_status_t path_attn_ring_finish(const void* state, void* o, float* lse, int B, int H, int L, int d,
+                                               path_dtype_t dt, void* stream) {
+    if (!state || !o || !lse) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
+    if (misaligned(state) || misaligned(o)) return PATH_ERR_ALIGN;
+    FwdParams p = {};
+    p.ul = layout_of(PATH_LAYOUT_BHLD, H, L, d);
+    p.B = B; p.H = H; p.L = L; p.NC = (L + CHUNK - 1) / CHUNK;
+    p.o = o; p.lse = lse; p.ring_state = const_cast<float*>(static_cast<const float*>(state));
+    clear_inherited_error();
+    if (!hip_ok(launch_ring_finish(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "ring normalisation")) return PATH_ERR_HIP;
+    return PATH_OK;
 }
 
 extern "C" path_status_t path_attn_fox_fwd(const void* q, const void* k, const void* v, const void* w,

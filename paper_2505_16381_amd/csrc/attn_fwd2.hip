@@ -52,7 +52,13 @@ __device__ __forceinline__ void wait_tiles_and_sync() {
 // in the arrangement of the backward's own states sweep (see states_bwd.hip): whenever a wave
 // meets a new key block -- a chunk j < cq of its own super-block, or a super-block further left --
 // it stores its state as the tiles xs and xsT of the pair (cq, block).
-template <typename TIO, int D, bool FOX, bool EMIT>
+//
+// RING (sequence-parallel forward, Sec. 3.5): 1 = the sweep over a device's own segment; it also applies the
+// product of the segment's first chunk / super-block at the end (the query state then stands at the segment's left
+// edge, ready for the keys of the segment before) and stores its registers instead of writing o and lse.
+// 2 = one hop: the registers are loaded, all chunks of an earlier segment are swept as "far" blocks (second-level
+// keys, one product per super-block, the first one's included), and the registers are stored again.
+template <typename TIO, int D, bool FOX, bool EMIT, int RING = 0>
 __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_kernel(FwdParams p) {
     using C = Fwd2Cfg<TIO, D>;
     using T = typename C::T;
@@ -70,7 +76,8 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     float* sC = reinterpret_cast<float*>(sP + DPF);             // FOX: [2 stages][32] gate sums of the stage's keys
 
     const int BH = p.B * p.H, NC = p.NC;            // NC: chunks per head in the workspace arrays and in the grid's numbering
-    const int ntiles = (NC + FWD2_CPT - 1) / FWD2_CPT;
+    const int NCq = RING == 2 ? p.NCq : NC;         // chunks of the query side (a hop's keys belong to another segment)
+    const int ntiles = (NCq + FWD2_CPT - 1) / FWD2_CPT;
     // XCD-aware numbering: workgroup b runs on XCD b % 8; that XCD takes heads xcd, xcd+8, ...
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     // (the division runs on the vector unit; its result, uniform over the workgroup, goes back to scalar
@@ -80,14 +87,16 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     if (bh >= BH) return;
     const int tid = threadIdx.x, lane = tid & 63, wv = __builtin_amdgcn_readfirstlane(tid >> 6), h = lane >> 5, l32 = lane & 31;
 
-    const int L = seq_len(p.ul, bh, p.L), NCown = (L + CHUNK - 1) / CHUNK;     // this head's own length (packed batches: may be shorter)
+    const int L = seq_len(p.ul, bh, p.L);
+    const int NCown = RING == 2 ? NCq : (L + CHUNK - 1) / CHUNK;     // this head's own length (packed batches: may be shorter)
     if (tile * FWD2_CPT >= NCown) return;
     const int cq = tile * FWD2_CPT + (wv >> 1);     // this wave's chunk
     const int qb = wv & 1;                          // ... and which 32-query half of it
     const bool active = cq < NCown;
-    const int jtop = (tile * FWD2_CPT + FWD2_CPT - 1 < NCown) ? tile * FWD2_CPT + FWD2_CPT - 1 : NCown - 1;
+    // (a hop sweeps every chunk of the other segment, all of them as far blocks)
+    const int jtop = RING == 2 ? NC - 1 : ((tile * FWD2_CPT + FWD2_CPT - 1 < NCown) ? tile * FWD2_CPT + FWD2_CPT - 1 : NCown - 1);
     static_assert(SBC % FWD2_CPT == 0, "a tile must lie in one super-block");
-    const int jsb = (tile * FWD2_CPT / SBC) * SBC;  // first chunk of the tile's own super-block
+    const int jsb = RING == 2 ? NC : (tile * FWD2_CPT / SBC) * SBC;  // first chunk of the tile's own super-block
     const int nsb = (NC + SBC - 1) / SBC;
     const float sl2 = p.scale * 1.44269504088896340736f;
 
@@ -95,12 +104,23 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     f32x16 O[DB], Xm[HAS_MASTER ? DB : 1];
     Frag Xh[DS];
     float m_run = -INFINITY, l_run = 0.f;           // m in base-2 logit units
+    float* const rec = RING ? p.ring_state + (((size_t)bh * NCq + cq) * 2 + qb) * ring_rec_floats(D) : nullptr;
+    if (RING == 2 && active) { m_run = rec[2 * DB * 1024 + lane]; l_run = rec[2 * DB * 1024 + 64 + lane]; }
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
         O[b] = zero16();
         f32x16 x = zero16();
+        if (RING == 2 && active) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 o4 = *reinterpret_cast<const f32x4*>(rec + (size_t)(DB + b) * 1024 + g * 256 + lane * 4);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) O[b][4 * g + r] = o4[r];
+            }
+        }
         if (active) {
-            const float* xs = p.xinit + (((size_t)bh * NC + cq) * 2 + qb) * (size_t)DB * 1024 + (size_t)b * 1024;
+            const float* xs = RING == 2 ? rec + (size_t)b * 1024
+                                        : p.xinit + (((size_t)bh * NC + cq) * 2 + qb) * (size_t)DB * 1024 + (size_t)b * 1024;
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const f32x4 v4 = *reinterpret_cast<const f32x4*>(xs + g * 256 + lane * 4);
@@ -134,8 +154,8 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     // processed (sP is free then: the previous update ended before this stage's barrier)
     auto issue_dp = [&](int j) {
         if (j >= jsb) {
-            if (j < jtop && j > 0) async_copy_tile<FWD2_THREADS, DPF>(reinterpret_cast<const Frag*>(dpg + (size_t)j * D * D), sP, tid, wv);
-        } else if (j % SBC == 0 && j > 0) {
+            if (j < jtop && (j > 0 || RING)) async_copy_tile<FWD2_THREADS, DPF>(reinterpret_cast<const Frag*>(dpg + (size_t)j * D * D), sP, tid, wv);
+        } else if (j % SBC == 0 && (j > 0 || RING)) {
             async_copy_tile<FWD2_THREADS, DPF>(reinterpret_cast<const Frag*>(dp2g + (size_t)(j / SBC) * D * D), sP, tid, wv);
         }
     };
@@ -252,7 +272,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
 
         if (!DIAG) {
             // ---- X <- X (I - dP) after the chunk (phase A) / after the super-block (phase B) -------
-            const bool upd = kb == 1 && j > 0 && (j >= jsb || (j % SBC) == 0);
+            const bool upd = kb == 1 && (j > 0 || RING) && (j >= jsb || (j % SBC) == 0);
             if (upd) {
                 f32x16 Xn[DB];
 #pragma unroll
@@ -281,17 +301,40 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
         if (u + 1 < nstage) issue_kv(u + 1);
         if ((u & 1) == 0) issue_dp(jtop - (u >> 1));
     };
-    const int u0 = active ? 2 * (jtop - cq) : nstage;      // this wave's first stage
+    const int u0 = RING == 2 ? (active ? 0 : nstage) : (active ? 2 * (jtop - cq) : nstage);      // this wave's first stage
     issue_kv(0);
     int u = 0;
     for (; u < u0; ++u) top_of_stage(u);
     if (active) {
-        top_of_stage(u); stage(u, std::true_type{}); ++u;
-        top_of_stage(u); stage(u, std::true_type{}); ++u;
+        if (RING != 2) {
+            top_of_stage(u); stage(u, std::true_type{}); ++u;
+            top_of_stage(u); stage(u, std::true_type{}); ++u;
+        }
         for (; u < nstage; ++u) {
             top_of_stage(u);
             stage(u, std::false_type{});
         }
+    }
+    if (RING) {
+        // the registers go to memory as they are (fp32): the next hop, or the final normalisation, continues from them
+        if (!active) return;
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                f32x4 x4, o4;
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int jj = 4 * g + r;
+                    x4[r] = HAS_MASTER ? Xm[HAS_MASTER ? b : 0][jj] : (float)Xh[b * SPB + jj / Tr<T>::FE][jj % Tr<T>::FE];
+                    o4[r] = O[b][jj];
+                }
+                *reinterpret_cast<f32x4*>(rec + (size_t)b * 1024 + g * 256 + lane * 4) = x4;
+                *reinterpret_cast<f32x4*>(rec + (size_t)(DB + b) * 1024 + g * 256 + lane * 4) = o4;
+            }
+        rec[2 * DB * 1024 + lane] = m_run;
+        rec[2 * DB * 1024 + 64 + lane] = l_run;
+        return;
     }
 
     // ---- epilogue: normalise, store o and lse (paper Sec. 3.3, last step) ---------------------
@@ -315,24 +358,63 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     }
 }
 
-template <typename TIO, int D, bool FOX, bool EMIT>
+template <typename TIO, int D, bool FOX, bool EMIT, int RING = 0>
 hipError_t launch_attn_fwd2_f(const FwdParams& p, hipStream_t stream) {
     using C = Fwd2Cfg<TIO, D>;
     // set once per process; a function-local static is initialised under the language's own lock
-    static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd2_kernel<TIO, D, FOX, EMIT>),
+    static const hipError_t attr_err = hipFuncSetAttribute(reinterpret_cast<const void*>(&attn_fwd2_kernel<TIO, D, FOX, EMIT, RING>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, (int)C::smem_bytes);
     if (attr_err != hipSuccess) return attr_err;
-    const int ntiles = (p.NC + FWD2_CPT - 1) / FWD2_CPT;
+    const int ntiles = ((RING == 2 ? p.NCq : p.NC) + FWD2_CPT - 1) / FWD2_CPT;
     const int BH = p.B * p.H;
     dim3 grid((unsigned)(((BH + 7) / 8) * 8 * ntiles));
     const size_t bytes = C::smem_bytes;
-    hipLaunchKernelGGL((attn_fwd2_kernel<TIO, D, FOX, EMIT>), grid, dim3(FWD2_THREADS), bytes, stream, p);
+    hipLaunchKernelGGL((attn_fwd2_kernel<TIO, D, FOX, EMIT, RING>), grid, dim3(FWD2_THREADS), bytes, stream, p);
     return hipGetLastError();
 }
 template <typename TIO, int D>
 hipError_t launch_attn_fwd2_t(const FwdParams& p, hipStream_t stream) {
+    if (p.ring == 1) return launch_attn_fwd2_f<TIO, D, false, false, 1>(p, stream);      // (plain PaTH, no state output)
+    if (p.ring == 2) return launch_attn_fwd2_f<TIO, D, false, false, 2>(p, stream);
     if (p.emit_states) return p.cum ? launch_attn_fwd2_f<TIO, D, true, true>(p, stream) : launch_attn_fwd2_f<TIO, D, false, true>(p, stream);
     return p.cum ? launch_attn_fwd2_f<TIO, D, true, false>(p, stream) : launch_attn_fwd2_f<TIO, D, false, false>(p, stream);
+}
+
+// Sequence-parallel forward, last step: o = O / l and lse = m + log l from the stored registers (the sweep's own
+// epilogue, on what the last hop left).  One wave per (head, chunk, 32-query half).
+template <typename TIO, int D>
+__global__ __launch_bounds__(64) void ring_finish_kernel(FwdParams p) {
+    using Vec4 = typename Tr<TIO>::Vec4;
+    constexpr int DB = D / 32;
+    const int lane = threadIdx.x, h = lane >> 5, l32 = lane & 31;
+    const int cq = blockIdx.x >> 1, qb = blockIdx.x & 1, bh = blockIdx.y;
+    const float* rec = p.ring_state + (((size_t)bh * p.NC + cq) * 2 + qb) * ring_rec_floats(D);
+    const float m_run = rec[2 * DB * 1024 + lane], l_run = rec[2 * DB * 1024 + 64 + lane];
+    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float inv = 1.f / l_tot;
+    const int tq = cq * CHUNK + 32 * qb + l32;
+    if (tq >= p.L) return;
+    TIO* orow = reinterpret_cast<TIO*>(p.o) + user_vec(p.ul, bh, tq) + 4 * h;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const f32x4 o4 = *reinterpret_cast<const f32x4*>(rec + (size_t)(DB + b) * 1024 + g * 256 + lane * 4);
+            Vec4 v4;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v4[r] = (TIO)(o4[r] * inv);
+            *reinterpret_cast<Vec4*>(orow + 32 * b + 8 * g) = v4;
+        }
+    if (h == 0) p.lse[user_scl(p.ul, bh, tq)] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+}
+template <typename TIO, int D>
+static hipError_t launch_ring_finish_t(const FwdParams& p, hipStream_t stream) {
+    hipLaunchKernelGGL((ring_finish_kernel<TIO, D>), dim3(2 * p.NC, p.B * p.H), dim3(64), 0, stream, p);
+    return hipGetLastError();
+}
+hipError_t launch_ring_finish(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {
+    if (is_bf16) return d == 64 ? launch_ring_finish_t<bf16_t, 64>(p, stream) : launch_ring_finish_t<bf16_t, 128>(p, stream);
+    return d == 64 ? launch_ring_finish_t<float, 64>(p, stream) : launch_ring_finish_t<float, 128>(p, stream);
 }
 
 hipError_t launch_attn_fwd2(const FwdParams& p, int d, int is_bf16, hipStream_t stream) {

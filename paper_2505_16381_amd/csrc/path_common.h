@@ -339,7 +339,19 @@ struct FwdParams {
     // the second level (operand type).
     void *fm, *gktm, *nm, *aim, *ytm, *utm, *kbm, *rm;
     float *gm, *sdm;
+    // Sequence-parallel forward (one device's share of the ring of Sec. 3.5): the sweep's per-query registers --
+    // the query state carried to the left edge of what has been attended so far, the unnormalised output, the
+    // running maximum and row sum -- kept in memory between the calls.  ring: 0 = ordinary forward; 1 = sweep over
+    // the device's own segment, leaving the registers in ring_state; 2 = one hop: the registers are loaded, every
+    // key of an earlier segment (whose tiles kt2, vt, dp2 this structure then points at; NC = ITS chunk count) is
+    // attended, and they are stored again.  NCq: chunks of the query side (ring = 2 only; else NC).
+    float* ring_state;
+    int ring, NCq;
 };
+// ring_state: per (head, query chunk, 32-query half) one record of RING_REC(d) floats, each quantity as the sweep
+// holds it: [X: d/32 blocks][O: d/32 blocks] of 1024 floats (register g*4+r of lane l at g*256 + l*4 + r), then the
+// running maximum and the row sum per lane (64 + 64).
+__host__ __device__ constexpr size_t ring_rec_floats(int d) { return (size_t)2 * (d / 32) * 1024 + 128; }
 
 // Key blocks of the backward, for query chunk i (own super-block I = i / SBC): the chunks
 // SBC*I <= j < i one by one ("near"), and the super-blocks J < I as a whole ("far": the state is

@@ -323,7 +323,8 @@ path_status_t path_decode_step(const void* q, const void* k, const void* v, cons
  * sequence is split into contiguous segments, one per device; a device attends its own segment, then the
  * segments to its left one hop at a time, applying one d x d product per super-block it has passed).  The three
  * calls below are what a device runs; moving the earlier segments' tiles between devices is the caller's
- * business (on one GPU a test walks the segments in turn).  Plain PaTH, [B,H,L,d] layout, forward only.
+ * business (on one GPU a test walks the segments in turn).  [B,H,L,d] layout, forward only; plain PaTH, or
+ * PaTH-FoX with the gates of each segment given to its own path_attn_ring_local (log_f [B,H,L], NULL = plain).
  *
  *   path_attn_ring_local   the device's own segment (L tokens, causal inside it): chunk transform, second level
  *                          and sweep.  Leaves in `state` (path_attn_ring_state_bytes(B,H,L,d) bytes, 16-byte
@@ -337,9 +338,11 @@ path_status_t path_decode_step(const void* q, const void* k, const void* v, cons
  *                          given as the workspace path_attn_ring_local filled on that segment (same B, H, d, dt),
  *                          and carries the state across that segment.  Hops are made nearest segment first.  Lk
  *                          must be a multiple of 64 (PATH_ERR_SHAPE): only the last segment of a sequence may be
- *                          ragged, and it is nobody's earlier segment.
+ *                          ragged, and it is nobody's earlier segment.  with_gates != 0: PaTH-FoX (the earlier
+ *                          segment's gate sums are in its workspace; every segment of a sequence uses gates or none).
  *   path_attn_ring_finish  o = O / l, lse = m + log l from `state` (after the last hop; for the first segment
- *                          right after path_attn_ring_local).
+ *                          right after path_attn_ring_local).  PaTH-FoX: gates_workspace = the workspace of the
+ *                          device's OWN path_attn_ring_local (it holds the segment's gate sums); NULL = plain.
  *
  * With segment lengths that are multiples of 1024 (the second blocking level) the result is bit-identical to
  * path_attn_fwd on the whole sequence: the same tiles, the same products in the same order, the state kept in
@@ -347,13 +350,14 @@ path_status_t path_decode_step(const void* q, const void* k, const void* v, cons
  */
 size_t path_attn_ring_state_bytes(int B, int H, int L, int d);
 path_status_t path_attn_ring_local(const void* q, const void* k, const void* v, const void* w, const void* beta,
-                                   void* state, int B, int H, int L, int d, float scale, path_dtype_t dt,
-                                   void* workspace, size_t workspace_bytes, void* stream);
+                                   const void* log_f, void* state, int B, int H, int L, int d, float scale,
+                                   path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);
 path_status_t path_attn_ring_hop(void* state, int B, int H, int Lq, const void* remote_workspace,
-                                 size_t remote_workspace_bytes, int Lk, int d, float scale, path_dtype_t dt,
-                                 void* stream);
+                                 size_t remote_workspace_bytes, int Lk, int d, int with_gates, float scale,
+                                 path_dtype_t dt, void* stream);
 path_status_t path_attn_ring_finish(const void* state, void* o, float* lse, int B, int H, int L, int d,
-                                    path_dtype_t dt, void* stream);
+                                    path_dtype_t dt, const void* gates_workspace, size_t gates_workspace_bytes,
+                                    void* stream);
 
 /*
  * Measurement aid, not part of the method: a register-resident chain of 32x32x16 fp16 MFMA products (four

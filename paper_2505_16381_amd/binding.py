@@ -102,11 +102,11 @@ def load_library():
     lib.path_attn_ring_state_bytes.restype = ctypes.c_size_t
     lib.path_attn_ring_state_bytes.argtypes = [ci, ci, ci, ci]
     lib.path_attn_ring_local.restype = ci
-    lib.path_attn_ring_local.argtypes = [vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, vp, ctypes.c_size_t, vp]
+    lib.path_attn_ring_local.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, vp, ctypes.c_size_t, vp]
     lib.path_attn_ring_hop.restype = ci
-    lib.path_attn_ring_hop.argtypes = [vp, ci, ci, ci, vp, ctypes.c_size_t, ci, ci, ctypes.c_float, ci, vp]
+    lib.path_attn_ring_hop.argtypes = [vp, ci, ci, ci, vp, ctypes.c_size_t, ci, ci, ci, ctypes.c_float, ci, vp]
     lib.path_attn_ring_finish.restype = ci
-    lib.path_attn_ring_finish.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp]
+    lib.path_attn_ring_finish.argtypes = [vp, vp, vp, ci, ci, ci, ci, ci, vp, ctypes.c_size_t, vp]
     lib.path_probe_mfma_operands.restype = ci
     lib.path_probe_mfma_operands.argtypes = [vp, ci, ci, ci, vp]
     lib.path_decode_static_scratch_bytes.restype = sz
@@ -376,28 +376,29 @@ def path_attn_ring_state_bytes(B, H, L, d) -> int:
     return int(load_library().path_attn_ring_state_bytes(B, H, L, d))
 
 
-def path_attn_ring_local(q, k, v, w, beta, state, workspace, scale=None, stream=None):
+def path_attn_ring_local(q, k, v, w, beta, state, workspace, log_f=None, scale=None, stream=None):
     """A device's own segment of a sequence-parallel forward: fills ``state`` (the sweep's per-query registers) and
-    ``workspace`` (the segment's tiles, which segments to the right attend)."""
+    ``workspace`` (the segment's tiles, which segments to the right attend).  log_f: the segment's gates (PaTH-FoX)."""
     B, H, L, d = q.shape
     if scale is None:
         scale = float(d) ** -0.5
-    _check(load_library().path_attn_ring_local(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(state), B, H, L, d,
+    _check(load_library().path_attn_ring_local(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _opt(log_f), _ptr(state), B, H, L, d,
                                                float(scale), _dt_of(q), _ptr(workspace), workspace.numel(), _stream_handle(stream)))
 
 
-def path_attn_ring_hop(state, B, H, Lq, remote_workspace, Lk, d, dt, scale=None, stream=None):
+def path_attn_ring_hop(state, B, H, Lq, remote_workspace, Lk, d, dt, with_gates=False, scale=None, stream=None):
     """One hop: the queries of ``state`` attend every key of an earlier segment of Lk tokens (its workspace)."""
     if scale is None:
         scale = float(d) ** -0.5
     _check(load_library().path_attn_ring_hop(_ptr(state), B, H, Lq, _ptr(remote_workspace), remote_workspace.numel(), Lk, d,
-                                             float(scale), dt, _stream_handle(stream)))
+                                             int(bool(with_gates)), float(scale), dt, _stream_handle(stream)))
 
 
-def path_attn_ring_finish(state, o, lse, stream=None):
-    """o, lse from the state after the last hop."""
+def path_attn_ring_finish(state, o, lse, gates_workspace=None, stream=None):
+    """o, lse from the state after the last hop (PaTH-FoX: with the workspace of the device's own segment)."""
     B, H, L, d = o.shape
-    _check(load_library().path_attn_ring_finish(_ptr(state), _ptr(o), _ptr(lse), B, H, L, d, _dt_of(o), _stream_handle(stream)))
+    _check(load_library().path_attn_ring_finish(_ptr(state), _ptr(o), _ptr(lse), B, H, L, d, _dt_of(o), _opt(gates_workspace),
+                                                gates_workspace.numel() if gates_workspace is not None else 0, _stream_handle(stream)))
 
 
 def path_attn_train_fwd_prep(q, k, v, w, beta, workspace, log_f=None, stream=None):

@@ -272,8 +272,8 @@ extern "C" size_t path_attn_ring_state_bytes(int B, int H, int L, int d) {
 }
 
 extern "C" path_status_t path_attn_ring_local(const void* q, const void* k, const void* v, const void* w, const void* beta,
-                                              void* state, int B, int H, int L, int d, float scale, path_dtype_t dt,
-                                              void* workspace, size_t workspace_bytes, void* stream) {
+                                              const void* log_f, void* state, int B, int H, int L, int d, float scale,
+                                              path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {
     if (!q || !k || !v || !w || !beta || !state || !workspace) return PATH_ERR_NULL;
     if (!(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
     FwdParams p = {};
@@ -285,14 +285,19 @@ extern "C" path_status_t path_attn_ring_local(const void* q, const void* k, cons
     p.q = q; p.k = k; p.v = v; p.w = w; p.beta = beta;
     if (!hip_ok(launch_prep_fwd(p, d, dt == PATH_BF16, hs), "chunk transform")) return PATH_ERR_HIP;
     if (!hip_ok(launch_prep2_fwd(p, d, dt == PATH_BF16, hs), "second-level transform")) return PATH_ERR_HIP;
+    if (log_f) {      // PaTH-FoX: gate sums counted from the segment's start
+        float* cum = reinterpret_cast<float*>(static_cast<unsigned char*>(workspace) + fwd_workspace(B, H, L, d, dt == PATH_BF16 ? 2 : 4).cum);
+        if (!hip_ok(launch_gate_sums(log_f, p.ul, cum, B, H, L, dt, hs), "gate sums")) return PATH_ERR_HIP;
+        p.cum = cum;
+    }
     p.scale = scale; p.ring = 1; p.ring_state = static_cast<float*>(state); p.NCq = p.NC;
     if (!hip_ok(launch_attn_fwd2(p, d, dt == PATH_BF16, hs), "sweep of the own segment")) return PATH_ERR_HIP;
     return PATH_OK;
 }
 
 extern "C" path_status_t path_attn_ring_hop(void* state, int B, int H, int Lq, const void* remote_workspace,
-                                            size_t remote_workspace_bytes, int Lk, int d, float scale, path_dtype_t dt,
-                                            void* stream) {
+                                            size_t remote_workspace_bytes, int Lk, int d, int with_gates, float scale,
+                                            path_dtype_t dt, void* stream) {
     if (!state || !remote_workspace) return PATH_ERR_NULL;
     if (!(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
     if (!shape_ok(B, H, Lq, d)) return PATH_ERR_SHAPE;
@@ -307,18 +312,26 @@ extern "C" path_status_t path_attn_ring_hop(void* state, int B, int H, int Lq, c
     if (st != PATH_OK) return st;
     if (misaligned(state)) return PATH_ERR_ALIGN;
     clear_inherited_error();
+    if (with_gates)
+        p.cum = reinterpret_cast<const float*>(static_cast<const unsigned char*>(remote_workspace) + fwd_workspace(B, H, Lk, d, dt == PATH_BF16 ? 2 : 4).cum);
     p.scale = scale; p.ring = 2; p.ring_state = static_cast<float*>(state); p.NCq = (Lq + CHUNK - 1) / CHUNK;
     if (!hip_ok(launch_attn_fwd2(p, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "ring hop")) return PATH_ERR_HIP;
     return PATH_OK;
 }
 
 extern "C" path_status_t path_attn_ring_finish(const void* state, void* o, float* lse, int B, int H, int L, int d,
-                                               path_dtype_t dt, void* stream) {
+                                               path_dtype_t dt, const void* gates_workspace, size_t gates_workspace_bytes,
+                                               void* stream) {
     if (!state || !o || !lse) return PATH_ERR_NULL;
     if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
     if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
     if (misaligned(state) || misaligned(o)) return PATH_ERR_ALIGN;
     FwdParams p = {};
+    if (gates_workspace) {      // PaTH-FoX: the segment's own gate sums, where path_attn_ring_local left them
+        const FwdWorkspace ws = fwd_workspace(B, H, L, d, dt == PATH_BF16 ? 2 : 4);
+        if (gates_workspace_bytes < ws.total || (reinterpret_cast<uintptr_t>(gates_workspace) & 255)) return PATH_ERR_WORKSPACE;
+        p.cum = reinterpret_cast<const float*>(static_cast<const unsigned char*>(gates_workspace) + ws.cum);
+    }
     p.ul = layout_of(PATH_LAYOUT_BHLD, H, L, d);
     p.B = B; p.H = H; p.L = L; p.NC = (L + CHUNK - 1) / CHUNK;
     p.o = o; p.lse = lse; p.ring_state = const_cast<float*>(static_cast<const float*>(state));

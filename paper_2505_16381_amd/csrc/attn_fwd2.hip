@@ -105,7 +105,14 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
     Frag Xh[DS];
     float m_run = -INFINITY, l_run = 0.f;           // m in base-2 logit units
     float* const rec = RING ? p.ring_state + (((size_t)bh * NCq + cq) * 2 + qb) * ring_rec_floats(D) : nullptr;
-    if (RING == 2 && active) { m_run = rec[2 * DB * 1024 + lane]; l_run = rec[2 * DB * 1024 + 64 + lane]; }
+    // PaTH-FoX in a hop: the gate sums of the other segment count from ITS start.  With T its total and g the totals of
+    // the segments already passed, key j's logit gets g + T - c_j (the query's own + c_i, local to its segment, is added
+    // at the end as always).
+    float goff = 0.f, koff = 0.f;
+    if (RING == 2 && active) {
+        m_run = rec[2 * DB * 1024 + lane]; l_run = rec[2 * DB * 1024 + 64 + lane];
+        if (FOX) { goff = rec[2 * DB * 1024 + 128 + lane]; koff = goff + p.cum[(size_t)bh * NC * CHUNK + (size_t)NC * CHUNK - 1]; }
+    }
 #pragma unroll
     for (int b = 0; b < DB; ++b) {
         O[b] = zero16();
@@ -224,7 +231,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
                 for (int g = 0; g < 4; ++g) {
                     const f32x4 c4 = *reinterpret_cast<const f32x4*>(ck + 8 * g);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) S[4 * g + r] = __builtin_fmaf(S[4 * g + r], sl2, -c4[r]);
+                    for (int r = 0; r < 4; ++r) S[4 * g + r] = __builtin_fmaf(S[4 * g + r], sl2, (RING == 2 ? koff : 0.f) - c4[r]);
                 }
             }
             const float sl = FOX ? 1.f : sl2;
@@ -334,6 +341,7 @@ __global__ __launch_bounds__(FWD2_THREADS, 512 / FWD2_THREADS) void attn_fwd2_ke
             }
         rec[2 * DB * 1024 + lane] = m_run;
         rec[2 * DB * 1024 + 64 + lane] = l_run;
+        rec[2 * DB * 1024 + 128 + lane] = (RING == 2 && FOX) ? koff : 0.f;
         return;
     }
 
@@ -374,8 +382,8 @@ hipError_t launch_attn_fwd2_f(const FwdParams& p, hipStream_t stream) {
 }
 template <typename TIO, int D>
 hipError_t launch_attn_fwd2_t(const FwdParams& p, hipStream_t stream) {
-    if (p.ring == 1) return launch_attn_fwd2_f<TIO, D, false, false, 1>(p, stream);      // (plain PaTH, no state output)
-    if (p.ring == 2) return launch_attn_fwd2_f<TIO, D, false, false, 2>(p, stream);
+    if (p.ring == 1) return p.cum ? launch_attn_fwd2_f<TIO, D, true, false, 1>(p, stream) : launch_attn_fwd2_f<TIO, D, false, false, 1>(p, stream);
+    if (p.ring == 2) return p.cum ? launch_attn_fwd2_f<TIO, D, true, false, 2>(p, stream) : launch_attn_fwd2_f<TIO, D, false, false, 2>(p, stream);
     if (p.emit_states) return p.cum ? launch_attn_fwd2_f<TIO, D, true, true>(p, stream) : launch_attn_fwd2_f<TIO, D, false, true>(p, stream);
     return p.cum ? launch_attn_fwd2_f<TIO, D, true, false>(p, stream) : launch_attn_fwd2_f<TIO, D, false, false>(p, stream);
 }
@@ -405,7 +413,8 @@ __global__ __launch_bounds__(64) void ring_finish_kernel(FwdParams p) {
             for (int r = 0; r < 4; ++r) v4[r] = (TIO)(o4[r] * inv);
             *reinterpret_cast<Vec4*>(orow + 32 * b + 8 * g) = v4;
         }
-    if (h == 0) p.lse[user_scl(p.ul, bh, tq)] = (m_run + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+    const float ci = p.cum ? p.cum[(size_t)bh * p.NC * CHUNK + tq] : 0.f;      // PaTH-FoX: the query's own gate sum, inside its segment
+    if (h == 0) p.lse[user_scl(p.ul, bh, tq)] = (m_run + __builtin_amdgcn_logf(l_tot) + ci) * 0.69314718055994530942f;
 }
 template <typename TIO, int D>
 static hipError_t launch_ring_finish_t(const FwdParams& p, hipStream_t stream) {

@@ -350,8 +350,9 @@ struct FwdParams {
 };
 // ring_state: per (head, query chunk, 32-query half) one record of RING_REC(d) floats, each quantity as the sweep
 // holds it: [X: d/32 blocks][O: d/32 blocks] of 1024 floats (register g*4+r of lane l at g*256 + l*4 + r), then the
-// running maximum and the row sum per lane (64 + 64).
-__host__ __device__ constexpr size_t ring_rec_floats(int d) { return (size_t)2 * (d / 32) * 1024 + 128; }
+// running maximum and the row sum per lane (64 + 64), then (PaTH-FoX; zero otherwise) the sum of the gate logarithms
+// of the segments passed so far, in base-2 units, once per lane (64).
+__host__ __device__ constexpr size_t ring_rec_floats(int d) { return (size_t)2 * (d / 32) * 1024 + 192; }
 
 // Key blocks of the backward, for query chunk i (own super-block I = i / SBC): the chunks
 // SBC*I <= j < i one by one ("near"), and the super-blocks J < I as a whole ("far": the state is

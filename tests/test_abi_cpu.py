@@ -101,21 +101,22 @@ def test_ring_argument_validation_without_gpu():
     lib = pa.load_library()
     z = 0x1000
     f = ctypes.c_float(0.125)
-    assert pa.path_attn_ring_state_bytes(2, 3, 130, 128) == 2 * 3 * 3 * 2 * (2 * 4 * 1024 + 128) * 4
+    assert pa.path_attn_ring_state_bytes(2, 3, 130, 128) == 2 * 3 * 3 * 2 * (2 * 4 * 1024 + 192) * 4
     assert pa.path_attn_ring_state_bytes(1, 1, 64, 96) == 0
-    local = lambda q=z, st=z, L=64, d=64, scale=f, dt=0, ws=z, wsb=1 << 40: lib.path_attn_ring_local(q, z, z, z, z, st, 1, 1, L, d, scale, dt, ws, wsb, None)
+    local = lambda q=z, st=z, L=64, d=64, scale=f, dt=0, ws=z, wsb=1 << 40: lib.path_attn_ring_local(q, z, z, z, z, None, st, 1, 1, L, d, scale, dt, ws, wsb, None)
     assert local(q=None) == 1 and local(st=None) == 1 and local(ws=None) == 1
     assert local(L=0) == 2 and local(d=80) == 2
     assert local(dt=7) == 3
     assert local(scale=ctypes.c_float(0.0)) == 4
     assert local(wsb=64) == 5
     assert local(st=0x1004) == 7
-    hop = lambda st=z, Lq=64, ws=z, wsb=1 << 40, Lk=64, d=64, dt=0: lib.path_attn_ring_hop(st, 1, 1, Lq, ws, wsb, Lk, d, f, dt, None)
+    hop = lambda st=z, Lq=64, ws=z, wsb=1 << 40, Lk=64, d=64, dt=0: lib.path_attn_ring_hop(st, 1, 1, Lq, ws, wsb, Lk, d, 0, f, dt, None)
     assert hop(st=None) == 1 and hop(ws=None) == 1
     assert hop(Lk=100) == 2 and "multiple of 64" in pa.path_attn_last_error()
     assert hop(Lq=0) == 2
     assert hop(wsb=128) == 5
     assert hop(dt=9) == 3
-    fin = lambda st=z, o=z, lse=z, L=64, d=64, dt=1: lib.path_attn_ring_finish(st, o, lse, 1, 1, L, d, dt, None)
+    fin = lambda st=z, o=z, lse=z, L=64, d=64, dt=1, gw=None, gwb=0: lib.path_attn_ring_finish(st, o, lse, 1, 1, L, d, dt, gw, gwb, None)
     assert fin(o=None) == 1 and fin(lse=None) == 1 and fin(st=None) == 1
     assert fin(d=100) == 2 and fin(dt=4) == 3 and fin(o=0x1002) == 7
+    assert fin(gw=z, gwb=64) == 5

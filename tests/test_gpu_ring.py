@@ -25,22 +25,23 @@ def gpu():
 
 def _ring_forward(torch, pa, dv, lengths, d, dt, scale):
     B, H = dv["q"].shape[:2]
+    gates = "logf" in dv
     starts = np.concatenate([[0], np.cumsum(lengths)]).astype(int)
     ws, st, seg = [], [], []
     for r, Ls in enumerate(lengths):
         a, b = int(starts[r]), int(starts[r + 1])
-        s = {n: dv[n][:, :, a:b].contiguous() for n in ("q", "k", "v", "w", "beta")}
+        s = {n: dv[n][:, :, a:b].contiguous() for n in dv}
         seg.append(s)
         ws.append(torch.empty(pa.path_attn_workspace_bytes(B, H, Ls, d, dt, False), dtype=torch.uint8, device="cuda"))
         st.append(torch.empty(pa.path_attn_ring_state_bytes(B, H, Ls, d), dtype=torch.uint8, device="cuda"))
-        pa.path_attn_ring_local(s["q"], s["k"], s["v"], s["w"], s["beta"], st[r], ws[r], scale=scale)
+        pa.path_attn_ring_local(s["q"], s["k"], s["v"], s["w"], s["beta"], st[r], ws[r], log_f=s.get("logf"), scale=scale)
     outs, lses = [], []
     for r, Ls in enumerate(lengths):
         for s in range(r - 1, -1, -1):             # nearest earlier segment first
-            pa.path_attn_ring_hop(st[r], B, H, Ls, ws[s], lengths[s], d, dt, scale=scale)
+            pa.path_attn_ring_hop(st[r], B, H, Ls, ws[s], lengths[s], d, dt, with_gates=gates, scale=scale)
         o = torch.empty_like(seg[r]["q"])
         lse = torch.empty((B, H, Ls), dtype=torch.float32, device="cuda")
-        pa.path_attn_ring_finish(st[r], o, lse)
+        pa.path_attn_ring_finish(st[r], o, lse, gates_workspace=ws[r] if gates else None)
         outs.append(o)
         lses.append(lse)
     torch.cuda.synchronize()
@@ -79,6 +80,33 @@ def test_ring_of_segments_matches_the_whole_sequence(gpu, oracle, dtype, d, leng
         assert (lse - lse1).abs().max().item() <= 1e-3
 
 
+@pytest.mark.parametrize("dtype,d,lengths", [("bf16", 128, [1024, 1088, 300]), ("fp32", 64, [320, 448, 130])])
+def test_ring_with_forget_gates(gpu, oracle, dtype, d, lengths):
+    """PaTH-FoX over the ring: every segment counts its gate sums from its own start; a hop adds the totals of the
+    segments passed.  Held against the oracle's gated forward of the whole sequence and the one-device gated forward."""
+    torch, pa = gpu
+    B, H, L = 1, 2, int(sum(lengths))
+    x = si.make_inputs(B, H, L, d, dtype, 4300 + L + d, 0.0)
+    rng = np.random.default_rng(4300 + L)
+    z = rng.normal(2.0, 1.0, size=(B, H, L)).astype(np.float32)
+    logf = (-np.log1p(np.exp(-z))).astype(np.float32)
+    x["logf"] = si.round_to_bf16(logf) if dtype == "bf16" else logf
+    td = torch.float32 if dtype == "fp32" else torch.bfloat16
+    dt = pa.PATH_F32 if dtype == "fp32" else pa.PATH_BF16
+    scale = d ** -0.5
+    dv = {n: torch.from_numpy(a).to("cuda").to(td).contiguous() for n, a in x.items()}
+    o, lse = _ring_forward(torch, pa, dv, lengths, d, dt, scale)
+    o_ref, lse_ref = oracle.fwd(x["q"], x["k"], x["v"], x["w"], x["beta"], scale, logf=x["logf"])
+    eo = np.abs(o.float().cpu().numpy().astype(np.float64) - o_ref).max()
+    el = np.abs(lse.cpu().numpy().astype(np.float64) - lse_ref).max()
+    print(f"[ring, gates] {dtype} d={d} segments {lengths}: o {eo:.2e} lse {el:.2e}", flush=True)
+    assert eo <= TOL_O[dtype] and el <= 1e-3
+    o1, lse1 = pa.path_attn_fox_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], dv["logf"], scale=scale)
+    torch.cuda.synchronize()
+    assert (o.float() - o1.float()).abs().max().item() <= TOL_O[dtype]
+    assert (lse - lse1).abs().max().item() <= 1e-3
+
+
 def test_ring_argument_checks(gpu):
     torch, pa = gpu
     B, H, d = 1, 2, 64
@@ -91,4 +119,4 @@ def test_ring_argument_checks(gpu):
     with pytest.raises(pa.PathAttnError) as e:
         pa.path_attn_ring_hop(st, B, H, 128, small, 128, d, pa.PATH_F32)       # not a segment's workspace
     assert e.value.code == 5                                                    # PATH_ERR_WORKSPACE
-    assert pa.path_attn_ring_state_bytes(B, H, 128, d) == B * H * 2 * 2 * (2 * (d // 32) * 1024 + 128) * 4
+    assert pa.path_attn_ring_state_bytes(B, H, 128, d) == B * H * 2 * 2 * (2 * (d // 32) * 1024 + 192) * 4

@@ -60,3 +60,78 @@ def test_chunk_product_and_boundary_rows():
         for s in range(t + 1, C):
             z = Hs[s] @ z                       # H_{C-1} ... H_{t+1} k_t
         np.testing.assert_allclose(pre["Kb"][t], z, atol=1e-12)
+
+
+@pytest.mark.parametrize("with_gates", [False, True])
+@pytest.mark.parametrize("lengths", [[48, 48, 48], [64, 32, 20], [16, 96, 1]])
+def test_sequence_split_into_segments_reproduces_the_walk(oracle, lengths, with_gates):
+    """The sequence-parallel scheme of Sec. 3.5 as the kernels read it, in fp64 on the CPU: every segment runs the
+    block recipe on its own tokens only (chunks of 16, super-blocks of 2 chunks here); a query's state is carried to
+    its segment's left edge; a hop attends ALL keys of an earlier segment -- keys carried to their super-block's
+    right edge, one product per super-block, the first one's included -- and partial softmaxes are merged through
+    their running maximum and sum.  With forget gates every segment counts its gate sums from its own start and a
+    hop adds the totals of the segments passed.  The result equals the token walk over the whole sequence."""
+    C, SB, d, scale = 16, 2, 8, 0.4
+    L = sum(lengths)
+    x = _head(L, d, 31 + L)
+    logf = None
+    if with_gates:
+        logf = -np.log1p(np.exp(-np.random.default_rng(L).normal(1.0, 1.0, L)))
+    args = [x[n][None, None] for n in ("q", "k", "v", "w", "beta")]
+    o_ref, lse_ref = oracle.fwd(*args, scale, logf=None if logf is None else logf[None, None])
+    starts = np.concatenate([[0], np.cumsum(lengths)])
+
+    def prep_segment(a, b):
+        n = b - a
+        nc = -(-n // C)
+        pad = lambda t: bm._pad(t[a:b], nc * C)
+        q, k, v, w, beta = (pad(x[m]) for m in ("q", "k", "v", "w", "beta"))
+        pre = [bm.chunk_prep(q[c * C:(c + 1) * C], k[c * C:(c + 1) * C], w[c * C:(c + 1) * C], beta[c * C:(c + 1) * C]) for c in range(nc)]
+        # second level: keys carried to their super-block's right edge, super-block products
+        kb2, p2 = [None] * nc, []
+        for J in range(-(-nc // SB)):
+            R = np.eye(d)
+            for c in range(min((J + 1) * SB, nc) - 1, J * SB - 1, -1):
+                kb2[c] = pre[c]["Kb"] @ R.T
+                R = R @ (np.eye(d) - pre[c]["dP"])
+            p2.append(R)
+        cum = np.cumsum(bm._pad(logf[a:b], nc * C)) if logf is not None else np.zeros(nc * C)
+        return dict(n=n, nc=nc, pre=pre, kb2=kb2, p2=p2, v=v, cum=cum)
+
+    seg = [prep_segment(int(starts[r]), int(starts[r + 1])) for r in range(len(lengths))]
+    o = np.zeros((L, d))
+    lse = np.zeros(L)
+    for r, s in enumerate(seg):
+        nc = s["nc"]
+        for c in range(nc):
+            rows = slice(c * C, (c + 1) * C)
+            # own segment: diagonal block, then the chunks to the left one by one; the product of chunk 0 too
+            X = s["pre"][c]["Qb"].copy()
+            S = [np.where(np.tril(np.ones((C, C))) > 0, scale * s["pre"][c]["Sd"] - s["cum"][None, rows], -np.inf)]
+            V = [s["v"][rows]]
+            for j in range(c - 1, -1, -1):
+                S.append(scale * X @ s["pre"][j]["Kb"].T - s["cum"][None, j * C:(j + 1) * C])
+                V.append(s["v"][j * C:(j + 1) * C])
+                X = X - X @ s["pre"][j]["dP"]
+            passed = 0.0
+            for t in range(r - 1, -1, -1):             # hops, nearest earlier segment first
+                e = seg[t]
+                assert e["n"] == e["nc"] * C            # an earlier segment is a whole number of chunks
+                total = e["cum"][-1]
+                for j in range(e["nc"] - 1, -1, -1):
+                    S.append(scale * X @ e["kb2"][j].T + (passed + total - e["cum"][None, j * C:(j + 1) * C]))
+                    V.append(e["v"][j * C:(j + 1) * C])
+                    if j % SB == 0:
+                        X = X @ e["p2"][j // SB]
+                passed += total
+            S = np.concatenate(S, axis=1)
+            V = np.concatenate(V, axis=0)
+            m = S.max(axis=1, keepdims=True)
+            P = np.exp(S - m)
+            l = P.sum(axis=1, keepdims=True)
+            g0 = int(starts[r]) + c * C
+            nrow = min(C, s["n"] - c * C)
+            o[g0:g0 + nrow] = (P @ V / l)[:nrow]
+            lse[g0:g0 + nrow] = (m + np.log(l) + s["cum"][rows, None])[:nrow, 0]
+    np.testing.assert_allclose(o, o_ref[0, 0], atol=1e-10)
+    np.testing.assert_allclose(lse, lse_ref[0, 0], atol=1e-10)

@@ -70,3 +70,42 @@ def test_training_step_replays_from_a_graph(gpu, dtype, B, H, L, d):
         # eager work of the program between the replays
         pa.path_attn_fwd(od["q"], od["k"], od["v"], od["w"], od["beta"], scale=0.125)
         torch.cuda.synchronize()
+
+
+def test_allocation_free_decode_step_replays_from_a_graph(gpu):
+    """path_decode_step_static is for callers that cannot allocate -- code under graph capture is one.  The step
+    refreshes the key cache in place, so every replay starts from a restored cache."""
+    torch, pa = gpu
+    B, H, n, d = 2, 8, 900, 128
+    x = si.make_inputs(B, H, n + 2, d, "bf16", 3300, 0.0)
+    dev = {k_: torch.from_numpy(a).to("cuda").to(torch.bfloat16).contiguous() for k_, a in x.items()}
+    tok = [dev[k_][:, :, n].contiguous() for k_ in ("q", "k", "v", "w")] + [dev["beta"][:, :, n].contiguous()]
+    kc0, vc0 = dev["k"].clone(), dev["v"].clone()
+    kc0[:, :, n:] = 0
+    vc0[:, :, n:] = 0
+    kc, vc = kc0.clone(), vc0.clone()
+    o = torch.empty((B, H, d), dtype=torch.bfloat16, device="cuda")
+    lse = torch.empty((B, H), dtype=torch.float32, device="cuda")
+    scale = d ** -0.5
+    pa.path_decode_step_static(*tok, kc, vc, n, scale, o, lse)            # eager (also looks the static array up, once per device)
+    torch.cuda.synchronize()
+    ref = [t.clone() for t in (o, lse, kc, vc)]
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    kc.copy_(kc0); vc.copy_(vc0)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        pa.path_decode_step_static(*tok, kc, vc, n, scale, o, lse)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        kc.copy_(kc0); vc.copy_(vc0); o.zero_(); lse.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, want in zip((o, lse, kc, vc), ref):
+            assert torch.equal(got, want), rep
+        pa.path_attn_fwd(dev["q"][:, :, :200].contiguous(), dev["k"][:, :, :200].contiguous(), dev["v"][:, :, :200].contiguous(),
+                         dev["w"][:, :, :200].contiguous(), dev["beta"][:, :, :200].contiguous())          # eager work in between
+        torch.cuda.synchronize()

@@ -137,3 +137,10 @@ def test_headline_shape_backward_sampled_head(gpu, oracle):
     against the oracle."""
     x, c = si.make_config(2, with_do=True)
     _check(gpu, oracle, x, "bf16", c["d"] ** -0.5, heads=[0, 13, 41, 50, 63], tag="headline shape")
+
+
+def test_bwd_long_context_with_beta_near_two(gpu, oracle):
+    """Sixteen super-blocks (16384 tokens, d = 128) with beta drawn as in the long-context configuration (near 2, some
+    exactly 2.0 after rounding): the far chains of the second level and their adjoint over many blocks."""
+    x = si.make_inputs(1, 1, 16384, 128, "bf16", 5555, 2.0, with_do=True)
+    _check(gpu, oracle, x, "bf16", 128 ** -0.5, tag="bwd long context, beta near 2")

@@ -36,13 +36,18 @@ def key_prefill(k, w, beta):
     return kc
 
 
-def decode_step(q_t, k_t, v_t, w_t, beta_t, kc, vc, scale, round_cache=None):
+def decode_step(q_t, k_t, v_t, w_t, beta_t, kc, vc, scale, round_cache=None, logf_t=None, cc=None):
     """One decoding step.  kc, vc [..., n, d]: caches before the step.
 
     Returns o_t [..., d], lse_t [...], and the caches after the step ([..., n+1, d]).
     ``round_cache`` (optional) is applied to the refreshed keys before they are used and
     stored: it models a cache kept in a narrower storage type, where the rounding of every
     in-place update is part of the method as run.
+
+    PaTH-FoX (Sec. 2.2 extension, at decode time): ``logf_t`` [...] is the arriving token's log gate and ``cc``
+    [..., n] the running sums c_i = sum_{s<=i} log f_s of the cached tokens.  The arriving token's sum is
+    c_t = c_{t-1} + log f_t, key i's logit gets c_t - c_i = sum_{s=i+1..t} log f_s (the token's own gets 0), and
+    the sums after the step, [..., n+1], are returned as a fifth value.
     """
     q_t = np.asarray(q_t, dtype=np.float64)
     kc = cache_update(kc, w_t, beta_t)
@@ -51,9 +56,16 @@ def decode_step(q_t, k_t, v_t, w_t, beta_t, kc, vc, scale, round_cache=None):
         kc = round_cache(kc)
     vc = np.concatenate([np.asarray(vc, dtype=np.float64), np.asarray(v_t, dtype=np.float64)[..., None, :]], axis=-2)
     s = scale * np.einsum("...nd,...d->...n", kc, q_t)
+    if logf_t is not None:
+        cc = np.asarray(cc, dtype=np.float64)
+        prev = cc[..., -1] if cc.shape[-1] else np.zeros(cc.shape[:-1])
+        cc = np.concatenate([cc, (prev + np.asarray(logf_t, dtype=np.float64))[..., None]], axis=-1)
+        s = s + (cc[..., -1:] - cc)
     m = s.max(axis=-1, keepdims=True)
     p = np.exp(s - m)
     z = p.sum(axis=-1, keepdims=True)
     o = np.einsum("...n,...nd->...d", p / z, vc)
     lse = (m + np.log(z))[..., 0]
+    if logf_t is not None:
+        return o, lse, kc, vc, cc
     return o, lse, kc, vc

@@ -42,6 +42,37 @@ def test_decode_steps_equal_forward_rows():
         assert np.abs(lse - lse_ref[:, :, t]).max() <= 1e-12
 
 
+def test_gated_decode_steps_equal_gated_forward_rows():
+    # PaTH-FoX at decode time: with the running gate sums of the cached tokens, prefill + decoding reproduces the
+    # gated forward oracle's rows (code the decode oracle shares nothing with); gates of exactly 1 (log f = 0)
+    # reproduce the plain steps.
+    x = _x(L=31, d=8, seed=6)
+    scale = 8 ** -0.5
+    rng = np.random.default_rng(6)
+    logf = -np.log1p(np.exp(-rng.normal(1.0, 1.0, size=x["beta"].shape)))
+    o_ref, lse_ref = path_oracle.fwd(x["q"], x["k"], x["v"], x["w"], x["beta"], scale, logf=logf)
+    l0 = 12
+    kc = dec.key_prefill(x["k"][:, :, :l0], x["w"][:, :, :l0], x["beta"][:, :, :l0])
+    vc = x["v"][:, :, :l0].astype(np.float64)
+    cc = np.cumsum(logf[:, :, :l0], axis=-1)
+    kc0, vc0 = kc.copy(), vc.copy()
+    for t in range(l0, 31):
+        o, lse, kc, vc, cc = dec.decode_step(x["q"][:, :, t], x["k"][:, :, t], x["v"][:, :, t], x["w"][:, :, t],
+                                             x["beta"][:, :, t], kc, vc, scale, logf_t=logf[:, :, t], cc=cc)
+        assert np.abs(o - o_ref[:, :, t]).max() <= 1e-12
+        assert np.abs(lse - lse_ref[:, :, t]).max() <= 1e-12
+    assert np.abs(cc - np.cumsum(logf, axis=-1)).max() <= 1e-12
+    plain = dec.decode_step(x["q"][:, :, l0], x["k"][:, :, l0], x["v"][:, :, l0], x["w"][:, :, l0], x["beta"][:, :, l0], kc0, vc0, scale)
+    unit = dec.decode_step(x["q"][:, :, l0], x["k"][:, :, l0], x["v"][:, :, l0], x["w"][:, :, l0], x["beta"][:, :, l0], kc0, vc0, scale,
+                           logf_t=np.zeros(x["beta"].shape[:2]), cc=np.zeros(x["beta"].shape[:2] + (l0,)))
+    assert np.array_equal(plain[0], unit[0]) and np.array_equal(plain[1], unit[1])
+    # an empty cache: the first token attends only itself, whatever its gate
+    e = dec.decode_step(x["q"][:, :, 0], x["k"][:, :, 0], x["v"][:, :, 0], x["w"][:, :, 0], x["beta"][:, :, 0],
+                        x["k"][:, :, :0].astype(np.float64), x["v"][:, :, :0].astype(np.float64), scale,
+                        logf_t=logf[:, :, 0], cc=logf[:, :, :0])
+    assert np.abs(e[0] - x["v"][:, :, 0]).max() <= 1e-12 and np.abs(e[4][..., 0] - logf[:, :, 0]).max() <= 1e-15
+
+
 def test_beta_zero_leaves_the_cache_alone_and_beta_two_reflects():
     x = _x(L=12, d=6, seed=3)
     kc = x["k"].astype(np.float64)

@@ -319,6 +319,23 @@ path_status_t path_decode_step(const void* q, const void* k, const void* v, cons
                                void* stream);
 
 /*
+ * PaTH-FoX at decode time (paper Sec. 2.2 "Extension: PaTH-FoX" applied to the decoding step of Sec. 3.4): key i's
+ * logit gets sum_{s=i+1..t} log f_s.  The running sums c_i = sum_{s<=i} log f_s of the cached tokens are a third
+ * cache, `ccache` [B,H,Lmax] fp32 (natural logarithm, caller-owned device memory like the other two).
+ *   path_gate_prefill     fills ccache[.., 0..L) from the prompt's gates log_f [B,H,L] (I/O type).
+ *   path_decode_step_fox  path_decode_step with the arriving token's log gate log_f [B,H] (I/O type): uses
+ *                         c_n = c_{n-1} + log f_n (c_{-1} = 0), adds c_n - c_i to key i's logit (nothing to the
+ *                         token's own) and appends c_n to ccache.  Everything else -- caches, workspace, errors --
+ *                         as for path_decode_step.
+ */
+path_status_t path_gate_prefill(const void* log_f, int B, int H, int L, path_dtype_t dt, float* ccache, int Lmax,
+                                void* stream);
+path_status_t path_decode_step_fox(const void* q, const void* k, const void* v, const void* w, const void* beta,
+                                   const void* log_f, void* kcache, void* vcache, float* ccache, int n, int Lmax,
+                                   void* o, float* lse, int B, int H, int d, float scale, path_dtype_t dt,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * Sequence-parallel forward: ONE device's share of the ring of paper Sec. 3.5 ("context parallelism": the
  * sequence is split into contiguous segments, one per device; a device attends its own segment, then the
  * segments to its left one hop at a time, applying one d x d product per super-block it has passed).  The three

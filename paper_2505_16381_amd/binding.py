@@ -99,6 +99,10 @@ def load_library():
     lib.path_probe_mfma_flops.argtypes = [ci, ci]
     lib.path_probe_mfma.restype = ci
     lib.path_probe_mfma.argtypes = [vp, ci, ci, vp]
+    lib.path_gate_prefill.restype = ci
+    lib.path_gate_prefill.argtypes = [vp, ci, ci, ci, ci, vp, ci, vp]
+    lib.path_decode_step_fox.restype = ci
+    lib.path_decode_step_fox.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, ci, ci, ci, ctypes.c_float, ci, vp, ctypes.c_size_t, vp]
     lib.path_attn_ring_state_bytes.restype = ctypes.c_size_t
     lib.path_attn_ring_state_bytes.argtypes = [ci, ci, ci, ci]
     lib.path_attn_ring_local.restype = ci
@@ -269,6 +273,27 @@ def path_decode_step(q, k, v, w, beta, kcache, vcache, n, scale, workspace=None,
     _check(load_library().path_decode_step(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(kcache), _ptr(vcache),
                                            int(n), kcache.shape[2], _ptr(o), _ptr(lse), B, H, d, float(scale), _dt_of(q),
                                            _ptr(workspace), workspace.numel(), _stream_handle(stream)))
+    return o, lse
+
+
+def path_gate_prefill(log_f, ccache, stream=None):
+    """Running sums of the prompt's log gates log_f [B,H,L] into ccache [B,H,Lmax] (fp32)."""
+    B, H, L = log_f.shape
+    _check(load_library().path_gate_prefill(_ptr(log_f), B, H, L, _dt_of(log_f), _ptr(ccache), ccache.shape[2], _stream_handle(stream)))
+
+
+def path_decode_step_fox(q, k, v, w, beta, log_f, kcache, vcache, ccache, n, scale, workspace=None, stream=None):
+    """path_decode_step with forget gates: log_f [B,H] is the arriving token's log gate, ccache [B,H,Lmax] (fp32)
+    the running sums of the cached tokens (updated in place)."""
+    import torch
+    B, H, d = q.shape
+    if workspace is None:
+        workspace = torch.empty(path_decode_workspace_bytes(B, H, d), dtype=torch.uint8, device=q.device)
+    o = torch.empty_like(q)
+    lse = torch.empty((B, H), dtype=torch.float32, device=q.device)
+    _check(load_library().path_decode_step_fox(_ptr(q), _ptr(k), _ptr(v), _ptr(w), _ptr(beta), _ptr(log_f), _ptr(kcache), _ptr(vcache),
+                                               _ptr(ccache), int(n), kcache.shape[2], _ptr(o), _ptr(lse), B, H, d, float(scale), _dt_of(q),
+                                               _ptr(workspace), workspace.numel(), _stream_handle(stream)))
     return o, lse
 
 

@@ -658,8 +658,41 @@ extern "C" path_status_t path_decode_step(const void* q, const void* k, const vo
     const void* al[] = {q, k, v, w, kcache, vcache, o};
     for (const void* ptr : al) if (misaligned(ptr)) return PATH_ERR_ALIGN;
     clear_inherited_error();
-    DecodeArgs a{q, k, v, w, beta, kcache, vcache, o, lse, static_cast<float*>(workspace), n, Lmax, scale};
+    DecodeArgs a{q, k, v, w, beta, kcache, vcache, o, lse, static_cast<float*>(workspace), n, Lmax, scale, nullptr, nullptr};
     if (!hip_ok(launch_decode_step(a, B * H, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "decode step"))
+        return PATH_ERR_HIP;
+    return PATH_OK;
+}
+
+// PaTH-FoX at decode time: the running sums of the log gates are a third cache.
+extern "C" path_status_t path_gate_prefill(const void* log_f, int B, int H, int L, path_dtype_t dt, float* ccache, int Lmax,
+                                           void* stream) {
+    if (!log_f || !ccache) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (B < 1 || H < 1 || L < 1 || L > Lmax || (long long)B * H > 65535) return PATH_ERR_SHAPE;
+    clear_inherited_error();
+    ScanArgs a{log_f, nullptr, ccache, L, Lmax, L, L, 1, 1.f, 0, 0, layout_of(PATH_LAYOUT_BHLD, H, L, 64)};
+    if (!hip_ok(launch_fox_scan(a, B * H, dt == PATH_BF16 ? 1 : 0, 0, static_cast<hipStream_t>(stream)), "gate sums of the prompt"))
+        return PATH_ERR_HIP;
+    return PATH_OK;
+}
+
+extern "C" path_status_t path_decode_step_fox(const void* q, const void* k, const void* v, const void* w,
+                                              const void* beta, const void* log_f, void* kcache, void* vcache,
+                                              float* ccache, int n, int Lmax, void* o, float* lse, int B, int H, int d,
+                                              float scale, path_dtype_t dt, void* workspace, size_t workspace_bytes,
+                                              void* stream) {
+    if (!q || !k || !v || !w || !beta || !log_f || !kcache || !vcache || !ccache || !o || !lse || !workspace) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (B < 1 || H < 1 || (d != 64 && d != 128) || (long long)B * H > 65535 || n < 0 || n >= Lmax) return PATH_ERR_SHAPE;
+    if (!(scale > 0.f)) return PATH_ERR_UNSUPPORTED;
+    if (workspace_bytes < path_decode_workspace_bytes(B, H, d) || (reinterpret_cast<uintptr_t>(workspace) & 255))
+        return PATH_ERR_WORKSPACE;
+    const void* al[] = {q, k, v, w, kcache, vcache, o};
+    for (const void* ptr : al) if (misaligned(ptr)) return PATH_ERR_ALIGN;
+    clear_inherited_error();
+    DecodeArgs a{q, k, v, w, beta, kcache, vcache, o, lse, static_cast<float*>(workspace), n, Lmax, scale, log_f, ccache};
+    if (!hip_ok(launch_decode_step(a, B * H, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "gated decode step"))
         return PATH_ERR_HIP;
     return PATH_OK;
 }
@@ -713,7 +746,7 @@ extern "C" path_status_t path_decode_step_static(const void* q, const void* k, c
     void* ws = scratch_on_current_device();
     if (!ws) return PATH_ERR_HIP;
     // (nothing in the array has to start at zero: every split writes its whole record before the merge reads it)
-    DecodeArgs a{q, k, v, w, beta, kcache, vcache, o, lse, static_cast<float*>(ws), n, Lmax, scale};
+    DecodeArgs a{q, k, v, w, beta, kcache, vcache, o, lse, static_cast<float*>(ws), n, Lmax, scale, nullptr, nullptr};
     if (!hip_ok(launch_decode_step(a, B * H, d, dt == PATH_BF16, static_cast<hipStream_t>(stream)), "decode step (static scratch)"))
         return PATH_ERR_HIP;
     return PATH_OK;

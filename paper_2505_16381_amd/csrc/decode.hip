@@ -18,6 +18,10 @@
 //    (read k, write k, read v: 3 n d elements per head -- HBM-bound), split over the cached
 //    positions; a second small kernel merges the splits, adds the arriving token's own key and
 //    value, and appends them to the caches.
+//
+//  * PaTH-FoX at decode time (Sec. 2.2 extension): with the running sums c_i of the log gates kept beside the
+//    caches, key i's logit gets c_t - c_i, c_t = c_{t-1} + log f_t; the arriving token's own logit gets nothing
+//    and its sum is appended (GATES instantiations of the two kernels).
 #include "path_common.h"
 #include "decode_decl.h"
 
@@ -131,7 +135,7 @@ __global__ __launch_bounds__(256) void key_prefill_kernel(PrefillArgs a) {
 // One pass over the cached keys of a split: refresh, logit, online softmax, P V.
 // A key is handled by LPK = D/8 consecutive lanes (8 elements each); a wave takes 64/LPK keys
 // per round.  Partial results (m, l, o[D]) per split go to the workspace.
-template <typename TIO, int D>
+template <typename TIO, int D, bool GATES>
 __global__ __launch_bounds__(256) void decode_partial_kernel(DecodeArgs a) {
     constexpr int LPK = D / 8, KPW = 64 / LPK, GROUPS = 4 * KPW;
     typedef TIO Vec8 __attribute__((ext_vector_type(8)));
@@ -152,6 +156,8 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecodeArgs a) {
         for (int e = 0; e < 8; ++e) { q8[e] = (float)qv[e]; w8[e] = (float)wv8[e]; }
     }
     const float beta = (float)reinterpret_cast<const TIO*>(a.beta)[bh];
+    const float* cc = GATES ? a.ccache + (size_t)bh * a.Lmax : nullptr;
+    const float c_t = GATES ? (n > 0 ? cc[n - 1] : 0.f) + (float)reinterpret_cast<const TIO*>(a.log_f)[bh] : 0.f;
     auto group_sum = [&](float x) {
 #pragma unroll
         for (int off = 1; off < LPK; off <<= 1) x += __shfl_xor(x, off);
@@ -193,7 +199,7 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecodeArgs a) {
         qk = group_sum(qk);
         if (ok) {
             *reinterpret_cast<Vec8*>(kc + (size_t)i * D) = kn;
-            const float s = a.scale * qk;
+            const float s = GATES ? a.scale * qk + (c_t - cc[i]) : a.scale * qk;
             const float mn = fmaxf(m, s);
             const float alpha = __expf(m - mn), pr = __expf(s - mn);      // m = -inf first time: alpha = 0
             l = l * alpha + pr;
@@ -224,7 +230,7 @@ __global__ __launch_bounds__(256) void decode_partial_kernel(DecodeArgs a) {
 }
 
 // Merge the splits, add the arriving token's own key/value, normalise; append to the caches.
-template <typename TIO, int D>
+template <typename TIO, int D, bool GATES>
 __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeArgs a, int nsplit) {
     __shared__ float sq[D];
     const int bh = blockIdx.x, c = threadIdx.x;
@@ -252,6 +258,10 @@ __global__ __launch_bounds__(D) void decode_combine_kernel(DecodeArgs a, int nsp
     if (c == 0) a.lse[bh] = M + __logf(Ls);
     reinterpret_cast<TIO*>(a.kcache)[((size_t)bh * a.Lmax + a.n) * D + c] = kt;
     reinterpret_cast<TIO*>(a.vcache)[((size_t)bh * a.Lmax + a.n) * D + c] = vt;
+    if (GATES && c == 0) {      // the arriving token's running gate sum joins the cache (its own logit carries no gate)
+        float* cc = a.ccache + (size_t)bh * a.Lmax;
+        cc[a.n] = (a.n > 0 ? cc[a.n - 1] : 0.f) + (float)reinterpret_cast<const TIO*>(a.log_f)[bh];
+    }
 }
 
 // ---------------------------------------------------------------------------------------
@@ -277,14 +287,18 @@ int decode_num_splits(int BH, int n) {
     return s < 1 ? 1 : s;
 }
 
-template <typename TIO, int D>
-static hipError_t launch_decode_t(const DecodeArgs& a, int BH, hipStream_t st) {
+template <typename TIO, int D, bool GATES>
+static hipError_t launch_decode_g(const DecodeArgs& a, int BH, hipStream_t st) {
     const int nsplit = decode_num_splits(BH, a.n);
-    hipLaunchKernelGGL((decode_partial_kernel<TIO, D>), dim3(nsplit, BH), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((decode_partial_kernel<TIO, D, GATES>), dim3(nsplit, BH), dim3(256), 0, st, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL((decode_combine_kernel<TIO, D>), dim3(BH), dim3(D), 0, st, a, nsplit);
+    hipLaunchKernelGGL((decode_combine_kernel<TIO, D, GATES>), dim3(BH), dim3(D), 0, st, a, nsplit);
     return hipGetLastError();
+}
+template <typename TIO, int D>
+static hipError_t launch_decode_t(const DecodeArgs& a, int BH, hipStream_t st) {
+    return a.ccache ? launch_decode_g<TIO, D, true>(a, BH, st) : launch_decode_g<TIO, D, false>(a, BH, st);
 }
 hipError_t launch_decode_step(const DecodeArgs& a, int BH, int d, int is_bf16, hipStream_t st) {
     if (is_bf16) return d == 64 ? launch_decode_t<bf16_t, 64>(a, BH, st) : launch_decode_t<bf16_t, 128>(a, BH, st);

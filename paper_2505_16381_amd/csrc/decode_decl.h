@@ -20,6 +20,10 @@ struct DecodeArgs {
     float* partial;                     // [BH][splits][d + 2]: m, l, o
     int n, Lmax;                        // cached tokens before the step
     float scale;
+    // PaTH-FoX (NULL for plain PaTH): the arriving token's log gate [BH] (I/O type) and the running sums
+    // c_i = sum_{s<=i} log f_s of the cached tokens, fp32 [BH][Lmax], natural logarithm; the step appends c_n
+    const void* log_f;
+    float* ccache;
 };
 
 hipError_t launch_key_prefill(const PrefillArgs& a, int BH, int d, int is_bf16, hipStream_t st);

@@ -188,3 +188,66 @@ def test_decode_argument_checks(gpu):
     with pytest.raises(pa.PathAttnError) as e:
         pa.path_decode_step(z, z, z, z, beta, kc, kc.clone(), 0, 0.0)            # scale must be positive
     assert e.value.code == 4
+
+
+@pytest.mark.parametrize("dtype,L0,steps,d", [("fp32", 130, 40, 64), ("fp32", 1, 24, 128), ("bf16", 600, 64, 128)])
+def test_gated_decode_steps_match_the_oracle(gpu, dec, oracle, dtype, L0, steps, d):
+    """PaTH-FoX at decode time: gate prefill + gated steps against the gated decode oracle (its own prefill, its own
+    running sums) and, for the last step, against the gated FORWARD oracle's row.  fp32 caches: the forward's bars.
+    bf16 caches: the drift law of the plain bf16 case, with one change.  There the log-sum-exp averages the logits'
+    errors over all L0 + n cached keys; gates concentrate the attention on the recent ones, so the average runs over
+    the effective number of keys of the gate profile g_i = exp(c_t - c_i), n_eff = (sum g)^2 / sum g^2 (here about 15),
+    and the bar is 1e-3 + 3 * 2^-9 * sqrt((n + 1) / n_eff).  The sums themselves are kept in fp32 and add nothing."""
+    torch, pa = gpu
+    L = L0 + steps
+    x = si.make_inputs(2, 2, L, d, dtype, 990 + L + d, 0.0)
+    rng = np.random.default_rng(990 + L)
+    logf = (-np.log1p(np.exp(-rng.normal(2.0, 1.0, size=(2, 2, L))))).astype(np.float32)
+    x["logf"] = si.round_to_bf16(logf) if dtype == "bf16" else logf
+    dv, td = _dev(gpu, x, dtype)
+    scale = d ** -0.5
+    kc, vc = _prefill(gpu, dv, td, L0, L)
+    cc = torch.zeros((2, 2, L), dtype=torch.float32, device="cuda")
+    pa.path_gate_prefill(dv["logf"][:, :, :L0].contiguous(), cc)
+    torch.cuda.synchronize()
+    occ = np.cumsum(x["logf"][:, :, :L0].astype(np.float64), axis=-1)
+    assert np.abs(cc[:, :, :L0].cpu().numpy() - occ).max() <= 1e-4 and float(cc[:, :, L0:].abs().max()) == 0.0
+    okc, ovc = _oracle_prefill(dec, x, L0)
+    wo = wl = 0.0
+    for t in range(L0, L):
+        tok = [dv[n][:, :, t].contiguous() for n in ("q", "k", "v", "w")] + [dv["beta"][:, :, t].contiguous(), dv["logf"][:, :, t].contiguous()]
+        o, lse = pa.path_decode_step_fox(*tok, kc, vc, cc, t, scale)
+        torch.cuda.synchronize()
+        o_ref, lse_ref, okc, ovc, occ = dec.decode_step(x["q"][:, :, t], x["k"][:, :, t], x["v"][:, :, t], x["w"][:, :, t], x["beta"][:, :, t],
+                                                        okc, ovc, scale, logf_t=x["logf"][:, :, t], cc=occ)
+        wo = max(wo, np.abs(o.float().cpu().numpy() - o_ref).max())
+        el = np.abs(lse.cpu().numpy() - lse_ref).max()
+        wl = max(wl, el)
+        if dtype == "bf16":
+            n = t - L0 + 1
+            g = np.exp(occ[..., -1:] - occ)
+            n_eff = min(float((g.sum(-1) ** 2 / (g ** 2).sum(-1)).min()), L0 + n)
+            assert el <= 1e-3 + 3.0 * 2.0 ** -9 * np.sqrt((n + 1) / n_eff), (n, el, n_eff)
+    assert np.abs(cc.cpu().numpy() - occ).max() <= 1e-4 * max(1.0, np.abs(occ).max())
+    # the last step is the gated forward's last row
+    o_fw, lse_fw = oracle.fwd(x["q"], x["k"], x["v"], x["w"], x["beta"], scale, rows=np.array([L - 1]), logf=x["logf"])
+    eo = np.abs(o.float().cpu().numpy() - o_fw[:, :, 0]).max()
+    ef = np.abs(lse.cpu().numpy() - lse_fw[:, :, 0]).max()
+    print(f"[gated decode {dtype} L0={L0} steps={steps} d={d}] max|do|={wo:.2e} max|dlse|={wl:.2e}; last step against the forward row: {eo:.2e} {ef:.2e}", flush=True)
+    if dtype == "fp32":
+        assert wo <= 1e-4 and wl <= 1e-3 and eo <= 1e-4 and ef <= 1e-3
+    else:
+        assert wo <= 2e-2 and eo <= 2e-2 and ef <= 1e-3 + 3.0 * 2.0 ** -9 * np.sqrt((steps + 1) / n_eff)
+
+
+def test_gated_decode_argument_checks(gpu):
+    torch, pa = gpu
+    z = torch.zeros((1, 2, 64), device="cuda")
+    cc = torch.zeros((1, 2, 8), device="cuda")
+    kc = torch.zeros((1, 2, 8, 64), device="cuda")
+    with pytest.raises(pa.PathAttnError) as e:
+        pa.path_decode_step_fox(z, z, z, z, torch.zeros((1, 2), device="cuda"), torch.zeros((1, 2), device="cuda"), kc, kc.clone(), cc, 8, 0.125)
+    assert e.value.code == 2                       # the cache is full: n must be < Lmax
+    with pytest.raises(pa.PathAttnError) as e:
+        pa.path_gate_prefill(torch.zeros((1, 2, 9), device="cuda"), cc)
+    assert e.value.code == 2                       # a prompt longer than the cache

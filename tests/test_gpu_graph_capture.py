@@ -3,7 +3,7 @@ forward + backward step can be captured in a HIP graph and replayed (run with -m
 
 The graph is replayed several times with new values in the same input buffers, with eager work and
 synchronisations of the program between the replays, and every replay is held bit for bit against the eager
-result for the same inputs.
+result for the same inputs.  A last test overlaps two steps on two streams, each with a workspace of its own.
 """
 import numpy as np
 import pytest
@@ -109,3 +109,46 @@ def test_allocation_free_decode_step_replays_from_a_graph(gpu):
         pa.path_attn_fwd(dev["q"][:, :, :200].contiguous(), dev["k"][:, :, :200].contiguous(), dev["v"][:, :, :200].contiguous(),
                          dev["w"][:, :, :200].contiguous(), dev["beta"][:, :, :200].contiguous())          # eager work in between
         torch.cuda.synchronize()
+
+
+def test_two_streams_with_their_own_workspaces_do_not_disturb_each_other(gpu):
+    """Calls that use distinct workspaces may overlap on different streams (the header's thread-safety rule): two
+    forward + backward steps enqueued alternately on two streams give the bits of the same steps run one after the other."""
+    torch, pa = gpu
+    probs = []
+    for i, (B, H, L, d) in enumerate(((1, 4, 1500, 128), (2, 3, 900, 64))):
+        x = si.make_inputs(B, H, L, d, "bf16", 3400 + i, 0.0, with_do=True)
+        dv = {n: torch.from_numpy(a).to("cuda").to(torch.bfloat16).contiguous() for n, a in x.items()}
+        ws = torch.empty(pa.path_attn_workspace_bytes(B, H, L, d, pa.PATH_BF16, True), dtype=torch.uint8, device="cuda")
+        probs.append((dv, ws, d ** -0.5))
+
+    def fwd(p, stream=None):
+        dv, ws, sc = p
+        return pa.path_attn_train_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], ws, scale=sc, stream=stream)
+
+    def bwd(p, o, lse, stream=None):
+        dv, ws, sc = p
+        return pa.path_attn_train_bwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], o, lse, dv["dO"], ws, scale=sc, stream=stream)
+
+    serial = []
+    for p in probs:
+        o, lse = fwd(p)
+        serial.append([t.clone() for t in (o, lse) + tuple(bwd(p, o, lse))])
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for s in streams:
+        s.wait_stream(torch.cuda.current_stream())
+    outs = [None, None]
+    for rep in range(2):
+        with torch.cuda.stream(streams[0]):
+            f0 = fwd(probs[0], streams[0])
+        with torch.cuda.stream(streams[1]):
+            f1 = fwd(probs[1], streams[1])
+        with torch.cuda.stream(streams[0]):
+            outs[0] = f0 + tuple(bwd(probs[0], *f0, streams[0]))
+        with torch.cuda.stream(streams[1]):
+            outs[1] = f1 + tuple(bwd(probs[1], *f1, streams[1]))
+        torch.cuda.synchronize()
+        for i in range(2):
+            for got, want in zip(outs[i], serial[i]):
+                assert torch.equal(got, want), (rep, i)

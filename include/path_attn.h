@@ -366,6 +366,11 @@ path_status_t path_decode_step_fox(const void* q, const void* k, const void* v, 
  * fp32 between the calls.  Other lengths differ from it by rounding only.  Errors as for path_attn_fwd.
  */
 size_t path_attn_ring_state_bytes(int B, int H, int L, int d);
+/* Byte offsets and lengths, inside a segment's workspace, of the four regions a hop reads (host arrays of 4):
+ * [0] second-level keys, [1] values, [2] super-block products, [3] gate sums (PaTH-FoX only).  A device that
+ * receives an earlier segment needs a buffer of path_attn_workspace_bytes(B,H,L,d,dt,0) bytes with these regions
+ * filled; the rest of it is never read by path_attn_ring_hop. */
+path_status_t path_attn_ring_regions(int B, int H, int L, int d, path_dtype_t dt, size_t offsets[4], size_t bytes[4]);
 path_status_t path_attn_ring_local(const void* q, const void* k, const void* v, const void* w, const void* beta,
                                    const void* log_f, void* state, int B, int H, int L, int d, float scale,
                                    path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream);

@@ -105,6 +105,8 @@ def load_library():
     lib.path_decode_step_fox.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp, ci, ci, vp, vp, ci, ci, ci, ctypes.c_float, ci, vp, ctypes.c_size_t, vp]
     lib.path_attn_ring_state_bytes.restype = ctypes.c_size_t
     lib.path_attn_ring_state_bytes.argtypes = [ci, ci, ci, ci]
+    lib.path_attn_ring_regions.restype = ci
+    lib.path_attn_ring_regions.argtypes = [ci, ci, ci, ci, ci, ctypes.POINTER(ctypes.c_size_t), ctypes.POINTER(ctypes.c_size_t)]
     lib.path_attn_ring_local.restype = ci
     lib.path_attn_ring_local.argtypes = [vp, vp, vp, vp, vp, vp, vp, ci, ci, ci, ci, ctypes.c_float, ci, vp, ctypes.c_size_t, vp]
     lib.path_attn_ring_hop.restype = ci
@@ -399,6 +401,14 @@ def path_probe_mfma(sink, waves_per_simd, iters, stream=None, random_operands=Fa
 
 def path_attn_ring_state_bytes(B, H, L, d) -> int:
     return int(load_library().path_attn_ring_state_bytes(B, H, L, d))
+
+
+def path_attn_ring_regions(B, H, L, d, dt):
+    """[(offset, bytes)] of the workspace regions a hop reads: second-level keys, values, super-block products, gate sums."""
+    off = (ctypes.c_size_t * 4)()
+    nb = (ctypes.c_size_t * 4)()
+    _check(load_library().path_attn_ring_regions(B, H, L, d, dt, off, nb))
+    return [(int(off[i]), int(nb[i])) for i in range(4)]
 
 
 def path_attn_ring_local(q, k, v, w, beta, state, workspace, log_f=None, scale=None, stream=None):

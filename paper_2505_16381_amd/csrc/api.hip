@@ -271,6 +271,22 @@ extern "C" size_t path_attn_ring_state_bytes(int B, int H, int L, int d) {
     return (size_t)B * H * NC * 2 * ring_rec_floats(d) * sizeof(float);
 }
 
+// The regions of a segment's workspace that a hop reads -- what has to travel between devices: second-level keys,
+// values, super-block products and (PaTH-FoX) the gate sums, as byte offsets into the workspace and lengths.
+extern "C" path_status_t path_attn_ring_regions(int B, int H, int L, int d, path_dtype_t dt, size_t offsets[4], size_t bytes[4]) {
+    if (!offsets || !bytes) return PATH_ERR_NULL;
+    if (dt != PATH_F32 && dt != PATH_BF16) return PATH_ERR_DTYPE;
+    if (!shape_ok(B, H, L, d)) return PATH_ERR_SHAPE;
+    const size_t es = dt == PATH_BF16 ? 2 : 4;
+    const FwdWorkspace ws = fwd_workspace(B, H, L, d, es);
+    const size_t BH = (size_t)B * H, NC = (size_t)(L + CHUNK - 1) / CHUNK, Lp = NC * CHUNK, NSB = (NC + SBC - 1) / SBC;
+    offsets[0] = ws.kt2; bytes[0] = BH * Lp * d * es;
+    offsets[1] = ws.vt;  bytes[1] = BH * Lp * d * es;
+    offsets[2] = ws.dp2; bytes[2] = BH * NSB * d * d * es;
+    offsets[3] = ws.cum; bytes[3] = BH * Lp * 4;
+    return PATH_OK;
+}
+
 extern "C" path_status_t path_attn_ring_local(const void* q, const void* k, const void* v, const void* w, const void* beta,
                                               const void* log_f, void* state, int B, int H, int L, int d, float scale,
                                               path_dtype_t dt, void* workspace, size_t workspace_bytes, void* stream) {

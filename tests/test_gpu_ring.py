@@ -107,6 +107,32 @@ def test_ring_with_forget_gates(gpu, oracle, dtype, d, lengths):
     assert (lse - lse1).abs().max().item() <= 1e-3
 
 
+def test_hop_reads_only_the_regions_it_names(gpu):
+    """What travels between devices: a receiving buffer that holds only the regions path_attn_ring_regions names
+    (everything else poisoned) gives the same hop as the sender's whole workspace."""
+    torch, pa = gpu
+    B, H, d, Ls = 1, 2, 128, 1088
+    x = si.make_inputs(B, H, 2 * Ls, d, "bf16", 4400, 0.0)
+    dv = {n: torch.from_numpy(a).to("cuda").to(torch.bfloat16).contiguous() for n, a in x.items()}
+    seg = [{n: dv[n][:, :, r * Ls:(r + 1) * Ls].contiguous() for n in dv} for r in range(2)]
+    nbytes = pa.path_attn_workspace_bytes(B, H, Ls, d, pa.PATH_BF16, False)
+    ws = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(2)]
+    st = [torch.empty(pa.path_attn_ring_state_bytes(B, H, Ls, d), dtype=torch.uint8, device="cuda") for _ in range(2)]
+    for r in range(2):
+        pa.path_attn_ring_local(seg[r]["q"], seg[r]["k"], seg[r]["v"], seg[r]["w"], seg[r]["beta"], st[r], ws[r])
+    st_ref = st[1].clone()
+    pa.path_attn_ring_hop(st_ref, B, H, Ls, ws[0], Ls, d, pa.PATH_BF16)
+    recv = torch.full((nbytes,), 0xFF, dtype=torch.uint8, device="cuda")          # NaN patterns everywhere else
+    regions = pa.path_attn_ring_regions(B, H, Ls, d, pa.PATH_BF16)
+    for off, nb in regions[:3]:
+        assert off % 256 == 0 and off + nb <= nbytes
+        recv[off:off + nb].copy_(ws[0][off:off + nb])
+    pa.path_attn_ring_hop(st[1], B, H, Ls, recv, Ls, d, pa.PATH_BF16)
+    torch.cuda.synchronize()
+    assert torch.equal(st[1], st_ref)
+    assert sum(nb for _, nb in regions[:3]) == (2 * Ls * d + 2 * d * d) * 2 * B * H      # 2 L d + ceil(L/1024) d^2 elements per head
+
+
 def test_ring_argument_checks(gpu):
     torch, pa = gpu
     B, H, d = 1, 2, 64

@@ -62,10 +62,12 @@ static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
     w.f = fwd_workspace(B, H, L, d, es);
     size_t off = w.f.total;
     auto take = [&](size_t& field, size_t bytes) { field = off; off = align256(off + bytes); };
-    for (size_t* f : {&w.ktT, &w.vk, &w.doq, &w.doT}) take(*f, BH * Lp * d * es);
+    // (the transposed key tiles ktT, kt2T exist for fp32 operands only: the 16-bit adjoint scan transposes in LDS)
+    take(w.ktT, (es == 4 ? 1 : 0) * BH * Lp * d * es);
+    for (size_t* f : {&w.vk, &w.doq, &w.doT}) take(*f, BH * Lp * d * es);
     take(w.dpt, BH * NC * d * d * es);
     for (size_t* f : {&w.xs, &w.xsT, &w.gs}) take(*f, BH * nslots * CHUNK * d * es);
-    take(w.kt2T, BH * Lp * d * es);
+    take(w.kt2T, (es == 4 ? 1 : 0) * BH * Lp * d * es);
     take(w.dpt2, BH * NSB * d * d * es);
     take(w.kbm, BH * Lp * d * es);
     take(w.rm, BH * NC * d * d * es);

@@ -329,12 +329,33 @@ __global__ __launch_bounds__(256) void bwd_adjoint2_kernel(BwdParams p) {
 }
 
 // ---------------------------------------------------------------------------------------
+// Fragment of the TRANSPOSE of a fragment-order tile (rows q in 32-row halves of DS slabs,
+// contraction c).  Element e of a fragment belongs to contraction index 16 s + acc_row(e, h) of
+// its slab s, in both tiles, so the lane needs tile[q = 16 qs + acc_row(e, h)][c = 32 b + l32],
+// e = 0..7: two transposing reads, of rows 16 qs + 4 h + 0..3 and the same + 8 (in each block of
+// 16 lanes, lane i points at 4 consecutive c of row .. + i/4 and receives column i of the four rows).
+template <typename E, int DS>
+__device__ __forceinline__ typename Tr<E>::Frag ld_tile_frag_tr(const E* tile, int qs, int b, int l32, int h) {
+    static_assert(sizeof(E) == 2, "16-bit transposing reads");
+    typedef short v4s __attribute__((ext_vector_type(4)));
+    const int i = l32 & 15;
+    const E* p = tile + (size_t)((((qs >> 1) * DS + 2 * b + (l32 >> 4)) * 64 + (i & 1) * 32 + 16 * (qs & 1) + 4 * h + (i >> 2)) * 8 + 4 * ((i >> 1) & 1));
+    union { v4s v[2]; typename Tr<E>::Frag f; } u;
+    u.v[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p));
+    u.v[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p + 64));
+    return u.f;
+}
+
+// ---------------------------------------------------------------------------------------
 // The adjoint scan for 16-bit operands with TWO workgroups per CU: the same arithmetic as
 // bwd_adjoint2_kernel, arranged to fit 256 registers per wave and one 80 KB stage per workgroup, so that
 // the second workgroup's waves fill the gaps of the first (tile requests, LDS latencies, the dependent
 // chain logits -> exponentials -> update) instead of hand-interleaved halves of one wave.  Per step: one
 // request for the chunk's four tiles, no prefetch; the state fragments of a new block are fetched while
 // those tiles are on their way; the operand copy of g exists only while a block boundary needs it.
+// The fragments of Kb^T for g^T += Kb^T dS^T are read out of the key tile itself with transposing LDS reads
+// (three tiles per step instead of four: the transposed key tiles are neither written nor copied; as a fourth
+// tile they cost 4 % of this kernel).  No copy is in flight while a step computes, so those reads wait for nothing.
 template <typename TIO, int D, bool FOX>
 __global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) {
     using C = Adj2Cfg<TIO, D>;
@@ -347,8 +368,7 @@ __global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) 
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     Frag* sK = reinterpret_cast<Frag*>(smem);
     const FragV* sV = reinterpret_cast<const FragV*>(sK + KVF);
-    const Frag* sKT = sK + 2 * KVF;
-    const Frag* sDP = sK + 3 * KVF;
+    const Frag* sDP = sK + 2 * KVF;
 
     const int BH = p.B * p.H, NC = p.NC;
     const int ntiles = (NC + 1) / 2;
@@ -394,11 +414,10 @@ __global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) 
             const size_t bhc = (size_t)bh * NC + j;
             async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2 : p.kt) + bhc * CHUNK * D), sK, tid, wv);
             async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const TIO*>(p.vk) + bhc * CHUNK * D), sK + KVF, tid, wv);
-            async_copy_tile<256, KVF>(reinterpret_cast<const Frag*>(reinterpret_cast<const T*>(far ? p.kt2T : p.ktT) + bhc * CHUNK * D), sK + 2 * KVF, tid, wv);
             if (j > 0 && first) {
                 const T* src = far ? reinterpret_cast<const T*>(p.dpt2) + ((size_t)bh * nsb + j / SBC) * (size_t)D * D
                                    : reinterpret_cast<const T*>(p.dpt) + bhc * (size_t)D * D;
-                async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(src), sK + 3 * KVF, tid, wv);
+                async_copy_tile<256, DPF>(reinterpret_cast<const Frag*>(src), sK + 2 * KVF, tid, wv);
             }
         }
         if (mine && first) {                       // the state of the block that starts here
@@ -460,7 +479,7 @@ __global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) 
             for (int b = 0; b < DB; ++b) {
                 Frag ta[SPB];
 #pragma unroll
-                for (int u = 0; u < SPB; ++u) ta[u] = sKT[(b * QS + kb * SPB + u) * 64 + lane];
+                for (int u = 0; u < SPB; ++u) ta[u] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sK), kb * SPB + u, b, l32, h);
 #pragma unroll
                 for (int u = 0; u < SPB; ++u) Gm[b] = Tr<T>::mma(ta[u], dSh[u], Gm[b]);
             }
@@ -518,23 +537,6 @@ __global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) 
 // space of the doT tile; the dO^T fragments are then read out of the doq tile with the
 // transposing LDS read.
 //
-// Fragment of the TRANSPOSE of a fragment-order tile (rows q in 32-row halves of DS slabs,
-// contraction c).  Element e of a fragment belongs to contraction index 16 s + acc_row(e, h) of
-// its slab s, in both tiles, so the lane needs tile[q = 16 qs + acc_row(e, h)][c = 32 b + l32],
-// e = 0..7: two transposing reads, of rows 16 qs + 4 h + 0..3 and the same + 8 (in each block of
-// 16 lanes, lane i points at 4 consecutive c of row .. + i/4 and receives column i of the four rows).
-template <typename E, int DS>
-__device__ __forceinline__ typename Tr<E>::Frag ld_tile_frag_tr(const E* tile, int qs, int b, int l32, int h) {
-    static_assert(sizeof(E) == 2, "16-bit transposing reads");
-    typedef short v4s __attribute__((ext_vector_type(4)));
-    const int i = l32 & 15;
-    const E* p = tile + (size_t)((((qs >> 1) * DS + 2 * b + (l32 >> 4)) * 64 + (i & 1) * 32 + 16 * (qs & 1) + 4 * h + (i >> 2)) * 8 + 4 * ((i >> 1) & 1));
-    union { v4s v[2]; typename Tr<E>::Frag f; } u;
-    u.v[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p));
-    u.v[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) v4s*)(p + 64));
-    return u.f;
-}
-
 template <typename TIO, int D> struct Key2Cfg {
     typedef typename Compute<TIO>::type T;
     static constexpr int FE = Tr<T>::FE;
@@ -1306,7 +1308,7 @@ static hipError_t launch_scan_t(const BwdParams& p, int stages, hipStream_t st) 
     if (p.cum) {       // PaTH-FoX instantiations
         if (stages & BWD_STAGE_SCAN) {
             if constexpr (sizeof(typename Compute<TIO>::type) == 2) {
-                const size_t lite_bytes = (size_t)Adj2Cfg<TIO, D>::STAGE_FRAGS * 16;
+                const size_t lite_bytes = (size_t)(2 * Adj2Cfg<TIO, D>::KV_FRAGS + Adj2Cfg<TIO, D>::DP_FRAGS) * 16;      // kt | vk | dpt
                 if ((e = set_smem(&bwd_adjoint2_lite_kernel<TIO, D, true>, lite_bytes)) != hipSuccess) return e;
                 hipLaunchKernelGGL((bwd_adjoint2_lite_kernel<TIO, D, true>), grid_adj, dim3(256), lite_bytes, st, p);
             } else {
@@ -1324,7 +1326,7 @@ static hipError_t launch_scan_t(const BwdParams& p, int stages, hipStream_t st) 
     } else {
         if (stages & BWD_STAGE_SCAN) {
             if constexpr (sizeof(typename Compute<TIO>::type) == 2) {
-                const size_t lite_bytes = (size_t)Adj2Cfg<TIO, D>::STAGE_FRAGS * 16;
+                const size_t lite_bytes = (size_t)(2 * Adj2Cfg<TIO, D>::KV_FRAGS + Adj2Cfg<TIO, D>::DP_FRAGS) * 16;      // kt | vk | dpt
                 if ((e = set_smem(&bwd_adjoint2_lite_kernel<TIO, D, false>, lite_bytes)) != hipSuccess) return e;
                 hipLaunchKernelGGL((bwd_adjoint2_lite_kernel<TIO, D, false>), grid_adj, dim3(256), lite_bytes, st, p);
             } else {

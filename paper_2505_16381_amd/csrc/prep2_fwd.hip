@@ -75,7 +75,8 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
         const Frag* k1 = stage + (size_t)(c & (NBUF - 1)) * (KVF + DPF);
         const Frag* dpn = k1 + KVF;                                                                                  // (rows b, contr a) = -dP[a][b]
         Frag* k2 = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2) + bhc * (size_t)CHUNK * D);
-        Frag* k2T = (BWD && p.kt2T) ? reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2T) + bhc * (size_t)CHUNK * D) : nullptr;
+        // (the transposed arrangement of the second-level keys: fp32 operands only, as for the chunk-level ones)
+        Frag* k2T = (BWD && p.kt2T && sizeof(T) == 4) ? reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.kt2T) + bhc * (size_t)CHUNK * D) : nullptr;
         if (BWD && p.rm) {      // backward only: R_c = I - E_c, row-major [a][b]
             typedef typename Tr<T>::Vec4 TVec4;
             T* rdst = reinterpret_cast<T*>(p.rm) + bhc * (size_t)D * D;

@@ -491,10 +491,11 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
         if (BWD && p.ktT) {
             // ---- backward-only tiles ------------------------------------------------------------
             constexpr int QS = CHUNK / KW;
-            // ktT (rows c, contraction s) = Kb[s][c]: accumulate with rows s, lane c
+            // ktT (rows c, contraction s) = Kb[s][c]: accumulate with rows s, lane c.  fp32 operands only: the 16-bit
+            // adjoint scan reads these fragments out of the key tile with transposing LDS reads.
             Frag* tdst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.ktT) + bhc * (size_t)CHUNK * D);
 #pragma unroll
-            for (int i = 0; i < NB / 4; ++i) {
+            for (int i = 0; i < (sizeof(T) == 4 ? NB / 4 : 0); ++i) {
                 const int blk = wv + 4 * i;
                 const int cb = blk >> 1, sb = blk & 1;
                 f32x16 acc = times_wt(Yt, 32 * sb, cb);

@@ -65,10 +65,10 @@ static BwdWorkspace bwd_workspace(int B, int H, int L, int d, size_t es) {
     // (the transposed key tiles ktT, kt2T exist for fp32 operands only: the 16-bit adjoint scan transposes in LDS)
     take(w.ktT, (es == 4 ? 1 : 0) * BH * Lp * d * es);
     for (size_t* f : {&w.vk, &w.doq, &w.doT}) take(*f, BH * Lp * d * es);
-    take(w.dpt, BH * NC * d * d * es);
+    take(w.dpt, (es == 4 ? 1 : 0) * BH * NC * d * d * es);       // (fp32 operands only, like ktT)
     for (size_t* f : {&w.xs, &w.xsT, &w.gs}) take(*f, BH * nslots * CHUNK * d * es);
     take(w.kt2T, (es == 4 ? 1 : 0) * BH * Lp * d * es);
-    take(w.dpt2, BH * NSB * d * d * es);
+    take(w.dpt2, (es == 4 ? 1 : 0) * BH * NSB * d * d * es);
     take(w.kbm, BH * Lp * d * es);
     take(w.rm, BH * NC * d * d * es);
     take(w.dk2, BH * Lp * d * 4);
@@ -476,8 +476,10 @@ static path_status_t bwd_run(BwdMode mode, int stages, const UserLayout& ul, con
     // 2.-4. delta, adjoint scan over key chunks, key-side reductions
     BwdParams bp = {};
     bp.q = q; bp.k = k; bp.v = v; bp.w = w; bp.beta = beta; bp.o = o; bp.dO = d_o; bp.lse = lse;
-    bp.kt = fp.kt; bp.vk = fp.vk; bp.ktT = fp.ktT; bp.dpt = fp.dpt; bp.xs = fp.xs; bp.xsT = fp.xsT;
-    bp.kt2 = fp.kt2; bp.kt2T = fp.kt2T; bp.dpt2 = fp.dpt2; bp.dk2 = F(ws.dk2); bp.dchain = F(ws.dchain);
+    bp.kt = fp.kt; bp.vk = fp.vk; bp.ktT = fp.ktT; bp.xs = fp.xs; bp.xsT = fp.xsT;
+    bp.kt2 = fp.kt2; bp.kt2T = fp.kt2T;
+    // the 16-bit adjoint scan reads the transposed arrangements out of the forward's own product tiles
+    bp.dpt = bf ? fp.dp : fp.dpt; bp.dpt2 = bf ? fp.dp2 : fp.dpt2; bp.dk2 = F(ws.dk2); bp.dchain = F(ws.dchain);
     bp.doq = base + ws.doq; bp.doT = base + ws.doT; bp.gs = base + ws.gs;
     bp.delta = F(ws.delta); bp.lse2p = F(ws.lse2p); bp.dqb = F(ws.dqb); bp.dkb = F(ws.dkb); bp.dvp = F(ws.dvp); bp.ddp = F(ws.ddp);
     bp.B = B; bp.H = H; bp.L = L; bp.NC = NC; bp.scale = scale; bp.ul = ul;

@@ -355,7 +355,9 @@ __device__ __forceinline__ typename Tr<E>::Frag ld_tile_frag_tr(const E* tile, i
 // those tiles are on their way; the operand copy of g exists only while a block boundary needs it.
 // The fragments of Kb^T for g^T += Kb^T dS^T are read out of the key tile itself with transposing LDS reads
 // (three tiles per step instead of four: the transposed key tiles are neither written nor copied; as a fourth
-// tile they cost 4 % of this kernel).  No copy is in flight while a step computes, so those reads wait for nothing.
+// tile they cost 4 % of this kernel), and likewise the fragments of -dP in the arrangement (rows a, contraction b)
+// out of the forward's tile (rows b, contraction a): p.dpt / p.dpt2 point at the FORWARD's tiles here.  No copy is in
+// flight while a step computes, so those reads wait for nothing.
 template <typename TIO, int D, bool FOX>
 __global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) {
     using C = Adj2Cfg<TIO, D>;
@@ -439,7 +441,7 @@ __global__ __launch_bounds__(256, 2) void bwd_adjoint2_lite_kernel(BwdParams p) 
                 for (int s0 = 0; s0 < DS; s0 += 4) {
                     Frag pa[4];
 #pragma unroll
-                    for (int u = 0; u < 4; ++u) pa[u] = sDP[(b * DS + s0 + u) * 64 + lane];
+                    for (int u = 0; u < 4; ++u) pa[u] = ld_tile_frag_tr<T, DS>(reinterpret_cast<const T*>(sDP), s0 + u, b, l32, h);
 #pragma unroll
                     for (int u = 0; u < 4; ++u) Gm[b] = Tr<T>::mma(pa[u], Gb[s0 + u], Gm[b]);
                 }

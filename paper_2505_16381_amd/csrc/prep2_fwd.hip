@@ -171,7 +171,7 @@ __global__ __launch_bounds__(256) void prep2_fwd_kernel(FwdParams p) {
         const int blk = wv + 4 * o, bb = blk / DB, ab = blk % DB;
         Frag fin[SPB];
         pack_block<T>(Fm[o], fin);                              // tile piece (rows a, contraction b)
-        if (BWD && p.dpt2) {      // backward only: -(I - P_superblock) in the arrangement (rows a, contraction b)
+        if (BWD && p.dpt2 && sizeof(T) == 4) {      // backward, fp32 operands only: -(I - P_superblock) in the arrangement (rows a, contraction b)
             Frag* dt = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dpt2) + ((size_t)bh * gridDim.x + sb) * (size_t)D * D);
 #pragma unroll
             for (int s = 0; s < SPB; ++s) {

@@ -470,9 +470,9 @@ __global__ __launch_bounds__(256, (PrepCfg<TIO, D>::WGS_PER_CU)) void prep_fwd_k
 #pragma unroll
             for (int s2 = 0; s2 < SPB; ++s2) __builtin_nontemporal_store(fr[s2], &vdst[(((size_t)sb * (D / 32) + cb) * SPB + s2) * 64 + lane]);   // [key half][d block][slab]
         }
-        if (BWD && p.dpt) {
+        if (BWD && p.dpt && sizeof(T) == 4) {
             // -dP in the transposed arrangement (rows c, contraction b) = -dP[c][b]: accumulate with rows b,
-            // lane c.  Read by the backward's adjoint scan.
+            // lane c.  Read by the backward's adjoint scan for fp32 operands (the 16-bit one transposes in LDS).
             Frag* pdst = reinterpret_cast<Frag*>(reinterpret_cast<T*>(p.dpt) + bhc * (size_t)D * D);
             constexpr int NBP = (D / 32) * (D / 32);
 #pragma unroll

@@ -80,6 +80,28 @@ def test_ring_of_segments_matches_the_whole_sequence(gpu, oracle, dtype, d, leng
         assert (lse - lse1).abs().max().item() <= 1e-3
 
 
+def test_ring_at_the_headline_head_shape(gpu, oracle):
+    """Four segments of 2048 tokens (the headline sequence split over four devices), d = 128, eight heads -- one per
+    XCD: bit-identical to the one-device forward, and rows on both sides of every segment edge against the oracle."""
+    torch, pa = gpu
+    B, H, d, lengths = 1, 8, 128, [2048] * 4
+    L = sum(lengths)
+    x = si.make_inputs(B, H, L, d, "bf16", 4500, 0.0)
+    dv = {n: torch.from_numpy(a).to("cuda").to(torch.bfloat16).contiguous() for n, a in x.items()}
+    scale = d ** -0.5
+    o, lse = _ring_forward(torch, pa, dv, lengths, d, pa.PATH_BF16, scale)
+    o1, lse1 = pa.path_attn_fwd(dv["q"], dv["k"], dv["v"], dv["w"], dv["beta"], scale=scale)
+    torch.cuda.synchronize()
+    assert torch.equal(o, o1) and torch.equal(lse, lse1)
+    rows = np.unique(np.concatenate([np.arange(e - 2, e + 3) for e in (2048, 4096, 6144)] + [[0, 1, 2047, 8190, 8191]]
+                                    + [np.random.default_rng(45).integers(0, L, 40)]))
+    o_ref, lse_ref = oracle.fwd(x["q"], x["k"], x["v"], x["w"], x["beta"], scale, rows=rows)
+    eo = np.abs(o[:, :, rows].float().cpu().numpy().astype(np.float64) - o_ref).max()
+    el = np.abs(lse[:, :, rows].cpu().numpy().astype(np.float64) - lse_ref).max()
+    print(f"[ring 4 x 2048, d=128, 8 heads] {len(rows)} rows against the oracle: o {eo:.2e} lse {el:.2e}", flush=True)
+    assert eo <= 2e-2 and el <= 1e-3
+
+
 @pytest.mark.parametrize("dtype,d,lengths", [("bf16", 128, [1024, 1088, 300]), ("fp32", 64, [320, 448, 130])])
 def test_ring_with_forget_gates(gpu, oracle, dtype, d, lengths):
     """PaTH-FoX over the ring: every segment counts its gate sums from its own start; a hop adds the totals of the
